@@ -1,0 +1,171 @@
+/*
+ * fastgs.h -- C ABI of the MI355X (gfx950) FastGS rasterizer hot path.
+ *
+ * What it computes (paper: FastGS, Sec. 3 "Background: 3D Gaussian Splatting", Sec. 4.2
+ * "Multi-view Consistent Densification", Sec. 4.4 "Compact Box" for the 3-sigma rule):
+ *   fs_preprocess        projection of every Gaussian to a screen-space splat   (Eqs. (2), (3))
+ *   fs_bin_sort          Gaussian-tile pairs, ordered by (tile, depth)          (Sec. 3, "sorted by depth")
+ *   fs_render_fwd        front-to-back alpha compositing                        (Eqs. (4), (5))
+ *   fs_l1_grad           L1 term of the training loss and dL/dC                 (Sec. 4.5)
+ *   fs_render_bwd        gradient of a loss w.r.t. every Gaussian parameter     (chain rule of Eqs. (2)-(5))
+ *   fs_error_mask        per-pixel L1 error map and high-error mask             (Sec. 4.2, first three equations)
+ *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
+ *                        one view per call                                      (Sec. 4.2, Eq. for s_d)
+ *
+ * General rules
+ *   - Every pointer inside the structs below is a DEVICE pointer (HIP, the ctx's device) owned
+ *     by the caller unless marked "ctx-owned"; structs themselves live in host memory.
+ *   - Arrays are dense, row-major, 4-byte aligned (16-byte for [n,4] float arrays); fp32 unless
+ *     stated.  Nothing is freed or reallocated on the caller's behalf.
+ *   - Work is enqueued on the stream given to fs_create.  fs_bin_sort reads one 8-byte value
+ *     back (the pair count) and therefore synchronises that stream; all other calls return as
+ *     soon as the work is enqueued.
+ *   - Every call returns FS_OK (0) or a negative fs_status and never throws or aborts;
+ *     fs_last_error gives a message for the last failure on that ctx.
+ *   - n = 0 Gaussians and P = 0 pairs are valid (the image is the background).
+ *   - A ctx must not be used from two threads at once.
+ */
+#ifndef FASTGS_H
+#define FASTGS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FS_OK = 0,
+    FS_EINVAL = -1,    /* null pointer, bad shape / degree / size                     */
+    FS_ENOMEM = -2,    /* growing the ctx's scratch memory failed                      */
+    FS_EHIP = -3,      /* a HIP runtime call failed (message has the HIP error name)  */
+    FS_ECAPACITY = -4  /* pair count does not fit the 32-bit index space              */
+} fs_status;
+
+enum { FS_SCORE_WEIGHT = 0, FS_SCORE_ALPHA = 1 };
+enum { FS_MASK_MEAN_STD = 0, FS_MASK_MINMAX_TAU = 1 };
+
+/* Conventions the paper leaves open; fs_default_config fills in the documented defaults. */
+typedef struct {
+    int32_t tile;       /* tile edge in pixels; only 16 is supported                                  */
+    float z_near;       /* Gaussians with camera depth <= z_near are culled (0.2)                     */
+    float lowpass;      /* added to both diagonal entries of Sigma_2D, in px^2 (0.3)                  */
+    float alpha_min;    /* alphas below it are not blended (1/255)                                    */
+    float alpha_max;    /* alpha cap (0.99)                                                           */
+    float T_min;        /* a pixel stops before its transmittance would fall below this (1e-4)        */
+    float bg[3];        /* background colour                                                          */
+    float jclamp;       /* t_x/t_z, t_y/t_z used inside J are limited to jclamp*tan(fov/2); <=0: off (1.3) */
+    int32_t score_mode; /* FS_SCORE_WEIGHT: count where alpha*T > alpha_min; FS_SCORE_ALPHA: where blended */
+} fs_config;
+
+/* Pinhole camera: x_cam = R x_world + t (the paper's viewing transformation W);
+ * pixel = (fx x/z + cx, fy y/z + cy); pixel (u,v) is sampled at (u+0.5, v+0.5). Host struct. */
+typedef struct {
+    int32_t width, height;
+    float fx, fy, cx, cy;
+    float R[9]; /* row-major */
+    float t[3];
+} fs_camera;
+
+/* The scene (Sec. 3): mean mu, scale s, rotation r, opacity sigma, SH colour coefficients c. */
+typedef struct {
+    int64_t n;
+    int32_t sh_degree;      /* 0..3, (sh_degree+1)^2 coefficients per channel                */
+    const float *means;     /* [n,3] world space                                             */
+    const float *scales;    /* [n,3] activated (> 0)                                         */
+    const float *quats;     /* [n,4] (w,x,y,z), unit length (not re-normalised)              */
+    const float *opacities; /* [n]   activated, in (0,1]                                     */
+    const float *sh;        /* [n,(sh_degree+1)^2,3]                                         */
+} fs_gaussians;
+
+/* Output of fs_preprocess, caller-owned.  Culled Gaussians get zeros everywhere. */
+typedef struct {
+    float *mean2d;           /* [n,2] mu_2D in pixels                                         */
+    float *depth;            /* [n]   camera-space z                                          */
+    float *conic_opacity;    /* [n,4] Sigma_2D^-1 as (a, b, c) with q = a dx^2 + 2 b dx dy + c dy^2, then sigma */
+    float *rgb;              /* [n,3] view-dependent colour max(0, 0.5 + SH)                  */
+    uint16_t *rect;          /* [n,4] tile rectangle x0,y0,x1,y1, half-open                   */
+    uint32_t *tiles_touched; /* [n]   (x1-x0)*(y1-y0); 0 = culled                             */
+    uint8_t *clamped;        /* [n,3] 1 where the colour channel was clamped at 0             */
+} fs_projected;
+
+/* Output of fs_bin_sort.  Arrays are ctx-owned and stay valid until the next fs_bin_sort or
+ * fs_destroy on the same ctx. */
+typedef struct {
+    int64_t num_pairs;            /* P, host-visible on return                                        */
+    const uint64_t *keys_sorted;  /* [P] tile_id << 32 | bits(depth), ascending; ties by Gaussian index */
+    const uint32_t *gauss_sorted; /* [P] Gaussian index of each entry                                 */
+    const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
+} fs_bins;
+
+/* Output of fs_render_bwd, caller-owned, OVERWRITTEN (not accumulated). dconic and drgb may be
+ * NULL (the ctx then keeps them in its own scratch). */
+typedef struct {
+    float *dmeans;     /* [n,3]              */
+    float *dscales;    /* [n,3]              */
+    float *dquats;     /* [n,4]              */
+    float *dopacities; /* [n]                */
+    float *dsh;        /* [n,(deg+1)^2,3]    */
+    float *dmean2d;    /* [n,2] dL/dmu_2D (the screen-space positional gradient used by densification) */
+    float *dconic;     /* [n,3] dL/d(a,b,c) of conic_opacity, b counted with its factor 2; may be NULL */
+    float *drgb;       /* [n,3] dL/d rgb; may be NULL                                                   */
+} fs_grads;
+
+typedef struct fs_ctx fs_ctx;
+
+/* Fills *cfg with the defaults listed in fs_config. */
+void fs_default_config(fs_config *cfg);
+
+/* Creates a context bound to HIP device `device` and stream `hip_stream` (a hipStream_t, NULL =
+ * the default stream).  cfg may be NULL (defaults).  The ctx owns scratch device memory that
+ * grows on demand and is released by fs_destroy.  Errors: FS_EINVAL (bad cfg: tile != 16,
+ * alpha_min <= 0, ...), FS_EHIP. */
+int fs_create(fs_ctx **out, int device, void *hip_stream, const fs_config *cfg);
+void fs_destroy(fs_ctx *ctx);
+const char *fs_last_error(const fs_ctx *ctx);
+
+/* Step a1 (Eqs. (2),(3); 3-sigma rule): camera-space mean, Sigma_3D = R S S^T R^T,
+ * Sigma_2D = upper-left 2x2 of J W Sigma_3D W^T J^T (+ low-pass), its inverse, mu_2D,
+ * radius ceil(3 sqrt(lambda_max)), tile rectangle, SH colour.  Errors: FS_EINVAL, FS_EHIP. */
+int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_projected *out);
+
+/* Steps a2-a5: exclusive scan of tiles_touched, one 64-bit key per (Gaussian, tile) pair, stable
+ * LSD radix sort by key, per-tile ranges.  n = number of Gaussians in `proj`.
+ * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (P >= 2^32). */
+int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int64_t n, fs_bins *out);
+
+/* Step a6 (Eqs. (4),(5)): image [3,H,W] planar, final_T [H,W] (transmittance left at each pixel),
+ * n_contrib [H,W] (1-based position, in the pixel's tile list, of the last Gaussian blended).
+ * All three are fully overwritten. */
+int fs_render_fwd(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
+                  float *image, float *final_T, uint32_t *n_contrib);
+
+/* Step a7: loss = mean |image - target| over 3*H*W values; dL_dimage = sign(image-target)/(3HW).
+ * loss_out (device pointer to one double) may be NULL. */
+int fs_l1_grad(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
+               float *dL_dimage, double *loss_out);
+
+/* Steps a8+a9: back-to-front gradient of the compositing, reduced per Gaussian, then chained
+ * through the projection to the scene parameters.  final_T / n_contrib are fs_render_fwd's. */
+int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, const fs_projected *proj,
+                  const fs_bins *bins, const float *final_T, const uint32_t *n_contrib,
+                  const float *dL_dimage, fs_grads *out);
+
+/* Step a10: e = mean over channels of |image - target|; threshold t = mean(e) + k*std(e)
+ * (FS_MASK_MEAN_STD; population std, fp64 accumulation) or min(e) + k*(max(e)-min(e))
+ * (FS_MASK_MINMAX_TAU, i.e. min-max normalised e > k); mask = e > t (uint8 0/1, [H,W]).
+ * threshold_out (device pointer to one float) may be NULL. */
+int fs_error_mask(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
+                  int32_t rule, float k, uint8_t *mask, float *threshold_out);
+
+/* Step a11: for one view, counts[i] += number of pixels p with mask[p] = 1 at which Gaussian i
+ * is blended by the forward pass (and, in FS_SCORE_WEIGHT mode, with alpha_i T_i > alpha_min).
+ * counts [n] int32 is ACCUMULATED: zero it before the first view; s_d = counts / K. */
+int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
+                        const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
+                        int32_t *counts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTGS_H */

@@ -1,0 +1,285 @@
+"""TEST INFRASTRUCTURE -- not part of the product.
+
+numpy front end of the plain-C CPU oracle (fastgs_oracle.c).  Only tests, the smoke check
+and the benchmark's CPU-baseline leg may import this package; the HIP path never does.
+
+`Oracle(np.float32)` is the pinned-operation-order build used for parity with the GPU;
+`Oracle(np.float64)` is the build used for finite differences and closed forms.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fastgs_oracle.c")
+_LIB = os.path.join(_HERE, "libfastgs_oracle.so")
+
+
+def _cpu_has_fma() -> bool:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("flags"):
+                    return " fma" in line
+    except OSError:
+        pass
+    return False
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no contraction).  Returns the .so path."""
+    deps = [_SRC, os.path.join(_HERE, "fastgs_oracle_impl.h")]
+    if (not force and os.path.exists(_LIB)
+            and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-Wall", "-Wno-unused-function", "-o", _LIB, _SRC, "-lm"]
+    if _cpu_has_fma():
+        cmd.insert(1, "-mfma")
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_exclusive_scan.restype = ctypes.c_uint64
+        _lib.orc_emit_pairs.restype = ctypes.c_uint64
+        _lib.orc_pairs_bruteforce.restype = ctypes.c_uint64
+        _lib.orc_exp_neg_f32.restype = ctypes.c_float
+        _lib.orc_exp_neg_f32.argtypes = [ctypes.c_float]
+        for sfx, ct in (("_f32", ctypes.c_float), ("_f64", ctypes.c_double)):
+            getattr(_lib, "orc_l1" + sfx).restype = ctypes.c_double
+            getattr(_lib, "orc_error_mask" + sfx).restype = ct
+            getattr(_lib, "orc_count_evals" + sfx).restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+@dataclass
+class Config:
+    """Blending / projection conventions the paper leaves open (see the design notes)."""
+    tile: int = 16
+    z_near: float = 0.2
+    lowpass: float = 0.3
+    alpha_min: float = 1.0 / 255.0
+    alpha_max: float = 0.99
+    T_min: float = 1e-4
+    bg: tuple = (0.0, 0.0, 0.0)
+    jclamp: float = 1.3
+    score_mode: int = 0  # 0 = WEIGHT (alpha*T > alpha_min), 1 = ALPHA
+
+    def array(self, dtype):
+        # fp32 build: constants are the fp32 roundings (1/255 computed in fp32 division)
+        if dtype == np.float32:
+            amin = np.float32(self.alpha_min)
+            if self.alpha_min == 1.0 / 255.0:
+                amin = np.float32(1.0) / np.float32(255.0)
+        else:
+            amin = self.alpha_min
+        return np.array([self.z_near, self.lowpass, amin, self.alpha_max, self.T_min,
+                         self.bg[0], self.bg[1], self.bg[2], self.jclamp], dtype=dtype)
+
+
+def cam_array(cam, dtype):
+    return np.concatenate([[cam.fx, cam.fy, cam.cx, cam.cy],
+                           np.asarray(cam.R, dtype=np.float64).reshape(9),
+                           np.asarray(cam.t, dtype=np.float64).reshape(3)]).astype(dtype)
+
+
+@dataclass
+class Projected:
+    mean2d: np.ndarray
+    depth: np.ndarray
+    conic_opacity: np.ndarray
+    rgb: np.ndarray
+    rect: np.ndarray          # int32 [n,4] x0,y0,x1,y1 (tiles, half-open)
+    tiles_touched: np.ndarray  # uint32 [n]
+    clamped: np.ndarray       # uint8 [n,3]
+    radius: np.ndarray        # int32 [n]
+
+
+@dataclass
+class Bins:
+    num_pairs: int
+    keys_sorted: np.ndarray   # uint64 [P]
+    gauss_sorted: np.ndarray  # uint32 [P]
+    tile_ranges: np.ndarray   # uint32 [T,2]
+    keys_unsorted: np.ndarray
+    gauss_unsorted: np.ndarray
+    offsets: np.ndarray
+
+
+class Oracle:
+    def __init__(self, dtype=np.float32, config: Config | None = None):
+        self.dtype = np.dtype(dtype).type
+        assert self.dtype in (np.float32, np.float64)
+        self.sfx = "_f32" if self.dtype == np.float32 else "_f64"
+        self.cfg = config or Config()
+        self.L = lib()
+
+    # -- helpers ---------------------------------------------------------------------
+    def _f(self, name):
+        return getattr(self.L, name + self.sfx)
+
+    def _a(self, x):
+        return np.ascontiguousarray(x, dtype=self.dtype)
+
+    def _tiles(self, cam):
+        t = self.cfg.tile
+        return (cam.width + t - 1) // t, (cam.height + t - 1) // t
+
+    @staticmethod
+    def _tl(tile_list):
+        if tile_list is None:
+            return None, 0
+        tl = np.ascontiguousarray(tile_list, dtype=np.int32)
+        return tl, int(tl.size)
+
+    # -- a1 --------------------------------------------------------------------------
+    def preprocess(self, sc, cam) -> Projected:
+        n, dt = sc.n, self.dtype
+        out = Projected(np.zeros((n, 2), dt), np.zeros(n, dt), np.zeros((n, 4), dt), np.zeros((n, 3), dt),
+                        np.zeros((n, 4), np.int32), np.zeros(n, np.uint32), np.zeros((n, 3), np.uint8),
+                        np.zeros(n, np.int32))
+        self._f("orc_preprocess")(
+            ctypes.c_int64(n), ctypes.c_int(sc.sh_degree), _p(self._a(sc.means)), _p(self._a(sc.scales)),
+            _p(self._a(sc.quats)), _p(self._a(sc.opacities)), _p(self._a(sc.sh)),
+            ctypes.c_int(cam.width), ctypes.c_int(cam.height), _p(cam_array(cam, dt)),
+            _p(self.cfg.array(dt)), ctypes.c_int(self.cfg.tile),
+            _p(out.mean2d), _p(out.depth), _p(out.conic_opacity), _p(out.rgb), _p(out.rect),
+            _p(out.tiles_touched), _p(out.clamped), _p(out.radius))
+        return out
+
+    # -- a2..a5 ----------------------------------------------------------------------
+    def bin_sort(self, proj: Projected, cam) -> Bins:
+        n = proj.depth.shape[0]
+        TX, TY = self._tiles(cam)
+        offsets = np.zeros(n, np.uint64)
+        P = int(self.L.orc_exclusive_scan(ctypes.c_int64(n), _p(proj.tiles_touched), _p(offsets)))
+        depth32 = np.ascontiguousarray(proj.depth, dtype=np.float32)
+        keys = np.zeros(max(P, 1), np.uint64)
+        vals = np.zeros(max(P, 1), np.uint32)
+        P2 = int(self.L.orc_emit_pairs(ctypes.c_int64(n), _p(proj.rect), _p(depth32), ctypes.c_int(TX),
+                                       _p(keys), _p(vals)))
+        assert P2 == P
+        keys, vals = keys[:P], vals[:P]
+        ks, vs = keys.copy(), vals.copy()
+        self.L.orc_sort_pairs(ctypes.c_uint64(P), _p(ks), _p(vs))
+        ranges = np.zeros((TX * TY, 2), np.uint32)
+        self.L.orc_tile_ranges(ctypes.c_uint64(P), _p(ks), ctypes.c_int(TX * TY), _p(ranges))
+        return Bins(P, ks, vs, ranges, keys, vals, offsets)
+
+    def pairs_bruteforce(self, proj: Projected, cam):
+        n = proj.depth.shape[0]
+        TX, TY = self._tiles(cam)
+        hit = np.zeros((n, TY * TX), np.uint8)
+        m2 = np.ascontiguousarray(proj.mean2d, dtype=np.float32)
+        tot = int(self.L.orc_pairs_bruteforce(ctypes.c_int64(n), _p(m2), _p(proj.radius), ctypes.c_int(cam.width),
+                                              ctypes.c_int(cam.height), ctypes.c_int(self.cfg.tile), _p(hit)))
+        return tot, hit
+
+    # -- a6 --------------------------------------------------------------------------
+    def render_fwd(self, proj: Projected, bins: Bins, cam, tile_list=None):
+        H, W, dt = cam.height, cam.width, self.dtype
+        image = np.zeros((3, H, W), dt)
+        final_T = np.ones((H, W), dt)
+        n_contrib = np.zeros((H, W), np.uint32)
+        tl, ntl = self._tl(tile_list)
+        self._f("orc_render_fwd")(
+            _p(proj.mean2d), _p(proj.conic_opacity), _p(proj.rgb), _p(bins.gauss_sorted), _p(bins.tile_ranges),
+            ctypes.c_int(W), ctypes.c_int(H), _p(self.cfg.array(dt)), ctypes.c_int(self.cfg.tile),
+            _p(tl), ctypes.c_int(ntl), _p(image), _p(final_T), _p(n_contrib))
+        return image, final_T, n_contrib
+
+    def count_evals(self, proj, bins, cam, tile_list=None) -> int:
+        tl, ntl = self._tl(tile_list)
+        return int(self._f("orc_count_evals")(
+            _p(proj.mean2d), _p(proj.conic_opacity), _p(bins.gauss_sorted), _p(bins.tile_ranges),
+            ctypes.c_int(cam.width), ctypes.c_int(cam.height), _p(self.cfg.array(self.dtype)),
+            ctypes.c_int(self.cfg.tile), _p(tl), ctypes.c_int(ntl)))
+
+    # -- a7 --------------------------------------------------------------------------
+    def l1(self, image, target):
+        H, W = image.shape[1:]
+        g = np.zeros_like(image)
+        loss = float(self._f("orc_l1")(_p(self._a(image)), _p(self._a(target)), ctypes.c_int(W),
+                                       ctypes.c_int(H), _p(g)))
+        return loss, g
+
+    # -- a8 --------------------------------------------------------------------------
+    def render_bwd(self, proj: Projected, bins: Bins, cam, dL_dimage, tile_list=None):
+        n, dt = proj.depth.shape[0], self.dtype
+        d_mean2d = np.zeros((n, 2)); d_conic = np.zeros((n, 3)); d_op = np.zeros(n); d_rgb = np.zeros((n, 3))
+        tl, ntl = self._tl(tile_list)
+        self._f("orc_render_bwd")(
+            _p(proj.mean2d), _p(proj.conic_opacity), _p(proj.rgb), _p(bins.gauss_sorted), _p(bins.tile_ranges),
+            ctypes.c_int(cam.width), ctypes.c_int(cam.height), _p(self.cfg.array(dt)),
+            ctypes.c_int(self.cfg.tile), _p(tl), ctypes.c_int(ntl), _p(self._a(dL_dimage)),
+            _p(d_mean2d), _p(d_conic), _p(d_op), _p(d_rgb))
+        return d_mean2d, d_conic, d_op, d_rgb
+
+    # -- a9 --------------------------------------------------------------------------
+    def preprocess_bwd(self, sc, cam, d_mean2d, d_conic, d_opacity, d_rgb):
+        n, dt = sc.n, self.dtype
+        K = (sc.sh_degree + 1) ** 2
+        g = dict(means=np.zeros((n, 3)), scales=np.zeros((n, 3)), quats=np.zeros((n, 4)),
+                 opacities=np.zeros(n), sh=np.zeros((n, K, 3)))
+        c = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+        self._f("orc_preprocess_bwd")(
+            ctypes.c_int64(n), ctypes.c_int(sc.sh_degree), _p(self._a(sc.means)), _p(self._a(sc.scales)),
+            _p(self._a(sc.quats)), _p(self._a(sc.sh)), ctypes.c_int(cam.width), ctypes.c_int(cam.height),
+            _p(cam_array(cam, dt)), _p(self.cfg.array(dt)), ctypes.c_int(self.cfg.tile),
+            _p(c(d_mean2d)), _p(c(d_conic)), _p(c(d_opacity)), _p(c(d_rgb)),
+            _p(g["means"]), _p(g["scales"]), _p(g["quats"]), _p(g["opacities"]), _p(g["sh"]))
+        return g
+
+    # -- a10 -------------------------------------------------------------------------
+    def error_mask(self, image, target, rule=0, k=1.0):
+        H, W = image.shape[1:]
+        mask = np.zeros((H, W), np.uint8)
+        err = np.zeros((H, W), self.dtype)
+        thr = self._f("orc_error_mask")(_p(self._a(image)), _p(self._a(target)), ctypes.c_int(W), ctypes.c_int(H),
+                                        ctypes.c_int(rule), self._ct(k), _p(mask), _p(err))
+        return mask, self.dtype(thr), err
+
+    def _ct(self, v):
+        return ctypes.c_float(v) if self.dtype == np.float32 else ctypes.c_double(v)
+
+    # -- a11 -------------------------------------------------------------------------
+    def score(self, proj, bins, cam, mask, counts, tile_list=None):
+        tl, ntl = self._tl(tile_list)
+        assert counts.dtype == np.int32 and mask.dtype == np.uint8
+        self._f("orc_score")(
+            _p(proj.mean2d), _p(proj.conic_opacity), _p(bins.gauss_sorted), _p(bins.tile_ranges),
+            ctypes.c_int(cam.width), ctypes.c_int(cam.height), _p(self.cfg.array(self.dtype)),
+            ctypes.c_int(self.cfg.tile), ctypes.c_int(self.cfg.score_mode), _p(np.ascontiguousarray(mask)),
+            _p(tl), ctypes.c_int(ntl), _p(counts))
+        return counts
+
+    # -- whole path (used by finite differences and by the timed CPU baseline) ---------
+    def forward(self, sc, cam):
+        proj = self.preprocess(sc, cam)
+        bins = self.bin_sort(proj, cam)
+        image, final_T, n_contrib = self.render_fwd(proj, bins, cam)
+        return proj, bins, image, final_T, n_contrib
+
+    def backward(self, sc, cam, proj, bins, dL_dimage, tile_list=None):
+        d2 = self.render_bwd(proj, bins, cam, dL_dimage, tile_list)
+        g = self.preprocess_bwd(sc, cam, *d2)
+        g["mean2d"] = d2[0]
+        g["conic"] = d2[1]
+        g["rgb"] = d2[3]
+        return g

@@ -1,0 +1,160 @@
+/*
+ * TEST INFRASTRUCTURE -- not part of the product.
+ *
+ * CPU oracle for the FastGS rasterizer hot path (projection, Gaussian-tile pairs, depth
+ * order, alpha compositing and its gradient, L1 term, error mask, per-Gaussian count of
+ * high-error pixels).  Plain C, single-threaded, written from the paper's equations; see
+ * fastgs_oracle_impl.h for the floating-point body, which is instantiated here for float
+ * (suffix _f32, the pinned-operation-order build used for parity with the GPU) and double
+ * (suffix _f64, used for finite differences and closed-form checks).
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC [-mfma] fastgs_oracle.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------------------- */
+/* exp(x) for x <= 0 in the pinned fp32 form shared (as a specification, not as code) with
+ * the GPU kernels:  t = x*log2(e) (clamped below at -125);  n = rint(t);  r = t - n;
+ * p = degree-5 polynomial for 2^r on [-1/2,1/2] by Horner with fused multiply-adds;
+ * result = p * 2^n.  Maximum relative error about 5e-7.                                   */
+static float exp_neg_f32(float x)
+{
+    float t = x * 0x1.715476p+0f;
+    if (t < -125.0f) t = -125.0f;
+    float n = rintf(t);
+    float r = t - n;
+    float p = 0x1.5bba14p-10f;
+    p = fmaf(p, r, 0x1.3cea88p-7f);
+    p = fmaf(p, r, 0x1.c6b752p-5f);
+    p = fmaf(p, r, 0x1.ebf9bcp-3f);
+    p = fmaf(p, r, 0x1.62e42ap-1f);
+    p = fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)n);
+}
+
+#define REAL float
+#define FN(name) name##_f32
+#define SQRT sqrtf
+#define CEIL ceilf
+#define FLOOR floorf
+#define FABS fabsf
+#define FMIN fminf
+#define FMAX fmaxf
+#define FMA fmaf
+#define EXPNEG exp_neg_f32
+#include "fastgs_oracle_impl.h"
+#undef REAL
+#undef FN
+#undef SQRT
+#undef CEIL
+#undef FLOOR
+#undef FABS
+#undef FMIN
+#undef FMAX
+#undef FMA
+#undef EXPNEG
+
+#define REAL double
+#define FN(name) name##_f64
+#define SQRT sqrt
+#define CEIL ceil
+#define FLOOR floor
+#define FABS fabs
+#define FMIN fmin
+#define FMAX fmax
+#define FMA(a, b, c) ((a) * (b) + (c))
+#define EXPNEG exp
+#include "fastgs_oracle_impl.h"
+
+/* exposed so a test can compare the pinned fp32 exponential with the library's */
+float orc_exp_neg_f32(float x) { return exp_neg_f32(x); }
+
+/* ------------------------------------------------------------------------------------- */
+/* Integer part of the path: Gaussian-tile pairs, their order, per-tile ranges.           */
+
+/* Step a2: exclusive prefix sum of tiles_touched; returns the total P.                   */
+uint64_t orc_exclusive_scan(int64_t n, const uint32_t *touched, uint64_t *offsets)
+{
+    uint64_t run = 0;
+    for (int64_t i = 0; i < n; i++) { offsets[i] = run; run += touched[i]; }
+    return run;
+}
+
+/* Step a3: one (key, Gaussian) entry per tile of each Gaussian's rectangle, emitted in
+ * Gaussian order, rows then columns.  key = tile_id << 32 | bit pattern of the fp32 depth
+ * (depth > 0, so the unsigned bit pattern orders like the value); tile_id = ty*TX + tx.   */
+uint64_t orc_emit_pairs(int64_t n, const int32_t *rect, const float *depth, int TX,
+                        uint64_t *keys, uint32_t *vals)
+{
+    uint64_t p = 0;
+    for (int64_t i = 0; i < n; i++) {
+        uint32_t dbits;
+        memcpy(&dbits, &depth[i], 4);
+        for (int ty = rect[4 * i + 1]; ty < rect[4 * i + 3]; ty++)
+            for (int tx = rect[4 * i + 0]; tx < rect[4 * i + 2]; tx++) {
+                if (keys) {
+                    keys[p] = ((uint64_t)(uint32_t)(ty * TX + tx) << 32) | dbits;
+                    vals[p] = (uint32_t)i;
+                }
+                p++;
+            }
+    }
+    return p;
+}
+
+/* Brute-force statement of which pairs exist: Gaussian i meets tile (tx,ty) iff the closed
+ * square [mx-r, mx+r] x [my-r, my+r] intersects [tile*tx, tile*tx+tile) x [tile*ty, ...).
+ * Evaluated in double on the stored fp32 values; used to pin the rectangle rounding.      */
+uint64_t orc_pairs_bruteforce(int64_t n, const float *mean2d, const int32_t *radius, int width, int height,
+                              int tile, uint8_t *hit /* [n, TY*TX] */)
+{
+    int TX = (width + tile - 1) / tile, TY = (height + tile - 1) / tile;
+    uint64_t total = 0;
+    for (int64_t i = 0; i < n; i++)
+        for (int ty = 0; ty < TY; ty++)
+            for (int tx = 0; tx < TX; tx++) {
+                int h = 0;
+                if (radius[i] > 0) {
+                    double x0 = (double)mean2d[2 * i] - radius[i], x1 = (double)mean2d[2 * i] + radius[i];
+                    double y0 = (double)mean2d[2 * i + 1] - radius[i], y1 = (double)mean2d[2 * i + 1] + radius[i];
+                    h = x1 >= (double)tile * tx && x0 < (double)tile * (tx + 1) &&
+                        y1 >= (double)tile * ty && y0 < (double)tile * (ty + 1);
+                }
+                hit[(size_t)i * TX * TY + (size_t)ty * TX + tx] = (uint8_t)h;
+                total += h;
+            }
+    return total;
+}
+
+struct kv { uint64_t key; uint32_t val; };
+static int kv_cmp(const void *pa, const void *pb)
+{
+    const struct kv *a = pa, *b = pb;
+    if (a->key != b->key) return a->key < b->key ? -1 : 1;
+    if (a->val != b->val) return a->val < b->val ? -1 : 1;
+    return 0;
+}
+
+/* Steps a4: order the pairs by (tile, depth), ties by Gaussian index -- the C library sort. */
+void orc_sort_pairs(uint64_t P, uint64_t *keys, uint32_t *vals)
+{
+    struct kv *a = malloc((P ? P : 1) * sizeof(*a));
+    for (uint64_t i = 0; i < P; i++) { a[i].key = keys[i]; a[i].val = vals[i]; }
+    qsort(a, P, sizeof(*a), kv_cmp);
+    for (uint64_t i = 0; i < P; i++) { keys[i] = a[i].key; vals[i] = a[i].val; }
+    free(a);
+}
+
+/* Step a5: ranges[t] = [first, last) positions of tile t in the ordered list (0,0 if empty). */
+void orc_tile_ranges(uint64_t P, const uint64_t *keys_sorted, int num_tiles, uint32_t *ranges)
+{
+    memset(ranges, 0, (size_t)num_tiles * 2 * sizeof(uint32_t));
+    for (uint64_t i = 0; i < P; i++) {
+        uint32_t t = (uint32_t)(keys_sorted[i] >> 32);
+        if (i == 0 || (uint32_t)(keys_sorted[i - 1] >> 32) != t) ranges[2 * t] = (uint32_t)i;
+        if (i + 1 == P || (uint32_t)(keys_sorted[i + 1] >> 32) != t) ranges[2 * t + 1] = (uint32_t)(i + 1);
+    }
+}

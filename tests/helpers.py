@@ -1,0 +1,56 @@
+"""Shared test helpers: an independent, tile-free numpy statement of Eq. (4) used to pin the
+oracle on tiny inputs.  Nothing here is used by the HIP path or by the oracle itself."""
+import numpy as np
+
+from paper_2511_04283_amd.scenes import Camera, Scene
+
+
+def one_gaussian_scene(mean, scale, quat, opacity, rgb, cam: Camera) -> Scene:
+    y00 = 0.5 / np.sqrt(np.pi)
+    sh = ((np.asarray(rgb, dtype=np.float64) - 0.5) / y00).reshape(1, 1, 3)
+    f64 = np.float64   # kept in double; each oracle build casts to its own type
+    return Scene("one", 0, np.asarray(mean, f64).reshape(1, 3), np.asarray(scale, f64).reshape(1, 3),
+                 np.asarray(quat, f64).reshape(1, 4), np.asarray([opacity], f64), sh, [cam], 0)
+
+
+def brute_composite(proj, cam, cfg, mask=None):
+    """Per-pixel front-to-back compositing straight from Eq. (4), float64, no tiles lists and
+    no keys: at each pixel take every Gaussian whose tile rectangle contains the pixel's tile,
+    order by (depth, index), blend.  Returns image, final_T, number blended, and per-Gaussian
+    counts (WEIGHT and ALPHA readings) over `mask` pixels."""
+    H, W, t = cam.height, cam.width, cfg.tile
+    n = proj.depth.shape[0]
+    image = np.zeros((3, H, W)); final_T = np.ones((H, W)); nblend = np.zeros((H, W), np.int64)
+    cw = np.zeros(n, np.int64); ca = np.zeros(n, np.int64)
+    order = np.lexsort((np.arange(n), proj.depth.astype(np.float64)))
+    order = [i for i in order if proj.tiles_touched[i] > 0]
+    for v in range(H):
+        for u in range(W):
+            tx, ty = u // t, v // t
+            T = 1.0
+            C = np.zeros(3)
+            for i in order:
+                x0, y0, x1, y1 = proj.rect[i]
+                if not (x0 <= tx < x1 and y0 <= ty < y1):
+                    continue
+                d = np.array([u + 0.5 - proj.mean2d[i, 0], v + 0.5 - proj.mean2d[i, 1]], dtype=np.float64)
+                a, b, c, sig = [float(x) for x in proj.conic_opacity[i]]
+                q = a * d[0] ** 2 + 2 * b * d[0] * d[1] + c * d[1] ** 2
+                if q < 0:
+                    continue
+                al = min(cfg.alpha_max, sig * np.exp(-0.5 * q))
+                if al < cfg.alpha_min:
+                    continue
+                if T * (1 - al) < cfg.T_min:
+                    break
+                w = al * T
+                C += w * proj.rgb[i].astype(np.float64)
+                if mask is not None and mask[v, u]:
+                    ca[i] += 1
+                    if w > cfg.alpha_min:
+                        cw[i] += 1
+                T *= 1 - al
+                nblend[v, u] += 1
+            image[:, v, u] = C + T * np.asarray(cfg.bg)
+            final_T[v, u] = T
+    return image, final_T, nblend, cw, ca

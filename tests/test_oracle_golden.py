@@ -1,0 +1,22 @@
+"""The fp32 oracle must reproduce, bit for bit, the digest stored by tests/golden/make_golden.py
+(written by the oracle itself on the development host): guards against drift of its arithmetic
+and shows that its pinned operation order gives the same bits on another CPU."""
+import importlib.util
+import json
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def test_oracle_digest_reproduces():
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(HERE, "golden", "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    with open(os.path.join(HERE, "golden", "oracle_digest.json")) as f:
+        want = json.load(f)
+    import pytest
+    for key, args in (("cfg1", (1,)), ("cfg2_n20000", (2, 20000))):
+        got = mg.digest(*args)
+        if got["inputs"] != want[key]["inputs"]:
+            pytest.skip("numpy on this host draws different inputs (libm/SIMD differences in the generator)")
+        assert got == want[key]
