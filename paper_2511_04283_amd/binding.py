@@ -1,0 +1,323 @@
+"""ctypes binding of libfastgs_hip.so (the C ABI of include/fastgs.h).
+
+Argument marshalling only: tensors are allocated with torch (device memory, stream), their
+`data_ptr()`s are handed to the library, and every step of the path runs in the HIP kernels.
+There is no fallback: if the library is missing or fails to load this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfastgs_hip.so")
+
+FS_OK = 0
+FS_SCORE_WEIGHT, FS_SCORE_ALPHA = 0, 1
+FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
+_STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
+
+EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
+           "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate")
+
+
+class fs_config(ctypes.Structure):
+    _fields_ = [("tile", ctypes.c_int32), ("z_near", ctypes.c_float), ("lowpass", ctypes.c_float),
+                ("alpha_min", ctypes.c_float), ("alpha_max", ctypes.c_float), ("T_min", ctypes.c_float),
+                ("bg", ctypes.c_float * 3), ("jclamp", ctypes.c_float), ("score_mode", ctypes.c_int32)]
+
+
+class fs_camera(ctypes.Structure):
+    _fields_ = [("width", ctypes.c_int32), ("height", ctypes.c_int32), ("fx", ctypes.c_float), ("fy", ctypes.c_float),
+                ("cx", ctypes.c_float), ("cy", ctypes.c_float), ("R", ctypes.c_float * 9), ("t", ctypes.c_float * 3)]
+
+
+class fs_gaussians(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("sh_degree", ctypes.c_int32), ("means", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("quats", ctypes.c_void_p), ("opacities", ctypes.c_void_p),
+                ("sh", ctypes.c_void_p)]
+
+
+class fs_projected(ctypes.Structure):
+    _fields_ = [("mean2d", ctypes.c_void_p), ("depth", ctypes.c_void_p), ("conic_opacity", ctypes.c_void_p),
+                ("rgb", ctypes.c_void_p), ("rect", ctypes.c_void_p), ("tiles_touched", ctypes.c_void_p),
+                ("clamped", ctypes.c_void_p)]
+
+
+class fs_bins(ctypes.Structure):
+    _fields_ = [("num_pairs", ctypes.c_int64), ("keys_sorted", ctypes.c_void_p), ("gauss_sorted", ctypes.c_void_p),
+                ("tile_ranges", ctypes.c_void_p)]
+
+
+class fs_grads(ctypes.Structure):
+    _fields_ = [("dmeans", ctypes.c_void_p), ("dscales", ctypes.c_void_p), ("dquats", ctypes.c_void_p),
+                ("dopacities", ctypes.c_void_p), ("dsh", ctypes.c_void_p), ("dmean2d", ctypes.c_void_p),
+                ("dconic", ctypes.c_void_p), ("drgb", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libfastgs_hip.so (building is a separate, explicit step: paper_2511_04283_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_04283_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    P = ctypes.POINTER
+    lib.fs_default_config.argtypes = [P(fs_config)]
+    lib.fs_default_config.restype = None
+    lib.fs_create.argtypes = [P(vp), ctypes.c_int, vp, P(fs_config)]
+    lib.fs_destroy.argtypes = [vp]
+    lib.fs_destroy.restype = None
+    lib.fs_last_error.argtypes = [vp]
+    lib.fs_last_error.restype = ctypes.c_char_p
+    lib.fs_preprocess.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected)]
+    lib.fs_bin_sort.argtypes = [vp, P(fs_projected), P(fs_camera), i64, P(fs_bins)]
+    lib.fs_render_fwd.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp]
+    lib.fs_l1_grad.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
+    lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
+    lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
+    for name in EXPORTS:
+        if name not in ("fs_default_config", "fs_destroy", "fs_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def default_config() -> fs_config:
+    c = fs_config()
+    load_library().fs_default_config(ctypes.byref(c))
+    return c
+
+
+def make_camera(cam) -> fs_camera:
+    """From any object with width,height,fx,fy,cx,cy,R(3x3),t(3) (e.g. scenes.Camera)."""
+    import numpy as np
+    c = fs_camera()
+    c.width, c.height = int(cam.width), int(cam.height)
+    c.fx, c.fy, c.cx, c.cy = float(cam.fx), float(cam.fy), float(cam.cx), float(cam.cy)
+    c.R = (ctypes.c_float * 9)(*[float(x) for x in np.asarray(cam.R, dtype=np.float32).reshape(9)])
+    c.t = (ctypes.c_float * 3)(*[float(x) for x in np.asarray(cam.t, dtype=np.float32).reshape(3)])
+    return c
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _chk(t, dtype, shape=None, name="tensor"):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise ValueError(f"{name}: need a contiguous CUDA tensor of dtype {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != {tuple(shape)}")
+    return t
+
+
+@dataclass
+class Gaussians:
+    """Device tensors of a scene (float32, contiguous)."""
+    means: torch.Tensor
+    scales: torch.Tensor
+    quats: torch.Tensor
+    opacities: torch.Tensor
+    sh: torch.Tensor
+    sh_degree: int
+
+    @property
+    def n(self) -> int:
+        return int(self.means.shape[0])
+
+    @staticmethod
+    def from_scene(sc, device="cuda:0") -> "Gaussians":
+        import numpy as np
+        f = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+        return Gaussians(f(sc.means), f(sc.scales), f(sc.quats), f(sc.opacities), f(sc.sh), int(sc.sh_degree))
+
+    def struct(self) -> fs_gaussians:
+        n, K = self.n, (self.sh_degree + 1) ** 2
+        f = torch.float32
+        _chk(self.means, f, (n, 3), "means"); _chk(self.scales, f, (n, 3), "scales")
+        _chk(self.quats, f, (n, 4), "quats"); _chk(self.opacities, f, (n,), "opacities")
+        _chk(self.sh, f, (n, K, 3), "sh")
+        g = fs_gaussians()
+        g.n, g.sh_degree = n, self.sh_degree
+        g.means, g.scales, g.quats = self.means.data_ptr(), self.scales.data_ptr(), self.quats.data_ptr()
+        g.opacities, g.sh = self.opacities.data_ptr(), self.sh.data_ptr()
+        return g
+
+
+@dataclass
+class Projected:
+    mean2d: torch.Tensor
+    depth: torch.Tensor
+    conic_opacity: torch.Tensor
+    rgb: torch.Tensor
+    rect: torch.Tensor           # int16 storage of the uint16 [n,4] rectangle
+    tiles_touched: torch.Tensor  # int32 storage of uint32
+    clamped: torch.Tensor
+
+    def struct(self) -> fs_projected:
+        p = fs_projected()
+        p.mean2d, p.depth, p.conic_opacity = self.mean2d.data_ptr(), self.depth.data_ptr(), self.conic_opacity.data_ptr()
+        p.rgb, p.rect, p.tiles_touched = self.rgb.data_ptr(), self.rect.data_ptr(), self.tiles_touched.data_ptr()
+        p.clamped = self.clamped.data_ptr()
+        return p
+
+
+@dataclass
+class Bins:
+    """Result of fs_bin_sort: P and raw device pointers into ctx-owned memory (valid until the next
+    fs_bin_sort on the same Context).  `copy_*` methods clone them into torch tensors for inspection."""
+    num_pairs: int
+    struct: fs_bins
+    num_tiles: int
+    device: torch.device
+
+    def _copy(self, ptr, count, dtype):
+        """Clone `count` elements at device address `ptr` into a new torch tensor (the ctx-owned
+        memory is wrapped without a copy through the CUDA array interface, then cloned)."""
+        if not count:
+            return torch.empty(0, dtype=dtype, device=self.device)
+        typestr = {torch.int64: "<i8", torch.int32: "<i4"}[dtype]
+
+        class _Raw:
+            __cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (int(ptr), False),
+                                        "version": 2}
+        return torch.as_tensor(_Raw(), device=self.device).clone()
+
+    def copy_keys(self):
+        return self._copy(self.struct.keys_sorted, self.num_pairs, torch.int64)
+
+    def copy_gauss(self):
+        return self._copy(self.struct.gauss_sorted, self.num_pairs, torch.int32)
+
+    def copy_ranges(self):
+        return self._copy(self.struct.tile_ranges, 2 * self.num_tiles, torch.int32).view(self.num_tiles, 2)
+
+
+class Context:
+    """Owns one fs_ctx bound to a torch device and (by default) torch's current stream on it."""
+
+    def __init__(self, device="cuda:0", config: fs_config | None = None, stream: torch.cuda.Stream | None = None):
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the FastGS HIP path has no CPU fallback")
+        self.device = torch.device(device)
+        self.config = config if config is not None else default_config()
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        h = ctypes.c_void_p()
+        rc = self.lib.fs_create(ctypes.byref(h), self.device.index or 0, ctypes.c_void_p(self.stream.cuda_stream),
+                                ctypes.byref(self.config))
+        if rc != FS_OK:
+            raise RuntimeError(f"fs_create failed: {_STATUS.get(rc, rc)}")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.fs_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc, what):
+        if rc != FS_OK:
+            msg = self.lib.fs_last_error(self.handle)
+            raise RuntimeError(f"{what}: {_STATUS.get(rc, rc)}: {msg.decode() if msg else ''}")
+
+    # ---- the calls of fastgs.h, same names ------------------------------------------------
+    def fs_preprocess(self, g: Gaussians, cam: fs_camera, out: Projected | None = None) -> Projected:
+        n, dev = g.n, self.device
+        if out is None:
+            out = Projected(torch.empty((n, 2), dtype=torch.float32, device=dev),
+                            torch.empty(n, dtype=torch.float32, device=dev),
+                            torch.empty((n, 4), dtype=torch.float32, device=dev),
+                            torch.empty((n, 3), dtype=torch.float32, device=dev),
+                            torch.empty((n, 4), dtype=torch.int16, device=dev),
+                            torch.empty(n, dtype=torch.int32, device=dev),
+                            torch.empty((n, 3), dtype=torch.uint8, device=dev))
+        gs, ps = g.struct(), out.struct()
+        self._check(self.lib.fs_preprocess(self.handle, ctypes.byref(gs), ctypes.byref(cam), ctypes.byref(ps)),
+                    "fs_preprocess")
+        return out
+
+    def fs_bin_sort(self, proj: Projected, cam: fs_camera) -> Bins:
+        b = fs_bins()
+        ps = proj.struct()
+        n = int(proj.depth.shape[0])
+        self._check(self.lib.fs_bin_sort(self.handle, ctypes.byref(ps), ctypes.byref(cam), n, ctypes.byref(b)),
+                    "fs_bin_sort")
+        tiles = ((cam.width + 15) // 16) * ((cam.height + 15) // 16)
+        return Bins(int(b.num_pairs), b, tiles, self.device)
+
+    def fs_render_fwd(self, proj: Projected, bins: Bins, cam: fs_camera, image=None, final_T=None, n_contrib=None):
+        H, W, dev = cam.height, cam.width, self.device
+        if image is None:
+            image = torch.empty((3, H, W), dtype=torch.float32, device=dev)
+        if final_T is None:
+            final_T = torch.empty((H, W), dtype=torch.float32, device=dev)
+        if n_contrib is None:
+            n_contrib = torch.empty((H, W), dtype=torch.int32, device=dev)
+        ps = proj.struct()
+        self._check(self.lib.fs_render_fwd(self.handle, ctypes.byref(ps), ctypes.byref(bins.struct), ctypes.byref(cam),
+                                           _ptr(image), _ptr(final_T), _ptr(n_contrib)), "fs_render_fwd")
+        return image, final_T, n_contrib
+
+    def fs_l1_grad(self, image, target, dL_dimage=None, loss_out=None):
+        _, H, W = image.shape
+        _chk(image, torch.float32, (3, H, W), "image"); _chk(target, torch.float32, (3, H, W), "target")
+        if dL_dimage is None:
+            dL_dimage = torch.empty_like(image)
+        self._check(self.lib.fs_l1_grad(self.handle, _ptr(image), _ptr(target), H, W, _ptr(dL_dimage), _ptr(loss_out)),
+                    "fs_l1_grad")
+        return dL_dimage
+
+    def fs_render_bwd(self, g: Gaussians, cam: fs_camera, proj: Projected, bins: Bins, final_T, n_contrib, dL_dimage,
+                      out: dict | None = None, want_2d: bool = False) -> dict:
+        n, K, dev = g.n, (g.sh_degree + 1) ** 2, self.device
+        if out is None:
+            e = lambda *s: torch.empty(s, dtype=torch.float32, device=dev)
+            out = dict(means=e(n, 3), scales=e(n, 3), quats=e(n, 4), opacities=e(n), sh=e(n, K, 3), mean2d=e(n, 2))
+            if want_2d:
+                out["conic"] = e(n, 3)
+                out["rgb"] = e(n, 3)
+        gr = fs_grads()
+        gr.dmeans, gr.dscales, gr.dquats = out["means"].data_ptr(), out["scales"].data_ptr(), out["quats"].data_ptr()
+        gr.dopacities, gr.dsh, gr.dmean2d = out["opacities"].data_ptr(), out["sh"].data_ptr(), out["mean2d"].data_ptr()
+        gr.dconic = out["conic"].data_ptr() if "conic" in out else None
+        gr.drgb = out["rgb"].data_ptr() if "rgb" in out else None
+        gs, ps = g.struct(), proj.struct()
+        self._check(self.lib.fs_render_bwd(self.handle, ctypes.byref(gs), ctypes.byref(cam), ctypes.byref(ps),
+                                           ctypes.byref(bins.struct), _ptr(final_T), _ptr(n_contrib), _ptr(dL_dimage),
+                                           ctypes.byref(gr)), "fs_render_bwd")
+        return out
+
+    def fs_error_mask(self, image, target, rule=FS_MASK_MEAN_STD, k=1.0, mask=None, threshold_out=None):
+        _, H, W = image.shape
+        if mask is None:
+            mask = torch.empty((H, W), dtype=torch.uint8, device=self.device)
+        if threshold_out is None:
+            threshold_out = torch.empty(1, dtype=torch.float32, device=self.device)
+        self._check(self.lib.fs_error_mask(self.handle, _ptr(image), _ptr(target), H, W, int(rule), float(k), _ptr(mask),
+                                           _ptr(threshold_out)), "fs_error_mask")
+        return mask, threshold_out
+
+    def fs_score_accumulate(self, proj: Projected, bins: Bins, cam: fs_camera, final_T, n_contrib, mask, counts):
+        _chk(counts, torch.int32, (int(proj.depth.shape[0]),), "counts")
+        ps = proj.struct()
+        self._check(self.lib.fs_score_accumulate(self.handle, ctypes.byref(ps), ctypes.byref(bins.struct),
+                                                 ctypes.byref(cam), _ptr(final_T), _ptr(n_contrib), _ptr(mask),
+                                                 _ptr(counts)), "fs_score_accumulate")
+        return counts

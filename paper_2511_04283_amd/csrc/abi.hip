@@ -1,0 +1,360 @@
+// C ABI of libfastgs_hip: argument checks, scratch memory, and the order of kernel launches for
+// each entry point of fastgs.h.  No arithmetic of the method lives here.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.hpp"
+
+using namespace fs;
+
+// A device buffer that only ever grows (capacity doubling), owned by the ctx.
+struct ScratchBuf {
+    void* ptr = nullptr;
+    size_t cap = 0;
+};
+
+struct fs_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    fs_config cfg;
+    char err[256];
+
+    ScratchBuf offsets;       // uint32 [n]
+    ScratchBuf scan_tmp;      // uint64 block sums for the scans
+    ScratchBuf keys[2];       // uint64 [P] ping-pong
+    ScratchBuf vals[2];       // uint32 [P] ping-pong
+    ScratchBuf hist;          // uint32 [256 * radix blocks]
+    ScratchBuf ranges;        // uint32 [tiles, 2]
+    ScratchBuf grad2d;        // float  [n, 3] dconic and [n, 3] drgb when the caller passes none
+    ScratchBuf err_map;       // float  [H*W]
+    ScratchBuf partial;       // double reduction partials
+    uint64_t* total_dev = nullptr;   // device: scan total
+    uint64_t* total_host = nullptr;  // pinned host copy
+};
+
+namespace {
+
+int fail(fs_ctx* c, int code, const char* fmt, const char* a = "")
+{
+    if (c) snprintf(c->err, sizeof(c->err), fmt, a);
+    return code;
+}
+
+int hip_fail(fs_ctx* c, hipError_t e, const char* where)
+{
+    if (c) snprintf(c->err, sizeof(c->err), "%s: %s", where, hipGetErrorString(e));
+    return FS_EHIP;
+}
+
+#define FS_HIP(call, where)                                   \
+    do {                                                      \
+        hipError_t e_ = (call);                               \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
+    } while (0)
+
+int ensure(fs_ctx* ctx, ScratchBuf& b, size_t bytes, const char* what)
+{
+    if (bytes <= b.cap) return FS_OK;
+    size_t want = b.cap ? b.cap : 4096;
+    while (want < bytes) want *= 2;
+    // nothing enqueued earlier may still use the old block when it is released
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipStreamSynchronize");
+    if (b.ptr) (void)hipFree(b.ptr);
+    b.ptr = nullptr;
+    b.cap = 0;
+    e = hipMalloc(&b.ptr, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        b.ptr = nullptr;
+        return fail(ctx, FS_ENOMEM, "scratch allocation failed (%s)", what);
+    }
+    b.cap = want;
+    return FS_OK;
+}
+
+#define FS_TRY(expr)            \
+    do {                        \
+        int rc_ = (expr);       \
+        if (rc_ != FS_OK) return rc_; \
+    } while (0)
+
+bool make_cam(const fs_camera* cam, CamDev& d)
+{
+    if (!cam || cam->width <= 0 || cam->height <= 0 || !(cam->fx > 0.f) || !(cam->fy > 0.f)) return false;
+    d.width = cam->width;
+    d.height = cam->height;
+    d.fx = cam->fx; d.fy = cam->fy; d.cx = cam->cx; d.cy = cam->cy;
+    memcpy(d.R, cam->R, sizeof(d.R));
+    memcpy(d.t, cam->t, sizeof(d.t));
+    d.tiles_x = (cam->width + TILE - 1) / TILE;
+    d.tiles_y = (cam->height + TILE - 1) / TILE;
+    return d.tiles_x <= 65535 && d.tiles_y <= 65535;
+}
+
+CfgDev make_cfg(const fs_config& c)
+{
+    CfgDev d;
+    d.z_near = c.z_near; d.lowpass = c.lowpass; d.alpha_min = c.alpha_min; d.alpha_max = c.alpha_max;
+    d.T_min = c.T_min;
+    d.bg[0] = c.bg[0]; d.bg[1] = c.bg[1]; d.bg[2] = c.bg[2];
+    d.jclamp = c.jclamp;
+    // conservative: for opacity <= 1, sigma*exp(power) < alpha_min whenever power < ln(alpha_min) - 0.01
+    d.power_min = (float)(log((double)c.alpha_min) - 0.01);
+    d.score_mode = c.score_mode;
+    return d;
+}
+
+int tile_bits(int tiles)
+{
+    int b = 0;
+    while ((1 << b) < tiles) b++;
+    return b;
+}
+
+bool proj_ok(const fs_projected* p)
+{
+    return p && p->mean2d && p->depth && p->conic_opacity && p->rgb && p->rect && p->tiles_touched && p->clamped;
+}
+
+}  // namespace
+
+extern "C" {
+
+void fs_default_config(fs_config* cfg)
+{
+    if (!cfg) return;
+    cfg->tile = TILE;
+    cfg->z_near = (float)0.2;
+    cfg->lowpass = (float)0.3;
+    cfg->alpha_min = 1.0f / 255.0f;
+    cfg->alpha_max = (float)0.99;
+    cfg->T_min = (float)1e-4;
+    cfg->bg[0] = cfg->bg[1] = cfg->bg[2] = 0.0f;
+    cfg->jclamp = (float)1.3;
+    cfg->score_mode = FS_SCORE_WEIGHT;
+}
+
+int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
+{
+    if (!out) return FS_EINVAL;
+    *out = nullptr;
+    fs_config c;
+    if (cfg) c = *cfg; else fs_default_config(&c);
+    if (c.tile != TILE || !(c.alpha_min > 0.f) || !(c.alpha_min < c.alpha_max) || !(c.alpha_max < 1.f) ||
+        !(c.T_min > 0.f) || !(c.T_min < 1.f) || !(c.lowpass >= 0.f) ||
+        (c.score_mode != FS_SCORE_WEIGHT && c.score_mode != FS_SCORE_ALPHA))
+        return FS_EINVAL;
+    if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return FS_EHIP; }
+    fs_ctx* ctx = new (std::nothrow) fs_ctx();
+    if (!ctx) return FS_ENOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->cfg = c;
+    ctx->err[0] = 0;
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), sizeof(uint64_t)) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        fs_destroy(ctx);
+        return FS_EHIP;
+    }
+    *out = ctx;
+    return FS_OK;
+}
+
+void fs_destroy(fs_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
+                         &ctx->hist, &ctx->ranges, &ctx->grad2d, &ctx->err_map, &ctx->partial};
+    for (ScratchBuf* b : all)
+        if (b->ptr) (void)hipFree(b->ptr);
+    if (ctx->total_dev) (void)hipFree(ctx->total_dev);
+    if (ctx->total_host) (void)hipHostFree(ctx->total_host);
+    delete ctx;
+}
+
+const char* fs_last_error(const fs_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int fs_preprocess(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, fs_projected* out)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!g || g->n < 0 || g->sh_degree < 0 || g->sh_degree > 3 || !make_cam(cam, cd))
+        return fail(ctx, FS_EINVAL, "fs_preprocess: bad scene or camera");
+    if (g->n > 0 && (!g->means || !g->scales || !g->quats || !g->opacities || !g->sh || !proj_ok(out)))
+        return fail(ctx, FS_EINVAL, "fs_preprocess: null array");
+    if (g->n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_preprocess: n does not fit 31 bits");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_preprocess(ctx->stream, g->n, g->sh_degree, *g, cd, make_cfg(ctx->cfg), *out), "k_preprocess");
+    return FS_OK;
+}
+
+int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int64_t n, fs_bins* out)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!out || n < 0 || !make_cam(cam, cd)) return fail(ctx, FS_EINVAL, "fs_bin_sort: bad arguments");
+    if (n > 0 && !proj_ok(proj)) return fail(ctx, FS_EINVAL, "fs_bin_sort: null array");
+    if (n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: n does not fit 31 bits");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    hipStream_t st = ctx->stream;
+    const int tiles = cd.tiles_x * cd.tiles_y;
+
+    FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * 2 * sizeof(uint32_t), "tile ranges"));
+    FS_TRY(ensure(ctx, ctx->offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "offsets"));
+    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
+
+    // a2: offsets and the pair count P (the one host read-back of the path)
+    FS_HIP(launch_exclusive_scan(st, proj ? proj->tiles_touched : nullptr, static_cast<uint32_t*>(ctx->offsets.ptr), n,
+                                 ctx->scan_tmp.ptr, ctx->total_dev),
+           "scan");
+    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
+    FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
+    const uint64_t P = *ctx->total_host;
+    if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
+
+    const int64_t nb = radix_num_blocks((int64_t)P);
+    for (int k = 0; k < 2; k++) {
+        FS_TRY(ensure(ctx, ctx->keys[k], (size_t)(P ? P : 1) * sizeof(uint64_t), "keys"));
+        FS_TRY(ensure(ctx, ctx->vals[k], (size_t)(P ? P : 1) * sizeof(uint32_t), "values"));
+    }
+    FS_TRY(ensure(ctx, ctx->hist, (size_t)(nb ? nb : 1) * 256 * sizeof(uint32_t), "histograms"));
+    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(256 * nb), "scan"));
+
+    uint64_t* keys[2] = {static_cast<uint64_t*>(ctx->keys[0].ptr), static_cast<uint64_t*>(ctx->keys[1].ptr)};
+    uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};
+    int res = 0;
+    if (P > 0) {
+        // a3
+        FS_HIP(launch_emit_pairs(st, n, proj->rect, proj->depth, static_cast<const uint32_t*>(ctx->offsets.ptr),
+                                 cd.tiles_x, keys[0], vals[0]),
+               "k_emit_pairs");
+        // a4: the sign bit of a positive depth is 0, so 31 depth bits + the tile bits are live
+        FS_HIP(launch_radix_sort(st, (int64_t)P, 32 + tile_bits(tiles), keys, vals, static_cast<uint32_t*>(ctx->hist.ptr),
+                                 ctx->scan_tmp.ptr, ctx->total_dev, &res),
+               "radix sort");
+    }
+    // a5
+    FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr)), "k_tile_ranges");
+    out->num_pairs = (int64_t)P;
+    out->keys_sorted = keys[res];
+    out->gauss_sorted = vals[res];
+    out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
+    return FS_OK;
+}
+
+int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, const fs_camera* cam, float* image,
+                  float* final_T, uint32_t* n_contrib)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !image || !final_T || !n_contrib)
+        return fail(ctx, FS_EINVAL, "fs_render_fwd: bad arguments");
+    if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted))
+        return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
+                             proj ? proj->mean2d : nullptr, proj ? proj->conic_opacity : nullptr,
+                             proj ? proj->rgb : nullptr, image, final_T, n_contrib),
+           "k_render_fwd");
+    return FS_OK;
+}
+
+int fs_l1_grad(fs_ctx* ctx, const float* image, const float* target, int32_t height, int32_t width, float* dL_dimage,
+               double* loss_out)
+{
+    if (!ctx) return FS_EINVAL;
+    if (!image || !target || !dL_dimage || height <= 0 || width <= 0)
+        return fail(ctx, FS_EINVAL, "fs_l1_grad: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
+    FS_HIP(launch_l1_grad(ctx->stream, image, target, (int64_t)3 * height * width, dL_dimage,
+                          static_cast<double*>(ctx->partial.ptr), loss_out),
+           "k_l1_grad");
+    return FS_OK;
+}
+
+int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, const fs_projected* proj,
+                  const fs_bins* bins, const float* final_T, const uint32_t* n_contrib, const float* dL_dimage,
+                  fs_grads* out)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!g || g->n < 0 || g->sh_degree < 0 || g->sh_degree > 3 || !make_cam(cam, cd) || !bins || !bins->tile_ranges ||
+        !final_T || !n_contrib || !dL_dimage || !out)
+        return fail(ctx, FS_EINVAL, "fs_render_bwd: bad arguments");
+    const int64_t n = g->n;
+    if (n == 0) return FS_OK;
+    if (!g->means || !g->scales || !g->quats || !g->opacities || !g->sh || !proj_ok(proj) || !out->dmeans ||
+        !out->dscales || !out->dquats || !out->dopacities || !out->dsh || !out->dmean2d ||
+        (bins->num_pairs > 0 && !bins->gauss_sorted))
+        return fail(ctx, FS_EINVAL, "fs_render_bwd: null array");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    hipStream_t st = ctx->stream;
+    float* dconic = out->dconic;
+    float* drgb = out->drgb;
+    if (!dconic || !drgb) {
+        FS_TRY(ensure(ctx, ctx->grad2d, (size_t)n * 6 * sizeof(float), "2D gradients"));
+        if (!dconic) dconic = static_cast<float*>(ctx->grad2d.ptr);
+        if (!drgb) drgb = static_cast<float*>(ctx->grad2d.ptr) + 3 * n;
+    }
+    // accumulators of the atomics start at zero (fill kernels, so the call can be graph-captured)
+    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dmean2d), 0u, 2 * n), "fill");
+    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dopacities), 0u, n), "fill");
+    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(dconic), 0u, 3 * n), "fill");
+    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(drgb), 0u, 3 * n), "fill");
+    const CfgDev cf = make_cfg(ctx->cfg);
+    // a8
+    if (bins->num_pairs > 0)
+        FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted, proj->mean2d, proj->conic_opacity,
+                                 proj->rgb, final_T, n_contrib, dL_dimage, out->dmean2d, dconic, out->dopacities, drgb),
+               "k_render_bwd");
+    // a9
+    FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, out->dmean2d, dconic, drgb, *out),
+           "k_preprocess_bwd");
+    return FS_OK;
+}
+
+int fs_error_mask(fs_ctx* ctx, const float* image, const float* target, int32_t height, int32_t width, int32_t rule,
+                  float k, uint8_t* mask, float* threshold_out)
+{
+    if (!ctx) return FS_EINVAL;
+    if (!image || !target || !mask || height <= 0 || width <= 0 ||
+        (rule != FS_MASK_MEAN_STD && rule != FS_MASK_MINMAX_TAU))
+        return fail(ctx, FS_EINVAL, "fs_error_mask: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    const int64_t pixels = (int64_t)height * width;
+    FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
+    FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
+    float* err = static_cast<float*>(ctx->err_map.ptr);
+    float* thr = threshold_out ? threshold_out : err + pixels;
+    FS_HIP(launch_error_mask(ctx->stream, image, target, pixels, rule, k, err, static_cast<double*>(ctx->partial.ptr),
+                             mask, thr),
+           "k_err_*");
+    return FS_OK;
+}
+
+int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, const fs_camera* cam,
+                        const float* final_T, const uint32_t* n_contrib, const uint8_t* mask, int32_t* counts)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    (void)final_T;  // the walk recomputes T from the front, exactly as the forward pass did
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !n_contrib || !mask)
+        return fail(ctx, FS_EINVAL, "fs_score_accumulate: bad arguments");
+    if (bins->num_pairs == 0) return FS_OK;
+    if (!proj_ok(proj) || !bins->gauss_sorted || !counts) return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted, proj->mean2d,
+                        proj->conic_opacity, n_contrib, mask, counts),
+           "k_score");
+    return FS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,324 @@
+// Gaussian-tile pair binning on gfx950: exclusive scan, key emission, stable LSD radix sort,
+// per-tile ranges.  All integer work; results are unique and reproducible bit for bit.
+//
+// FastGS Sec. 3 blends "Gaussians sorted by depth" per pixel; Sec. 4.4 names the Gaussian-tile
+// pairs the 3-sigma rule produces.  A pair's key is tile_id << 32 | bits(depth): one global sort
+// yields, for every tile, its Gaussians front to back.
+#include "common.hpp"
+
+namespace fs {
+
+namespace {
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_ITEMS = 8;
+constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_ITEMS;  // 2048 values per workgroup
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+// Inclusive scan across the 64 lanes of a wavefront (log-step shuffles).
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(v, d, 64);
+        if ((int)lane_id() >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan over the 256 threads of a workgroup; returns the thread's exclusive prefix and
+// the workgroup total.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* total, uint32_t* smem /*[4]*/)
+{
+    const uint32_t inc = wave_inclusive_scan(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane_id() == 63) smem[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        const uint32_t s = smem[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+// Pass 1: per-workgroup sums (64-bit, so that a total beyond 2^32 is detected by the caller).
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_block_sums(const uint32_t* __restrict__ in, int64_t n,
+                                                                 uint64_t* __restrict__ block_sums)
+{
+    __shared__ uint32_t smem[4];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_ITEMS;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; k++)
+        if (base + k < n) s += in[base + k];
+    uint32_t tot;
+    block_exclusive_scan(s, &tot, smem);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+}
+
+// Pass 2: one workgroup turns the block sums into exclusive block offsets (sequential chunks).
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_block_offsets(uint64_t* __restrict__ block_sums,
+                                                                    int64_t num_blocks,
+                                                                    uint64_t* __restrict__ total_out)
+{
+    __shared__ uint64_t wave_tot[4];
+    __shared__ uint64_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t c = 0; c < num_blocks; c += SCAN_THREADS) {
+        const int64_t i = c + threadIdx.x;
+        const uint64_t v = i < num_blocks ? block_sums[i] : 0;
+        // 64-bit inclusive scan within the wave
+        uint64_t inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t lo = __shfl_up((uint32_t)inc, d, 64);
+            const uint32_t hi = __shfl_up((uint32_t)(inc >> 32), d, 64);
+            if ((int)lane_id() >= d) inc += ((uint64_t)hi << 32) | lo;
+        }
+        const int wave = threadIdx.x >> 6;
+        if (lane_id() == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        uint64_t base = carry_s;
+        for (int w = 0; w < wave; w++) base += wave_tot[w];
+        if (i < num_blocks) block_sums[i] = base + inc - v;
+        __syncthreads();
+        if (threadIdx.x == SCAN_THREADS - 1) carry_s = base + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total_out = carry_s;
+}
+
+// Pass 3: exclusive scan inside each workgroup plus its block offset.
+// `in` and `out` may be the same array (each thread reads its values before writing them).
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_apply(const uint32_t* in, uint32_t* out, int64_t n,
+                                                            const uint64_t* __restrict__ block_offsets)
+{
+    __shared__ uint32_t smem[4];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_ITEMS;
+    uint32_t v[SCAN_ITEMS];
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; k++) {
+        v[k] = base + k < n ? in[base + k] : 0u;
+        s += v[k];
+    }
+    uint32_t tot;
+    uint32_t run = block_exclusive_scan(s, &tot, smem) + (uint32_t)block_offsets[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; k++) {
+        if (base + k < n) out[base + k] = run;
+        run += v[k];
+    }
+}
+
+// One key per tile of each Gaussian's rectangle, rows then columns, starting at offsets[i].
+__global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const uint16_t* __restrict__ rect,
+                                                    const float* __restrict__ depth,
+                                                    const uint32_t* __restrict__ offsets, int tiles_x,
+                                                    uint64_t* __restrict__ keys, uint32_t* __restrict__ vals)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const ushort4 r = *reinterpret_cast<const ushort4*>(rect + 4 * i);
+    if (r.z <= r.x || r.w <= r.y) return;
+    const uint32_t dbits = __float_as_uint(depth[i]);
+    uint32_t o = offsets[i];
+    for (uint32_t ty = r.y; ty < r.w; ty++)
+        for (uint32_t tx = r.x; tx < r.z; tx++) {
+            keys[o] = ((uint64_t)(ty * (uint32_t)tiles_x + tx) << 32) | dbits;
+            vals[o] = (uint32_t)i;
+            o++;
+        }
+}
+
+// ---- radix sort -------------------------------------------------------------------------
+// One pass ranks RADIX_BLOCK_KEYS keys per workgroup on a digit of up to 8 bits.  Wave w of the
+// workgroup owns the contiguous chunk [w*512, w*512+512) of the block's keys and walks it in 8
+// rounds of 64 consecutive keys, so (wave, round, lane) order is the input order and the ranking
+// is stable.
+
+constexpr int RADIX_ROUNDS = RADIX_BLOCK_KEYS / 256;  // rounds per wave
+
+// Per-workgroup digit histogram, stored digit-major: hist[digit * num_blocks + block].
+__global__ __launch_bounds__(256) void k_radix_hist(const uint64_t* __restrict__ keys, uint32_t P, int shift,
+                                                    uint32_t mask, uint32_t num_blocks,
+                                                    uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t cnt[256];
+    cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t base = blockIdx.x * RADIX_BLOCK_KEYS;
+#pragma unroll
+    for (int r = 0; r < RADIX_ROUNDS; r++) {
+        const uint32_t i = base + r * 256 + threadIdx.x;
+        if (i < P) atomicAdd(&cnt[(uint32_t)(keys[i] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    hist[threadIdx.x * num_blocks + blockIdx.x] = cnt[threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void k_radix_scatter(const uint64_t* __restrict__ kin,
+                                                       const uint32_t* __restrict__ vin,
+                                                       uint64_t* __restrict__ kout, uint32_t* __restrict__ vout,
+                                                       const uint32_t* __restrict__ hist_scanned, uint32_t P,
+                                                       int shift, int bits, uint32_t num_blocks)
+{
+    __shared__ uint32_t cnt[4][256];
+    const int wave = threadIdx.x >> 6;
+    const uint32_t lane = lane_id();
+    const uint32_t mask = (1u << bits) - 1u;
+#pragma unroll
+    for (int w = 0; w < 4; w++) cnt[w][threadIdx.x] = 0;
+    __syncthreads();
+
+    const uint32_t wave_start = blockIdx.x * RADIX_BLOCK_KEYS + wave * (RADIX_ROUNDS * 64);
+    uint64_t key[RADIX_ROUNDS];
+    uint32_t val[RADIX_ROUNDS], rank[RADIX_ROUNDS];
+#pragma unroll
+    for (int r = 0; r < RADIX_ROUNDS; r++) {
+        const uint32_t i = wave_start + r * 64 + lane;
+        const bool valid = i < P;
+        key[r] = valid ? kin[i] : 0ull;
+        val[r] = valid ? vin[i] : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < RADIX_ROUNDS; r++) {
+        const uint32_t i = wave_start + r * 64 + lane;
+        const bool valid = i < P;
+        const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+        // lanes of this wave holding the same digit
+        uint64_t peers = __ballot(valid);
+        for (int b = 0; b < bits; b++) {
+            const bool bit = (d >> b) & 1u;
+            const uint64_t bal = __ballot(valid && bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const uint32_t below = __popcll(peers & ((1ull << lane) - 1ull));
+        const uint32_t count = __popcll(peers);
+        uint32_t prev = 0;
+        if (valid) prev = cnt[wave][d];
+        __builtin_amdgcn_wave_barrier();
+        if (valid && below == 0) cnt[wave][d] = prev + count;
+        __builtin_amdgcn_wave_barrier();
+        rank[r] = prev + below;
+    }
+    __syncthreads();
+    // thread = digit: global start of this block's run of that digit, then per-wave starts
+    {
+        const uint32_t d = threadIdx.x;
+        uint32_t run = hist_scanned[d * num_blocks + blockIdx.x];
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const uint32_t c = cnt[w][d];
+            cnt[w][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RADIX_ROUNDS; r++) {
+        const uint32_t i = wave_start + r * 64 + lane;
+        if (i < P) {
+            const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+            const uint32_t pos = cnt[wave][d] + rank[r];
+            kout[pos] = key[r];
+            vout[pos] = val[r];
+        }
+    }
+}
+
+// ranges[t] = [first,last) for every tile present in the sorted keys (ranges pre-filled with 0).
+__global__ __launch_bounds__(256) void k_tile_ranges(const uint64_t* __restrict__ keys, uint32_t P,
+                                                     uint32_t* __restrict__ ranges)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P) return;
+    const uint32_t t = (uint32_t)(keys[i] >> 32);
+    if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != t) ranges[2 * t] = i;
+    if (i + 1 == P || (uint32_t)(keys[i + 1] >> 32) != t) ranges[2 * t + 1] = i + 1;
+}
+
+__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+}  // namespace
+
+size_t scan_tmp_bytes(int64_t n)
+{
+    const int64_t nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    return (size_t)(nb > 0 ? nb : 1) * sizeof(uint64_t);
+}
+
+hipError_t launch_exclusive_scan(hipStream_t st, const uint32_t* in, uint32_t* out, int64_t n, void* tmp,
+                                 uint64_t* total_dev)
+{
+    const int64_t nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    uint64_t* bs = static_cast<uint64_t*>(tmp);
+    if (nb > 0) hipLaunchKernelGGL(k_scan_block_sums, dim3((unsigned)nb), dim3(SCAN_THREADS), 0, st, in, n, bs);
+    hipLaunchKernelGGL(k_scan_block_offsets, dim3(1), dim3(SCAN_THREADS), 0, st, bs, nb, total_dev);
+    if (nb > 0) hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(SCAN_THREADS), 0, st, in, out, n, bs);
+    return hipGetLastError();
+}
+
+hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const uint16_t* rect, const float* depth,
+                             const uint32_t* offsets, int tiles_x, uint64_t* keys, uint32_t* vals)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_emit_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, rect, depth, offsets,
+                       tiles_x, keys, vals);
+    return hipGetLastError();
+}
+
+hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t* keys[2], uint32_t* vals[2],
+                             uint32_t* hist, void* scan_tmp, uint64_t* scan_total_dev, int* result_index)
+{
+    int cur = 0;
+    if (P > 0) {
+        const uint32_t nb = (uint32_t)radix_num_blocks(P);
+        const int passes = (total_bits + 7) / 8;
+        for (int p = 0; p < passes; p++) {
+            const int shift = 8 * p;
+            const int bits = total_bits - shift < 8 ? total_bits - shift : 8;
+            const uint32_t mask = (1u << bits) - 1u;
+            hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(256), 0, st, keys[cur], (uint32_t)P, shift, mask, nb,
+                               hist);
+            hipError_t e = launch_exclusive_scan(st, hist, hist, (int64_t)256 * nb, scan_tmp, scan_total_dev);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(256), 0, st, keys[cur], vals[cur], keys[cur ^ 1],
+                               vals[cur ^ 1], hist, (uint32_t)P, shift, bits, nb);
+            cur ^= 1;
+        }
+    }
+    *result_index = cur;
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
+                              uint32_t* ranges)
+{
+    hipError_t e = launch_fill_u32(st, ranges, 0u, (int64_t)2 * num_tiles);
+    if (e != hipSuccess) return e;
+    if (P > 0)
+        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, keys_sorted,
+                           (uint32_t)P, ranges);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t count)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, v, count);
+    return hipGetLastError();
+}
+
+}  // namespace fs

@@ -1,0 +1,420 @@
+// Projection of Gaussians to screen-space splats and its reverse-mode derivative (gfx950).
+//
+// FastGS Sec. 3: Sigma_3D = R S S^T R^T (Eq. (2)); Sigma' = J W Sigma_3D W^T J^T (Eq. (3)), of
+// which the upper-left 2x2 block is Sigma_2D; Sec. 4.4: the 3-sigma rule gives the tiles a
+// Gaussian is paired with.  One Gaussian per lane.
+//
+// Everything that decides an integer output (culling, tile rectangle, depth key, colour clamp)
+// is computed in a fixed IEEE fp32 operation order, left to right as written, with no fused
+// multiply-adds (this file is compiled with -ffp-contract=off), so that a CPU implementation
+// following the same order reproduces it bit for bit.
+#include "common.hpp"
+
+namespace fs {
+
+namespace {
+
+// Real spherical-harmonics constants (orthonormal, no Condon-Shortley sign); double literals
+// rounded once to float.
+__device__ constexpr float K0 = (float)0.28209479177387814;
+__device__ constexpr float K1 = (float)0.4886025119029199;
+__device__ constexpr float K2A = (float)1.0925484305920792;
+__device__ constexpr float K2B = (float)0.31539156525252005;
+__device__ constexpr float K2C = (float)0.5462742152960396;
+__device__ constexpr float K3A = (float)0.5900435899266435;
+__device__ constexpr float K3B = (float)2.890611442640554;
+__device__ constexpr float K3C = (float)0.4570457994644658;
+__device__ constexpr float K3D = (float)0.3731763325901154;
+__device__ constexpr float K3E = (float)1.445305721320277;
+
+__device__ __forceinline__ void sh_basis(int deg, float x, float y, float z, float* Y)
+{
+    Y[0] = K0;
+    if (deg < 1) return;
+    Y[1] = K1 * y;
+    Y[2] = K1 * z;
+    Y[3] = K1 * x;
+    if (deg < 2) return;
+    float xx = x * x, yy = y * y, zz = z * z;
+    Y[4] = K2A * (x * y);
+    Y[5] = K2A * (y * z);
+    Y[6] = K2B * (2.0f * zz - xx - yy);
+    Y[7] = K2A * (x * z);
+    Y[8] = K2C * (xx - yy);
+    if (deg < 3) return;
+    Y[9] = K3A * (y * (3.0f * xx - yy));
+    Y[10] = K3B * ((x * y) * z);
+    Y[11] = K3C * (y * (4.0f * zz - xx - yy));
+    Y[12] = K3D * (z * (2.0f * zz - 3.0f * xx - 3.0f * yy));
+    Y[13] = K3C * (x * (4.0f * zz - xx - yy));
+    Y[14] = K3E * (z * (xx - yy));
+    Y[15] = K3A * (x * (xx - 3.0f * yy));
+}
+
+// Intermediate quantities of one projection, shared by the forward and the backward kernels.
+struct Splat {
+    bool visible;
+    float tx, ty, tz;    // camera-space mean
+    float txz, tyz;      // t_x/t_z, t_y/t_z
+    float cxz, cyz;      // limited copies used inside J
+    bool xin, yin;
+    float T00, T01, T02, T10, T11, T12;  // J * R_cam (2x3)
+    float r00, r01, r02, r10, r11, r12, r20, r21, r22;  // R(q)
+    float s00, s01, s02, s11, s12, s22;  // Sigma_3D (symmetric)
+    float a, b, c, det;
+    float mx, my, radius;
+    int x0, y0, x1, y1;
+};
+
+__device__ __forceinline__ void project(const float* __restrict__ means, const float* __restrict__ scales,
+                                        const float* __restrict__ quats, int64_t i, const CamDev& cam,
+                                        const CfgDev& cfg, Splat& s)
+{
+    s.visible = false;
+    const float m0 = means[3 * i], m1 = means[3 * i + 1], m2 = means[3 * i + 2];
+    s.tx = cam.R[0] * m0 + cam.R[1] * m1 + cam.R[2] * m2 + cam.t[0];
+    s.ty = cam.R[3] * m0 + cam.R[4] * m1 + cam.R[5] * m2 + cam.t[1];
+    s.tz = cam.R[6] * m0 + cam.R[7] * m1 + cam.R[8] * m2 + cam.t[2];
+    if (!(s.tz > cfg.z_near)) return;
+
+    const float4 q = *reinterpret_cast<const float4*>(quats + 4 * i);
+    const float w = q.x, x = q.y, y = q.z, z = q.w;
+    s.r00 = 1.0f - 2.0f * (y * y + z * z);
+    s.r01 = 2.0f * (x * y - w * z);
+    s.r02 = 2.0f * (x * z + w * y);
+    s.r10 = 2.0f * (x * y + w * z);
+    s.r11 = 1.0f - 2.0f * (x * x + z * z);
+    s.r12 = 2.0f * (y * z - w * x);
+    s.r20 = 2.0f * (x * z - w * y);
+    s.r21 = 2.0f * (y * z + w * x);
+    s.r22 = 1.0f - 2.0f * (x * x + y * y);
+    const float sx = scales[3 * i], sy = scales[3 * i + 1], sz = scales[3 * i + 2];
+    const float M00 = s.r00 * sx, M01 = s.r01 * sy, M02 = s.r02 * sz;
+    const float M10 = s.r10 * sx, M11 = s.r11 * sy, M12 = s.r12 * sz;
+    const float M20 = s.r20 * sx, M21 = s.r21 * sy, M22 = s.r22 * sz;
+    s.s00 = M00 * M00 + M01 * M01 + M02 * M02;
+    s.s01 = M00 * M10 + M01 * M11 + M02 * M12;
+    s.s02 = M00 * M20 + M01 * M21 + M02 * M22;
+    s.s11 = M10 * M10 + M11 * M11 + M12 * M12;
+    s.s12 = M10 * M20 + M11 * M21 + M12 * M22;
+    s.s22 = M20 * M20 + M21 * M21 + M22 * M22;
+
+    s.txz = s.tx / s.tz;
+    s.tyz = s.ty / s.tz;
+    s.cxz = s.txz; s.cyz = s.tyz; s.xin = true; s.yin = true;
+    if (cfg.jclamp > 0.0f) {
+        const float limx = cfg.jclamp * (0.5f * (float)cam.width / cam.fx);
+        const float limy = cfg.jclamp * (0.5f * (float)cam.height / cam.fy);
+        if (s.txz > limx) { s.cxz = limx; s.xin = false; }
+        if (s.txz < -limx) { s.cxz = -limx; s.xin = false; }
+        if (s.tyz > limy) { s.cyz = limy; s.yin = false; }
+        if (s.tyz < -limy) { s.cyz = -limy; s.yin = false; }
+    }
+    const float X = s.cxz * s.tz, Y = s.cyz * s.tz;
+    const float iz = 1.0f / s.tz;
+    const float iz2 = iz * iz;
+    const float J00 = cam.fx * iz;
+    const float J02 = -(cam.fx * X) * iz2;
+    const float J11 = cam.fy * iz;
+    const float J12 = -(cam.fy * Y) * iz2;
+    s.T00 = J00 * cam.R[0] + J02 * cam.R[6];
+    s.T01 = J00 * cam.R[1] + J02 * cam.R[7];
+    s.T02 = J00 * cam.R[2] + J02 * cam.R[8];
+    s.T10 = J11 * cam.R[3] + J12 * cam.R[6];
+    s.T11 = J11 * cam.R[4] + J12 * cam.R[7];
+    s.T12 = J11 * cam.R[5] + J12 * cam.R[8];
+    const float U00 = s.T00 * s.s00 + s.T01 * s.s01 + s.T02 * s.s02;
+    const float U01 = s.T00 * s.s01 + s.T01 * s.s11 + s.T02 * s.s12;
+    const float U02 = s.T00 * s.s02 + s.T01 * s.s12 + s.T02 * s.s22;
+    const float U10 = s.T10 * s.s00 + s.T11 * s.s01 + s.T12 * s.s02;
+    const float U11 = s.T10 * s.s01 + s.T11 * s.s11 + s.T12 * s.s12;
+    const float U12 = s.T10 * s.s02 + s.T11 * s.s12 + s.T12 * s.s22;
+    const float c00 = U00 * s.T00 + U01 * s.T01 + U02 * s.T02;
+    const float c01 = U00 * s.T10 + U01 * s.T11 + U02 * s.T12;
+    const float c11 = U10 * s.T10 + U11 * s.T11 + U12 * s.T12;
+    s.a = c00 + cfg.lowpass;
+    s.b = c01;
+    s.c = c11 + cfg.lowpass;
+    s.det = s.a * s.c - s.b * s.b;
+    if (!(s.det > 0.0f)) return;
+
+    const float mid = 0.5f * (s.a + s.c);
+    const float hd = 0.5f * (s.a - s.c);
+    const float lam = mid + sqrtf(hd * hd + s.b * s.b);
+    s.radius = ceilf(3.0f * sqrtf(lam));
+    s.mx = cam.fx * s.txz + cam.cx;
+    s.my = cam.fy * s.tyz + cam.cy;
+    if (!(s.radius < 1e6f) || !(fabsf(s.mx) < 1e7f) || !(fabsf(s.my) < 1e7f)) return;
+
+    const float it = 1.0f / (float)TILE;
+    const float fx0 = floorf((s.mx - s.radius) * it);
+    const float fy0 = floorf((s.my - s.radius) * it);
+    const float fx1 = floorf((s.mx + s.radius) * it) + 1.0f;
+    const float fy1 = floorf((s.my + s.radius) * it) + 1.0f;
+    const float TXf = (float)cam.tiles_x, TYf = (float)cam.tiles_y;
+    s.x0 = (int)fminf(fmaxf(fx0, 0.0f), TXf);
+    s.y0 = (int)fminf(fmaxf(fy0, 0.0f), TYf);
+    s.x1 = (int)fminf(fmaxf(fx1, 0.0f), TXf);
+    s.y1 = (int)fminf(fmaxf(fy1, 0.0f), TYf);
+    if ((s.x1 - s.x0) * (s.y1 - s.y0) <= 0) return;
+    s.visible = true;
+}
+
+// Unit direction from the camera centre (-R^T t) to the mean, and its length.
+__device__ __forceinline__ void view_dir(const float* __restrict__ means, int64_t i, const CamDev& cam,
+                                         float d[3], float& len)
+{
+    float dir[3];
+    for (int k = 0; k < 3; k++) {
+        const float campos = -(cam.R[0 + k] * cam.t[0] + cam.R[3 + k] * cam.t[1] + cam.R[6 + k] * cam.t[2]);
+        dir[k] = means[3 * i + k] - campos;
+    }
+    len = sqrtf(dir[0] * dir[0] + dir[1] * dir[1] + dir[2] * dir[2]);
+    d[0] = dir[0] / len;
+    d[1] = dir[1] / len;
+    d[2] = dir[2] / len;
+}
+
+template <int DEG>
+__global__ __launch_bounds__(256) void k_preprocess(int64_t n, const float* __restrict__ means,
+                                                    const float* __restrict__ scales,
+                                                    const float* __restrict__ quats,
+                                                    const float* __restrict__ opac, const float* __restrict__ sh,
+                                                    CamDev cam, CfgDev cfg, float* __restrict__ mean2d,
+                                                    float* __restrict__ depth, float* __restrict__ conic_opacity,
+                                                    float* __restrict__ rgb, uint16_t* __restrict__ rect,
+                                                    uint32_t* __restrict__ touched, uint8_t* __restrict__ clamped)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    Splat s;
+    project(means, scales, quats, i, cam, cfg, s);
+    float2 m2 = make_float2(0.f, 0.f);
+    float4 co = make_float4(0.f, 0.f, 0.f, 0.f);
+    float col[3] = {0.f, 0.f, 0.f};
+    uint8_t cl[3] = {0, 0, 0};
+    float dep = 0.f;
+    ushort4 rc = make_ushort4(0, 0, 0, 0);
+    uint32_t tt = 0;
+    if (s.visible) {
+        const float idet = 1.0f / s.det;
+        co = make_float4(s.c * idet, -s.b * idet, s.a * idet, opac[i]);
+        m2 = make_float2(s.mx, s.my);
+        dep = s.tz;
+        rc = make_ushort4((unsigned short)s.x0, (unsigned short)s.y0, (unsigned short)s.x1, (unsigned short)s.y1);
+        tt = (uint32_t)((s.x1 - s.x0) * (s.y1 - s.y0));
+        float d[3], len;
+        view_dir(means, i, cam, d, len);
+        constexpr int K = (DEG + 1) * (DEG + 1);
+        float Y[K];
+        sh_basis(DEG, d[0], d[1], d[2], Y);
+        const float* c = sh + (int64_t)3 * K * i;
+        float v0 = Y[0] * c[0], v1 = Y[0] * c[1], v2 = Y[0] * c[2];
+#pragma unroll
+        for (int k = 1; k < K; k++) {
+            v0 = v0 + Y[k] * c[3 * k + 0];
+            v1 = v1 + Y[k] * c[3 * k + 1];
+            v2 = v2 + Y[k] * c[3 * k + 2];
+        }
+        v0 = v0 + 0.5f; v1 = v1 + 0.5f; v2 = v2 + 0.5f;
+        cl[0] = v0 < 0.0f; cl[1] = v1 < 0.0f; cl[2] = v2 < 0.0f;
+        col[0] = cl[0] ? 0.0f : v0;
+        col[1] = cl[1] ? 0.0f : v1;
+        col[2] = cl[2] ? 0.0f : v2;
+    }
+    *reinterpret_cast<float2*>(mean2d + 2 * i) = m2;
+    depth[i] = dep;
+    *reinterpret_cast<float4*>(conic_opacity + 4 * i) = co;
+    rgb[3 * i + 0] = col[0]; rgb[3 * i + 1] = col[1]; rgb[3 * i + 2] = col[2];
+    *reinterpret_cast<ushort4*>(rect + 4 * i) = rc;
+    touched[i] = tt;
+    clamped[3 * i + 0] = cl[0]; clamped[3 * i + 1] = cl[1]; clamped[3 * i + 2] = cl[2];
+}
+
+// d(Y_k)/d(x,y,z) dotted with per-channel weights: accumulates g_d += sum_k w_k * grad Y_k.
+template <int DEG>
+__device__ __forceinline__ void sh_dir_grad(float x, float y, float z, const float* wk /*[K]*/, float g[3])
+{
+    float gx = 0.f, gy = 0.f, gz = 0.f;
+    if (DEG >= 1) {
+        gy += K1 * wk[1];
+        gz += K1 * wk[2];
+        gx += K1 * wk[3];
+    }
+    if (DEG >= 2) {
+        gx += K2A * y * wk[4];  gy += K2A * x * wk[4];
+        gy += K2A * z * wk[5];  gz += K2A * y * wk[5];
+        gx += K2B * -2.f * x * wk[6];  gy += K2B * -2.f * y * wk[6];  gz += K2B * 4.f * z * wk[6];
+        gx += K2A * z * wk[7];  gz += K2A * x * wk[7];
+        gx += K2C * 2.f * x * wk[8];  gy += K2C * -2.f * y * wk[8];
+    }
+    if (DEG >= 3) {
+        const float xx = x * x, yy = y * y, zz = z * z;
+        gx += K3A * 6.f * x * y * wk[9];   gy += K3A * (3.f * xx - 3.f * yy) * wk[9];
+        gx += K3B * y * z * wk[10];  gy += K3B * x * z * wk[10];  gz += K3B * x * y * wk[10];
+        gx += K3C * -2.f * x * y * wk[11];  gy += K3C * (4.f * zz - xx - 3.f * yy) * wk[11];  gz += K3C * 8.f * y * z * wk[11];
+        gx += K3D * -6.f * x * z * wk[12];  gy += K3D * -6.f * y * z * wk[12];  gz += K3D * (6.f * zz - 3.f * xx - 3.f * yy) * wk[12];
+        gx += K3C * (4.f * zz - 3.f * xx - yy) * wk[13];  gy += K3C * -2.f * x * y * wk[13];  gz += K3C * 8.f * x * z * wk[13];
+        gx += K3E * 2.f * x * z * wk[14];  gy += K3E * -2.f * y * z * wk[14];  gz += K3E * (xx - yy) * wk[14];
+        gx += K3A * (3.f * xx - 3.f * yy) * wk[15];  gy += K3A * -6.f * x * y * wk[15];
+    }
+    g[0] = gx; g[1] = gy; g[2] = gz;
+}
+
+// Reverse of project(): screen-space gradients -> gradients of mean, scale, quaternion, opacity
+// and SH coefficients (dL/d opacity needs no chaining: the compositing gradient is already
+// w.r.t. the input opacity).  Outputs are overwritten; culled Gaussians get zeros.  Plain fp32
+// (sums here are not bit-pinned).
+template <int DEG>
+__global__ __launch_bounds__(256) void k_preprocess_bwd(
+    int64_t n, const float* __restrict__ means, const float* __restrict__ scales, const float* __restrict__ quats,
+    const float* __restrict__ sh, CamDev cam, CfgDev cfg, const uint8_t* __restrict__ clamped,
+    const float* __restrict__ g_mean2d, const float* __restrict__ g_conic, const float* __restrict__ g_rgb,
+    float* __restrict__ d_means, float* __restrict__ d_scales, float* __restrict__ d_quats,
+    float* __restrict__ d_sh)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    constexpr int K = (DEG + 1) * (DEG + 1);
+    Splat s;
+    project(means, scales, quats, i, cam, cfg, s);
+    float* osh = d_sh + (int64_t)3 * K * i;
+    if (!s.visible) {
+        for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
+        *reinterpret_cast<float4*>(d_quats + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < 3 * K; k++) osh[k] = 0.f;
+        return;
+    }
+    // ---- colour -> SH coefficients and, through the view direction, the mean ----
+    float d[3], len;
+    view_dir(means, i, cam, d, len);
+    float Y[K];
+    sh_basis(DEG, d[0], d[1], d[2], Y);
+    const float* c = sh + (int64_t)3 * K * i;
+    float gcol[3];
+    for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb[3 * i + ch];
+    float wk[K];
+#pragma unroll
+    for (int k = 0; k < K; k++) {
+        osh[3 * k + 0] = gcol[0] * Y[k];
+        osh[3 * k + 1] = gcol[1] * Y[k];
+        osh[3 * k + 2] = gcol[2] * Y[k];
+        wk[k] = gcol[0] * c[3 * k] + gcol[1] * c[3 * k + 1] + gcol[2] * c[3 * k + 2];
+    }
+    float gd[3];
+    sh_dir_grad<DEG>(d[0], d[1], d[2], wk, gd);
+    const float dot = gd[0] * d[0] + gd[1] * d[1] + gd[2] * d[2];
+    const float ilen = 1.0f / len;
+    float gm0 = (gd[0] - d[0] * dot) * ilen;
+    float gm1 = (gd[1] - d[1] * dot) * ilen;
+    float gm2 = (gd[2] - d[2] * dot) * ilen;
+
+    // ---- conic = Sigma_2D^-1 -> (a,b,c) ----
+    const float idet = 1.0f / s.det;
+    const float g0 = g_conic[3 * i], g1 = g_conic[3 * i + 1], g2 = g_conic[3 * i + 2];
+    const float g_det = -(g0 * s.c - g1 * s.b + g2 * s.a) * idet * idet;
+    const float ga = g2 * idet + g_det * s.c;
+    const float gb = -g1 * idet - 2.f * g_det * s.b;
+    const float gc = g0 * idet + g_det * s.a;
+    const float hb = 0.5f * gb;
+    // Sigma_2D = T Sigma_3D T^T:  dSigma_3D = T^T G T ;  dT = 2 G T Sigma_3D   (G = [[ga,hb],[hb,gc]])
+    const float T0[3] = {s.T00, s.T01, s.T02}, T1[3] = {s.T10, s.T11, s.T12};
+    const float S3[3][3] = {{s.s00, s.s01, s.s02}, {s.s01, s.s11, s.s12}, {s.s02, s.s12, s.s22}};
+    float GT0[3], GT1[3];  // rows of G*T
+    for (int k = 0; k < 3; k++) { GT0[k] = ga * T0[k] + hb * T1[k]; GT1[k] = hb * T0[k] + gc * T1[k]; }
+    float gS[3][3];
+    for (int r = 0; r < 3; r++)
+        for (int q = 0; q < 3; q++) gS[r][q] = T0[r] * GT0[q] + T1[r] * GT1[q];
+    float gT0[3], gT1[3];
+    for (int r = 0; r < 3; r++) {
+        gT0[r] = 2.f * (GT0[0] * S3[0][r] + GT0[1] * S3[1][r] + GT0[2] * S3[2][r]);
+        gT1[r] = 2.f * (GT1[0] * S3[0][r] + GT1[1] * S3[1][r] + GT1[2] * S3[2][r]);
+    }
+    // T = J R_cam
+    const float gJ00 = gT0[0] * cam.R[0] + gT0[1] * cam.R[1] + gT0[2] * cam.R[2];
+    const float gJ02 = gT0[0] * cam.R[6] + gT0[1] * cam.R[7] + gT0[2] * cam.R[8];
+    const float gJ11 = gT1[0] * cam.R[3] + gT1[1] * cam.R[4] + gT1[2] * cam.R[5];
+    const float gJ12 = gT1[0] * cam.R[6] + gT1[1] * cam.R[7] + gT1[2] * cam.R[8];
+    // J00 = fx/tz, J02 = -fx X/tz^2, J11 = fy/tz, J12 = -fy Y/tz^2, X = cxz*tz, Y = cyz*tz
+    const float iz = 1.0f / s.tz, iz2 = iz * iz;
+    const float X = s.cxz * s.tz, Yc = s.cyz * s.tz;
+    const float g_iz = cam.fx * gJ00 + cam.fy * gJ11 - 2.f * cam.fx * X * iz * gJ02 - 2.f * cam.fy * Yc * iz * gJ12;
+    const float gX = -cam.fx * iz2 * gJ02, gY = -cam.fy * iz2 * gJ12;
+    float gtz = gX * s.cxz + gY * s.cyz - g_iz * iz2;
+    float gtxz = s.xin ? gX * s.tz : 0.f;
+    float gtyz = s.yin ? gY * s.tz : 0.f;
+    gtxz += cam.fx * g_mean2d[2 * i];
+    gtyz += cam.fy * g_mean2d[2 * i + 1];
+    const float gtx = gtxz * iz, gty = gtyz * iz;
+    gtz -= (gtxz * s.tx + gtyz * s.ty) * iz2;
+    gm0 += cam.R[0] * gtx + cam.R[3] * gty + cam.R[6] * gtz;
+    gm1 += cam.R[1] * gtx + cam.R[4] * gty + cam.R[7] * gtz;
+    gm2 += cam.R[2] * gtx + cam.R[5] * gty + cam.R[8] * gtz;
+    d_means[3 * i] = gm0; d_means[3 * i + 1] = gm1; d_means[3 * i + 2] = gm2;
+
+    // ---- Sigma_3D = M M^T, M = R(q) diag(s) ----
+    const float Rq[3][3] = {{s.r00, s.r01, s.r02}, {s.r10, s.r11, s.r12}, {s.r20, s.r21, s.r22}};
+    const float sc[3] = {scales[3 * i], scales[3 * i + 1], scales[3 * i + 2]};
+    float gR[3][3];
+    float gs[3] = {0.f, 0.f, 0.f};
+    for (int r = 0; r < 3; r++)
+        for (int q = 0; q < 3; q++) {
+            float gM = 0.f;
+            for (int k = 0; k < 3; k++) gM += (gS[r][k] + gS[k][r]) * (Rq[k][q] * sc[q]);
+            gs[q] += gM * Rq[r][q];
+            gR[r][q] = gM * sc[q];
+        }
+    d_scales[3 * i] = gs[0]; d_scales[3 * i + 1] = gs[1]; d_scales[3 * i + 2] = gs[2];
+    const float4 qq = *reinterpret_cast<const float4*>(quats + 4 * i);
+    const float w = qq.x, x = qq.y, y = qq.z, z = qq.w;
+    float4 gq;
+    gq.x = 2.f * (-z * gR[0][1] + y * gR[0][2] + z * gR[1][0] - x * gR[1][2] - y * gR[2][0] + x * gR[2][1]);
+    gq.y = 2.f * (y * gR[0][1] + z * gR[0][2] + y * gR[1][0] - 2.f * x * gR[1][1] - w * gR[1][2] + z * gR[2][0] +
+                  w * gR[2][1] - 2.f * x * gR[2][2]);
+    gq.z = 2.f * (-2.f * y * gR[0][0] + x * gR[0][1] + w * gR[0][2] + x * gR[1][0] + z * gR[1][2] - w * gR[2][0] +
+                  z * gR[2][1] - 2.f * y * gR[2][2]);
+    gq.w = 2.f * (-2.f * z * gR[0][0] - w * gR[0][1] + x * gR[0][2] + w * gR[1][0] - 2.f * z * gR[1][1] +
+                  y * gR[1][2] + x * gR[2][0] + y * gR[2][1]);
+    *reinterpret_cast<float4*>(d_quats + 4 * i) = gq;
+}
+
+}  // namespace
+
+hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
+                             const CfgDev& cfg, const fs_projected& o)
+{
+    if (n == 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+#define FS_LAUNCH(D)                                                                                         \
+    hipLaunchKernelGGL(k_preprocess<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.opacities, g.sh, \
+                       cam, cfg, o.mean2d, o.depth, o.conic_opacity, o.rgb, o.rect, o.tiles_touched, o.clamped)
+    switch (deg) {
+        case 0: FS_LAUNCH(0); break;
+        case 1: FS_LAUNCH(1); break;
+        case 2: FS_LAUNCH(2); break;
+        default: FS_LAUNCH(3); break;
+    }
+#undef FS_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
+                                 const CfgDev& cfg, const uint8_t* clamped, const float* dmean2d,
+                                 const float* dconic, const float* drgb, const fs_grads& o)
+{
+    if (n == 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+#define FS_LAUNCH(D)                                                                                      \
+    hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.sh, cam, cfg, \
+                       clamped, dmean2d, dconic, drgb, o.dmeans, o.dscales, o.dquats, o.dsh)
+    switch (deg) {
+        case 0: FS_LAUNCH(0); break;
+        case 1: FS_LAUNCH(1); break;
+        case 2: FS_LAUNCH(2); break;
+        default: FS_LAUNCH(3); break;
+    }
+#undef FS_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace fs

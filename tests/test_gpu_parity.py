@@ -1,0 +1,196 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp32 CPU oracle on the same seeded
+inputs.  Integer outputs (tile rectangles, keys, order, ranges, n_contrib, mask, counts) must be
+bit-exact; images within 1e-4 relative; gradients within 1e-3 relative with the 2e-3 floor."""
+import numpy as np
+import pytest
+
+from oracle import Config, Oracle
+from paper_2511_04283_amd import scenes
+from gpu_common import assert_grads_close, gpu_pipeline
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2511_04283_amd import binding as B
+    c = B.Context("cuda:0")
+    yield c
+    c.close()
+
+
+def oracle_pipeline(o, sc, cam, target=None, dL=None):
+    proj, bins, img, fT, nc = o.forward(sc, cam)
+    out = dict(proj=proj, bins=bins, image=img, final_T=fT, n_contrib=nc)
+    if target is not None:
+        out["loss"], dl = o.l1(img, target)
+        out["dL"] = dl
+        out["mask"], out["thr"], out["err"] = o.error_mask(img, target, rule=0, k=1.0)
+        out["counts"] = o.score(proj, bins, cam, out["mask"], np.zeros(sc.n, np.int32))
+    else:
+        dl = dL
+    if dl is not None:
+        out["grads"] = o.backward(sc, cam, proj, bins, dl)
+    return out
+
+
+def check_all(g, r, sc, image_rtol=1e-4):
+    p, b = r["proj"], r["bins"]
+    # a1: integer decisions bit-exact; floats bit-exact too (same operation order)
+    assert np.array_equal(g["tiles_touched"], p.tiles_touched)
+    assert np.array_equal(g["rect"], p.rect)
+    assert np.array_equal(g["clamped"], p.clamped)
+    assert np.array_equal(g["depth"].view(np.uint32), p.depth.view(np.uint32))
+    for k in ("mean2d", "conic_opacity", "rgb"):
+        assert np.array_equal(g[k].view(np.uint32), getattr(p, k).view(np.uint32)), k
+    # a2-a5
+    assert g["num_pairs"] == b.num_pairs
+    assert np.array_equal(g["keys_sorted"], b.keys_sorted)
+    assert np.array_equal(g["gauss_sorted"], b.gauss_sorted)
+    assert np.array_equal(g["tile_ranges"], b.tile_ranges)
+    # a6
+    assert np.array_equal(g["n_contrib"], r["n_contrib"])
+    assert np.abs(g["final_T"] - r["final_T"]).max() <= 1e-6
+    err = np.abs(g["image"] - r["image"])
+    assert (err <= image_rtol * np.maximum(np.abs(r["image"]), 1e-2)).all(), float(err.max())
+    if "loss" in r and "loss" in g:
+        assert g["loss"] == pytest.approx(r["loss"], rel=1e-6)
+        assert np.array_equal(g["dL"], r["dL"])
+    if "mask" in r and "mask" in g:
+        assert np.float32(g["thr"]).view(np.uint32) == np.float32(r["thr"]).view(np.uint32)
+        assert np.array_equal(g["mask"], r["mask"])
+        assert np.array_equal(g["counts"], r["counts"])
+    if "grads" in r and "grads" in g:
+        ref = dict(r["grads"])
+        assert_grads_close(g["grads"], ref)
+
+
+def test_config1_everything(ctx, orc32):
+    sc = scenes.make_scene(1)
+    cam = sc.cameras[0]
+    tgt = scenes.target_image(1, 0, cam)
+    g = gpu_pipeline(ctx, sc, cam, target=tgt)
+    r = oracle_pipeline(orc32, sc, cam, target=tgt)
+    assert r["bins"].num_pairs == 10642 and r["counts"].sum() > 1000
+    check_all(g, r, sc)
+    assert np.array_equal(g["image"], r["image"])     # same operation order: identical bits expected
+
+
+@pytest.mark.parametrize("deg", [0, 1, 2, 3])
+def test_tiny_scenes_all_sh_degrees_ragged_image(ctx, orc32, deg):
+    # 203x117 is not a multiple of the tile size: ragged right and bottom tiles; wide spread -> culling
+    sc = scenes.tiny_scene(300 + deg, 3000, 203, 117, sh_degree=deg, log_scale=(-2.6, 0.8), spread=1.4)
+    sc.sh[:, 0, :] = sc.sh[:, 0, :] * 3.0 - 1.0          # some colours go negative: clamp path
+    cam = sc.cameras[0]
+    tgt = np.random.default_rng(deg).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    g = gpu_pipeline(ctx, sc, cam, target=tgt)
+    r = oracle_pipeline(orc32, sc, cam, target=tgt)
+    assert (r["proj"].tiles_touched == 0).any() and r["proj"].clamped.any()
+    L = r["bins"].tile_ranges[:, 1] - r["bins"].tile_ranges[:, 0]
+    assert L.max() > 256                                   # several LDS batches per tile
+    check_all(g, r, sc)
+
+
+def test_config2_cut_20k(ctx, orc32):
+    sc = scenes.make_scene(2, 20000)
+    cam = sc.cameras[0]
+    tgt = scenes.target_image(2, 0, cam)
+    g = gpu_pipeline(ctx, sc, cam, target=tgt)
+    r = oracle_pipeline(orc32, sc, cam, target=tgt)
+    check_all(g, r, sc)
+
+
+def test_both_score_modes_and_minmax_mask(ctx):
+    from paper_2511_04283_amd import binding as B
+    import torch
+    sc = scenes.tiny_scene(77, 1500, 160, 96, sh_degree=1, log_scale=(-2.5, 0.6))
+    cam = sc.cameras[0]
+    tgt = np.random.default_rng(5).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    for mode in (0, 1):
+        cfg = B.default_config()
+        cfg.score_mode = mode
+        c = B.Context("cuda:0", cfg)
+        o = Oracle(np.float32, Config(score_mode=mode))
+        g = gpu_pipeline(c, sc, cam, target=tgt, mask_rule=1, mask_k=0.35, want_bwd=False)
+        proj, bins, img, fT, nc = o.forward(sc, cam)
+        mask, thr, _ = o.error_mask(img, tgt, rule=1, k=0.35)
+        counts = o.score(proj, bins, cam, mask, np.zeros(sc.n, np.int32))
+        assert np.float32(g["thr"]).view(np.uint32) == np.float32(thr).view(np.uint32)
+        assert np.array_equal(g["mask"], mask) and 0.02 < mask.mean() < 0.9
+        assert np.array_equal(g["counts"], counts) and counts.sum() > 0
+        c.close()
+
+
+def test_counts_accumulate_over_views(ctx, orc32):
+    """Config-4 shape in small: several cameras, counts summed over views (bit-exact)."""
+    import torch
+    from paper_2511_04283_amd import binding as B
+    sc = scenes.make_scene(4, 6000)
+    views = sc.cameras[::3]
+    g = B.Gaussians.from_scene(sc, ctx.device)
+    counts = torch.zeros(sc.n, dtype=torch.int32, device=ctx.device)
+    ref = np.zeros(sc.n, np.int32)
+    for v, cam0 in enumerate(views):
+        cam = scenes.Camera(333, 219, cam0.fx / 4, cam0.fy / 4, 333 / 2.0, 219 / 2.0, cam0.R, cam0.t)
+        tgt = scenes.target_image(4, v, cam)
+        fcam = B.make_camera(cam)
+        proj = ctx.fs_preprocess(g, fcam)
+        bins = ctx.fs_bin_sort(proj, fcam)
+        image, fT, nc = ctx.fs_render_fwd(proj, bins, fcam)
+        mask, thr = ctx.fs_error_mask(image, torch.from_numpy(tgt).to(ctx.device))
+        ctx.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, counts)
+        r = oracle_pipeline(orc32, sc, cam, target=tgt)
+        assert np.array_equal(mask.cpu().numpy(), r["mask"])
+        ref += r["counts"]
+    assert np.array_equal(counts.cpu().numpy(), ref) and ref.sum() > 0
+
+
+def test_degenerate_inputs(ctx, orc32):
+    from paper_2511_04283_amd import binding as B
+    import torch
+    cam = scenes.Camera(70, 50, 60.0, 60.0, 35.0, 25.0)
+    # (1) no Gaussians at all; (2) every Gaussian culled: the image is the background
+    empty = scenes.Scene("empty", 1, np.zeros((0, 3), np.float32), np.zeros((0, 3), np.float32), np.zeros((0, 4), np.float32),
+                         np.zeros(0, np.float32), np.zeros((0, 4, 3), np.float32), [cam], 0)
+    behind = scenes.tiny_scene(5, 40, 70, 50, sh_degree=1)
+    behind.means = (behind.means - 100 * behind.cameras[0].R[2]).astype(np.float32)   # push behind the camera
+    cfg = B.default_config()
+    cfg.bg[0], cfg.bg[1], cfg.bg[2] = 0.25, 0.5, 0.75
+    c = B.Context("cuda:0", cfg)
+    for sc, cm in ((empty, cam), (behind, behind.cameras[0])):
+        dL = np.ones((3, cm.height, cm.width), np.float32)
+        g = gpu_pipeline(c, sc, cm, dL=dL)
+        assert g["num_pairs"] == 0 and not g["tile_ranges"].any() and not g["n_contrib"].any()
+        assert np.array_equal(g["final_T"], np.ones_like(g["final_T"]))
+        assert np.allclose(g["image"], np.array([0.25, 0.5, 0.75], np.float32)[:, None, None])
+        for k, v in g["grads"].items():
+            assert not v.any(), k
+    c.close()
+    # (3) one huge Gaussian over every tile, plus equal-depth ties
+    n = 40
+    means = np.tile([[0.0, 0.0, 3.0]], (n, 1)).astype(np.float32)
+    means[:, 0] = np.linspace(-0.3, 0.3, n)
+    sc = scenes.Scene("ties", 0, means, np.full((n, 3), 0.08, np.float32), np.tile([1.0, 0, 0, 0], (n, 1)).astype(np.float32),
+                      np.full(n, 0.6, np.float32), np.random.default_rng(1).normal(0.5, 1.0, (n, 1, 3)).astype(np.float32), [cam], 0)
+    sc.scales[0] = 5.0
+    tgt = np.random.default_rng(2).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    g = gpu_pipeline(ctx, sc, cam, target=tgt)
+    r = oracle_pipeline(orc32, sc, cam, target=tgt)
+    assert r["proj"].tiles_touched[0] == 5 * 4
+    check_all(g, r, sc)
+
+
+def test_error_codes(ctx):
+    import ctypes
+    from paper_2511_04283_amd import binding as B
+    lib = B.load_library()
+    assert lib.fs_preprocess(None, None, None, None) == -1
+    bad = B.default_config()
+    bad.tile = 8
+    h = ctypes.c_void_p()
+    assert lib.fs_create(ctypes.byref(h), 0, None, ctypes.byref(bad)) == -1
+    cam = B.make_camera(scenes.Camera(0, 10, 1.0, 1.0, 0.0, 0.0))
+    g = B.fs_gaussians()
+    p = B.fs_projected()
+    assert lib.fs_preprocess(ctx.handle, ctypes.byref(g), ctypes.byref(cam), ctypes.byref(p)) == -1
+    assert b"fs_preprocess" in lib.fs_last_error(ctx.handle)
