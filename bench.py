@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the FastGS rasterizer hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic view of the workload:
+fs_preprocess, fs_bin_sort, fs_render_fwd, fs_l1_grad, fs_render_bwd, fs_error_mask,
+fs_score_accumulate (every row of the scope table), inputs resident in HBM.  The headline
+workload is benchmark config 3 (500k Gaussians, SH degree 3, 1600x1064).
+
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this build is
+single-GPU by construction.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Algorithmic work per unit: flops per examined list entry ("evaluation")
+# and per blended (Gaussian, pixel) pair, for the forward and backward compositing kernels.
+FWD_FLOPS_PER_EVAL = 11     # dx, dy, q (2 mul + 2 fma + mul), -0.5*q
+FWD_FLOPS_PER_BLEND = 26    # exp (mul, rint, sub, 5 fma, ldexp) 14; alpha 2; T 2; w 1; colour 3 fma 6; + min
+BWD_FLOPS_PER_EVAL = 11
+BWD_FLOPS_PER_BLEND = 66    # exp 14; alpha 2; 1/(1-a), T, w 4; colour/alpha grads 17; conic/mean grads 20; 9-value sum 9
+PEAK_FP32_TFLOPS = 157.3    # MI355X vector fp32 (packed FMA), 256 CU x 4 SIMD x 16 lanes x 2 x 2 x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2511_04283_amd import binding as B
+    from paper_2511_04283_amd import scenes
+
+    sc = scenes.make_scene(args.config)
+    cam = sc.cameras[0]
+    target_np = scenes.target_image(args.config, 0, cam)
+    dev = torch.device("cuda:0")
+    ctx = B.Context(dev)
+    g = B.Gaussians.from_scene(sc, dev)
+    fcam = B.make_camera(cam)
+    target = torch.from_numpy(target_np).to(dev)
+    n, H, W, K = sc.n, cam.height, cam.width, (sc.sh_degree + 1) ** 2
+
+    # every output is allocated once, before the timed region
+    e = lambda *s, dt=torch.float32: torch.empty(s, dtype=dt, device=dev)
+    proj = B.Projected(e(n, 2), e(n), e(n, 4), e(n, 3), e(n, 4, dt=torch.int16), e(n, dt=torch.int32), e(n, 3, dt=torch.uint8))
+    image, final_T, n_contrib = e(3, H, W), e(H, W), e(H, W, dt=torch.int32)
+    dL = e(3, H, W)
+    loss = torch.zeros(1, dtype=torch.float64, device=dev)
+    grads = dict(means=e(n, 3), scales=e(n, 3), quats=e(n, 4), opacities=e(n), sh=e(n, K, 3), mean2d=e(n, 2))
+    mask, thr = e(H, W, dt=torch.uint8), e(1)
+    counts = torch.zeros(n, dtype=torch.int32, device=dev)
+    state = {}
+
+    def step():
+        ctx.fs_preprocess(g, fcam, proj)
+        bins = ctx.fs_bin_sort(proj, fcam)
+        ctx.fs_render_fwd(proj, bins, fcam, image, final_T, n_contrib)
+        ctx.fs_l1_grad(image, target, dL, loss)
+        ctx.fs_render_bwd(g, fcam, proj, bins, final_T, n_contrib, dL, grads)
+        ctx.fs_error_mask(image, target, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+        counts.zero_()
+        ctx.fs_score_accumulate(proj, bins, fcam, final_T, n_contrib, mask, counts)
+        state["bins"] = bins
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: K steps; the dominant kernel (backward compositing) is also timed on its own
+    # with HIP events recorded on the stream it is launched on
+    ctx.fs_profile_enable(["render_bwd", "render_fwd"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timed = ctx.fs_profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # untimed: per-kernel breakdown of the same steps
+    ctx.fs_profile_enable(None)
+    for _ in range(max(3, args.steps // 2)):
+        step()
+    prof = ctx.fs_profile_read()
+    ctx.fs_profile_enable(())
+    kernels_ms = {k: (ms / c if c else 0.0) for k, (ms, c) in prof.items()}
+
+    # units of work of one step (exact, from the path's own outputs)
+    P = state["bins"].num_pairs
+    ranges = state["bins"].copy_ranges().to(torch.int64)
+    tile_len = ranges[:, 1] - ranges[:, 0]
+    evals_bwd = int(n_contrib.to(torch.int64).sum().item())          # entries walked back per pixel
+    evals_fwd_bound = int(P) * 256                                    # upper bound: every pixel walks its whole list
+    cfgA = B.default_config()
+    cfgA.score_mode = B.FS_SCORE_ALPHA
+    ctxA = B.Context(dev, cfgA)
+    projA = ctxA.fs_preprocess(g, fcam)
+    binsA = ctxA.fs_bin_sort(projA, fcam)
+    imA, TA, ncA = ctxA.fs_render_fwd(projA, binsA, fcam)
+    blends_t = torch.zeros(n, dtype=torch.int32, device=dev)
+    ctxA.fs_score_accumulate(projA, binsA, fcam, TA, ncA, torch.ones((H, W), dtype=torch.uint8, device=dev), blends_t)
+    blends = int(blends_t.to(torch.int64).sum().item())               # blended (Gaussian, pixel) pairs
+    ctxA.close()
+
+    bwd_ms = timed["render_bwd"][0] / max(1, timed["render_bwd"][1])
+    fwd_ms = timed["render_fwd"][0] / max(1, timed["render_fwd"][1])
+    bwd_flops = BWD_FLOPS_PER_EVAL * evals_bwd + BWD_FLOPS_PER_BLEND * blends
+    fwd_flops = FWD_FLOPS_PER_EVAL * evals_fwd_bound + FWD_FLOPS_PER_BLEND * blends
+    dominant = max(kernels_ms, key=kernels_ms.get)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_cfg{args.config}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("render_bwd_bytes_per_launch")
+    achieved = bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
+    roofline = {"kernel": "k_render_bwd", "bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4), "traffic": traffic,
+                "avg_launch_ms": round(bwd_ms, 4), "flops_per_launch": bwd_flops,
+                "dominant_group_by_time": dominant}
+
+    out = {
+        "metric": "rasterizer fwd+bwd iters/s at 500k Gaussians, 1600x1064" if args.config == 3
+                  else f"rasterizer fwd+bwd iters/s (config {args.config})",
+        "value": round(1e3 / ms_per_step, 3), "unit": "iters/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": sc.name, "gaussians": n, "sh_degree": sc.sh_degree, "image": [W, H],
+                   "pairs": int(P), "max_tile_list": int(tile_len.max().item()),
+                   "step": "preprocess+bin_sort+render_fwd+l1_grad+render_bwd+error_mask+score_accumulate"},
+        "roofline": roofline,
+        "kernels_ms": {k: round(v, 4) for k, v in kernels_ms.items()},
+        "gaussian_pixel_evals_per_s": round((evals_fwd_bound + evals_bwd) / (ms_per_step * 1e-3), 1),
+        "render_fwd": {"avg_launch_ms": round(fwd_ms, 4),
+                       "achieved_tflops": round(fwd_flops / (fwd_ms * 1e-3) / 1e12, 3) if fwd_ms > 0 else 0.0},
+        "work": {"evals_fwd_upper_bound": evals_fwd_bound, "evals_bwd": evals_bwd, "blends": blends},
+        "loss": float(loss.item()),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import Oracle
+        o = Oracle(np.float32)
+        c0 = time.perf_counter()
+        p_o, b_o, img_o, T_o, nc_o = o.forward(sc, cam)
+        l_o, dL_o = o.l1(img_o, target_np)
+        o.backward(sc, cam, p_o, b_o, dL_o)
+        m_o, thr_o, _ = o.error_mask(img_o, target_np)
+        o.score(p_o, b_o, cam, m_o, np.zeros(n, np.int32))
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(1.0 / (c1 - c0), 5), "unit": "iters/s", "cores": 1, "kind": "oracle",
+                               "sample": f"one full step of {sc.name} (all tiles, same arrays), single thread, "
+                                         f"{c1 - c0:.1f} s", "host_cores_visible": os.cpu_count()}
+        out["cpu_baseline"]["loss_matches_gpu"] = bool(abs(l_o - out["loss"]) <= 1e-6 * max(1.0, abs(l_o)))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

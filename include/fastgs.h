@@ -165,6 +165,30 @@ int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bi
                         const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
                         int32_t *counts);
 
+/* ---- measurement helpers (no part of the method) ------------------------------------------
+ * Per-kernel timing with HIP events recorded on the ctx stream around the launches of the
+ * selected kernel groups.  fs_profile_enable(mask) clears the accumulated times and selects the
+ * groups (bit k = group k below; 0 switches timing off).  fs_profile_read synchronises the
+ * stream and returns the accumulated duration and the number of timed launches of one group.
+ * Errors: FS_EINVAL (bad group), FS_EHIP. */
+enum {
+    FS_K_PREPROCESS = 0, /* k_preprocess                                  */
+    FS_K_SCAN,           /* the three kernels of the tiles_touched scan   */
+    FS_K_EMIT,           /* k_emit_pairs                                  */
+    FS_K_RADIX_SORT,     /* all passes: histogram, scan, scatter          */
+    FS_K_RANGES,         /* fill + k_tile_ranges                          */
+    FS_K_RENDER_FWD,     /* k_render_fwd                                  */
+    FS_K_L1,             /* k_l1_grad (+ final reduction)                 */
+    FS_K_FILL,           /* zeroing of the gradient accumulators          */
+    FS_K_RENDER_BWD,     /* k_render_bwd                                  */
+    FS_K_PREPROCESS_BWD, /* k_preprocess_bwd                              */
+    FS_K_ERR_MASK,       /* the kernels of fs_error_mask                  */
+    FS_K_SCORE,          /* k_score                                       */
+    FS_K_COUNT
+};
+int fs_profile_enable(fs_ctx *ctx, uint32_t group_mask);
+int fs_profile_read(fs_ctx *ctx, int32_t group, const char **name, double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -192,11 +192,11 @@ class Oracle:
         return tot, hit
 
     # -- a6 --------------------------------------------------------------------------
-    def render_fwd(self, proj: Projected, bins: Bins, cam, tile_list=None):
+    def render_fwd(self, proj: Projected, bins: Bins, cam, tile_list=None, out=None):
         H, W, dt = cam.height, cam.width, self.dtype
-        image = np.zeros((3, H, W), dt)
-        final_T = np.ones((H, W), dt)
-        n_contrib = np.zeros((H, W), np.uint32)
+        if out is None:
+            out = (np.zeros((3, H, W), dt), np.ones((H, W), dt), np.zeros((H, W), np.uint32))
+        image, final_T, n_contrib = out
         tl, ntl = self._tl(tile_list)
         self._f("orc_render_fwd")(
             _p(proj.mean2d), _p(proj.conic_opacity), _p(proj.rgb), _p(bins.gauss_sorted), _p(bins.tile_ranges),
@@ -268,6 +268,51 @@ class Oracle:
             ctypes.c_int(self.cfg.tile), ctypes.c_int(self.cfg.score_mode), _p(np.ascontiguousarray(mask)),
             _p(tl), ctypes.c_int(ntl), _p(counts))
         return counts
+
+    # -- test-harness convenience: the same single-threaded routines called from several Python
+    #    threads on disjoint tile subsets (ctypes releases the GIL).  Forward outputs are disjoint
+    #    per tile; accumulated outputs get one private array per thread, added up in thread order.
+    def _split(self, cam, tile_list, threads):
+        TX, TY = self._tiles(cam)
+        tl = np.arange(TX * TY, dtype=np.int32) if tile_list is None else np.asarray(tile_list, np.int32)
+        return [tl[k::threads] for k in range(threads) if tl[k::threads].size]
+
+    def render_fwd_mt(self, proj, bins, cam, tile_list=None, threads=8):
+        from concurrent.futures import ThreadPoolExecutor
+        H, W, dt = cam.height, cam.width, self.dtype
+        out = (np.zeros((3, H, W), dt), np.ones((H, W), dt), np.zeros((H, W), np.uint32))
+        parts = self._split(cam, tile_list, threads)
+        with ThreadPoolExecutor(len(parts) or 1) as ex:
+            list(ex.map(lambda tl: self.render_fwd(proj, bins, cam, tl, out), parts))
+        return out
+
+    def render_bwd_mt(self, proj, bins, cam, dL_dimage, tile_list=None, threads=8):
+        from concurrent.futures import ThreadPoolExecutor
+        parts = self._split(cam, tile_list, threads)
+        with ThreadPoolExecutor(len(parts) or 1) as ex:
+            res = list(ex.map(lambda tl: self.render_bwd(proj, bins, cam, dL_dimage, tl), parts))
+        if not res:
+            return self.render_bwd(proj, bins, cam, dL_dimage, np.zeros(0, np.int32))
+        acc = [a.copy() for a in res[0]]
+        for r in res[1:]:
+            for a, b in zip(acc, r):
+                a += b
+        return tuple(acc)
+
+    def score_mt(self, proj, bins, cam, mask, counts, tile_list=None, threads=8):
+        from concurrent.futures import ThreadPoolExecutor
+        parts = self._split(cam, tile_list, threads)
+        with ThreadPoolExecutor(len(parts) or 1) as ex:
+            res = list(ex.map(lambda tl: self.score(proj, bins, cam, mask, np.zeros_like(counts), tl), parts))
+        for r in res:
+            counts += r
+        return counts
+
+    def backward_mt(self, sc, cam, proj, bins, dL_dimage, tile_list=None, threads=8):
+        d2 = self.render_bwd_mt(proj, bins, cam, dL_dimage, tile_list, threads)
+        g = self.preprocess_bwd(sc, cam, *d2)
+        g["mean2d"], g["conic"], g["rgb"] = d2[0], d2[1], d2[3]
+        return g
 
     # -- whole path (used by finite differences and by the timed CPU baseline) ---------
     def forward(self, sc, cam):

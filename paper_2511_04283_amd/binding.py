@@ -21,7 +21,10 @@ FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate")
+           "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
+           "fs_profile_enable", "fs_profile_read")
+KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "fill",
+                 "render_bwd", "preprocess_bwd", "error_mask", "score")
 
 
 class fs_config(ctypes.Structure):
@@ -86,6 +89,8 @@ def load_library() -> ctypes.CDLL:
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
+    lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
+    lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
     for name in EXPORTS:
         if name not in ("fs_default_config", "fs_destroy", "fs_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -236,6 +241,23 @@ class Context:
         if rc != FS_OK:
             msg = self.lib.fs_last_error(self.handle)
             raise RuntimeError(f"{what}: {_STATUS.get(rc, rc)}: {msg.decode() if msg else ''}")
+
+    # ---- measurement helpers --------------------------------------------------------------
+    def fs_profile_enable(self, groups=None):
+        """groups: iterable of names from KERNEL_GROUPS (None = all, () = off)."""
+        mask = (1 << len(KERNEL_GROUPS)) - 1 if groups is None else sum(1 << KERNEL_GROUPS.index(g) for g in groups)
+        self._check(self.lib.fs_profile_enable(self.handle, mask), "fs_profile_enable")
+
+    def fs_profile_read(self) -> dict:
+        """{group: (total_ms, launches)} accumulated since fs_profile_enable."""
+        out = {}
+        for k, nm in enumerate(KERNEL_GROUPS):
+            name, ms, cnt = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_int64()
+            self._check(self.lib.fs_profile_read(self.handle, k, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(cnt)),
+                        "fs_profile_read")
+            assert name.value.decode() == nm
+            out[nm] = (ms.value, cnt.value)
+        return out
 
     # ---- the calls of fastgs.h, same names ------------------------------------------------
     def fs_preprocess(self, g: Gaussians, cam: fs_camera, out: Projected | None = None) -> Projected:

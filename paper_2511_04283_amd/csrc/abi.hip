@@ -5,6 +5,8 @@
 #include <string.h>
 
 #include <new>
+#include <utility>
+#include <vector>
 
 #include "common.hpp"
 
@@ -33,6 +35,13 @@ struct fs_ctx {
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: scan total
     uint64_t* total_host = nullptr;  // pinned host copy
+
+    // per-group event timing (measurement only)
+    uint32_t prof_mask = 0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pending[FS_K_COUNT];
+    std::vector<hipEvent_t> prof_free;
+    double prof_ms[FS_K_COUNT] = {};
+    int64_t prof_launches[FS_K_COUNT] = {};
 };
 
 namespace {
@@ -81,6 +90,42 @@ int ensure(fs_ctx* ctx, ScratchBuf& b, size_t bytes, const char* what)
         int rc_ = (expr);       \
         if (rc_ != FS_OK) return rc_; \
     } while (0)
+
+const char* const kGroupNames[FS_K_COUNT] = {"preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges",
+                                             "render_fwd", "l1_grad", "fill", "render_bwd", "preprocess_bwd",
+                                             "error_mask", "score"};
+
+hipEvent_t prof_event(fs_ctx* ctx)
+{
+    if (!ctx->prof_free.empty()) {
+        hipEvent_t e = ctx->prof_free.back();
+        ctx->prof_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return e;
+}
+
+// Records an event pair around the launches issued during its lifetime when the group is selected.
+struct ProfScope {
+    fs_ctx* ctx;
+    int group;
+    hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(fs_ctx* c, int g) : ctx(c), group(g)
+    {
+        if (!(ctx->prof_mask >> g & 1u)) return;
+        a = prof_event(ctx);
+        b = prof_event(ctx);
+        if (a && b) (void)hipEventRecord(a, ctx->stream);
+    }
+    ~ProfScope()
+    {
+        if (!a || !b) return;
+        (void)hipEventRecord(b, ctx->stream);
+        ctx->prof_pending[group].emplace_back(a, b);
+    }
+};
 
 bool make_cam(const fs_camera* cam, CamDev& d)
 {
@@ -176,6 +221,9 @@ void fs_destroy(fs_ctx* ctx)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
     if (ctx->total_host) (void)hipHostFree(ctx->total_host);
+    for (auto& v : ctx->prof_pending)
+        for (auto& pr : v) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+    for (hipEvent_t e : ctx->prof_free) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -191,6 +239,7 @@ int fs_preprocess(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, fs_p
         return fail(ctx, FS_EINVAL, "fs_preprocess: null array");
     if (g->n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_preprocess: n does not fit 31 bits");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    ProfScope prof(ctx, FS_K_PREPROCESS);
     FS_HIP(launch_preprocess(ctx->stream, g->n, g->sh_degree, *g, cd, make_cfg(ctx->cfg), *out), "k_preprocess");
     return FS_OK;
 }
@@ -211,9 +260,12 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
 
     // a2: offsets and the pair count P (the one host read-back of the path)
-    FS_HIP(launch_exclusive_scan(st, proj ? proj->tiles_touched : nullptr, static_cast<uint32_t*>(ctx->offsets.ptr), n,
-                                 ctx->scan_tmp.ptr, ctx->total_dev),
-           "scan");
+    {
+        ProfScope prof(ctx, FS_K_SCAN);
+        FS_HIP(launch_exclusive_scan(st, proj ? proj->tiles_touched : nullptr, static_cast<uint32_t*>(ctx->offsets.ptr),
+                                     n, ctx->scan_tmp.ptr, ctx->total_dev),
+               "scan");
+    }
     FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
     FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
     const uint64_t P = *ctx->total_host;
@@ -232,16 +284,24 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     int res = 0;
     if (P > 0) {
         // a3
-        FS_HIP(launch_emit_pairs(st, n, proj->rect, proj->depth, static_cast<const uint32_t*>(ctx->offsets.ptr),
-                                 cd.tiles_x, keys[0], vals[0]),
-               "k_emit_pairs");
-        // a4: the sign bit of a positive depth is 0, so 31 depth bits + the tile bits are live
+        {
+            ProfScope prof(ctx, FS_K_EMIT);
+            FS_HIP(launch_emit_pairs(st, n, proj->rect, proj->depth, static_cast<const uint32_t*>(ctx->offsets.ptr),
+                                     cd.tiles_x, keys[0], vals[0]),
+                   "k_emit_pairs");
+        }
+        // a4: 32 depth bits + the tile bits are live
+        ProfScope prof(ctx, FS_K_RADIX_SORT);
         FS_HIP(launch_radix_sort(st, (int64_t)P, 32 + tile_bits(tiles), keys, vals, static_cast<uint32_t*>(ctx->hist.ptr),
                                  ctx->scan_tmp.ptr, ctx->total_dev, &res),
                "radix sort");
     }
     // a5
-    FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr)), "k_tile_ranges");
+    {
+        ProfScope prof(ctx, FS_K_RANGES);
+        FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr)),
+               "k_tile_ranges");
+    }
     out->num_pairs = (int64_t)P;
     out->keys_sorted = keys[res];
     out->gauss_sorted = vals[res];
@@ -259,6 +319,7 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    ProfScope prof(ctx, FS_K_RENDER_FWD);
     FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
                              proj ? proj->mean2d : nullptr, proj ? proj->conic_opacity : nullptr,
                              proj ? proj->rgb : nullptr, image, final_T, n_contrib),
@@ -274,6 +335,7 @@ int fs_l1_grad(fs_ctx* ctx, const float* image, const float* target, int32_t hei
         return fail(ctx, FS_EINVAL, "fs_l1_grad: bad arguments");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
+    ProfScope prof(ctx, FS_K_L1);
     FS_HIP(launch_l1_grad(ctx->stream, image, target, (int64_t)3 * height * width, dL_dimage,
                           static_cast<double*>(ctx->partial.ptr), loss_out),
            "k_l1_grad");
@@ -305,17 +367,23 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
         if (!drgb) drgb = static_cast<float*>(ctx->grad2d.ptr) + 3 * n;
     }
     // accumulators of the atomics start at zero (fill kernels, so the call can be graph-captured)
-    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dmean2d), 0u, 2 * n), "fill");
-    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dopacities), 0u, n), "fill");
-    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(dconic), 0u, 3 * n), "fill");
-    FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(drgb), 0u, 3 * n), "fill");
+    {
+        ProfScope prof(ctx, FS_K_FILL);
+        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dmean2d), 0u, 2 * n), "fill");
+        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dopacities), 0u, n), "fill");
+        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(dconic), 0u, 3 * n), "fill");
+        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(drgb), 0u, 3 * n), "fill");
+    }
     const CfgDev cf = make_cfg(ctx->cfg);
     // a8
-    if (bins->num_pairs > 0)
+    if (bins->num_pairs > 0) {
+        ProfScope prof(ctx, FS_K_RENDER_BWD);
         FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted, proj->mean2d, proj->conic_opacity,
                                  proj->rgb, final_T, n_contrib, dL_dimage, out->dmean2d, dconic, out->dopacities, drgb),
                "k_render_bwd");
+    }
     // a9
+    ProfScope prof(ctx, FS_K_PREPROCESS_BWD);
     FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, out->dmean2d, dconic, drgb, *out),
            "k_preprocess_bwd");
     return FS_OK;
@@ -334,6 +402,7 @@ int fs_error_mask(fs_ctx* ctx, const float* image, const float* target, int32_t 
     FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
     float* err = static_cast<float*>(ctx->err_map.ptr);
     float* thr = threshold_out ? threshold_out : err + pixels;
+    ProfScope prof(ctx, FS_K_ERR_MASK);
     FS_HIP(launch_error_mask(ctx->stream, image, target, pixels, rule, k, err, static_cast<double*>(ctx->partial.ptr),
                              mask, thr),
            "k_err_*");
@@ -351,9 +420,52 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (bins->num_pairs == 0) return FS_OK;
     if (!proj_ok(proj) || !bins->gauss_sorted || !counts) return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    ProfScope prof(ctx, FS_K_SCORE);
     FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted, proj->mean2d,
                         proj->conic_opacity, n_contrib, mask, counts),
            "k_score");
+    return FS_OK;
+}
+
+static int prof_collect(fs_ctx* ctx)
+{
+    FS_HIP(hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");
+    for (int g = 0; g < FS_K_COUNT; g++) {
+        for (auto& pr : ctx->prof_pending[g]) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) {
+                ctx->prof_ms[g] += (double)ms;
+                ctx->prof_launches[g] += 1;
+            } else {
+                (void)hipGetLastError();
+            }
+            ctx->prof_free.push_back(pr.first);
+            ctx->prof_free.push_back(pr.second);
+        }
+        ctx->prof_pending[g].clear();
+    }
+    return FS_OK;
+}
+
+int fs_profile_enable(fs_ctx* ctx, uint32_t group_mask)
+{
+    if (!ctx) return FS_EINVAL;
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_TRY(prof_collect(ctx));
+    for (int g = 0; g < FS_K_COUNT; g++) { ctx->prof_ms[g] = 0.0; ctx->prof_launches[g] = 0; }
+    ctx->prof_mask = group_mask & ((1u << FS_K_COUNT) - 1u);
+    return FS_OK;
+}
+
+int fs_profile_read(fs_ctx* ctx, int32_t group, const char** name, double* total_ms, int64_t* launches)
+{
+    if (!ctx) return FS_EINVAL;
+    if (group < 0 || group >= FS_K_COUNT) return fail(ctx, FS_EINVAL, "fs_profile_read: bad group");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_TRY(prof_collect(ctx));
+    if (name) *name = kGroupNames[group];
+    if (total_ms) *total_ms = ctx->prof_ms[group];
+    if (launches) *launches = ctx->prof_launches[group];
     return FS_OK;
 }
 
