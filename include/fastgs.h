@@ -96,6 +96,8 @@ typedef struct {
     const uint64_t *keys_sorted;  /* [P] tile_id << 32 | bits(depth), ascending; ties by Gaussian index */
     const uint32_t *gauss_sorted; /* [P] Gaussian index of each entry                                 */
     const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
+    const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted at
+                                     pair_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0), before the sort         */
 } fs_bins;
 
 /* Output of fs_render_bwd, caller-owned, OVERWRITTEN (not accumulated). dconic and drgb may be
@@ -146,7 +148,10 @@ int fs_l1_grad(fs_ctx *ctx, const float *image, const float *target, int32_t hei
                float *dL_dimage, double *loss_out);
 
 /* Steps a8+a9: back-to-front gradient of the compositing, reduced per Gaussian, then chained
- * through the projection to the scene parameters.  final_T / n_contrib are fs_render_fwd's. */
+ * through the projection to the scene parameters.  final_T / n_contrib are fs_render_fwd's; bins
+ * must be the result of the last fs_bin_sort on this ctx for the same proj (its pair_offsets are
+ * used to give every Gaussian-tile pair its own slot of partial sums, so no atomics are needed
+ * and the result is reproducible run to run).  Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP. */
 int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, const fs_projected *proj,
                   const fs_bins *bins, const float *final_T, const uint32_t *n_contrib,
                   const float *dL_dimage, fs_grads *out);

@@ -13,7 +13,8 @@ from dataclasses import dataclass
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libfastgs_hip.so")
+# FASTGS_HIP_LIB names another build of the same library (e.g. an experimental variant)
+LIB_PATH = os.environ.get("FASTGS_HIP_LIB") or os.path.join(_PKG, "libfastgs_hip.so")
 
 FS_OK = 0
 FS_SCORE_WEIGHT, FS_SCORE_ALPHA = 0, 1
@@ -52,7 +53,7 @@ class fs_projected(ctypes.Structure):
 
 class fs_bins(ctypes.Structure):
     _fields_ = [("num_pairs", ctypes.c_int64), ("keys_sorted", ctypes.c_void_p), ("gauss_sorted", ctypes.c_void_p),
-                ("tile_ranges", ctypes.c_void_p)]
+                ("tile_ranges", ctypes.c_void_p), ("pair_offsets", ctypes.c_void_p)]
 
 
 class fs_grads(ctypes.Structure):

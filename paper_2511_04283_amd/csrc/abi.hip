@@ -30,7 +30,7 @@ struct fs_ctx {
     ScratchBuf vals[2];       // uint32 [P] ping-pong
     ScratchBuf hist;          // uint32 [256 * radix blocks]
     ScratchBuf ranges;        // uint32 [tiles, 2]
-    ScratchBuf grad2d;        // float  [n, 3] dconic and [n, 3] drgb when the caller passes none
+    ScratchBuf pair_grad;     // float  [P, PAIR_REC] per-pair partial gradients of the backward pass
     ScratchBuf err_map;       // float  [H*W]
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: scan total
@@ -216,7 +216,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
-                         &ctx->hist, &ctx->ranges, &ctx->grad2d, &ctx->err_map, &ctx->partial};
+                         &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->err_map, &ctx->partial};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -306,6 +306,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->keys_sorted = keys[res];
     out->gauss_sorted = vals[res];
     out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
+    out->pair_offsets = static_cast<const uint32_t*>(ctx->offsets.ptr);
     return FS_OK;
 }
 
@@ -359,32 +360,22 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
         return fail(ctx, FS_EINVAL, "fs_render_bwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
-    float* dconic = out->dconic;
-    float* drgb = out->drgb;
-    if (!dconic || !drgb) {
-        FS_TRY(ensure(ctx, ctx->grad2d, (size_t)n * 6 * sizeof(float), "2D gradients"));
-        if (!dconic) dconic = static_cast<float*>(ctx->grad2d.ptr);
-        if (!drgb) drgb = static_cast<float*>(ctx->grad2d.ptr) + 3 * n;
-    }
-    // accumulators of the atomics start at zero (fill kernels, so the call can be graph-captured)
-    {
-        ProfScope prof(ctx, FS_K_FILL);
-        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dmean2d), 0u, 2 * n), "fill");
-        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(out->dopacities), 0u, n), "fill");
-        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(dconic), 0u, 3 * n), "fill");
-        FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(drgb), 0u, 3 * n), "fill");
-    }
+    if (bins->num_pairs > 0 && !bins->pair_offsets) return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without pair_offsets");
+    FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_pairs ? bins->num_pairs : 1) * PAIR_REC * sizeof(float),
+                  "pair gradients"));
+    float* pair_grad = static_cast<float*>(ctx->pair_grad.ptr);
     const CfgDev cf = make_cfg(ctx->cfg);
-    // a8
+    // a8: every pair's record is written exactly once
     if (bins->num_pairs > 0) {
         ProfScope prof(ctx, FS_K_RENDER_BWD);
         FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted, proj->mean2d, proj->conic_opacity,
-                                 proj->rgb, final_T, n_contrib, dL_dimage, out->dmean2d, dconic, out->dopacities, drgb),
+                                 proj->rgb, final_T, n_contrib, dL_dimage, proj->rect, bins->pair_offsets, pair_grad),
                "k_render_bwd");
     }
-    // a9
+    // a9: per-Gaussian sum of its records, then the chain through the projection
     ProfScope prof(ctx, FS_K_PREPROCESS_BWD);
-    FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, out->dmean2d, dconic, drgb, *out),
+    FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, proj->tiles_touched, bins->pair_offsets,
+                                 pair_grad, *out),
            "k_preprocess_bwd");
     return FS_OK;
 }

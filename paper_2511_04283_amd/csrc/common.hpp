@@ -31,9 +31,11 @@ struct CfgDev {
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) ------------------------
 hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                              const CfgDev& cfg, const fs_projected& out);
+// pair_grad: [P] records of PAIR_REC floats (see render.hip); offsets/touched as in fs_bins/fs_projected
+constexpr int PAIR_REC = 12;
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
-                                 const CfgDev& cfg, const uint8_t* clamped, const float* dmean2d,
-                                 const float* dconic, const float* drgb, const fs_grads& out);
+                                 const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
+                                 const uint32_t* offsets, const float* pair_grad, const fs_grads& out);
 
 // exclusive scan of n uint32 values; total (uint64) written to *total_dev. tmp: >= scan_tmp_bytes(n).
 size_t scan_tmp_bytes(int64_t n);
@@ -60,8 +62,8 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
                              const float* rgb, const float* final_T, const uint32_t* n_contrib,
-                             const float* dL_dimage, float* dmean2d, float* dconic, float* dopac,
-                             float* drgb);
+                             const float* dL_dimage, const uint16_t* rect, const uint32_t* offsets,
+                             float* pair_grad);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                         const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,

@@ -261,21 +261,61 @@ __device__ __forceinline__ void sh_dir_grad(float x, float y, float z, const flo
     g[0] = gx; g[1] = gy; g[2] = gz;
 }
 
-// Reverse of project(): screen-space gradients -> gradients of mean, scale, quaternion, opacity
-// and SH coefficients (dL/d opacity needs no chaining: the compositing gradient is already
-// w.r.t. the input opacity).  Outputs are overwritten; culled Gaussians get zeros.  Plain fp32
-// (sums here are not bit-pinned).
+// Reverse of project().  First the screen-space gradients of Gaussian i are formed by adding up
+// its pairs' records (contiguous: pair_offsets[i] .. + tiles_touched[i], each record = dL/drgb 3,
+// dL/dsigma, dL/dconic 3, dL/dmu_2D 2, padded to PAIR_REC floats), in a fixed order; then they are
+// chained to the gradients of mean, scale, quaternion and SH coefficients (dL/d opacity needs no
+// chaining).  Outputs are overwritten; culled Gaussians get zeros.  Plain fp32 (not bit-pinned).
 template <int DEG>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(
     int64_t n, const float* __restrict__ means, const float* __restrict__ scales, const float* __restrict__ quats,
     const float* __restrict__ sh, CamDev cam, CfgDev cfg, const uint8_t* __restrict__ clamped,
-    const float* __restrict__ g_mean2d, const float* __restrict__ g_conic, const float* __restrict__ g_rgb,
-    float* __restrict__ d_means, float* __restrict__ d_scales, float* __restrict__ d_quats,
-    float* __restrict__ d_sh)
+    const uint32_t* __restrict__ touched, const uint32_t* __restrict__ offsets,
+    const float4* __restrict__ pair_grad, float* __restrict__ d_means, float* __restrict__ d_scales,
+    float* __restrict__ d_quats, float* __restrict__ d_sh, float* __restrict__ d_opac,
+    float* __restrict__ d_mean2d, float* __restrict__ d_conic /* may be null */,
+    float* __restrict__ d_rgb /* may be null */)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
     constexpr int K = (DEG + 1) * (DEG + 1);
+
+    // ---- screen-space gradients: sum of this Gaussian's pair records, in tile order ----------
+    // The 64 Gaussians of a wavefront own one contiguous run of records.  The wavefront streams that
+    // run through LDS in chunks with coalesced 16-byte loads; each lane then adds up its own records.
+    constexpr int CH = 128;                       // records per chunk and wavefront
+    __shared__ float4 s_rec[4][CH * (PAIR_REC / 4)];
+    float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb = ra;
+    float rc = 0.f;
+    {
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const uint32_t off = i < n ? offsets[i] : 0u;
+        const uint32_t cnt = i < n ? touched[i] : 0u;
+        uint32_t lo_all = cnt ? off : 0xffffffffu, hi_all = cnt ? off + cnt : 0u;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            lo_all = min(lo_all, (uint32_t)__shfl_xor((int)lo_all, d, 64));
+            hi_all = max(hi_all, (uint32_t)__shfl_xor((int)hi_all, d, 64));
+        }
+        float4* buf = s_rec[wave];
+        for (uint32_t cs = lo_all; cs < hi_all; cs += CH) {
+            const uint32_t nrec = min((uint32_t)CH, hi_all - cs);
+            const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
+            for (uint32_t q = lane; q < nrec * (PAIR_REC / 4); q += 64) buf[q] = src[q];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t r0 = max(off, cs), r1 = min(off + cnt, cs + nrec);
+            for (uint32_t r = r0; r < r1; r++) {
+                const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1];
+                const float c = buf[(r - cs) * 3 + 2].x;
+                ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
+                rb.x += b.x; rb.y += b.y; rb.z += b.z; rb.w += b.w;
+                rc += c;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    if (i >= n) return;
     Splat s;
     project(means, scales, quats, i, cam, cfg, s);
     float* osh = d_sh + (int64_t)3 * K * i;
@@ -283,8 +323,19 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
         *reinterpret_cast<float4*>(d_quats + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int k = 0; k < 3 * K; k++) osh[k] = 0.f;
+        d_opac[i] = 0.f;
+        d_mean2d[2 * i] = 0.f; d_mean2d[2 * i + 1] = 0.f;
+        if (d_conic) for (int k = 0; k < 3; k++) d_conic[3 * i + k] = 0.f;
+        if (d_rgb) for (int k = 0; k < 3; k++) d_rgb[3 * i + k] = 0.f;
         return;
     }
+    const float g_rgb3[3] = {ra.x, ra.y, ra.z};
+    const float g_conic3[3] = {rb.x, rb.y, rb.z};
+    const float g_m2[2] = {rb.w, rc};
+    d_opac[i] = ra.w;
+    d_mean2d[2 * i] = g_m2[0]; d_mean2d[2 * i + 1] = g_m2[1];
+    if (d_conic) { d_conic[3 * i] = g_conic3[0]; d_conic[3 * i + 1] = g_conic3[1]; d_conic[3 * i + 2] = g_conic3[2]; }
+    if (d_rgb) { d_rgb[3 * i] = g_rgb3[0]; d_rgb[3 * i + 1] = g_rgb3[1]; d_rgb[3 * i + 2] = g_rgb3[2]; }
     // ---- colour -> SH coefficients and, through the view direction, the mean ----
     float d[3], len;
     view_dir(means, i, cam, d, len);
@@ -292,7 +343,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     sh_basis(DEG, d[0], d[1], d[2], Y);
     const float* c = sh + (int64_t)3 * K * i;
     float gcol[3];
-    for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb[3 * i + ch];
+    for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb3[ch];
     float wk[K];
 #pragma unroll
     for (int k = 0; k < K; k++) {
@@ -311,7 +362,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
 
     // ---- conic = Sigma_2D^-1 -> (a,b,c) ----
     const float idet = 1.0f / s.det;
-    const float g0 = g_conic[3 * i], g1 = g_conic[3 * i + 1], g2 = g_conic[3 * i + 2];
+    const float g0 = g_conic3[0], g1 = g_conic3[1], g2 = g_conic3[2];
     const float g_det = -(g0 * s.c - g1 * s.b + g2 * s.a) * idet * idet;
     const float ga = g2 * idet + g_det * s.c;
     const float gb = -g1 * idet - 2.f * g_det * s.b;
@@ -343,8 +394,8 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     float gtz = gX * s.cxz + gY * s.cyz - g_iz * iz2;
     float gtxz = s.xin ? gX * s.tz : 0.f;
     float gtyz = s.yin ? gY * s.tz : 0.f;
-    gtxz += cam.fx * g_mean2d[2 * i];
-    gtyz += cam.fy * g_mean2d[2 * i + 1];
+    gtxz += cam.fx * g_m2[0];
+    gtyz += cam.fy * g_m2[1];
     const float gtx = gtxz * iz, gty = gtyz * iz;
     gtz -= (gtxz * s.tx + gtyz * s.ty) * iz2;
     gm0 += cam.R[0] * gtx + cam.R[3] * gty + cam.R[6] * gtz;
@@ -399,14 +450,15 @@ hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussi
 }
 
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
-                                 const CfgDev& cfg, const uint8_t* clamped, const float* dmean2d,
-                                 const float* dconic, const float* drgb, const fs_grads& o)
+                                 const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
+                                 const uint32_t* offsets, const float* pair_grad, const fs_grads& o)
 {
     if (n == 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
 #define FS_LAUNCH(D)                                                                                      \
     hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.sh, cam, cfg, \
-                       clamped, dmean2d, dconic, drgb, o.dmeans, o.dscales, o.dquats, o.dsh)
+                       clamped, touched, offsets, reinterpret_cast<const float4*>(pair_grad), o.dmeans, o.dscales,  \
+                       o.dquats, o.dsh, o.dopacities, o.dmean2d, o.dconic, o.drgb)
     switch (deg) {
         case 0: FS_LAUNCH(0); break;
         case 1: FS_LAUNCH(1); break;

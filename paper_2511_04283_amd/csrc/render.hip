@@ -5,13 +5,20 @@
 // Eq. (5): G'_i(p) = exp(-1/2 (p - mu_2D)^T Sigma_2D^-1 (p - mu_2D)).
 // Sec. 4.2, Eq. for s_d: per Gaussian, the number of high-error pixels in its footprint.
 //
-// One workgroup (4 wavefronts) per 16x16 tile; wavefront w owns the 8x8 quadrant (w&1, w>>1), one
-// pixel per lane.  The tile's depth-ordered Gaussians are staged through LDS in batches of 256;
-// a wavefront stops evaluating as soon as all of its 64 pixels have terminated.
+// One workgroup (4 wavefronts) per 16x16 tile, one pixel per lane.  Wavefront w owns the 8x8
+// quadrant (w&1, w>>1); each of its four rows of 16 lanes (the unit of the DPP row operations) owns
+// one 4x4 sub-tile of that quadrant.  The tile's depth-ordered Gaussians are staged through LDS in
+// batches of 256.  While staging, every Gaussian's support {alpha >= alpha_min} is bounded by an
+// axis-aligned box (conservatively, see stage_batch) and each of the 16 sub-tiles gets its own
+// order-preserving list of the staged Gaussians whose box meets it.  In the inner loops the four
+// rows of a wavefront walk their own lists side by side, so one wavefront iteration evaluates
+// four different Gaussians on 16 pixels each.  A wavefront stops as soon as all of its 64 pixels
+// have terminated.
 //
 // alpha, T and the blend weights follow a fixed fp32 operation order (fused multiply-adds only
 // where written as __builtin_fmaf; the file is compiled with -ffp-contract=off) so that the
-// integer outputs they decide (n_contrib, counts) can be reproduced bit for bit on a CPU.
+// integer outputs they decide (n_contrib, counts) can be reproduced bit for bit on a CPU.  The
+// box test only ever drops (Gaussian, pixel) pairs that this arithmetic would reject as well.
 #include "common.hpp"
 
 namespace fs {
@@ -46,29 +53,132 @@ __device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int tx = tile % cam.tiles_x, ty = tile / cam.tiles_x;
+    const int row = lane >> 4;  // 4x4 sub-tile (row & 1, row >> 1) of the quadrant
     Pixel p;
-    p.x = tx * TILE + (wave & 1) * 8 + (lane & 7);
-    p.y = ty * TILE + (wave >> 1) * 8 + (lane >> 3);
+    p.x = tx * TILE + (wave & 1) * 8 + (row & 1) * 4 + (lane & 3);
+    p.y = ty * TILE + (wave >> 1) * 8 + (row >> 1) * 4 + ((lane >> 2) & 3);
     p.inside = p.x < cam.width && p.y < cam.height;
     p.px = (float)p.x + 0.5f;
     p.py = (float)p.y + 0.5f;
     return p;
 }
 
-// alpha of one Gaussian at one pixel; false if it takes no part (exponent > 0, alpha < alpha_min).
-// xy = mu_2D, co = (a, 2b, c, sigma).
-__device__ __forceinline__ bool alpha_at(const Pixel& p, float2 xy, float4 co, const CfgDev& cfg, float& alpha,
-                                         float& dx, float& dy, float& G)
+// LDS image of one batch of a tile's list, shared by the three kernels.
+struct Stage {
+    float2 xy[BATCH];          // mu_2D
+    float4 co[BATCH];          // (a, 2b, c, sigma)
+    uint64_t bits[16][4];      // per sub-tile, per staging wavefront: which of its 64 slots the sub-tile visits
+    uint8_t list[16][BATCH];   // per sub-tile (index wave*4 + row): batch slots to visit, in list order
+};
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_shr_add(uint32_t v)
 {
-    dx = p.px - xy.x;
-    dy = p.py - xy.y;
-    const float u = __builtin_fmaf(co.y, dy, co.x * dx);
-    const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
-    const float power = -0.5f * q;
-    if (power > 0.0f || power < cfg.power_min) return false;
-    G = exp_c(power);
-    alpha = fminf(cfg.alpha_max, co.w * G);
-    return alpha >= cfg.alpha_min;
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// Loads entries [first, first+m) of the tile's list into `s` (slot t <- entry first+t) and builds
+// the 16 per-sub-tile slot lists.  Returns the length of the list of the calling lane's sub-tile.
+// Contains two workgroup barriers; every thread of the workgroup must call it.
+//
+// Box of a Gaussian: it can only be blended where sigma*G >= alpha_min, i.e. where
+// q <= qg = 2 ln(sigma/alpha_min), and the kernels also reject q > -2*power_min.  With
+// Sigma_2D = conic^-1, the set {q <= Q} lies within |dx| <= sqrt(Q Sigma_xx), |dy| <= sqrt(Q Sigma_yy).
+// Q is taken as min(qg, -2 power_min) + 0.1 + e, where e bounds the rounding error of the fp32 q
+// for any pixel of a tile the Gaussian is paired with (|dx|,|dy| <= 3 sqrt(lambda_max) + 17), and the
+// half-widths get a further 0.2 % + 0.01 px (the box itself is computed with the fast reciprocal,
+// square root and logarithm): outside the box the pinned arithmetic yields alpha < 0.96 alpha_min
+// (or power < power_min), so dropping the pair cannot change any result.
+//
+// Lists: each staging wavefront ballots, per sub-tile, which of its 64 slots are kept (phase 1);
+// then the 16 lanes that own a sub-tile in the render loops expand its 256-bit mask into slot
+// numbers, 16 slots per lane, with a prefix sum over the row (phase 2).
+template <bool WITH_RGB, bool WITH_ID>
+__device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_id, const CamDev& cam,
+                                           const CfgDev& cfg, int tile, const uint32_t* __restrict__ gauss_sorted,
+                                           const float2* __restrict__ mean2d,
+                                           const float4* __restrict__ conic_opacity, const float* __restrict__ rgb,
+                                           uint32_t first, int m)
+{
+    const int t = threadIdx.x;
+    const int swave = t >> 6, lane = t & 63;
+    uint32_t sub_mask = 0;  // bit (wave*4 + row) of every sub-tile the box meets
+    if (t < m) {
+        const uint32_t g = gauss_sorted[first + t];
+        const float4 co = conic_opacity[g];
+        const float2 xy = mean2d[g];
+        s.xy[t] = xy;
+        s.co[t] = make_float4(co.x, co.y + co.y, co.z, co.w);
+        if (WITH_RGB) s_rgb[t] = make_float4(rgb[3 * g + 0], rgb[3 * g + 1], rgb[3 * g + 2], 0.f);
+        if (WITH_ID) s_id[t] = g;
+        const float ratio = co.w * __builtin_amdgcn_rcpf(cfg.alpha_min);
+        if (ratio >= 1.0f) {
+            const float det = co.x * co.z - co.y * co.y;
+            const float inv = __builtin_amdgcn_rcpf(det);
+            const float sxx = co.z * inv, syy = co.x * inv;
+            const float D = 3.0f * __builtin_amdgcn_sqrtf(sxx + syy) + 17.0f;
+            const float e = 1e-6f * (fabsf(co.x) + 2.0f * fabsf(co.y) + fabsf(co.z)) * D * D;
+            const float Q = fminf(2.0f * __logf(ratio), -2.0f * cfg.power_min) + 0.1f + e;
+            const float hx = __builtin_amdgcn_sqrtf(Q * sxx) * 1.002f + 0.01f;
+            const float hy = __builtin_amdgcn_sqrtf(Q * syy) * 1.002f + 0.01f;
+            // sub-tile column k has its centre at +4k+2 from the tile origin; pixel centres reach 1.5 from it
+            const float ox = xy.x - (float)((tile % cam.tiles_x) * TILE), oy = xy.y - (float)((tile / cam.tiles_x) * TILE);
+            uint32_t colx = 0, rowy = 0;
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                colx |= (fabsf(ox - (float)(4 * k + 2)) <= hx + 1.5f) ? 1u << k : 0u;
+                rowy |= (fabsf(oy - (float)(4 * k + 2)) <= hy + 1.5f) ? 1u << k : 0u;
+            }
+            // NaN half-widths (degenerate conic) keep the Gaussian everywhere: the exact test decides
+            if (!(hx == hx) || !(hy == hy)) { colx = 15u; rowy = 15u; }
+            // sub-tile st = wave*4 + row sits at column (wave&1)*2 + (row&1), line (wave>>1)*2 + (row>>1)
+            const uint32_t cpair0 = colx & 3u, cpair1 = colx >> 2;          // columns of the left / right quadrants
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                const uint32_t cp = (w & 1) ? cpair1 : cpair0;
+                const uint32_t rp = (rowy >> ((w >> 1) * 2)) & 3u;
+                // rows of the quadrant: bit0 = (sx0,sy0), bit1 = (sx1,sy0), bit2 = (sx0,sy1), bit3 = (sx1,sy1)
+                const uint32_t q4 = ((rp & 1u) ? cp : 0u) | ((rp & 2u) ? cp << 2 : 0u);
+                sub_mask |= q4 << (4 * w);
+            }
+        }
+    }
+    // phase 1: one 64-bit keep mask per (sub-tile, staging wavefront)
+    uint64_t keep = 0;
+#pragma unroll
+    for (int st = 0; st < 16; st++) {
+        const uint64_t bal = __ballot((sub_mask >> st) & 1u);
+        keep = lane == st ? bal : keep;
+    }
+    if (lane < 16) s.bits[lane][swave] = keep;
+    __syncthreads();
+    // phase 2: lane i of the row that owns sub-tile st expands slots [16 i, 16 i + 16)
+    const int st = swave * 4 + (lane >> 4);
+    const int i = lane & 15;
+    uint32_t b16 = (uint32_t)(s.bits[st][i >> 2] >> ((i & 3) * 16)) & 0xffffu;
+    const uint32_t cnt = __popc(b16);
+    uint32_t inc = cnt;
+    inc = dpp_shr_add<0x111>(inc);  // row_shr:1
+    inc = dpp_shr_add<0x112>(inc);  // row_shr:2
+    inc = dpp_shr_add<0x114>(inc);  // row_shr:4
+    inc = dpp_shr_add<0x118>(inc);  // row_shr:8
+    uint32_t pos = inc - cnt;
+    while (b16) {
+        const uint32_t b = __builtin_ctz(b16);
+        s.list[st][pos++] = (uint8_t)(16 * i + b);
+        b16 &= b16 - 1u;
+    }
+    const int mine = __shfl((int)inc, (lane & 48) | 15, 64);
+    __syncthreads();
+    return mine;
+}
+
+// Longest of the four sub-tile lists of the calling wavefront (`mine` is uniform within a row).
+__device__ __forceinline__ int wave_max_of_rows(int mine)
+{
+    const int a = __builtin_amdgcn_readlane(mine, 0), b = __builtin_amdgcn_readlane(mine, 16);
+    const int c = __builtin_amdgcn_readlane(mine, 32), d = __builtin_amdgcn_readlane(mine, 48);
+    return max(max(a, b), max(c, d));
 }
 
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
@@ -78,11 +188,11 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                                                     const float* __restrict__ rgb, float* __restrict__ image,
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib)
 {
-    __shared__ float2 s_xy[BATCH];
-    __shared__ float4 s_co[BATCH];
-    __shared__ float s_rgb[BATCH * 3];
+    __shared__ Stage s;
+    __shared__ float4 s_rgb[BATCH];
 
     const int tile = blockIdx.x;
+    const int sub = (threadIdx.x >> 6) * 4 + ((threadIdx.x & 63) >> 4);  // this lane's sub-tile list
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
     const int total = (int)(range.y - range.x);
@@ -91,33 +201,45 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     float T = 1.0f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
     uint32_t last = 0;
 
+    // Slots a batch does not fill must still hold finite numbers: lanes past the end of their list
+    // read a stale slot and multiply its colour by a zero weight.
+    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
+    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+
     for (int start = 0; start < total; start += BATCH) {
         if (__syncthreads_count(!done) == 0) break;
         const int m = min(BATCH, total - start);
-        if ((int)threadIdx.x < m) {
-            const uint32_t g = gauss_sorted[range.x + start + threadIdx.x];
-            float4 co = conic_opacity[g];
-            co.y = co.y + co.y;
-            s_xy[threadIdx.x] = mean2d[g];
-            s_co[threadIdx.x] = co;
-            s_rgb[3 * threadIdx.x + 0] = rgb[3 * g + 0];
-            s_rgb[3 * threadIdx.x + 1] = rgb[3 * g + 1];
-            s_rgb[3 * threadIdx.x + 2] = rgb[3 * g + 2];
-        }
-        __syncthreads();
-        for (int j = 0; j < m; j++) {
+        const int mine = stage_batch<true, false>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, mean2d,
+                                                  conic_opacity, rgb, range.x + start, m);
+        const int longest = wave_max_of_rows(mine);
+        // Straight-line body with selects: lanes past their list's end (or finished) read a stale
+        // slot and discard the result; only two wave-uniform branches per iteration.
+        for (int k = 0; k < longest; k++) {
             if (__ballot(!done) == 0) break;
-            if (done) continue;
-            float alpha, dx, dy, G;
-            if (!alpha_at(p, s_xy[j], s_co[j], cfg, alpha, dx, dy, G)) continue;
+            const int j = s.list[sub][k];
+            const float2 xy = s.xy[j];
+            const float4 co = s.co[j];
+            const float dx = p.px - xy.x, dy = p.py - xy.y;
+            const float u = __builtin_fmaf(co.y, dy, co.x * dx);
+            const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+            const float power = -0.5f * q;
+            bool ok = (k < mine) & !done & !(power > 0.0f) & !(power < cfg.power_min);
+            if (__ballot(ok) == 0) continue;
+            const float4 col = s_rgb[j];
+            const float G = exp_c(power);
+            const float alpha = fminf(cfg.alpha_max, co.w * G);
+            ok = ok & (alpha >= cfg.alpha_min);
             const float Tn = T * (1.0f - alpha);
-            if (Tn < cfg.T_min) { done = true; continue; }
-            const float w = alpha * T;
-            C0 = __builtin_fmaf(s_rgb[3 * j + 0], w, C0);
-            C1 = __builtin_fmaf(s_rgb[3 * j + 1], w, C1);
-            C2 = __builtin_fmaf(s_rgb[3 * j + 2], w, C2);
-            T = Tn;
-            last = (uint32_t)(start + j + 1);
+            const bool stop = ok & (Tn < cfg.T_min);
+            const bool blend = ok & !stop;
+            done = done | stop;
+            const float w = blend ? alpha * T : 0.0f;  // a zero weight leaves C unchanged bit for bit
+            C0 = __builtin_fmaf(col.x, w, C0);
+            C1 = __builtin_fmaf(col.y, w, C1);
+            C2 = __builtin_fmaf(col.z, w, C2);
+            T = blend ? Tn : T;
+            last = blend ? (uint32_t)(start + j + 1) : last;
         }
     }
     if (p.inside) {
@@ -131,50 +253,85 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     }
 }
 
-// Sum over the 64 lanes of a wavefront; the total is returned in every lane of the last row
-// (callers read lane 63).  Cross-lane moves use DPP: quad swaps, half-row and row mirrors, then
-// the row broadcasts of the gfx9 family.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_step(float v)
+// ---- row reduction of 9 values -------------------------------------------------------------
+// A row of 16 lanes (one 4x4 sub-tile) sums 9 per-pixel values.  Instead of 9 separate butterflies
+// the first three steps halve the number of live registers: at the step for lane bit b, a lane
+// keeps the value whose index has that bit equal to its own and hands the other one to its partner.
+// After the four steps lane i of the row holds the row total of value (i & 7); value 8 is summed
+// the plain way and ends up in every lane.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v)
 {
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false);
-    return v + __int_as_float(moved);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
 
-__device__ __forceinline__ float wave_sum_to_lane63(float v)
+// lanes with `bit` clear end up with sum(a) over the exchanged pair, lanes with it set with sum(b)
+template <int CTRL>
+__device__ __forceinline__ float fold(bool bit, float a, float b)
 {
-    v = dpp_step<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
-    v = dpp_step<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
-    v = dpp_step<0x141, 0xF>(v);  // row_half_mirror
-    v = dpp_step<0x140, 0xF>(v);  // row_mirror: every lane of a row of 16 holds the row sum
-    v = dpp_step<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
-    v = dpp_step<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
-    return v;
+    const float keep = bit ? b : a, give = bit ? a : b;
+    return keep + dpp_get<CTRL>(give);
 }
 
-// Backward of the compositing.  Walks each tile's list back to front from the furthest blended
-// Gaussian; per Gaussian, the 9 partial gradients of the 64 pixels of a wavefront are summed
-// across lanes, combined across the 4 wavefronts in LDS, and flushed with one atomic per value.
+__device__ __forceinline__ void row_reduce9(const float v[9], int lane, float& packed, float& ninth)
+{
+    constexpr int XOR1 = 0xB1, XOR2 = 0x4E, ROR4 = 0x124, ROR8 = 0x128;  // quad_perm swaps, row rotations
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+    const float r01 = fold<XOR1>(b0, v[0], v[1]);
+    const float r23 = fold<XOR1>(b0, v[2], v[3]);
+    const float r45 = fold<XOR1>(b0, v[4], v[5]);
+    const float r67 = fold<XOR1>(b0, v[6], v[7]);
+    float r8 = v[8] + dpp_get<XOR1>(v[8]);
+    const float s03 = fold<XOR2>(b1, r01, r23);
+    const float s47 = fold<XOR2>(b1, r45, r67);
+    r8 = r8 + dpp_get<XOR2>(r8);
+    // lane i+4 has the opposite bit 2, so a rotation by 4 pairs the lanes like the earlier swaps did
+    float u = fold<ROR4>(b2, s03, s47);
+    r8 = r8 + dpp_get<ROR4>(r8);
+    u = u + dpp_get<ROR8>(u);
+    r8 = r8 + dpp_get<ROR8>(r8);
+    packed = u;
+    ninth = r8;
+}
+
+// Backward of the compositing.  Walks each sub-tile's list back to front from the furthest blended
+// Gaussian; per Gaussian, 9 partial sums over the 16 pixels of a sub-tile are formed across the
+// row's lanes and combined across the sub-tiles in LDS.  The 9 sums: dL/drgb (3), dL/dsigma, and with
+// g = dL/dq the moments sum g dx^2, g dx dy, g dy^2, g dx, g dy, from which dL/dconic and dL/dmu_2D
+// follow at the flush (dq/dmu is linear in d = p - mu).
+//
+// Every Gaussian-tile pair owns one record of PAIR_REC floats in `pair_grad`, at the position the
+// pair had when it was emitted (pair_offsets[g] + its place in g's tile rectangle): the flush is a
+// plain store (rgb 3, sigma, conic 3, mu_2D 2), every pair of the tile is written exactly once (zeros
+// for the ones nothing blended), and the per-Gaussian sum over its contiguous records is left to the
+// projection's backward kernel.  No global atomics, and the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void k_render_bwd(
     CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ gauss_sorted,
     const float2* __restrict__ mean2d, const float4* __restrict__ conic_opacity, const float* __restrict__ rgb,
     const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib, const float* __restrict__ dL_dimage,
-    float* __restrict__ d_mean2d, float* __restrict__ d_conic, float* __restrict__ d_opac, float* __restrict__ d_rgb)
+    const ushort4* __restrict__ rect, const uint32_t* __restrict__ offsets, float4* __restrict__ pair_grad)
 {
-    __shared__ float2 s_xy[BATCH];
-    __shared__ float4 s_co[BATCH];
-    __shared__ float s_rgb[BATCH * 3];
+    __shared__ Stage s;
+    __shared__ float4 s_rgb[BATCH];
     __shared__ uint32_t s_id[BATCH];
     __shared__ float s_acc[BATCH][9];
-    __shared__ uint32_t s_touched[BATCH];
     __shared__ int s_max;
 
     const int tile = blockIdx.x;
+    const uint32_t tile_x = tile % cam.tiles_x, tile_y = tile / cam.tiles_x;
+    // record of the pair (g, this tile): where the pair was emitted before the sort
+    auto record_of = [&](uint32_t g) -> float4* {
+        const ushort4 r = rect[g];
+        const uint32_t idx = offsets[g] + (tile_y - r.y) * (uint32_t)(r.z - r.x) + (tile_x - r.x);
+        return pair_grad + (size_t)idx * (PAIR_REC / 4);
+    };
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
     const size_t hw = (size_t)cam.width * cam.height;
     const size_t pix = (size_t)p.y * cam.width + p.x;
     const int lane = threadIdx.x & 63;
+    const int sub = (threadIdx.x >> 6) * 4 + (lane >> 4);
 
     const int last = p.inside ? (int)n_contrib[pix] : 0;
     float T = p.inside ? final_T[pix] : 0.f;
@@ -186,6 +343,11 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     }
     float B0 = cfg.bg[0], B1 = cfg.bg[1], B2 = cfg.bg[2];
 
+    // unfilled slots must hold finite numbers (lanes past their list's end compute with them and
+    // contribute exact zeros)
+    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
+    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     atomicMax(&s_max, last);
@@ -195,84 +357,85 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     // batches from the back: batch b covers positions [b*BATCH, min(total,(b+1)*BATCH))
     for (int start = ((total - 1) / BATCH) * BATCH; start >= 0 && total > 0; start -= BATCH) {
         const int m = min(BATCH, total - start);
-        __syncthreads();
-        if ((int)threadIdx.x < m) {
-            const uint32_t g = gauss_sorted[range.x + start + threadIdx.x];
-            float4 co = conic_opacity[g];
-            co.y = co.y + co.y;
-            s_id[threadIdx.x] = g;
-            s_xy[threadIdx.x] = mean2d[g];
-            s_co[threadIdx.x] = co;
-            s_rgb[3 * threadIdx.x + 0] = rgb[3 * g + 0];
-            s_rgb[3 * threadIdx.x + 1] = rgb[3 * g + 1];
-            s_rgb[3 * threadIdx.x + 2] = rgb[3 * g + 2];
-        }
+        __syncthreads();  // the previous batch's flush has read s_acc / s_id
 #pragma unroll
         for (int k = 0; k < 9; k++) s_acc[threadIdx.x][k] = 0.f;
-        s_touched[threadIdx.x] = 0;
-        __syncthreads();
-
-        for (int j = m - 1; j >= 0; j--) {
-            const float2 xy = s_xy[j];
-            const float4 co = s_co[j];
-            float alpha = 0.f, dx = 0.f, dy = 0.f, G = 0.f;
-            const bool act = (start + j < last) && alpha_at(p, xy, co, cfg, alpha, dx, dy, G);
+        const int mine = stage_batch<true, true>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, mean2d, conic_opacity,
+                                                 rgb, range.x + start, m);
+        const int longest = wave_max_of_rows(mine);
+        for (int it = 0; it < longest; it++) {
+            const int k = mine - 1 - it;      // every row walks its own list from the back
+            const int j = s.list[sub][k & (BATCH - 1)];
+            const float2 xy = s.xy[j];
+            const float4 co = s.co[j];
+            const float dx = p.px - xy.x, dy = p.py - xy.y;
+            const float u = __builtin_fmaf(co.y, dy, co.x * dx);
+            const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+            const float power = -0.5f * q;
+            bool act = (k >= 0) & (start + j < last) & !(power > 0.0f) & !(power < cfg.power_min);
             if (__ballot(act) == 0) continue;
+            float G = exp_c(power);
+            const float sG = co.w * G;
+            float alpha = fminf(cfg.alpha_max, sG);
+            act = act & (alpha >= cfg.alpha_min);
+            const uint64_t act_mask = __ballot(act);
+            if (act_mask == 0) continue;
+            // lanes that do not blend this Gaussian run the same arithmetic with alpha = G = 0:
+            // every one of their 9 contributions is then an exact zero
+            alpha = act ? alpha : 0.f;
+            G = act ? G : 0.f;
+            const float4 col = s_rgb[j];
+            const float Tfront = T * __builtin_amdgcn_rcpf(1.0f - alpha);  // transmittance in front of this Gaussian
+            T = act ? Tfront : T;
+            const float w = alpha * T;
             float v[9];
-#pragma unroll
-            for (int k = 0; k < 9; k++) v[k] = 0.f;
-            if (act) {
-                const float c0 = s_rgb[3 * j + 0], c1 = s_rgb[3 * j + 1], c2 = s_rgb[3 * j + 2];
-                const float om = 1.0f - alpha;
-                T = T * __builtin_amdgcn_rcpf(om);  // transmittance in front of this Gaussian
-                const float w = alpha * T;
-                v[0] = w * dC0;
-                v[1] = w * dC1;
-                v[2] = w * dC2;
-                const float e0 = c0 - B0, e1 = c1 - B1, e2 = c2 - B2;
-                float dL_dalpha = T * (e0 * dC0 + e1 * dC1 + e2 * dC2);
-                B0 = B0 + alpha * e0;
-                B1 = B1 + alpha * e1;
-                B2 = B2 + alpha * e2;
-                const float sG = co.w * G;
-                if (sG > cfg.alpha_max) dL_dalpha = 0.f;  // capped alpha is a constant
-                v[3] = G * dL_dalpha;                      // d/d sigma
-                const float gq = -0.5f * sG * dL_dalpha;   // d/d q,  q = a dx^2 + 2 b dx dy + c dy^2
-                v[4] = gq * dx * dx;
-                v[5] = gq * 2.0f * dx * dy;
-                v[6] = gq * dy * dy;
-                // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy);  co.y already holds 2b
-                v[7] = -gq * (2.0f * co.x * dx + co.y * dy);
-                v[8] = -gq * (co.y * dx + 2.0f * co.z * dy);
-            }
-#pragma unroll
-            for (int k = 0; k < 9; k++) v[k] = wave_sum_to_lane63(v[k]);
-            if (lane == 63) {
-#pragma unroll
-                for (int k = 0; k < 9; k++) atomicAdd(&s_acc[j][k], v[k]);
-                s_touched[j] = 1;
-            }
+            v[0] = w * dC0;
+            v[1] = w * dC1;
+            v[2] = w * dC2;
+            const float e0 = col.x - B0, e1 = col.y - B1, e2 = col.z - B2;
+            float dL_dalpha = T * __builtin_fmaf(e2, dC2, __builtin_fmaf(e1, dC1, e0 * dC0));
+            B0 = __builtin_fmaf(alpha, e0, B0);
+            B1 = __builtin_fmaf(alpha, e1, B1);
+            B2 = __builtin_fmaf(alpha, e2, B2);
+            dL_dalpha = sG > cfg.alpha_max ? 0.f : dL_dalpha;  // capped alpha is a constant
+            v[3] = G * dL_dalpha;                              // d/d sigma
+            const float gq = -0.5f * (co.w * G) * dL_dalpha;   // d/d q
+            const float gx = gq * dx, gy = gq * dy;
+            v[4] = gx * dx;
+            v[5] = gx * dy;
+            v[6] = gy * dy;
+            v[7] = gx;
+            v[8] = gy;
+            float packed, ninth;
+            row_reduce9(v, lane, packed, ninth);
+            // lanes 0..7 of a row hold the totals of values 0..7, lane 8 adds the ninth
+            const int li = lane & 15;
+            if (li < 9 && ((act_mask >> (lane & 48)) & 0xffffull) != 0)
+                atomicAdd(&s_acc[j][li], li < 8 ? packed : ninth);
         }
         __syncthreads();
-        if ((int)threadIdx.x < m && s_touched[threadIdx.x]) {
-            const uint32_t g = s_id[threadIdx.x];
+        if ((int)threadIdx.x < m) {
             const float* a = s_acc[threadIdx.x];
-            atomicAdd(&d_rgb[3 * g + 0], a[0]);
-            atomicAdd(&d_rgb[3 * g + 1], a[1]);
-            atomicAdd(&d_rgb[3 * g + 2], a[2]);
-            atomicAdd(&d_opac[g], a[3]);
-            atomicAdd(&d_conic[3 * g + 0], a[4]);
-            atomicAdd(&d_conic[3 * g + 1], a[5]);
-            atomicAdd(&d_conic[3 * g + 2], a[6]);
-            atomicAdd(&d_mean2d[2 * g + 0], a[7]);
-            atomicAdd(&d_mean2d[2 * g + 1], a[8]);
+            const float4 co = s.co[threadIdx.x];  // co.y holds 2b
+            float4* rec = record_of(s_id[threadIdx.x]);
+            rec[0] = make_float4(a[0], a[1], a[2], a[3]);
+            // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
+            rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
+            rec[2].x = -(co.y * a[7] + 2.0f * co.z * a[8]);
         }
+    }
+    // pairs behind the furthest blended Gaussian of the tile received nothing
+    for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
+        float4* rec = record_of(gauss_sorted[pos]);
+        rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
+        rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        rec[2].x = 0.f;
     }
 }
 
 // Count pass: re-walks the forward loop for the mask pixels only (other pixels cannot add to a
 // count) up to each pixel's n_contrib, and counts per Gaussian the pixels where it is blended
-// (and, in weight mode, alpha*T > alpha_min).  A ballot + population count gives the wavefront's
+// (and, in weight mode, alpha*T > alpha_min).  A ballot + population count gives each sub-tile's
 // count without any cross-lane arithmetic.
 __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                const uint32_t* __restrict__ gauss_sorted,
@@ -281,8 +444,7 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
                                                const uint32_t* __restrict__ n_contrib,
                                                const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
 {
-    __shared__ float2 s_xy[BATCH];
-    __shared__ float4 s_co[BATCH];
+    __shared__ Stage s;
     __shared__ uint32_t s_id[BATCH];
     __shared__ int s_cnt[BATCH];
     __shared__ int s_max;
@@ -292,8 +454,11 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     const uint2 range = ranges[tile];
     const size_t pix = (size_t)p.y * cam.width + p.x;
     const int lane = threadIdx.x & 63;
+    const int sub = (threadIdx.x >> 6) * 4 + (lane >> 4);
     int last = 0;
     if (p.inside && mask[pix]) last = (int)n_contrib[pix];
+    s.xy[threadIdx.x] = make_float2(0.f, 0.f);  // unfilled slots must hold finite numbers
+    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     atomicMax(&s_max, last);
@@ -303,28 +468,30 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 
     for (int start = 0; start < total; start += BATCH) {
         const int m = min(BATCH, total - start);
-        __syncthreads();
-        if ((int)threadIdx.x < m) {
-            const uint32_t g = gauss_sorted[range.x + start + threadIdx.x];
-            float4 co = conic_opacity[g];
-            co.y = co.y + co.y;
-            s_id[threadIdx.x] = g;
-            s_xy[threadIdx.x] = mean2d[g];
-            s_co[threadIdx.x] = co;
-        }
+        __syncthreads();  // the previous batch's flush has read s_cnt / s_id
         s_cnt[threadIdx.x] = 0;
-        __syncthreads();
-        for (int j = 0; j < m; j++) {
-            float alpha = 0.f, dx, dy, G;
-            const bool act = (start + j < last) && alpha_at(p, s_xy[j], s_co[j], cfg, alpha, dx, dy, G);
-            bool hit = false;
-            if (act) {
+        const int mine = stage_batch<false, true>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, mean2d,
+                                                  conic_opacity, nullptr, range.x + start, m);
+        if (__ballot(start < last) != 0) {
+            const int longest = wave_max_of_rows(mine);
+            for (int k = 0; k < longest; k++) {
+                const int j = s.list[sub][k];
+                const float2 xy = s.xy[j];
+                const float4 co = s.co[j];
+                const float dx = p.px - xy.x, dy = p.py - xy.y;
+                const float u = __builtin_fmaf(co.y, dy, co.x * dx);
+                const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+                const float power = -0.5f * q;
+                bool act = (k < mine) & (start + j < last) & !(power > 0.0f) & !(power < cfg.power_min);
+                if (__ballot(act) == 0) continue;
+                const float alpha = fminf(cfg.alpha_max, co.w * exp_c(power));
+                act = act & (alpha >= cfg.alpha_min);
                 const float w = alpha * T;
-                hit = cfg.score_mode == FS_SCORE_ALPHA || w > cfg.alpha_min;
-                T = T * (1.0f - alpha);
+                const bool hit = act & (cfg.score_mode == FS_SCORE_ALPHA || w > cfg.alpha_min);
+                T = act ? T * (1.0f - alpha) : T;
+                const uint32_t b = (uint32_t)(__ballot(hit) >> (lane & 48)) & 0xffffu;  // this row's pixels
+                if (b != 0 && (lane & 15) == 0) atomicAdd(&s_cnt[j], (int)__popc(b));
             }
-            const uint64_t b = __ballot(hit);
-            if (b != 0 && lane == 0) atomicAdd(&s_cnt[j], (int)__popcll(b));
         }
         __syncthreads();
         if ((int)threadIdx.x < m && s_cnt[threadIdx.x] != 0) atomicAdd(&counts[s_id[threadIdx.x]], s_cnt[threadIdx.x]);
@@ -348,14 +515,15 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
                              const float* rgb, const float* final_T, const uint32_t* n_contrib,
-                             const float* dL_dimage, float* dmean2d, float* dconic, float* dopac, float* drgb)
+                             const float* dL_dimage, const uint16_t* rect, const uint32_t* offsets,
+                             float* pair_grad)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_render_bwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
                        gauss_sorted, reinterpret_cast<const float2*>(mean2d),
-                       reinterpret_cast<const float4*>(conic_opacity), rgb, final_T, n_contrib, dL_dimage, dmean2d,
-                       dconic, dopac, drgb);
+                       reinterpret_cast<const float4*>(conic_opacity), rgb, final_T, n_contrib, dL_dimage,
+                       reinterpret_cast<const ushort4*>(rect), offsets, reinterpret_cast<float4*>(pair_grad));
     return hipGetLastError();
 }
 
