@@ -10,7 +10,7 @@ namespace fs {
 
 namespace {
 
-constexpr int RED_BLOCKS = 256;   // partial sums per reduction
+constexpr int RED_BLOCKS = 1024;  // partial sums per reduction (a multiple of RED_THREADS)
 constexpr int RED_THREADS = 256;
 
 __device__ __forceinline__ double shfl_down_f64(double v, int d)
@@ -52,11 +52,14 @@ __device__ __forceinline__ double red_identity()
     return -1.0e300;
 }
 
-// final reduction of RED_BLOCKS partials by one workgroup (thread i takes partial i)
+// final reduction of RED_BLOCKS partials by one workgroup (thread i takes partials i, i+256, ... in order)
 template <RedOp OP>
 __device__ __forceinline__ double final_reduce(const double* partial, double* smem)
 {
-    return block_reduce<OP>(partial[threadIdx.x], smem);
+    double v = partial[threadIdx.x];
+#pragma unroll
+    for (int k = 1; k < RED_BLOCKS / RED_THREADS; k++) v = red_combine<OP>(v, partial[k * RED_THREADS + threadIdx.x]);
+    return block_reduce<OP>(v, smem);
 }
 
 __global__ __launch_bounds__(RED_THREADS) void k_l1_grad(const float* __restrict__ image,

@@ -88,7 +88,8 @@ __device__ __forceinline__ uint32_t dpp_shr_add(uint32_t v)
 // for any pixel of a tile the Gaussian is paired with (|dx|,|dy| <= 3 sqrt(lambda_max) + 17), and the
 // half-widths get a further 0.2 % + 0.01 px (the box itself is computed with the fast reciprocal,
 // square root and logarithm): outside the box the pinned arithmetic yields alpha < 0.96 alpha_min
-// (or power < power_min), so dropping the pair cannot change any result.
+// (or power < power_min), so dropping the pair cannot change any result.  The same argument gives
+// bounds on dx + dy and dx - dy (an octagon around the support).
 //
 // Lists: each staging wavefront ballots, per sub-tile, which of its 64 slots are kept (phase 1);
 // then the 16 lanes that own a sub-tile in the render loops expand its 256-bit mask into slot
@@ -131,15 +132,22 @@ __device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_
             }
             // NaN half-widths (degenerate conic) keep the Gaussian everywhere: the exact test decides
             if (!(hx == hx) || !(hy == hy)) { colx = 15u; rowy = 15u; }
+            // The same set also lies between the tangent lines at +-45 degrees: |dx + dy| <= sqrt(Q (Sxx + Syy + 2 Sxy)),
+            // |dx - dy| <= sqrt(Q (Sxx + Syy - 2 Sxy)) with Sxy = -b/det; a sub-tile's pixel centres reach 3 from
+            // its centre in these sums.  This trims the corners of the box for slanted, elongated Gaussians.
+            const float sxy = -co.y * inv;
+            const float hu = __builtin_amdgcn_sqrtf(fmaxf(Q * (sxx + syy + 2.0f * sxy), 0.f)) * 1.002f + 0.02f;
+            const float hv = __builtin_amdgcn_sqrtf(fmaxf(Q * (sxx + syy - 2.0f * sxy), 0.f)) * 1.002f + 0.02f;
+            const float su = ox + oy, sv = ox - oy;
+            const bool nan8 = !(hu == hu) || !(hv == hv);
             // sub-tile st = wave*4 + row sits at column (wave&1)*2 + (row&1), line (wave>>1)*2 + (row>>1)
-            const uint32_t cpair0 = colx & 3u, cpair1 = colx >> 2;          // columns of the left / right quadrants
 #pragma unroll
-            for (int w = 0; w < 4; w++) {
-                const uint32_t cp = (w & 1) ? cpair1 : cpair0;
-                const uint32_t rp = (rowy >> ((w >> 1) * 2)) & 3u;
-                // rows of the quadrant: bit0 = (sx0,sy0), bit1 = (sx1,sy0), bit2 = (sx0,sy1), bit3 = (sx1,sy1)
-                const uint32_t q4 = ((rp & 1u) ? cp : 0u) | ((rp & 2u) ? cp << 2 : 0u);
-                sub_mask |= q4 << (4 * w);
+            for (int st = 0; st < 16; st++) {
+                const int kx = ((st >> 2) & 1) * 2 + (st & 1), ky = (st >> 3) * 2 + ((st >> 1) & 1);
+                const bool box = (colx >> kx & 1u) && (rowy >> ky & 1u);
+                const bool diag = (fabsf(su - (float)(4 * (kx + ky) + 4)) <= hu + 3.0f) &&
+                                  (fabsf(sv - (float)(4 * (kx - ky))) <= hv + 3.0f);
+                sub_mask |= (box && (diag || nan8)) ? 1u << st : 0u;
             }
         }
     }
