@@ -98,6 +98,9 @@ typedef struct {
     const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
     const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted at
                                      pair_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0), before the sort         */
+    const void *splats;           /* [n] 64-byte records (opaque): fs_bin_sort's copy of mean2d, conic_opacity, rgb,
+                                     rect and pair_offsets of every visible Gaussian, one cache line per gather.
+                                     The render, backward and score calls read the splats from here.             */
 } fs_bins;
 
 /* Output of fs_render_bwd, caller-owned, OVERWRITTEN (not accumulated). dconic and drgb may be
@@ -132,7 +135,8 @@ const char *fs_last_error(const fs_ctx *ctx);
 int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_projected *out);
 
 /* Steps a2-a5: exclusive scan of tiles_touched, one 64-bit key per (Gaussian, tile) pair, stable
- * LSD radix sort by key, per-tile ranges.  n = number of Gaussians in `proj`.
+ * LSD radix sort by key, per-tile ranges.  n = number of Gaussians in `proj`.  Also packs the
+ * projected splats into bins->splats; later calls that take `bins` must be given the same `proj`.
  * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (P >= 2^32). */
 int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int64_t n, fs_bins *out);
 

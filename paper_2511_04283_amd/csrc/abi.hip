@@ -31,6 +31,7 @@ struct fs_ctx {
     ScratchBuf hist;          // uint32 [256 * radix blocks]
     ScratchBuf ranges;        // uint32 [tiles, 2]
     ScratchBuf pair_grad;     // float  [P, PAIR_REC] per-pair partial gradients of the backward pass
+    ScratchBuf splats;        // float  [n, SPLAT_REC] packed projected splats (written by fs_bin_sort)
     ScratchBuf err_map;       // float  [H*W]
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: scan total
@@ -216,7 +217,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
-                         &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->err_map, &ctx->partial};
+                         &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->err_map, &ctx->partial};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -258,6 +259,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * 2 * sizeof(uint32_t), "tile ranges"));
     FS_TRY(ensure(ctx, ctx->offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "offsets"));
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
+    FS_TRY(ensure(ctx, ctx->splats, (size_t)(n > 0 ? n : 1) * SPLAT_REC * sizeof(float), "splats"));
 
     // a2: offsets and the pair count P (the one host read-back of the path)
     {
@@ -286,8 +288,8 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
         // a3
         {
             ProfScope prof(ctx, FS_K_EMIT);
-            FS_HIP(launch_emit_pairs(st, n, proj->rect, proj->depth, static_cast<const uint32_t*>(ctx->offsets.ptr),
-                                     cd.tiles_x, keys[0], vals[0]),
+            FS_HIP(launch_emit_pairs(st, n, *proj, static_cast<const uint32_t*>(ctx->offsets.ptr), cd.tiles_x, keys[0],
+                                     vals[0], static_cast<float*>(ctx->splats.ptr)),
                    "k_emit_pairs");
         }
         // a4: 32 depth bits + the tile bits are live
@@ -307,6 +309,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->gauss_sorted = vals[res];
     out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
     out->pair_offsets = static_cast<const uint32_t*>(ctx->offsets.ptr);
+    out->splats = ctx->splats.ptr;
     return FS_OK;
 }
 
@@ -317,13 +320,12 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     CamDev cd;
     if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !image || !final_T || !n_contrib)
         return fail(ctx, FS_EINVAL, "fs_render_fwd: bad arguments");
-    if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted))
+    if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_RENDER_FWD);
     FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
-                             proj ? proj->mean2d : nullptr, proj ? proj->conic_opacity : nullptr,
-                             proj ? proj->rgb : nullptr, image, final_T, n_contrib),
+                             static_cast<const float*>(bins->splats), image, final_T, n_contrib),
            "k_render_fwd");
     return FS_OK;
 }
@@ -360,7 +362,8 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
         return fail(ctx, FS_EINVAL, "fs_render_bwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
-    if (bins->num_pairs > 0 && !bins->pair_offsets) return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without pair_offsets");
+    if (bins->num_pairs > 0 && (!bins->pair_offsets || !bins->splats))
+        return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without pair_offsets / splats");
     FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_pairs ? bins->num_pairs : 1) * PAIR_REC * sizeof(float),
                   "pair gradients"));
     float* pair_grad = static_cast<float*>(ctx->pair_grad.ptr);
@@ -368,8 +371,8 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     // a8: every pair's record is written exactly once
     if (bins->num_pairs > 0) {
         ProfScope prof(ctx, FS_K_RENDER_BWD);
-        FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted, proj->mean2d, proj->conic_opacity,
-                                 proj->rgb, final_T, n_contrib, dL_dimage, proj->rect, bins->pair_offsets, pair_grad),
+        FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted,
+                                 static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad),
                "k_render_bwd");
     }
     // a9: per-Gaussian sum of its records, then the chain through the projection
@@ -409,11 +412,12 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !n_contrib || !mask)
         return fail(ctx, FS_EINVAL, "fs_score_accumulate: bad arguments");
     if (bins->num_pairs == 0) return FS_OK;
-    if (!proj_ok(proj) || !bins->gauss_sorted || !counts) return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
+    if (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats || !counts)
+        return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_SCORE);
-    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted, proj->mean2d,
-                        proj->conic_opacity, n_contrib, mask, counts),
+    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
+                        static_cast<const float*>(bins->splats), n_contrib, mask, counts),
            "k_score");
     return FS_OK;
 }

@@ -118,18 +118,33 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_apply(const uint32_t* in,
     }
 }
 
-// One key per tile of each Gaussian's rectangle, rows then columns, starting at offsets[i].
-__global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const uint16_t* __restrict__ rect,
+// One key per tile of each Gaussian's rectangle, rows then columns, starting at offsets[i].  The same
+// thread also packs the Gaussian's projected splat, rectangle and pair offset into one 64-byte record,
+// so that the render kernels gather one cache line per (Gaussian, tile) pair instead of five.
+__global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __restrict__ rect,
                                                     const float* __restrict__ depth,
+                                                    const float2* __restrict__ mean2d,
+                                                    const float4* __restrict__ conic_opacity,
+                                                    const float* __restrict__ rgb,
                                                     const uint32_t* __restrict__ offsets, int tiles_x,
-                                                    uint64_t* __restrict__ keys, uint32_t* __restrict__ vals)
+                                                    uint64_t* __restrict__ keys, uint32_t* __restrict__ vals,
+                                                    float4* __restrict__ splats)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const ushort4 r = *reinterpret_cast<const ushort4*>(rect + 4 * i);
+    const ushort4 r = rect[i];
     if (r.z <= r.x || r.w <= r.y) return;
     const uint32_t dbits = __float_as_uint(depth[i]);
     uint32_t o = offsets[i];
+    {
+        const float2 m = mean2d[i];
+        const float4 co = conic_opacity[i];
+        float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
+        rec[0] = make_float4(m.x, m.y, co.x, co.y);
+        rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
+        rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(o), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
+                             __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
+    }
     for (uint32_t ty = r.y; ty < r.w; ty++)
         for (uint32_t tx = r.x; tx < r.z; tx++) {
             keys[o] = ((uint64_t)(ty * (uint32_t)tiles_x + tx) << 32) | dbits;
@@ -270,12 +285,14 @@ hipError_t launch_exclusive_scan(hipStream_t st, const uint32_t* in, uint32_t* o
     return hipGetLastError();
 }
 
-hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const uint16_t* rect, const float* depth,
-                             const uint32_t* offsets, int tiles_x, uint64_t* keys, uint32_t* vals)
+hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const fs_projected& proj, const uint32_t* offsets,
+                             int tiles_x, uint64_t* keys, uint32_t* vals, float* splats)
 {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_emit_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, rect, depth, offsets,
-                       tiles_x, keys, vals);
+    hipLaunchKernelGGL(k_emit_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n,
+                       reinterpret_cast<const ushort4*>(proj.rect), proj.depth,
+                       reinterpret_cast<const float2*>(proj.mean2d), reinterpret_cast<const float4*>(proj.conic_opacity),
+                       proj.rgb, offsets, tiles_x, keys, vals, reinterpret_cast<float4*>(splats));
     return hipGetLastError();
 }
 

@@ -42,8 +42,10 @@ size_t scan_tmp_bytes(int64_t n);
 hipError_t launch_exclusive_scan(hipStream_t st, const uint32_t* in, uint32_t* out, int64_t n, void* tmp,
                                  uint64_t* total_dev);
 
-hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const uint16_t* rect, const float* depth,
-                             const uint32_t* offsets, int tiles_x, uint64_t* keys, uint32_t* vals);
+// Splat record (SPLAT_REC floats = 64 bytes, one per Gaussian): mx my a b | c sigma r g | b offset rect01 rect23 | unused
+constexpr int SPLAT_REC = 16;
+hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const fs_projected& proj, const uint32_t* offsets,
+                             int tiles_x, uint64_t* keys, uint32_t* vals, float* splats);
 
 constexpr int RADIX_BLOCK_KEYS = 2048;  // keys ranked by one workgroup per pass
 inline int64_t radix_num_blocks(int64_t P) { return (P + RADIX_BLOCK_KEYS - 1) / RADIX_BLOCK_KEYS; }
@@ -56,18 +58,16 @@ hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_so
                               uint32_t* ranges);
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                             const float* rgb, float* image, float* final_T, uint32_t* n_contrib);
+                             const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
+                             uint32_t* n_contrib);
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                             const float* rgb, const float* final_T, const uint32_t* n_contrib,
-                             const float* dL_dimage, const uint16_t* rect, const uint32_t* offsets,
-                             float* pair_grad);
+                             const uint32_t* gauss_sorted, const float* splats, const float* final_T,
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                        const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                        const uint32_t* n_contrib, const uint8_t* mask, int32_t* counts);
+                        const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
+                        const uint8_t* mask, int32_t* counts);
 
 hipError_t launch_l1_grad(hipStream_t st, const float* image, const float* target, int64_t count,
                           float* dL, double* partial /* >= l1_partials() doubles */, double* loss_out);

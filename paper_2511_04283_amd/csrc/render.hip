@@ -94,24 +94,32 @@ __device__ __forceinline__ uint32_t dpp_shr_add(uint32_t v)
 // Lists: each staging wavefront ballots, per sub-tile, which of its 64 slots are kept (phase 1);
 // then the 16 lanes that own a sub-tile in the render loops expand its 256-bit mask into slot
 // numbers, 16 slots per lane, with a prefix sum over the row (phase 2).
-template <bool WITH_RGB, bool WITH_ID>
+// ID_MODE: 0 = s_id unused, 1 = s_id[t] <- Gaussian index, 2 = s_id[t] <- index of the pair's
+// gradient record (where the pair was emitted before the sort: offset + place in the rectangle).
+template <bool WITH_RGB, int ID_MODE>
 __device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_id, const CamDev& cam,
                                            const CfgDev& cfg, int tile, const uint32_t* __restrict__ gauss_sorted,
-                                           const float2* __restrict__ mean2d,
-                                           const float4* __restrict__ conic_opacity, const float* __restrict__ rgb,
-                                           uint32_t first, int m)
+                                           const float4* __restrict__ splats, uint32_t first, int m)
 {
     const int t = threadIdx.x;
     const int swave = t >> 6, lane = t & 63;
     uint32_t sub_mask = 0;  // bit (wave*4 + row) of every sub-tile the box meets
     if (t < m) {
         const uint32_t g = gauss_sorted[first + t];
-        const float4 co = conic_opacity[g];
-        const float2 xy = mean2d[g];
+        const float4* rec = splats + (size_t)g * (SPLAT_REC / 4);  // one 64-byte line
+        const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
+        const float2 xy = make_float2(r0.x, r0.y);
+        const float4 co = make_float4(r0.z, r0.w, r1.x, r1.y);
         s.xy[t] = xy;
         s.co[t] = make_float4(co.x, co.y + co.y, co.z, co.w);
-        if (WITH_RGB) s_rgb[t] = make_float4(rgb[3 * g + 0], rgb[3 * g + 1], rgb[3 * g + 2], 0.f);
-        if (WITH_ID) s_id[t] = g;
+        if (WITH_RGB) s_rgb[t] = make_float4(r1.z, r1.w, r2.x, 0.f);
+        if (ID_MODE == 1) s_id[t] = g;
+        if (ID_MODE == 2) {
+            const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
+            const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
+            s_id[t] = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
+                      ((uint32_t)(tile % cam.tiles_x) - x0);
+        }
         const float ratio = co.w * __builtin_amdgcn_rcpf(cfg.alpha_min);
         if (ratio >= 1.0f) {
             const float det = co.x * co.z - co.y * co.y;
@@ -191,9 +199,7 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                     const uint32_t* __restrict__ gauss_sorted,
-                                                    const float2* __restrict__ mean2d,
-                                                    const float4* __restrict__ conic_opacity,
-                                                    const float* __restrict__ rgb, float* __restrict__ image,
+                                                    const float4* __restrict__ splats, float* __restrict__ image,
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib)
 {
     __shared__ Stage s;
@@ -218,8 +224,8 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     for (int start = 0; start < total; start += BATCH) {
         if (__syncthreads_count(!done) == 0) break;
         const int m = min(BATCH, total - start);
-        const int mine = stage_batch<true, false>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, mean2d,
-                                                  conic_opacity, rgb, range.x + start, m);
+        const int mine = stage_batch<true, 0>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, splats,
+                                              range.x + start, m);
         const int longest = wave_max_of_rows(mine);
         // Straight-line body with selects: lanes past their list's end (or finished) read a stale
         // slot and discard the result; only two wave-uniform branches per iteration.
@@ -316,9 +322,8 @@ __device__ __forceinline__ void row_reduce9(const float v[9], int lane, float& p
 // projection's backward kernel.  No global atomics, and the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void k_render_bwd(
     CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ gauss_sorted,
-    const float2* __restrict__ mean2d, const float4* __restrict__ conic_opacity, const float* __restrict__ rgb,
-    const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib, const float* __restrict__ dL_dimage,
-    const ushort4* __restrict__ rect, const uint32_t* __restrict__ offsets, float4* __restrict__ pair_grad)
+    const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
+    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
 {
     __shared__ Stage s;
     __shared__ float4 s_rgb[BATCH];
@@ -327,13 +332,6 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     __shared__ int s_max;
 
     const int tile = blockIdx.x;
-    const uint32_t tile_x = tile % cam.tiles_x, tile_y = tile / cam.tiles_x;
-    // record of the pair (g, this tile): where the pair was emitted before the sort
-    auto record_of = [&](uint32_t g) -> float4* {
-        const ushort4 r = rect[g];
-        const uint32_t idx = offsets[g] + (tile_y - r.y) * (uint32_t)(r.z - r.x) + (tile_x - r.x);
-        return pair_grad + (size_t)idx * (PAIR_REC / 4);
-    };
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
     const size_t hw = (size_t)cam.width * cam.height;
@@ -368,8 +366,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         __syncthreads();  // the previous batch's flush has read s_acc / s_id
 #pragma unroll
         for (int k = 0; k < 9; k++) s_acc[threadIdx.x][k] = 0.f;
-        const int mine = stage_batch<true, true>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, mean2d, conic_opacity,
-                                                 rgb, range.x + start, m);
+        const int mine = stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         const int longest = wave_max_of_rows(mine);
         for (int it = 0; it < longest; it++) {
             const int k = mine - 1 - it;      // every row walks its own list from the back
@@ -425,7 +422,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         if ((int)threadIdx.x < m) {
             const float* a = s_acc[threadIdx.x];
             const float4 co = s.co[threadIdx.x];  // co.y holds 2b
-            float4* rec = record_of(s_id[threadIdx.x]);
+            float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
             rec[0] = make_float4(a[0], a[1], a[2], a[3]);
             // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
             rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
@@ -434,7 +431,12 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     }
     // pairs behind the furthest blended Gaussian of the tile received nothing
     for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
-        float4* rec = record_of(gauss_sorted[pos]);
+        const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
+        const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
+        const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
+        const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
+                             ((uint32_t)(tile % cam.tiles_x) - x0);
+        float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
         rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
         rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
         rec[2].x = 0.f;
@@ -447,8 +449,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
 // count without any cross-lane arithmetic.
 __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                const uint32_t* __restrict__ gauss_sorted,
-                                               const float2* __restrict__ mean2d,
-                                               const float4* __restrict__ conic_opacity,
+                                               const float4* __restrict__ splats,
                                                const uint32_t* __restrict__ n_contrib,
                                                const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
 {
@@ -478,8 +479,8 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
         const int m = min(BATCH, total - start);
         __syncthreads();  // the previous batch's flush has read s_cnt / s_id
         s_cnt[threadIdx.x] = 0;
-        const int mine = stage_batch<false, true>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, mean2d,
-                                                  conic_opacity, nullptr, range.x + start, m);
+        const int mine = stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats,
+                                               range.x + start, m);
         if (__ballot(start < last) != 0) {
             const int longest = wave_max_of_rows(mine);
             for (int k = 0; k < longest; k++) {
@@ -509,41 +510,36 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 }  // namespace
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                             const float* rgb, float* image, float* final_T, uint32_t* n_contrib)
+                             const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
+                             uint32_t* n_contrib)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_render_fwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float2*>(mean2d),
-                       reinterpret_cast<const float4*>(conic_opacity), rgb, image, final_T, n_contrib);
+                       gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib);
     return hipGetLastError();
 }
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                             const float* rgb, const float* final_T, const uint32_t* n_contrib,
-                             const float* dL_dimage, const uint16_t* rect, const uint32_t* offsets,
-                             float* pair_grad)
+                             const uint32_t* gauss_sorted, const float* splats, const float* final_T,
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_render_bwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float2*>(mean2d),
-                       reinterpret_cast<const float4*>(conic_opacity), rgb, final_T, n_contrib, dL_dimage,
-                       reinterpret_cast<const ushort4*>(rect), offsets, reinterpret_cast<float4*>(pair_grad));
+                       gauss_sorted, reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
+                       reinterpret_cast<float4*>(pair_grad));
     return hipGetLastError();
 }
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                        const uint32_t* gauss_sorted, const float* mean2d, const float* conic_opacity,
-                        const uint32_t* n_contrib, const uint8_t* mask, int32_t* counts)
+                        const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
+                        const uint8_t* mask, int32_t* counts)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_score, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float2*>(mean2d),
-                       reinterpret_cast<const float4*>(conic_opacity), n_contrib, mask, counts);
+                       gauss_sorted, reinterpret_cast<const float4*>(splats), n_contrib, mask, counts);
     return hipGetLastError();
 }
 
