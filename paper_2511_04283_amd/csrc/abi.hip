@@ -278,8 +278,8 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
         FS_TRY(ensure(ctx, ctx->keys[k], (size_t)(P ? P : 1) * sizeof(uint64_t), "keys"));
         FS_TRY(ensure(ctx, ctx->vals[k], (size_t)(P ? P : 1) * sizeof(uint32_t), "values"));
     }
-    FS_TRY(ensure(ctx, ctx->hist, (size_t)(nb ? nb : 1) * 256 * sizeof(uint32_t), "histograms"));
-    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(256 * nb), "scan"));
+    FS_TRY(ensure(ctx, ctx->hist, (size_t)(nb ? nb : 1) * RADIX_DIGITS * sizeof(uint32_t), "histograms"));
+    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(RADIX_DIGITS * nb), "scan"));
 
     uint64_t* keys[2] = {static_cast<uint64_t*>(ctx->keys[0].ptr), static_cast<uint64_t*>(ctx->keys[1].ptr)};
     uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};

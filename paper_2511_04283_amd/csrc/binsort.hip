@@ -118,9 +118,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_apply(const uint32_t* in,
     }
 }
 
-// One key per tile of each Gaussian's rectangle, rows then columns, starting at offsets[i].  The same
-// thread also packs the Gaussian's projected splat, rectangle and pair offset into one 64-byte record,
-// so that the render kernels gather one cache line per (Gaussian, tile) pair instead of five.
+// One key per tile of each Gaussian's rectangle, rows then columns, starting at offsets[i].  A
+// wavefront takes 64 consecutive Gaussians; their pairs occupy one contiguous run of the output, and
+// the wavefront writes that run 64 pairs at a time (lane j of a round finds the Gaussian that owns
+// output slot j by a binary search over the lanes' running counts), so a Gaussian that touches
+// hundreds of tiles does not stall its 63 neighbours and every store is coalesced.  Each lane also
+// packs its own Gaussian's projected splat, rectangle and pair offset into one 64-byte record, so
+// that the render kernels gather one cache line per (Gaussian, tile) pair instead of five.
 __global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __restrict__ rect,
                                                     const float* __restrict__ depth,
                                                     const float2* __restrict__ mean2d,
@@ -131,33 +135,59 @@ __global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __
                                                     float4* __restrict__ splats)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const ushort4 r = rect[i];
-    if (r.z <= r.x || r.w <= r.y) return;
-    const uint32_t dbits = __float_as_uint(depth[i]);
-    uint32_t o = offsets[i];
-    {
+    const bool valid = i < n;
+    const uint32_t lane = lane_id();
+    const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
+    const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
+    const uint32_t cnt = w * h;
+    const uint32_t off = valid ? offsets[i] : 0u;
+    const uint32_t dbits = cnt ? __float_as_uint(depth[i]) : 0u;
+    if (cnt) {
         const float2 m = mean2d[i];
         const float4 co = conic_opacity[i];
         float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
         rec[0] = make_float4(m.x, m.y, co.x, co.y);
         rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
-        rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(o), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
+        rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(off), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
                              __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
     }
-    for (uint32_t ty = r.y; ty < r.w; ty++)
-        for (uint32_t tx = r.x; tx < r.z; tx++) {
-            keys[o] = ((uint64_t)(ty * (uint32_t)tiles_x + tx) << 32) | dbits;
-            vals[o] = (uint32_t)i;
-            o++;
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    const uint32_t excl = inc - cnt;                       // this lane's first slot within the wave's run
+    const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
+    const uint32_t run_start = (uint32_t)__shfl((int)off, 0, 64);  // offsets[] of the wave's first Gaussian
+    const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
+    for (uint32_t j0 = 0; j0 < total; j0 += 64) {
+        const uint32_t j = min(j0 + lane, total - 1);     // clamped: every lane takes part in the shuffles
+        // owner = last lane whose first slot is <= j (lanes without pairs share their successor's first slot)
+        uint32_t s = 0;
+#pragma unroll
+        for (uint32_t step = 32; step >= 1; step >>= 1) {
+            const uint32_t t = s + step;
+            const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
+            s = e <= j ? t : s;
         }
+        const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);  // place in the owner's rectangle, row-major
+        const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
+        const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
+        const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
+        uint32_t row = (uint32_t)((float)k / (float)ow);    // estimate, corrected below (exact for any k)
+        while (row * ow > k) row--;
+        while ((row + 1) * ow <= k) row++;
+        const uint32_t col = k - row * ow;
+        const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
+        if (j0 + lane < total) {
+            const size_t o = (size_t)run_start + j0 + lane;
+            keys[o] = ((uint64_t)(ty * (uint32_t)tiles_x + tx) << 32) | od;
+            vals[o] = (uint32_t)(i - lane + s);
+        }
+    }
 }
 
 // ---- radix sort -------------------------------------------------------------------------
-// One pass ranks RADIX_BLOCK_KEYS keys per workgroup on a digit of up to 8 bits.  Wave w of the
-// workgroup owns the contiguous chunk [w*512, w*512+512) of the block's keys and walks it in 8
-// rounds of 64 consecutive keys, so (wave, round, lane) order is the input order and the ranking
-// is stable.
+// One pass ranks RADIX_BLOCK_KEYS keys per workgroup on a digit of up to RADIX_BITS bits (the live key
+// bits are split into the fewest such digits, of equal width).  Wave w of the workgroup owns the
+// contiguous chunk [w*512, w*512+512) of the block's keys and walks it in 8 rounds of 64 consecutive
+// keys, so (wave, round, lane) order is the input order and the ranking is stable.
 
 constexpr int RADIX_ROUNDS = RADIX_BLOCK_KEYS / 256;  // rounds per wave
 
@@ -166,8 +196,8 @@ __global__ __launch_bounds__(256) void k_radix_hist(const uint64_t* __restrict__
                                                     uint32_t mask, uint32_t num_blocks,
                                                     uint32_t* __restrict__ hist)
 {
-    __shared__ uint32_t cnt[256];
-    cnt[threadIdx.x] = 0;
+    __shared__ uint32_t cnt[RADIX_DIGITS];
+    for (int d = threadIdx.x; d < RADIX_DIGITS; d += 256) cnt[d] = 0;
     __syncthreads();
     const uint32_t base = blockIdx.x * RADIX_BLOCK_KEYS;
 #pragma unroll
@@ -176,7 +206,7 @@ __global__ __launch_bounds__(256) void k_radix_hist(const uint64_t* __restrict__
         if (i < P) atomicAdd(&cnt[(uint32_t)(keys[i] >> shift) & mask], 1u);
     }
     __syncthreads();
-    hist[threadIdx.x * num_blocks + blockIdx.x] = cnt[threadIdx.x];
+    for (uint32_t d = threadIdx.x; d <= mask; d += 256) hist[d * num_blocks + blockIdx.x] = cnt[d];
 }
 
 __global__ __launch_bounds__(256) void k_radix_scatter(const uint64_t* __restrict__ kin,
@@ -185,12 +215,13 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint64_t* __restric
                                                        const uint32_t* __restrict__ hist_scanned, uint32_t P,
                                                        int shift, int bits, uint32_t num_blocks)
 {
-    __shared__ uint32_t cnt[4][256];
+    __shared__ uint32_t cnt[4][RADIX_DIGITS];
     const int wave = threadIdx.x >> 6;
     const uint32_t lane = lane_id();
     const uint32_t mask = (1u << bits) - 1u;
 #pragma unroll
-    for (int w = 0; w < 4; w++) cnt[w][threadIdx.x] = 0;
+    for (int w = 0; w < 4; w++)
+        for (int d = threadIdx.x; d < RADIX_DIGITS; d += 256) cnt[w][d] = 0;
     __syncthreads();
 
     const uint32_t wave_start = blockIdx.x * RADIX_BLOCK_KEYS + wave * (RADIX_ROUNDS * 64);
@@ -225,9 +256,8 @@ __global__ __launch_bounds__(256) void k_radix_scatter(const uint64_t* __restric
         rank[r] = prev + below;
     }
     __syncthreads();
-    // thread = digit: global start of this block's run of that digit, then per-wave starts
-    {
-        const uint32_t d = threadIdx.x;
+    // per digit: global start of this block's run of that digit, then per-wave starts
+    for (uint32_t d = threadIdx.x; d <= mask; d += 256) {
         uint32_t run = hist_scanned[d * num_blocks + blockIdx.x];
 #pragma unroll
         for (int w = 0; w < 4; w++) {
@@ -302,14 +332,14 @@ hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t
     int cur = 0;
     if (P > 0) {
         const uint32_t nb = (uint32_t)radix_num_blocks(P);
-        const int passes = (total_bits + 7) / 8;
+        const int passes = (total_bits + RADIX_BITS - 1) / RADIX_BITS;
+        const int bits = (total_bits + passes - 1) / passes;  // equal-width digits, at most RADIX_BITS
         for (int p = 0; p < passes; p++) {
-            const int shift = 8 * p;
-            const int bits = total_bits - shift < 8 ? total_bits - shift : 8;
+            const int shift = bits * p;
             const uint32_t mask = (1u << bits) - 1u;
             hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(256), 0, st, keys[cur], (uint32_t)P, shift, mask, nb,
                                hist);
-            hipError_t e = launch_exclusive_scan(st, hist, hist, (int64_t)256 * nb, scan_tmp, scan_total_dev);
+            hipError_t e = launch_exclusive_scan(st, hist, hist, (int64_t)(mask + 1) * nb, scan_tmp, scan_total_dev);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(256), 0, st, keys[cur], vals[cur], keys[cur ^ 1],
                                vals[cur ^ 1], hist, (uint32_t)P, shift, bits, nb);

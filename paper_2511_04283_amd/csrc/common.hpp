@@ -48,9 +48,11 @@ hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const fs_projected& proj
                              int tiles_x, uint64_t* keys, uint32_t* vals, float* splats);
 
 constexpr int RADIX_BLOCK_KEYS = 2048;  // keys ranked by one workgroup per pass
+constexpr int RADIX_BITS = 9;            // widest digit
+constexpr int RADIX_DIGITS = 1 << RADIX_BITS;
 inline int64_t radix_num_blocks(int64_t P) { return (P + RADIX_BLOCK_KEYS - 1) / RADIX_BLOCK_KEYS; }
 // Stable LSD sort of P (key,val) pairs on key bits [0,total_bits). Result ends in *keys_out/*vals_out,
-// which point into one of the two ping-pong buffers. hist: 256*radix_num_blocks(P) uint32.
+// which point into one of the two ping-pong buffers. hist: RADIX_DIGITS*radix_num_blocks(P) uint32.
 hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t* keys[2], uint32_t* vals[2],
                              uint32_t* hist, void* scan_tmp, uint64_t* scan_total_dev, int* result_index);
 
