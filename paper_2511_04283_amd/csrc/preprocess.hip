@@ -278,25 +278,30 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     constexpr int K = (DEG + 1) * (DEG + 1);
+    constexpr int F = 3 * K;                      // SH floats per Gaussian
+    constexpr int ROW = F + 1;                    // padded row: lane-strided LDS access without bank conflicts
+    constexpr int CH = 128;                       // pair records per chunk and wavefront
+    constexpr int WAVE_FLOATS = 64 * ROW > CH * PAIR_REC ? 64 * ROW : CH * PAIR_REC;
+    // one buffer per wavefront, used in turn for the pair records, the SH coefficients and the SH gradients
+    __shared__ __attribute__((aligned(16))) float s_buf[4][(WAVE_FLOATS + 3) / 4 * 4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool in_range = i < n;
 
     // ---- screen-space gradients: sum of this Gaussian's pair records, in tile order ----------
     // The 64 Gaussians of a wavefront own one contiguous run of records.  The wavefront streams that
     // run through LDS in chunks with coalesced 16-byte loads; each lane then adds up its own records.
-    constexpr int CH = 128;                       // records per chunk and wavefront
-    __shared__ float4 s_rec[4][CH * (PAIR_REC / 4)];
     float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb = ra;
     float rc = 0.f;
     {
-        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        const uint32_t off = i < n ? offsets[i] : 0u;
-        const uint32_t cnt = i < n ? touched[i] : 0u;
+        const uint32_t off = in_range ? offsets[i] : 0u;
+        const uint32_t cnt = in_range ? touched[i] : 0u;
         uint32_t lo_all = cnt ? off : 0xffffffffu, hi_all = cnt ? off + cnt : 0u;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             lo_all = min(lo_all, (uint32_t)__shfl_xor((int)lo_all, d, 64));
             hi_all = max(hi_all, (uint32_t)__shfl_xor((int)hi_all, d, 64));
         }
-        float4* buf = s_rec[wave];
+        float4* buf = reinterpret_cast<float4*>(s_buf[wave]);
         for (uint32_t cs = lo_all; cs < hi_all; cs += CH) {
             const uint32_t nrec = min((uint32_t)CH, hi_all - cs);
             const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
@@ -315,118 +320,189 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
             __builtin_amdgcn_wave_barrier();
         }
     }
-    if (i >= n) return;
+
+    // ---- SH coefficients of the wavefront's 64 Gaussians: one contiguous block of 64*F floats, copied
+    //      to LDS with coalesced loads (a lane reading its own F floats straight from memory would touch
+    //      64 different cache lines per instruction) ----
+    float* rows = s_buf[wave];
+    float* c = rows + lane * ROW;                 // this lane's coefficients, later its gradients
+    const int64_t wave_first = (int64_t)blockIdx.x * blockDim.x + wave * 64;
+    const int valid_rows = (int)min((int64_t)64, max((int64_t)0, n - wave_first));
+    {
+        const float* src = sh + wave_first * F;
+        if (valid_rows == 64) {
+            // full wavefront: 16 F aligned float4s, all loads issued before the first LDS write
+            constexpr int NV = (16 * F + 63) / 64;
+            const float4* src4 = reinterpret_cast<const float4*>(src);
+            float4 v[NV];
+#pragma unroll
+            for (int it = 0; it < NV; it++) {
+                const int q = lane + 64 * it;
+                v[it] = q < 16 * F ? src4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int it = 0; it < NV; it++) {
+                const int q = lane + 64 * it;
+                if (q < 16 * F) {
+                    const float comp[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
+                    int row = (4 * q) / F, col = 4 * q - row * F;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        rows[row * ROW + col] = comp[j];
+                        if (++col == F) { col = 0; row++; }
+                    }
+                }
+            }
+        } else {
+            for (int e = lane; e < 64 * F; e += 64) {
+                const int row = e / F;
+                if (row < valid_rows) rows[row * ROW + (e - row * F)] = src[e];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
     Splat s;
-    project(means, scales, quats, i, cam, cfg, s);
-    float* osh = d_sh + (int64_t)3 * K * i;
-    if (!s.visible) {
+    s.visible = false;
+    if (in_range) project(means, scales, quats, i, cam, cfg, s);
+    if (in_range && !s.visible) {
         for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
         *reinterpret_cast<float4*>(d_quats + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int k = 0; k < 3 * K; k++) osh[k] = 0.f;
+        for (int k = 0; k < F; k++) c[k] = 0.f;
         d_opac[i] = 0.f;
         d_mean2d[2 * i] = 0.f; d_mean2d[2 * i + 1] = 0.f;
         if (d_conic) for (int k = 0; k < 3; k++) d_conic[3 * i + k] = 0.f;
         if (d_rgb) for (int k = 0; k < 3; k++) d_rgb[3 * i + k] = 0.f;
-        return;
     }
-    const float g_rgb3[3] = {ra.x, ra.y, ra.z};
-    const float g_conic3[3] = {rb.x, rb.y, rb.z};
-    const float g_m2[2] = {rb.w, rc};
-    d_opac[i] = ra.w;
-    d_mean2d[2 * i] = g_m2[0]; d_mean2d[2 * i + 1] = g_m2[1];
-    if (d_conic) { d_conic[3 * i] = g_conic3[0]; d_conic[3 * i + 1] = g_conic3[1]; d_conic[3 * i + 2] = g_conic3[2]; }
-    if (d_rgb) { d_rgb[3 * i] = g_rgb3[0]; d_rgb[3 * i + 1] = g_rgb3[1]; d_rgb[3 * i + 2] = g_rgb3[2]; }
-    // ---- colour -> SH coefficients and, through the view direction, the mean ----
-    float d[3], len;
-    view_dir(means, i, cam, d, len);
-    float Y[K];
-    sh_basis(DEG, d[0], d[1], d[2], Y);
-    const float* c = sh + (int64_t)3 * K * i;
-    float gcol[3];
-    for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb3[ch];
-    float wk[K];
+    if (in_range && s.visible) {
+        const float g_rgb3[3] = {ra.x, ra.y, ra.z};
+        const float g_conic3[3] = {rb.x, rb.y, rb.z};
+        const float g_m2[2] = {rb.w, rc};
+        d_opac[i] = ra.w;
+        d_mean2d[2 * i] = g_m2[0]; d_mean2d[2 * i + 1] = g_m2[1];
+        if (d_conic) { d_conic[3 * i] = g_conic3[0]; d_conic[3 * i + 1] = g_conic3[1]; d_conic[3 * i + 2] = g_conic3[2]; }
+        if (d_rgb) { d_rgb[3 * i] = g_rgb3[0]; d_rgb[3 * i + 1] = g_rgb3[1]; d_rgb[3 * i + 2] = g_rgb3[2]; }
+        // ---- colour -> SH coefficients and, through the view direction, the mean ----
+        float d[3], len;
+        view_dir(means, i, cam, d, len);
+        float Y[K];
+        sh_basis(DEG, d[0], d[1], d[2], Y);
+        float gcol[3];
+        for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb3[ch];
+        float wk[K];
 #pragma unroll
-    for (int k = 0; k < K; k++) {
-        osh[3 * k + 0] = gcol[0] * Y[k];
-        osh[3 * k + 1] = gcol[1] * Y[k];
-        osh[3 * k + 2] = gcol[2] * Y[k];
-        wk[k] = gcol[0] * c[3 * k] + gcol[1] * c[3 * k + 1] + gcol[2] * c[3 * k + 2];
-    }
-    float gd[3];
-    sh_dir_grad<DEG>(d[0], d[1], d[2], wk, gd);
-    const float dot = gd[0] * d[0] + gd[1] * d[1] + gd[2] * d[2];
-    const float ilen = 1.0f / len;
-    float gm0 = (gd[0] - d[0] * dot) * ilen;
-    float gm1 = (gd[1] - d[1] * dot) * ilen;
-    float gm2 = (gd[2] - d[2] * dot) * ilen;
-
-    // ---- conic = Sigma_2D^-1 -> (a,b,c) ----
-    const float idet = 1.0f / s.det;
-    const float g0 = g_conic3[0], g1 = g_conic3[1], g2 = g_conic3[2];
-    const float g_det = -(g0 * s.c - g1 * s.b + g2 * s.a) * idet * idet;
-    const float ga = g2 * idet + g_det * s.c;
-    const float gb = -g1 * idet - 2.f * g_det * s.b;
-    const float gc = g0 * idet + g_det * s.a;
-    const float hb = 0.5f * gb;
-    // Sigma_2D = T Sigma_3D T^T:  dSigma_3D = T^T G T ;  dT = 2 G T Sigma_3D   (G = [[ga,hb],[hb,gc]])
-    const float T0[3] = {s.T00, s.T01, s.T02}, T1[3] = {s.T10, s.T11, s.T12};
-    const float S3[3][3] = {{s.s00, s.s01, s.s02}, {s.s01, s.s11, s.s12}, {s.s02, s.s12, s.s22}};
-    float GT0[3], GT1[3];  // rows of G*T
-    for (int k = 0; k < 3; k++) { GT0[k] = ga * T0[k] + hb * T1[k]; GT1[k] = hb * T0[k] + gc * T1[k]; }
-    float gS[3][3];
-    for (int r = 0; r < 3; r++)
-        for (int q = 0; q < 3; q++) gS[r][q] = T0[r] * GT0[q] + T1[r] * GT1[q];
-    float gT0[3], gT1[3];
-    for (int r = 0; r < 3; r++) {
-        gT0[r] = 2.f * (GT0[0] * S3[0][r] + GT0[1] * S3[1][r] + GT0[2] * S3[2][r]);
-        gT1[r] = 2.f * (GT1[0] * S3[0][r] + GT1[1] * S3[1][r] + GT1[2] * S3[2][r]);
-    }
-    // T = J R_cam
-    const float gJ00 = gT0[0] * cam.R[0] + gT0[1] * cam.R[1] + gT0[2] * cam.R[2];
-    const float gJ02 = gT0[0] * cam.R[6] + gT0[1] * cam.R[7] + gT0[2] * cam.R[8];
-    const float gJ11 = gT1[0] * cam.R[3] + gT1[1] * cam.R[4] + gT1[2] * cam.R[5];
-    const float gJ12 = gT1[0] * cam.R[6] + gT1[1] * cam.R[7] + gT1[2] * cam.R[8];
-    // J00 = fx/tz, J02 = -fx X/tz^2, J11 = fy/tz, J12 = -fy Y/tz^2, X = cxz*tz, Y = cyz*tz
-    const float iz = 1.0f / s.tz, iz2 = iz * iz;
-    const float X = s.cxz * s.tz, Yc = s.cyz * s.tz;
-    const float g_iz = cam.fx * gJ00 + cam.fy * gJ11 - 2.f * cam.fx * X * iz * gJ02 - 2.f * cam.fy * Yc * iz * gJ12;
-    const float gX = -cam.fx * iz2 * gJ02, gY = -cam.fy * iz2 * gJ12;
-    float gtz = gX * s.cxz + gY * s.cyz - g_iz * iz2;
-    float gtxz = s.xin ? gX * s.tz : 0.f;
-    float gtyz = s.yin ? gY * s.tz : 0.f;
-    gtxz += cam.fx * g_m2[0];
-    gtyz += cam.fy * g_m2[1];
-    const float gtx = gtxz * iz, gty = gtyz * iz;
-    gtz -= (gtxz * s.tx + gtyz * s.ty) * iz2;
-    gm0 += cam.R[0] * gtx + cam.R[3] * gty + cam.R[6] * gtz;
-    gm1 += cam.R[1] * gtx + cam.R[4] * gty + cam.R[7] * gtz;
-    gm2 += cam.R[2] * gtx + cam.R[5] * gty + cam.R[8] * gtz;
-    d_means[3 * i] = gm0; d_means[3 * i + 1] = gm1; d_means[3 * i + 2] = gm2;
-
-    // ---- Sigma_3D = M M^T, M = R(q) diag(s) ----
-    const float Rq[3][3] = {{s.r00, s.r01, s.r02}, {s.r10, s.r11, s.r12}, {s.r20, s.r21, s.r22}};
-    const float sc[3] = {scales[3 * i], scales[3 * i + 1], scales[3 * i + 2]};
-    float gR[3][3];
-    float gs[3] = {0.f, 0.f, 0.f};
-    for (int r = 0; r < 3; r++)
-        for (int q = 0; q < 3; q++) {
-            float gM = 0.f;
-            for (int k = 0; k < 3; k++) gM += (gS[r][k] + gS[k][r]) * (Rq[k][q] * sc[q]);
-            gs[q] += gM * Rq[r][q];
-            gR[r][q] = gM * sc[q];
+        for (int k = 0; k < K; k++) {
+            wk[k] = gcol[0] * c[3 * k] + gcol[1] * c[3 * k + 1] + gcol[2] * c[3 * k + 2];
+            c[3 * k + 0] = gcol[0] * Y[k];   // the coefficient has been read: its slot now holds its gradient
+            c[3 * k + 1] = gcol[1] * Y[k];
+            c[3 * k + 2] = gcol[2] * Y[k];
         }
-    d_scales[3 * i] = gs[0]; d_scales[3 * i + 1] = gs[1]; d_scales[3 * i + 2] = gs[2];
-    const float4 qq = *reinterpret_cast<const float4*>(quats + 4 * i);
-    const float w = qq.x, x = qq.y, y = qq.z, z = qq.w;
-    float4 gq;
-    gq.x = 2.f * (-z * gR[0][1] + y * gR[0][2] + z * gR[1][0] - x * gR[1][2] - y * gR[2][0] + x * gR[2][1]);
-    gq.y = 2.f * (y * gR[0][1] + z * gR[0][2] + y * gR[1][0] - 2.f * x * gR[1][1] - w * gR[1][2] + z * gR[2][0] +
-                  w * gR[2][1] - 2.f * x * gR[2][2]);
-    gq.z = 2.f * (-2.f * y * gR[0][0] + x * gR[0][1] + w * gR[0][2] + x * gR[1][0] + z * gR[1][2] - w * gR[2][0] +
-                  z * gR[2][1] - 2.f * y * gR[2][2]);
-    gq.w = 2.f * (-2.f * z * gR[0][0] - w * gR[0][1] + x * gR[0][2] + w * gR[1][0] - 2.f * z * gR[1][1] +
-                  y * gR[1][2] + x * gR[2][0] + y * gR[2][1]);
-    *reinterpret_cast<float4*>(d_quats + 4 * i) = gq;
+        float gd[3];
+        sh_dir_grad<DEG>(d[0], d[1], d[2], wk, gd);
+        const float dot = gd[0] * d[0] + gd[1] * d[1] + gd[2] * d[2];
+        const float ilen = 1.0f / len;
+        float gm0 = (gd[0] - d[0] * dot) * ilen;
+        float gm1 = (gd[1] - d[1] * dot) * ilen;
+        float gm2 = (gd[2] - d[2] * dot) * ilen;
+
+        // ---- conic = Sigma_2D^-1 -> (a,b,c) ----
+        const float idet = 1.0f / s.det;
+        const float g0 = g_conic3[0], g1 = g_conic3[1], g2 = g_conic3[2];
+        const float g_det = -(g0 * s.c - g1 * s.b + g2 * s.a) * idet * idet;
+        const float ga = g2 * idet + g_det * s.c;
+        const float gb = -g1 * idet - 2.f * g_det * s.b;
+        const float gc = g0 * idet + g_det * s.a;
+        const float hb = 0.5f * gb;
+        // Sigma_2D = T Sigma_3D T^T:  dSigma_3D = T^T G T ;  dT = 2 G T Sigma_3D   (G = [[ga,hb],[hb,gc]])
+        const float T0[3] = {s.T00, s.T01, s.T02}, T1[3] = {s.T10, s.T11, s.T12};
+        const float S3[3][3] = {{s.s00, s.s01, s.s02}, {s.s01, s.s11, s.s12}, {s.s02, s.s12, s.s22}};
+        float GT0[3], GT1[3];  // rows of G*T
+        for (int k = 0; k < 3; k++) { GT0[k] = ga * T0[k] + hb * T1[k]; GT1[k] = hb * T0[k] + gc * T1[k]; }
+        float gS[3][3];
+        for (int r = 0; r < 3; r++)
+            for (int q = 0; q < 3; q++) gS[r][q] = T0[r] * GT0[q] + T1[r] * GT1[q];
+        float gT0[3], gT1[3];
+        for (int r = 0; r < 3; r++) {
+            gT0[r] = 2.f * (GT0[0] * S3[0][r] + GT0[1] * S3[1][r] + GT0[2] * S3[2][r]);
+            gT1[r] = 2.f * (GT1[0] * S3[0][r] + GT1[1] * S3[1][r] + GT1[2] * S3[2][r]);
+        }
+        // T = J R_cam
+        const float gJ00 = gT0[0] * cam.R[0] + gT0[1] * cam.R[1] + gT0[2] * cam.R[2];
+        const float gJ02 = gT0[0] * cam.R[6] + gT0[1] * cam.R[7] + gT0[2] * cam.R[8];
+        const float gJ11 = gT1[0] * cam.R[3] + gT1[1] * cam.R[4] + gT1[2] * cam.R[5];
+        const float gJ12 = gT1[0] * cam.R[6] + gT1[1] * cam.R[7] + gT1[2] * cam.R[8];
+        // J00 = fx/tz, J02 = -fx X/tz^2, J11 = fy/tz, J12 = -fy Y/tz^2, X = cxz*tz, Y = cyz*tz
+        const float iz = 1.0f / s.tz, iz2 = iz * iz;
+        const float X = s.cxz * s.tz, Yc = s.cyz * s.tz;
+        const float g_iz = cam.fx * gJ00 + cam.fy * gJ11 - 2.f * cam.fx * X * iz * gJ02 - 2.f * cam.fy * Yc * iz * gJ12;
+        const float gX = -cam.fx * iz2 * gJ02, gY = -cam.fy * iz2 * gJ12;
+        float gtz = gX * s.cxz + gY * s.cyz - g_iz * iz2;
+        float gtxz = s.xin ? gX * s.tz : 0.f;
+        float gtyz = s.yin ? gY * s.tz : 0.f;
+        gtxz += cam.fx * g_m2[0];
+        gtyz += cam.fy * g_m2[1];
+        const float gtx = gtxz * iz, gty = gtyz * iz;
+        gtz -= (gtxz * s.tx + gtyz * s.ty) * iz2;
+        gm0 += cam.R[0] * gtx + cam.R[3] * gty + cam.R[6] * gtz;
+        gm1 += cam.R[1] * gtx + cam.R[4] * gty + cam.R[7] * gtz;
+        gm2 += cam.R[2] * gtx + cam.R[5] * gty + cam.R[8] * gtz;
+        d_means[3 * i] = gm0; d_means[3 * i + 1] = gm1; d_means[3 * i + 2] = gm2;
+
+        // ---- Sigma_3D = M M^T, M = R(q) diag(s) ----
+        const float Rq[3][3] = {{s.r00, s.r01, s.r02}, {s.r10, s.r11, s.r12}, {s.r20, s.r21, s.r22}};
+        const float sc[3] = {scales[3 * i], scales[3 * i + 1], scales[3 * i + 2]};
+        float gR[3][3];
+        float gs[3] = {0.f, 0.f, 0.f};
+        for (int r = 0; r < 3; r++)
+            for (int q = 0; q < 3; q++) {
+                float gM = 0.f;
+                for (int k = 0; k < 3; k++) gM += (gS[r][k] + gS[k][r]) * (Rq[k][q] * sc[q]);
+                gs[q] += gM * Rq[r][q];
+                gR[r][q] = gM * sc[q];
+            }
+        d_scales[3 * i] = gs[0]; d_scales[3 * i + 1] = gs[1]; d_scales[3 * i + 2] = gs[2];
+        const float4 qq = *reinterpret_cast<const float4*>(quats + 4 * i);
+        const float w = qq.x, x = qq.y, y = qq.z, z = qq.w;
+        float4 gq;
+        gq.x = 2.f * (-z * gR[0][1] + y * gR[0][2] + z * gR[1][0] - x * gR[1][2] - y * gR[2][0] + x * gR[2][1]);
+        gq.y = 2.f * (y * gR[0][1] + z * gR[0][2] + y * gR[1][0] - 2.f * x * gR[1][1] - w * gR[1][2] + z * gR[2][0] +
+                      w * gR[2][1] - 2.f * x * gR[2][2]);
+        gq.z = 2.f * (-2.f * y * gR[0][0] + x * gR[0][1] + w * gR[0][2] + x * gR[1][0] + z * gR[1][2] - w * gR[2][0] +
+                      z * gR[2][1] - 2.f * y * gR[2][2]);
+        gq.w = 2.f * (-2.f * z * gR[0][0] - w * gR[0][1] + x * gR[0][2] + w * gR[1][0] - 2.f * z * gR[1][1] +
+                      y * gR[1][2] + x * gR[2][0] + y * gR[2][1]);
+        *reinterpret_cast<float4*>(d_quats + 4 * i) = gq;
+    }
+    // ---- SH gradients of the wavefront back to memory, coalesced ----
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    {
+        float* dst = d_sh + wave_first * F;
+        if (valid_rows == 64) {
+            constexpr int NV = (16 * F + 63) / 64;
+            float4* dst4 = reinterpret_cast<float4*>(dst);
+#pragma unroll
+            for (int it = 0; it < NV; it++) {
+                const int q = lane + 64 * it;
+                if (q < 16 * F) {
+                    float comp[4];
+                    int row = (4 * q) / F, col = 4 * q - row * F;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        comp[j] = rows[row * ROW + col];
+                        if (++col == F) { col = 0; row++; }
+                    }
+                    dst4[q] = make_float4(comp[0], comp[1], comp[2], comp[3]);
+                }
+            }
+        } else {
+            for (int e = lane; e < 64 * F; e += 64) {
+                const int row = e / F;
+                if (row < valid_rows) dst[e] = rows[row * ROW + (e - row * F)];
+            }
+        }
+    }
 }
 
 }  // namespace
