@@ -98,6 +98,7 @@ typedef struct {
     const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
     const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted at
                                      pair_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0), before the sort         */
+    const uint32_t *tile_order;   /* [tiles] the tiles by decreasing list length: the order the render kernels take them in */
     const void *splats;           /* [n] 64-byte records (opaque): fs_bin_sort's copy of mean2d, conic_opacity, rgb,
                                      rect and pair_offsets of every visible Gaussian, one cache line per gather.
                                      The render, backward and score calls read the splats from here.             */

@@ -54,7 +54,7 @@ class fs_projected(ctypes.Structure):
 class fs_bins(ctypes.Structure):
     _fields_ = [("num_pairs", ctypes.c_int64), ("keys_sorted", ctypes.c_void_p), ("gauss_sorted", ctypes.c_void_p),
                 ("tile_ranges", ctypes.c_void_p), ("pair_offsets", ctypes.c_void_p),
-                ("splats", ctypes.c_void_p)]
+                ("tile_order", ctypes.c_void_p), ("splats", ctypes.c_void_p)]
 
 
 class fs_grads(ctypes.Structure):

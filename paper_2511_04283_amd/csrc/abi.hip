@@ -256,7 +256,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     hipStream_t st = ctx->stream;
     const int tiles = cd.tiles_x * cd.tiles_y;
 
-    FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * 2 * sizeof(uint32_t), "tile ranges"));
+    FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * 3 * sizeof(uint32_t), "tile ranges and order"));
     FS_TRY(ensure(ctx, ctx->offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "offsets"));
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
     FS_TRY(ensure(ctx, ctx->splats, (size_t)(n > 0 ? n : 1) * SPLAT_REC * sizeof(float), "splats"));
@@ -301,7 +301,8 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     // a5
     {
         ProfScope prof(ctx, FS_K_RANGES);
-        FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr)),
+        FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr),
+                                  static_cast<uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles),
                "k_tile_ranges");
     }
     out->num_pairs = (int64_t)P;
@@ -310,6 +311,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
     out->pair_offsets = static_cast<const uint32_t*>(ctx->offsets.ptr);
     out->splats = ctx->splats.ptr;
+    out->tile_order = static_cast<const uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles;
     return FS_OK;
 }
 
@@ -318,13 +320,13 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
 {
     if (!ctx) return FS_EINVAL;
     CamDev cd;
-    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !image || !final_T || !n_contrib)
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !bins->tile_order || !image || !final_T || !n_contrib)
         return fail(ctx, FS_EINVAL, "fs_render_fwd: bad arguments");
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_RENDER_FWD);
-    FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
+    FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                              static_cast<const float*>(bins->splats), image, final_T, n_contrib),
            "k_render_fwd");
     return FS_OK;
@@ -352,7 +354,7 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     if (!ctx) return FS_EINVAL;
     CamDev cd;
     if (!g || g->n < 0 || g->sh_degree < 0 || g->sh_degree > 3 || !make_cam(cam, cd) || !bins || !bins->tile_ranges ||
-        !final_T || !n_contrib || !dL_dimage || !out)
+        !bins->tile_order || !final_T || !n_contrib || !dL_dimage || !out)
         return fail(ctx, FS_EINVAL, "fs_render_bwd: bad arguments");
     const int64_t n = g->n;
     if (n == 0) return FS_OK;
@@ -371,7 +373,7 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     // a8: every pair's record is written exactly once
     if (bins->num_pairs > 0) {
         ProfScope prof(ctx, FS_K_RENDER_BWD);
-        FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->gauss_sorted,
+        FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                                  static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad),
                "k_render_bwd");
     }
@@ -409,14 +411,14 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (!ctx) return FS_EINVAL;
     CamDev cd;
     (void)final_T;  // the walk recomputes T from the front, exactly as the forward pass did
-    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !n_contrib || !mask)
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !bins->tile_order || !n_contrib || !mask)
         return fail(ctx, FS_EINVAL, "fs_score_accumulate: bad arguments");
     if (bins->num_pairs == 0) return FS_OK;
     if (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats || !counts)
         return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_SCORE);
-    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->gauss_sorted,
+    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                         static_cast<const float*>(bins->splats), n_contrib, mask, counts),
            "k_score");
     return FS_OK;

@@ -290,6 +290,30 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const uint64_t* __restrict_
     if (i + 1 == P || (uint32_t)(keys[i + 1] >> 32) != t) ranges[2 * t + 1] = i + 1;
 }
 
+// Order in which the render kernels take the tiles: longest list first (bucketed by length / 8), so
+// that the last workgroups of a launch are the cheapest ones.  One workgroup; any order is valid.
+__global__ __launch_bounds__(1024) void k_tile_order(const uint2* __restrict__ ranges, int num_tiles,
+                                                     uint32_t* __restrict__ order)
+{
+    constexpr int NB = 512;
+    __shared__ uint32_t cnt[NB];
+    for (int b = threadIdx.x; b < NB; b += 1024) cnt[b] = 0;
+    __syncthreads();
+    auto bucket = [](uint2 r) { const uint32_t len = r.y - r.x; return (int)(NB - 1 - min(len >> 3, (uint32_t)NB - 1)); };
+    for (int t = threadIdx.x; t < num_tiles; t += 1024) atomicAdd(&cnt[bucket(ranges[t])], 1u);
+    __syncthreads();
+    if (threadIdx.x < 64) {  // exclusive prefix over the 512 buckets by one wavefront, 8 buckets per lane
+        uint32_t c[8], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 8; k++) { c[k] = cnt[threadIdx.x * 8 + k]; sum += c[k]; }
+        uint32_t run = wave_inclusive_scan(sum) - sum;
+#pragma unroll
+        for (int k = 0; k < 8; k++) { cnt[threadIdx.x * 8 + k] = run; run += c[k]; }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < num_tiles; t += 1024) order[atomicAdd(&cnt[bucket(ranges[t])], 1u)] = (uint32_t)t;
+}
+
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int64_t count)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -351,13 +375,16 @@ hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t
 }
 
 hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
-                              uint32_t* ranges)
+                              uint32_t* ranges, uint32_t* tile_order)
 {
     hipError_t e = launch_fill_u32(st, ranges, 0u, (int64_t)2 * num_tiles);
     if (e != hipSuccess) return e;
     if (P > 0)
         hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, keys_sorted,
                            (uint32_t)P, ranges);
+    if (num_tiles > 0)
+        hipLaunchKernelGGL(k_tile_order, dim3(1), dim3(1024), 0, st, reinterpret_cast<const uint2*>(ranges), num_tiles,
+                           tile_order);
     return hipGetLastError();
 }
 

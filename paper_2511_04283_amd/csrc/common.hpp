@@ -56,19 +56,20 @@ inline int64_t radix_num_blocks(int64_t P) { return (P + RADIX_BLOCK_KEYS - 1) /
 hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t* keys[2], uint32_t* vals[2],
                              uint32_t* hist, void* scan_tmp, uint64_t* scan_total_dev, int* result_index);
 
+// ranges [num_tiles,2] and tile_order [num_tiles] (tiles by decreasing list length)
 hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
-                              uint32_t* ranges);
+                              uint32_t* ranges, uint32_t* tile_order);
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
+                             const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
                              uint32_t* n_contrib);
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* splats, const float* final_T,
+                             const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
                              const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                        const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
+                        const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
                         const uint8_t* mask, int32_t* counts);
 
 hipError_t launch_l1_grad(hipStream_t st, const float* image, const float* target, int64_t count,

@@ -198,6 +198,7 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 }
 
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
+                                                    const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
                                                     const float4* __restrict__ splats, float* __restrict__ image,
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib)
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     __shared__ Stage s;
     __shared__ float4 s_rgb[BATCH];
 
-    const int tile = blockIdx.x;
+    const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const int sub = (threadIdx.x >> 6) * 4 + ((threadIdx.x & 63) >> 4);  // this lane's sub-tile list
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
@@ -321,7 +322,8 @@ __device__ __forceinline__ void row_reduce9(const float v[9], int lane, float& p
 // for the ones nothing blended), and the per-Gaussian sum over its contiguous records is left to the
 // projection's backward kernel.  No global atomics, and the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void k_render_bwd(
-    CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ gauss_sorted,
+    CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+    const uint32_t* __restrict__ gauss_sorted,
     const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
     const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
 {
@@ -331,7 +333,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     __shared__ float s_acc[BATCH][9];
     __shared__ int s_max;
 
-    const int tile = blockIdx.x;
+    const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
     const size_t hw = (size_t)cam.width * cam.height;
@@ -448,6 +450,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
 // (and, in weight mode, alpha*T > alpha_min).  A ballot + population count gives each sub-tile's
 // count without any cross-lane arithmetic.
 __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
+                                               const uint32_t* __restrict__ tile_order,
                                                const uint32_t* __restrict__ gauss_sorted,
                                                const float4* __restrict__ splats,
                                                const uint32_t* __restrict__ n_contrib,
@@ -458,7 +461,7 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     __shared__ int s_cnt[BATCH];
     __shared__ int s_max;
 
-    const int tile = blockIdx.x;
+    const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const Pixel p = pixel_of_thread(cam, tile);
     const uint2 range = ranges[tile];
     const size_t pix = (size_t)p.y * cam.width + p.x;
@@ -510,36 +513,36 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 }  // namespace
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
+                             const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
                              uint32_t* n_contrib)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_render_fwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib);
+                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib);
     return hipGetLastError();
 }
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                             const uint32_t* gauss_sorted, const float* splats, const float* final_T,
+                             const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
                              const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_render_bwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
+                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
                        reinterpret_cast<float4*>(pair_grad));
     return hipGetLastError();
 }
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
-                        const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
+                        const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
                         const uint8_t* mask, int32_t* counts)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_score, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       gauss_sorted, reinterpret_cast<const float4*>(splats), n_contrib, mask, counts);
+                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), n_contrib, mask, counts);
     return hipGetLastError();
 }
 
