@@ -57,10 +57,13 @@ def lib() -> ctypes.CDLL:
         _lib.orc_pairs_bruteforce.restype = ctypes.c_uint64
         _lib.orc_exp_neg_f32.restype = ctypes.c_float
         _lib.orc_exp_neg_f32.argtypes = [ctypes.c_float]
+        _lib.orc_log_c_f32.restype = ctypes.c_float
+        _lib.orc_log_c_f32.argtypes = [ctypes.c_float]
         for sfx, ct in (("_f32", ctypes.c_float), ("_f64", ctypes.c_double)):
             getattr(_lib, "orc_l1" + sfx).restype = ctypes.c_double
             getattr(_lib, "orc_error_mask" + sfx).restype = ct
             getattr(_lib, "orc_count_evals" + sfx).restype = ctypes.c_int64
+            getattr(_lib, "orc_emit_pairs_cb" + sfx).restype = ctypes.c_uint64
     return _lib
 
 
@@ -80,6 +83,8 @@ class Config:
     bg: tuple = (0.0, 0.0, 0.0)
     jclamp: float = 1.3
     score_mode: int = 0  # 0 = WEIGHT (alpha*T > alpha_min), 1 = ALPHA
+    compact_box: bool = False  # pairs from the exact ellipse-tile test of the Compact Box instead of the 3-sigma square
+    cb_beta: float = 1.0
 
     def array(self, dtype):
         # fp32 build: constants are the fp32 roundings (1/255 computed in fp32 division)
@@ -90,7 +95,8 @@ class Config:
         else:
             amin = self.alpha_min
         return np.array([self.z_near, self.lowpass, amin, self.alpha_max, self.T_min,
-                         self.bg[0], self.bg[1], self.bg[2], self.jclamp], dtype=dtype)
+                         self.bg[0], self.bg[1], self.bg[2], self.jclamp, 1.0 if self.compact_box else 0.0,
+                         self.cb_beta], dtype=dtype)
 
 
 def cam_array(cam, dtype):
@@ -172,8 +178,14 @@ class Oracle:
         depth32 = np.ascontiguousarray(proj.depth, dtype=np.float32)
         keys = np.zeros(max(P, 1), np.uint64)
         vals = np.zeros(max(P, 1), np.uint32)
-        P2 = int(self.L.orc_emit_pairs(ctypes.c_int64(n), _p(proj.rect), _p(depth32), ctypes.c_int(TX),
-                                       _p(keys), _p(vals)))
+        if self.cfg.compact_box:
+            P2 = int(self._f("orc_emit_pairs_cb")(
+                ctypes.c_int64(n), _p(proj.rect), _p(depth32.view(np.uint32)), _p(self._a(proj.mean2d)),
+                _p(self._a(proj.conic_opacity)), _p(self.cfg.array(self.dtype)), ctypes.c_int(TX),
+                ctypes.c_int(self.cfg.tile), _p(keys), _p(vals)))
+        else:
+            P2 = int(self.L.orc_emit_pairs(ctypes.c_int64(n), _p(proj.rect), _p(depth32), ctypes.c_int(TX),
+                                           _p(keys), _p(vals)))
         assert P2 == P
         keys, vals = keys[:P], vals[:P]
         ks, vs = keys.copy(), vals.copy()
@@ -240,8 +252,8 @@ class Oracle:
         c = lambda a: np.ascontiguousarray(a, dtype=np.float64)
         self._f("orc_preprocess_bwd")(
             ctypes.c_int64(n), ctypes.c_int(sc.sh_degree), _p(self._a(sc.means)), _p(self._a(sc.scales)),
-            _p(self._a(sc.quats)), _p(self._a(sc.sh)), ctypes.c_int(cam.width), ctypes.c_int(cam.height),
-            _p(cam_array(cam, dt)), _p(self.cfg.array(dt)), ctypes.c_int(self.cfg.tile),
+            _p(self._a(sc.quats)), _p(self._a(sc.opacities)), _p(self._a(sc.sh)), ctypes.c_int(cam.width),
+            ctypes.c_int(cam.height), _p(cam_array(cam, dt)), _p(self.cfg.array(dt)), ctypes.c_int(self.cfg.tile),
             _p(c(d_mean2d)), _p(c(d_conic)), _p(c(d_opacity)), _p(c(d_rgb)),
             _p(g["means"]), _p(g["scales"]), _p(g["quats"]), _p(g["opacities"]), _p(g["sh"]))
         return g

@@ -35,6 +35,26 @@ static float exp_neg_f32(float x)
     return ldexpf(p, (int)n);
 }
 
+/* ln(x), x > 0, in a pinned fp32 form (used once per Gaussian by the Compact Box threshold):
+ * x = m 2^e with m in [sqrt(1/2), sqrt(2)); s = (m-1)/(m+1); z = s*s;
+ * ln m = 2 s (1 + z/3 + z^2/5 + z^3/7 + z^4/9) by Horner with fused multiply-adds; result = fma(e, ln2, ln m). */
+static float log_c_f32(float x)
+{
+    int e;
+    float m = frexpf(x, &e);                    /* m in [0.5, 1) */
+    if (m < 0x1.6a09e6p-1f) { m = m + m; e = e - 1; }
+    float s = (m - 1.0f) / (m + 1.0f);
+    float z = s * s;
+    float p = 0x1.c71c72p-4f;                   /* 1/9 */
+    p = fmaf(p, z, 0x1.24924ap-3f);             /* 1/7 */
+    p = fmaf(p, z, 0x1.99999ap-3f);             /* 1/5 */
+    p = fmaf(p, z, 0x1.555556p-2f);             /* 1/3 */
+    p = fmaf(p, z, 1.0f);
+    float lnm = (s + s) * p;
+    return fmaf((float)e, 0x1.62e43p-1f, lnm);
+}
+float orc_log_c_f32(float x) { return log_c_f32(x); }
+
 #define REAL float
 #define FN(name) name##_f32
 #define SQRT sqrtf
@@ -45,6 +65,7 @@ static float exp_neg_f32(float x)
 #define FMAX fmaxf
 #define FMA fmaf
 #define EXPNEG exp_neg_f32
+#define LOGC log_c_f32
 #include "fastgs_oracle_impl.h"
 #undef REAL
 #undef FN
@@ -56,6 +77,7 @@ static float exp_neg_f32(float x)
 #undef FMAX
 #undef FMA
 #undef EXPNEG
+#undef LOGC
 
 #define REAL double
 #define FN(name) name##_f64
@@ -67,6 +89,7 @@ static float exp_neg_f32(float x)
 #define FMAX fmax
 #define FMA(a, b, c) ((a) * (b) + (c))
 #define EXPNEG exp
+#define LOGC log
 #include "fastgs_oracle_impl.h"
 
 /* exposed so a test can compare the pinned fp32 exponential with the library's */

@@ -19,7 +19,7 @@
  */
 
 /* camera array layout: fx fy cx cy R[9] (row-major, x_cam = R x_world + t) t[3]          */
-/* config array layout: z_near lowpass alpha_min alpha_max T_min bg[3] jclamp              */
+/* config array layout: z_near lowpass alpha_min alpha_max T_min bg[3] jclamp compact_box cb_beta */
 #define CAM_FX(c) ((c)[0])
 #define CAM_FY(c) ((c)[1])
 #define CAM_CX(c) ((c)[2])
@@ -33,6 +33,8 @@
 #define CFG_TMIN(c) ((c)[4])
 #define CFG_BG(c) ((c) + 5)
 #define CFG_JCLAMP(c) ((c)[8])
+#define CFG_CB(c) ((c)[9] != (REAL)0)
+#define CFG_CB_BETA(c) ((c)[10])
 
 /* Real spherical harmonics, bands 0..3, orthonormal on the sphere, in the textbook
  * Cartesian closed forms (no Condon-Shortley sign).  Order: (l,m) = (0,0), (1,-1), (1,0),
@@ -128,16 +130,67 @@ typedef struct {
     REAL lam_max, radius;
     REAL mx, my;        /* mu_2D                                                           */
     int  rect[4];       /* tile rectangle x0,y0,x1,y1 (half-open)                          */
+    int  touched;       /* number of Gaussian-tile pairs                                    */
+    REAL Q;             /* Compact Box: Mahalanobis threshold beta * 2 ln(sigma / tau_alpha) */
     REAL dir[3], len, d[3];
     REAL rgb[3]; int clamped[3];
 } FN(proj);
+
+/*
+ * Compact Box (Sec. 4.4 and its supplement): the support of a Gaussian is the ellipse
+ *   (p - mu_2D)^T Sigma_2D^-1 (p - mu_2D) <= Q,   Q = beta * 2 ln(sigma / tau_alpha)
+ * (the supplement's equation for beta; tau_alpha is read as alpha_min), and a Gaussian-tile pair
+ * exists iff the tile's closed rectangle [tile*tx, tile*tx+tile] x [tile*ty, ...] meets that ellipse,
+ * i.e. iff the minimum of the quadratic form over the rectangle is <= Q.  The form is convex with its
+ * minimum at mu_2D, so the minimum over the rectangle is 0 if mu_2D lies inside and otherwise sits on
+ * an edge that faces mu_2D (at most one vertical and one horizontal edge); along an edge it is a
+ * 1-D quadratic whose minimiser is clamped to the edge.
+ * fp32 order: dxl = X0 - mx; dxr = X1 - mx; dyt = Y0 - my; dyb = Y1 - my;  vertical edge at ex:
+ * dy* = min(max(-(B*ex)/C, dyt), dyb); horizontal edge at ey: dx* = min(max(-(B*ey)/A, dxl), dxr);
+ * form(dx,dy) = fma(dx, fma(B+B, dy, A*dx), (C*dy)*dy).
+ */
+static int FN(cb_tile_hit)(REAL mx, REAL my, REAL A, REAL B, REAL C, REAL Q, int tx, int ty, int tile)
+{
+    REAL X0 = (REAL)(tx * tile), X1 = (REAL)(tx * tile + tile);
+    REAL Y0 = (REAL)(ty * tile), Y1 = (REAL)(ty * tile + tile);
+    REAL dxl = X0 - mx, dxr = X1 - mx, dyt = Y0 - my, dyb = Y1 - my;
+    int in_x = dxl <= (REAL)0 && dxr >= (REAL)0;
+    int in_y = dyt <= (REAL)0 && dyb >= (REAL)0;
+    if (in_x && in_y) return 1;
+    REAL B2 = B + B;
+    int have = 0;
+    REAL qmin = 0;
+    if (!in_x) {
+        REAL ex = dxl > (REAL)0 ? dxl : dxr;
+        REAL dys = -(B * ex) / C;
+        dys = FMIN(FMAX(dys, dyt), dyb);
+        REAL q = FMA(ex, FMA(B2, dys, A * ex), (C * dys) * dys);
+        qmin = q; have = 1;
+    }
+    if (!in_y) {
+        REAL ey = dyt > (REAL)0 ? dyt : dyb;
+        REAL dxs = -(B * ey) / A;
+        dxs = FMIN(FMAX(dxs, dxl), dxr);
+        REAL q = FMA(dxs, FMA(B2, ey, A * dxs), (C * ey) * ey);
+        if (!have || q < qmin) qmin = q;
+    }
+    return qmin <= Q;
+}
+
+/* Q of the Compact Box for opacity sigma; <= 0 means the Gaussian can never reach tau_alpha. */
+static REAL FN(cb_threshold)(REAL sigma, const REAL *cfg)
+{
+    REAL ratio = sigma / CFG_AMIN(cfg);
+    if (!(ratio > (REAL)1)) return (REAL)0;
+    return CFG_CB_BETA(cfg) * ((REAL)2 * LOGC(ratio));
+}
 
 /*
  * Projection of one Gaussian (Sec. 3, Eqs. (2)-(3) and the text around them).
  * fp32 operation order (the contract the HIP path must reproduce bit for bit): every
  * expression below is evaluated exactly as written, left to right, with no fused ops.
  */
-static void FN(project_one)(const REAL mu[3], const REAL s[3], const REAL q[4], int deg,
+static void FN(project_one)(const REAL mu[3], const REAL s[3], const REAL q[4], REAL sigma, int deg,
                             const REAL *sh /* [(deg+1)^2][3] */, int width, int height,
                             const REAL *cam, const REAL *cfg, int tile, FN(proj) *o)
 {
@@ -203,28 +256,49 @@ static void FN(project_one)(const REAL mu[3], const REAL s[3], const REAL q[4], 
     o->conic[1] = -o->b * idet;
     o->conic[2] = o->a * idet;
 
-    /* 3-sigma rule (Sec. 4.4): radius from the larger eigenvalue of Sigma_2D               */
-    REAL mid = (REAL)0.5 * (o->a + o->c);
-    REAL hd = (REAL)0.5 * (o->a - o->c);
-    o->lam_max = mid + SQRT(hd * hd + o->b * o->b);
-    o->radius = CEIL((REAL)3 * SQRT(o->lam_max));
     o->mx = fx * o->txz + CAM_CX(cam);
     o->my = fy * o->tyz + CAM_CY(cam);
-    if (!(o->radius < (REAL)1e6) || !(FABS(o->mx) < (REAL)1e7) || !(FABS(o->my) < (REAL)1e7)) return;
-
-    /* tiles met by the closed square [mu-r, mu+r]^2; tile (tx,ty) covers
-     * [tile*tx, tile*tx+tile) x [tile*ty, ...)                                              */
     int TX = (width + tile - 1) / tile, TY = (height + tile - 1) / tile;
     REAL inv_tile = (REAL)1 / (REAL)tile;            /* tile is a power of two: exact     */
-    REAL fx0 = FLOOR((o->mx - o->radius) * inv_tile);
-    REAL fy0 = FLOOR((o->my - o->radius) * inv_tile);
-    REAL fx1 = FLOOR((o->mx + o->radius) * inv_tile) + (REAL)1;
-    REAL fy1 = FLOOR((o->my + o->radius) * inv_tile) + (REAL)1;
+    REAL hx, hy;                                     /* half-widths of the box around mu_2D */
+    if (!CFG_CB(cfg)) {
+        /* 3-sigma rule (Sec. 4.4): radius from the larger eigenvalue of Sigma_2D           */
+        REAL mid = (REAL)0.5 * (o->a + o->c);
+        REAL hd = (REAL)0.5 * (o->a - o->c);
+        o->lam_max = mid + SQRT(hd * hd + o->b * o->b);
+        o->radius = CEIL((REAL)3 * SQRT(o->lam_max));
+        hx = hy = o->radius;
+    } else {
+        /* Compact Box: axis-aligned bounds of the ellipse q <= Q are sqrt(Q Sigma_xx), sqrt(Q Sigma_yy) */
+        o->Q = FN(cb_threshold)(sigma, cfg);
+        if (!(o->Q > (REAL)0)) return;
+        hx = SQRT(o->Q * o->a);
+        hy = SQRT(o->Q * o->c);
+        o->radius = CEIL(hx > hy ? hx : hy);
+    }
+    if (!(hx < (REAL)1e6) || !(hy < (REAL)1e6) || !(FABS(o->mx) < (REAL)1e7) || !(FABS(o->my) < (REAL)1e7)) return;
+
+    /* tiles met by the closed box [mu-h, mu+h]; tile (tx,ty) covers
+     * [tile*tx, tile*tx+tile) x [tile*ty, ...)                                              */
+    REAL fx0 = FLOOR((o->mx - hx) * inv_tile);
+    REAL fy0 = FLOOR((o->my - hy) * inv_tile);
+    REAL fx1 = FLOOR((o->mx + hx) * inv_tile) + (REAL)1;
+    REAL fy1 = FLOOR((o->my + hy) * inv_tile) + (REAL)1;
     o->rect[0] = (int)FMIN(FMAX(fx0, (REAL)0), (REAL)TX);
     o->rect[1] = (int)FMIN(FMAX(fy0, (REAL)0), (REAL)TY);
     o->rect[2] = (int)FMIN(FMAX(fx1, (REAL)0), (REAL)TX);
     o->rect[3] = (int)FMIN(FMAX(fy1, (REAL)0), (REAL)TY);
     if ((o->rect[2] - o->rect[0]) * (o->rect[3] - o->rect[1]) <= 0) return;
+    if (!CFG_CB(cfg)) {
+        o->touched = (o->rect[2] - o->rect[0]) * (o->rect[3] - o->rect[1]);
+    } else {
+        /* within the box, only the tiles whose rectangle really meets the ellipse */
+        o->touched = 0;
+        for (int ty = o->rect[1]; ty < o->rect[3]; ty++)
+            for (int tx = o->rect[0]; tx < o->rect[2]; tx++)
+                o->touched += FN(cb_tile_hit)(o->mx, o->my, o->conic[0], o->conic[1], o->conic[2], o->Q, tx, ty, tile);
+        if (o->touched == 0) return;
+    }
 
     /* view-dependent colour: direction from the camera centre to the mean                  */
     REAL campos[3];
@@ -256,7 +330,7 @@ void FN(orc_preprocess)(int64_t n, int deg, const REAL *means, const REAL *scale
     int K = (deg + 1) * (deg + 1);
     for (int64_t i = 0; i < n; i++) {
         FN(proj) p;
-        FN(project_one)(means + 3 * i, scales + 3 * i, quats + 4 * i, deg, sh + 3 * K * i, width, height,
+        FN(project_one)(means + 3 * i, scales + 3 * i, quats + 4 * i, opac[i], deg, sh + 3 * K * i, width, height,
                         cam, cfg, tile, &p);
         if (!p.visible) {
             mean2d[2 * i] = mean2d[2 * i + 1] = 0; depth[i] = 0;
@@ -270,9 +344,35 @@ void FN(orc_preprocess)(int64_t n, int deg, const REAL *means, const REAL *scale
         conic_opacity[4 * i + 2] = p.conic[2]; conic_opacity[4 * i + 3] = opac[i];
         for (int k = 0; k < 3; k++) { rgb[3 * i + k] = p.rgb[k]; clamped[3 * i + k] = (uint8_t)p.clamped[k]; }
         for (int k = 0; k < 4; k++) rect[4 * i + k] = p.rect[k];
-        touched[i] = (uint32_t)((p.rect[2] - p.rect[0]) * (p.rect[3] - p.rect[1]));
+        touched[i] = (uint32_t)p.touched;
         radius[i] = (int32_t)p.radius;
     }
+}
+
+/* Step a3 with the Compact Box: one (key, Gaussian) entry per tile of the Gaussian's box whose
+ * rectangle meets its support ellipse, in Gaussian order, rows then columns (same key layout as the
+ * 3-sigma emission).  depth_bits are the fp32 bit patterns of the depths. */
+uint64_t FN(orc_emit_pairs_cb)(int64_t n, const int32_t *rect, const uint32_t *depth_bits, const REAL *mean2d,
+                               const REAL *conic_opacity, const REAL *cfg, int TX, int tile,
+                               uint64_t *keys, uint32_t *vals)
+{
+    uint64_t p = 0;
+    for (int64_t i = 0; i < n; i++) {
+        if (rect[4 * i + 2] <= rect[4 * i] || rect[4 * i + 3] <= rect[4 * i + 1]) continue;
+        REAL Q = FN(cb_threshold)(conic_opacity[4 * i + 3], cfg);
+        for (int ty = rect[4 * i + 1]; ty < rect[4 * i + 3]; ty++)
+            for (int tx = rect[4 * i + 0]; tx < rect[4 * i + 2]; tx++) {
+                if (!FN(cb_tile_hit)(mean2d[2 * i], mean2d[2 * i + 1], conic_opacity[4 * i], conic_opacity[4 * i + 1],
+                                     conic_opacity[4 * i + 2], Q, tx, ty, tile))
+                    continue;
+                if (keys) {
+                    keys[p] = ((uint64_t)(uint32_t)(ty * TX + tx) << 32) | depth_bits[i];
+                    vals[p] = (uint32_t)i;
+                }
+                p++;
+            }
+    }
+    return p;
 }
 
 /*
@@ -427,7 +527,7 @@ void FN(orc_render_bwd)(const REAL *mean2d, const REAL *conic_opacity, const REA
  * Outputs are OVERWRITTEN.  Invisible Gaussians get zero gradients.
  */
 void FN(orc_preprocess_bwd)(int64_t n, int deg, const REAL *means, const REAL *scales, const REAL *quats,
-                            const REAL *sh, int width, int height, const REAL *cam, const REAL *cfg,
+                            const REAL *opac, const REAL *sh, int width, int height, const REAL *cam, const REAL *cfg,
                             int tile, const double *d_mean2d, const double *d_conic,
                             const double *d_opacity_in, const double *d_rgb,
                             double *d_means, double *d_scales, double *d_quats, double *d_opac,
@@ -443,7 +543,7 @@ void FN(orc_preprocess_bwd)(int64_t n, int deg, const REAL *means, const REAL *s
         for (int k = 0; k < 3 * K; k++) gsh[k] = 0;
         d_opac[i] = 0;
         FN(proj) p;
-        FN(project_one)(means + 3 * i, scales + 3 * i, quats + 4 * i, deg, sh + 3 * K * i, width, height,
+        FN(project_one)(means + 3 * i, scales + 3 * i, quats + 4 * i, opac[i], deg, sh + 3 * K * i, width, height,
                         cam, cfg, tile, &p);
         if (!p.visible) continue;
         d_opac[i] = d_opacity_in[i];

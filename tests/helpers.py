@@ -13,11 +13,12 @@ def one_gaussian_scene(mean, scale, quat, opacity, rgb, cam: Camera) -> Scene:
                  np.asarray(quat, f64).reshape(1, 4), np.asarray([opacity], f64), sh, [cam], 0)
 
 
-def brute_composite(proj, cam, cfg, mask=None):
+def brute_composite(proj, cam, cfg, mask=None, use_rect=True):
     """Per-pixel front-to-back compositing straight from Eq. (4), float64, no tiles lists and
     no keys: at each pixel take every Gaussian whose tile rectangle contains the pixel's tile,
     order by (depth, index), blend.  Returns image, final_T, number blended, and per-Gaussian
-    counts (WEIGHT and ALPHA readings) over `mask` pixels."""
+    counts (WEIGHT and ALPHA readings) over `mask` pixels.  With use_rect=False every visible
+    Gaussian is a candidate at every pixel (no pair structure at all)."""
     H, W, t = cam.height, cam.width, cfg.tile
     n = proj.depth.shape[0]
     image = np.zeros((3, H, W)); final_T = np.ones((H, W)); nblend = np.zeros((H, W), np.int64)
@@ -31,7 +32,7 @@ def brute_composite(proj, cam, cfg, mask=None):
             C = np.zeros(3)
             for i in order:
                 x0, y0, x1, y1 = proj.rect[i]
-                if not (x0 <= tx < x1 and y0 <= ty < y1):
+                if use_rect and not (x0 <= tx < x1 and y0 <= ty < y1):
                     continue
                 d = np.array([u + 0.5 - proj.mean2d[i, 0], v + 0.5 - proj.mean2d[i, 1]], dtype=np.float64)
                 a, b, c, sig = [float(x) for x in proj.conic_opacity[i]]
