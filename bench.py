@@ -37,6 +37,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compact-box", action="store_true",
+                    help="pairs from the Compact Box (ellipse-tile test, Sec. 4.4) instead of the 3-sigma square")
+    ap.add_argument("--cb-beta", type=float, default=1.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -53,7 +56,10 @@ def main() -> int:
     cam = sc.cameras[0]
     target_np = scenes.target_image(args.config, 0, cam)
     dev = torch.device("cuda:0")
-    ctx = B.Context(dev)
+    cfg0 = B.default_config()
+    cfg0.compact_box = 1 if args.compact_box else 0
+    cfg0.cb_beta = args.cb_beta
+    ctx = B.Context(dev, cfg0)
     g = B.Gaussians.from_scene(sc, dev)
     fcam = B.make_camera(cam)
     target = torch.from_numpy(target_np).to(dev)
@@ -120,6 +126,7 @@ def main() -> int:
     evals_bwd = int(n_contrib.to(torch.int64).sum().item())          # entries walked back per pixel
     evals_fwd_bound = int(P) * 256                                    # upper bound: every pixel walks its whole list
     cfgA = B.default_config()
+    cfgA.compact_box, cfgA.cb_beta = cfg0.compact_box, cfg0.cb_beta
     cfgA.score_mode = B.FS_SCORE_ALPHA
     ctxA = B.Context(dev, cfgA)
     projA = ctxA.fs_preprocess(g, fcam)
@@ -137,7 +144,7 @@ def main() -> int:
     dominant = max(kernels_ms, key=kernels_ms.get)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_cfg{args.config}.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.compact_box:
         with open(tpath) as f:
             traffic = json.load(f).get("render_bwd_bytes_per_launch")
     achieved = bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
@@ -152,7 +159,8 @@ def main() -> int:
         "value": round(1e3 / ms_per_step, 3), "unit": "iters/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": sc.name, "gaussians": n, "sh_degree": sc.sh_degree, "image": [W, H],
+        "config": {"workload": sc.name + (f"+compact_box(beta={args.cb_beta:g})" if args.compact_box else ""),
+                   "gaussians": n, "sh_degree": sc.sh_degree, "image": [W, H],
                    "pairs": int(P), "max_tile_list": int(tile_len.max().item()),
                    "step": "preprocess+bin_sort+render_fwd+l1_grad+render_bwd+error_mask+score_accumulate"},
         "roofline": roofline,
@@ -165,8 +173,8 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        from oracle import Oracle
-        o = Oracle(np.float32)
+        from oracle import Config, Oracle
+        o = Oracle(np.float32, Config(compact_box=args.compact_box, cb_beta=args.cb_beta))
         c0 = time.perf_counter()
         p_o, b_o, img_o, T_o, nc_o = o.forward(sc, cam)
         l_o, dL_o = o.l1(img_o, target_np)

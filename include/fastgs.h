@@ -56,6 +56,10 @@ typedef struct {
     float bg[3];        /* background colour                                                          */
     float jclamp;       /* t_x/t_z, t_y/t_z used inside J are limited to jclamp*tan(fov/2); <=0: off (1.3) */
     int32_t score_mode; /* FS_SCORE_WEIGHT: count where alpha*T > alpha_min; FS_SCORE_ALPHA: where blended */
+    int32_t compact_box; /* 0: pairs from the 3-sigma square; 1: Compact Box (Sec. 4.4): a (Gaussian, tile) pair
+                            exists iff the tile's closed rectangle meets the ellipse
+                            (p-mu_2D)^T Sigma_2D^-1 (p-mu_2D) <= cb_beta * 2 ln(sigma / alpha_min)  (0)          */
+    float cb_beta;       /* Compact Box threshold scale beta in (0, 1]; 1 keeps every pixel with alpha >= alpha_min (1) */
 } fs_config;
 
 /* Pinhole camera: x_cam = R x_world + t (the paper's viewing transformation W);
@@ -84,8 +88,10 @@ typedef struct {
     float *depth;            /* [n]   camera-space z                                          */
     float *conic_opacity;    /* [n,4] Sigma_2D^-1 as (a, b, c) with q = a dx^2 + 2 b dx dy + c dy^2, then sigma */
     float *rgb;              /* [n,3] view-dependent colour max(0, 0.5 + SH)                  */
-    uint16_t *rect;          /* [n,4] tile rectangle x0,y0,x1,y1, half-open                   */
-    uint32_t *tiles_touched; /* [n]   (x1-x0)*(y1-y0); 0 = culled                             */
+    uint16_t *rect;          /* [n,4] tile rectangle x0,y0,x1,y1, half-open (Compact Box: the tiles met by the
+                                      ellipse's axis-aligned bounding box)                              */
+    uint32_t *tiles_touched; /* [n]   number of pairs: (x1-x0)*(y1-y0), or with the Compact Box the tiles
+                                      of rect that meet the ellipse; 0 = culled                         */
     uint8_t *clamped;        /* [n,3] 1 where the colour channel was clamped at 0             */
 } fs_projected;
 
@@ -96,11 +102,16 @@ typedef struct {
     const uint64_t *keys_sorted;  /* [P] tile_id << 32 | bits(depth), ascending; ties by Gaussian index */
     const uint32_t *gauss_sorted; /* [P] Gaussian index of each entry                                 */
     const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
-    const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted at
-                                     pair_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0), before the sort         */
+    const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted from
+                                     pair_offsets[i] on, rows then columns of rect, before the sort             */
+    int64_t num_records;          /* backward scratch records: P, or with the Compact Box the sum of rect areas  */
+    const uint32_t *record_offsets; /* [n] Gaussian i's backward records start here; the record of tile (tx,ty) is
+                                     record_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0).  Equals pair_offsets
+                                     without the Compact Box.                                                   */
+    const uint32_t *record_counts;  /* [n] records per Gaussian (rect area); NULL = proj->tiles_touched           */
     const uint32_t *tile_order;   /* [tiles] the tiles by decreasing list length: the order the render kernels take them in */
     const void *splats;           /* [n] 64-byte records (opaque): fs_bin_sort's copy of mean2d, conic_opacity, rgb,
-                                     rect and pair_offsets of every visible Gaussian, one cache line per gather.
+                                     rect and record_offsets of every visible Gaussian, one cache line per gather.
                                      The render, backward and score calls read the splats from here.             */
 } fs_bins;
 

@@ -31,7 +31,8 @@ KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges"
 class fs_config(ctypes.Structure):
     _fields_ = [("tile", ctypes.c_int32), ("z_near", ctypes.c_float), ("lowpass", ctypes.c_float),
                 ("alpha_min", ctypes.c_float), ("alpha_max", ctypes.c_float), ("T_min", ctypes.c_float),
-                ("bg", ctypes.c_float * 3), ("jclamp", ctypes.c_float), ("score_mode", ctypes.c_int32)]
+                ("bg", ctypes.c_float * 3), ("jclamp", ctypes.c_float), ("score_mode", ctypes.c_int32),
+                ("compact_box", ctypes.c_int32), ("cb_beta", ctypes.c_float)]
 
 
 class fs_camera(ctypes.Structure):
@@ -54,6 +55,8 @@ class fs_projected(ctypes.Structure):
 class fs_bins(ctypes.Structure):
     _fields_ = [("num_pairs", ctypes.c_int64), ("keys_sorted", ctypes.c_void_p), ("gauss_sorted", ctypes.c_void_p),
                 ("tile_ranges", ctypes.c_void_p), ("pair_offsets", ctypes.c_void_p),
+                ("num_records", ctypes.c_int64), ("record_offsets", ctypes.c_void_p),
+                ("record_counts", ctypes.c_void_p),
                 ("tile_order", ctypes.c_void_p), ("splats", ctypes.c_void_p)]
 
 

@@ -32,9 +32,11 @@ struct fs_ctx {
     ScratchBuf ranges;        // uint32 [tiles, 2]
     ScratchBuf pair_grad;     // float  [P, PAIR_REC] per-pair partial gradients of the backward pass
     ScratchBuf splats;        // float  [n, SPLAT_REC] packed projected splats (written by fs_bin_sort)
+    ScratchBuf rec_counts;    // uint32 [n] Compact Box: tiles in each Gaussian's box
+    ScratchBuf rec_offsets;   // uint32 [n] Compact Box: exclusive prefix sum of rec_counts
     ScratchBuf err_map;       // float  [H*W]
     ScratchBuf partial;       // double reduction partials
-    uint64_t* total_dev = nullptr;   // device: scan total
+    uint64_t* total_dev = nullptr;   // device: scan totals [2] (pairs, backward records)
     uint64_t* total_host = nullptr;  // pinned host copy
 
     // per-group event timing (measurement only)
@@ -151,6 +153,8 @@ CfgDev make_cfg(const fs_config& c)
     // conservative: for opacity <= 1, sigma*exp(power) < alpha_min whenever power < ln(alpha_min) - 0.01
     d.power_min = (float)(log((double)c.alpha_min) - 0.01);
     d.score_mode = c.score_mode;
+    d.compact_box = c.compact_box != 0;
+    d.cb_beta = c.cb_beta;
     return d;
 }
 
@@ -182,6 +186,8 @@ void fs_default_config(fs_config* cfg)
     cfg->bg[0] = cfg->bg[1] = cfg->bg[2] = 0.0f;
     cfg->jclamp = (float)1.3;
     cfg->score_mode = FS_SCORE_WEIGHT;
+    cfg->compact_box = 0;
+    cfg->cb_beta = 1.0f;
 }
 
 int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
@@ -192,7 +198,8 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     if (cfg) c = *cfg; else fs_default_config(&c);
     if (c.tile != TILE || !(c.alpha_min > 0.f) || !(c.alpha_min < c.alpha_max) || !(c.alpha_max < 1.f) ||
         !(c.T_min > 0.f) || !(c.T_min < 1.f) || !(c.lowpass >= 0.f) ||
-        (c.score_mode != FS_SCORE_WEIGHT && c.score_mode != FS_SCORE_ALPHA))
+        (c.score_mode != FS_SCORE_WEIGHT && c.score_mode != FS_SCORE_ALPHA) ||
+        (c.compact_box != 0 && c.compact_box != 1) || (c.compact_box && !(c.cb_beta > 0.f && c.cb_beta <= 1.f)))
         return FS_EINVAL;
     if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return FS_EHIP; }
     fs_ctx* ctx = new (std::nothrow) fs_ctx();
@@ -201,8 +208,8 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->cfg = c;
     ctx->err[0] = 0;
-    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), sizeof(uint64_t)) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 2 * sizeof(uint64_t)) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), 2 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         fs_destroy(ctx);
         return FS_EHIP;
@@ -217,7 +224,8 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
-                         &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->err_map, &ctx->partial};
+                         &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
+                         &ctx->err_map, &ctx->partial};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -261,17 +269,34 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
     FS_TRY(ensure(ctx, ctx->splats, (size_t)(n > 0 ? n : 1) * SPLAT_REC * sizeof(float), "splats"));
 
-    // a2: offsets and the pair count P (the one host read-back of the path)
+    // a2: offsets and the pair count P (the one host read-back of the path).  With the Compact Box the
+    // backward records are indexed by candidate tile, so the boxes' areas get a prefix sum of their own.
+    const bool cb = ctx->cfg.compact_box != 0;
+    const CfgDev cf = make_cfg(ctx->cfg);
     {
         ProfScope prof(ctx, FS_K_SCAN);
         FS_HIP(launch_exclusive_scan(st, proj ? proj->tiles_touched : nullptr, static_cast<uint32_t*>(ctx->offsets.ptr),
                                      n, ctx->scan_tmp.ptr, ctx->total_dev),
                "scan");
+        if (cb) {
+            FS_TRY(ensure(ctx, ctx->rec_counts, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record counts"));
+            FS_TRY(ensure(ctx, ctx->rec_offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record offsets"));
+            FS_HIP(launch_rect_area(st, n, proj ? proj->rect : nullptr, static_cast<uint32_t*>(ctx->rec_counts.ptr)),
+                   "k_rect_area");
+            FS_HIP(launch_exclusive_scan(st, static_cast<const uint32_t*>(ctx->rec_counts.ptr),
+                                         static_cast<uint32_t*>(ctx->rec_offsets.ptr), n, ctx->scan_tmp.ptr,
+                                         ctx->total_dev + 1),
+                   "scan");
+        }
     }
-    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
+    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, (cb ? 2 : 1) * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
+           "hipMemcpyAsync");
     FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
-    const uint64_t P = *ctx->total_host;
+    const uint64_t P = ctx->total_host[0];
+    const uint64_t NR = cb ? ctx->total_host[1] : P;
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
+    if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
+    if (cb) FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(NR ? NR : 1) * PAIR_REC * sizeof(float), "pair gradients"));
 
     const int64_t nb = radix_num_blocks((int64_t)P);
     for (int k = 0; k < 2; k++) {
@@ -288,9 +313,16 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
         // a3
         {
             ProfScope prof(ctx, FS_K_EMIT);
-            FS_HIP(launch_emit_pairs(st, n, *proj, static_cast<const uint32_t*>(ctx->offsets.ptr), cd.tiles_x, keys[0],
-                                     vals[0], static_cast<float*>(ctx->splats.ptr)),
-                   "k_emit_pairs");
+            if (cb)
+                FS_HIP(launch_emit_pairs_cb(st, n, *proj, cf, static_cast<const uint32_t*>(ctx->offsets.ptr),
+                                            static_cast<const uint32_t*>(ctx->rec_offsets.ptr), cd.tiles_x, (int64_t)P,
+                                            keys[0], vals[0], static_cast<float*>(ctx->splats.ptr),
+                                            static_cast<float*>(ctx->pair_grad.ptr)),
+                       "k_emit_pairs_cb");
+            else
+                FS_HIP(launch_emit_pairs(st, n, *proj, static_cast<const uint32_t*>(ctx->offsets.ptr), cd.tiles_x,
+                                         keys[0], vals[0], static_cast<float*>(ctx->splats.ptr)),
+                       "k_emit_pairs");
         }
         // a4: 32 depth bits + the tile bits are live
         ProfScope prof(ctx, FS_K_RADIX_SORT);
@@ -310,6 +342,9 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->gauss_sorted = vals[res];
     out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
     out->pair_offsets = static_cast<const uint32_t*>(ctx->offsets.ptr);
+    out->num_records = (int64_t)NR;
+    out->record_offsets = cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr) : out->pair_offsets;
+    out->record_counts = cb ? static_cast<const uint32_t*>(ctx->rec_counts.ptr) : nullptr;
     out->splats = ctx->splats.ptr;
     out->tile_order = static_cast<const uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles;
     return FS_OK;
@@ -364,9 +399,13 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
         return fail(ctx, FS_EINVAL, "fs_render_bwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
-    if (bins->num_pairs > 0 && (!bins->pair_offsets || !bins->splats))
-        return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without pair_offsets / splats");
-    FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_pairs ? bins->num_pairs : 1) * PAIR_REC * sizeof(float),
+    if (bins->num_pairs > 0 && (!bins->record_offsets || !bins->splats || bins->num_records < bins->num_pairs))
+        return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without record_offsets / splats");
+    // (with the Compact Box fs_bin_sort has already sized this buffer and zeroed the records of the
+    // candidate tiles that are no pairs; growing it here would lose them, and never happens)
+    if (bins->record_counts && (size_t)bins->num_records * PAIR_REC * sizeof(float) > ctx->pair_grad.cap)
+        return fail(ctx, FS_EINVAL, "fs_render_bwd: bins do not come from this context's last fs_bin_sort");
+    FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_records ? bins->num_records : 1) * PAIR_REC * sizeof(float),
                   "pair gradients"));
     float* pair_grad = static_cast<float*>(ctx->pair_grad.ptr);
     const CfgDev cf = make_cfg(ctx->cfg);
@@ -379,7 +418,8 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     }
     // a9: per-Gaussian sum of its records, then the chain through the projection
     ProfScope prof(ctx, FS_K_PREPROCESS_BWD);
-    FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, proj->tiles_touched, bins->pair_offsets,
+    FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, proj->tiles_touched,
+                                 bins->record_counts ? bins->record_counts : proj->tiles_touched, bins->record_offsets,
                                  pair_grad, *out),
            "k_preprocess_bwd");
     return FS_OK;

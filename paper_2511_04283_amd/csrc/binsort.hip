@@ -183,6 +183,110 @@ __global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __
     }
 }
 
+// Compact Box: tiles in each Gaussian's box (the candidates of the ellipse test).
+__global__ __launch_bounds__(256) void k_rect_area(int64_t n, const ushort4* __restrict__ rect,
+                                                   uint32_t* __restrict__ area)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const ushort4 r = rect[i];
+    area[i] = r.z > r.x && r.w > r.y ? (uint32_t)(r.z - r.x) * (uint32_t)(r.w - r.y) : 0u;
+}
+
+// Compact Box emission.  Same wave-cooperative walk as k_emit_pairs, but over the candidates (all tiles
+// of each box): the lane that takes a candidate runs the ellipse-tile test; a hit becomes a key at
+// offsets[owner] + (hits of the same Gaussian before it, in row-major order), a miss gets its gradient
+// record zeroed.  Hits of one Gaussian before a candidate = those of earlier rounds (kept by the owner
+// lane in `emitted`) + those on lower lanes of this round (one ballot, masked to the owner's lanes).
+__global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4* __restrict__ rect,
+                                                       const float* __restrict__ depth,
+                                                       const float2* __restrict__ mean2d,
+                                                       const float4* __restrict__ conic_opacity,
+                                                       const float* __restrict__ rgb, CfgDev cfg,
+                                                       const uint32_t* __restrict__ offsets,
+                                                       const uint32_t* __restrict__ rec_offsets, int tiles_x,
+                                                       uint32_t P, uint64_t* __restrict__ keys,
+                                                       uint32_t* __restrict__ vals,
+                                                       float4* __restrict__ splats, float4* __restrict__ pair_grad)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = i < n;
+    const uint32_t lane = lane_id();
+    const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
+    const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
+    const uint32_t cnt = w * h;                              // candidates
+    const uint32_t off = valid ? offsets[i] : 0u;           // first pair
+    const uint32_t roff = valid ? rec_offsets[i] : 0u;      // first gradient record
+    const uint32_t dbits = cnt ? __float_as_uint(depth[i]) : 0u;
+    float mx = 0.f, my = 0.f, A = 1.f, B = 0.f, C = 1.f, Q = 0.f;
+    if (cnt) {
+        const float2 m = mean2d[i];
+        const float4 co = conic_opacity[i];
+        mx = m.x; my = m.y; A = co.x; B = co.y; C = co.z;
+        Q = cb_threshold(co.w, cfg);
+        float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
+        rec[0] = make_float4(m.x, m.y, co.x, co.y);
+        rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
+        rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(roff), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
+                             __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
+    }
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    const uint32_t excl = inc - cnt;
+    const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
+    const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
+    uint32_t emitted = 0;                                    // hits of this lane's own Gaussian so far
+    for (uint32_t j0 = 0; j0 < total; j0 += 64) {
+        const bool live = j0 + lane < total;
+        const uint32_t j = min(j0 + lane, total - 1);
+        uint32_t s = 0;
+#pragma unroll
+        for (uint32_t step = 32; step >= 1; step >>= 1) {
+            const uint32_t t = s + step;
+            const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
+            s = e <= j ? t : s;
+        }
+        const uint32_t oexcl = (uint32_t)__shfl((int)excl, (int)s, 64);
+        const uint32_t k = j - oexcl;
+        const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
+        const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
+        const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
+        const uint32_t ooff = (uint32_t)__shfl((int)off, (int)s, 64);
+        const uint32_t oroff = (uint32_t)__shfl((int)roff, (int)s, 64);
+        const uint32_t oem = (uint32_t)__shfl((int)emitted, (int)s, 64);
+        const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
+        const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
+        const float oQ = __shfl(Q, (int)s, 64);
+        uint32_t row = (uint32_t)((float)k / (float)ow);
+        while (row * ow > k) row--;
+        while ((row + 1) * ow <= k) row++;
+        const uint32_t col = k - row * ow;
+        const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
+        const bool hit = live && cb_tile_hit(omx, omy, oA, oB, oC, oQ, (int)tx, (int)ty);
+        const uint64_t hb = __ballot(hit);
+        // lanes of this round that belong to the same Gaussian and come before this one
+        const uint32_t seg0 = oexcl > j0 ? oexcl - j0 : 0u;                 // first lane of the owner's run
+        const uint64_t below = (lane ? (~0ull >> (64 - lane)) : 0ull) & (~0ull << seg0);
+        if (hit) {
+            const size_t o = (size_t)ooff + oem + (uint32_t)__popcll(hb & below);
+            if (o < P) {   // always true when tiles_touched came from k_preprocess with the same configuration
+                keys[o] = ((uint64_t)(ty * (uint32_t)tiles_x + tx) << 32) | od;
+                vals[o] = (uint32_t)(i - lane + s);
+            }
+        } else if (live) {
+            float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            g[0] = z; g[1] = z; g[2] = z;
+        }
+        // each owner adds the hits of its own run in this round
+        const uint32_t a0 = excl > j0 ? excl - j0 : 0u;                      // run of this lane's Gaussian: [a0, a1)
+        const uint32_t a1 = inc > j0 ? min(inc - j0, 64u) : 0u;
+        if (a1 > a0) {
+            const uint64_t mine = (a1 >= 64 ? ~0ull : ((1ull << a1) - 1ull)) & (~0ull << a0);
+            emitted += (uint32_t)__popcll(hb & mine);
+        }
+    }
+}
+
 // ---- radix sort -------------------------------------------------------------------------
 // One pass ranks RADIX_BLOCK_KEYS keys per workgroup on a digit of up to RADIX_BITS bits (the live key
 // bits are split into the fewest such digits, of equal width).  Wave w of the workgroup owns the
@@ -347,6 +451,28 @@ hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const fs_projected& proj
                        reinterpret_cast<const ushort4*>(proj.rect), proj.depth,
                        reinterpret_cast<const float2*>(proj.mean2d), reinterpret_cast<const float4*>(proj.conic_opacity),
                        proj.rgb, offsets, tiles_x, keys, vals, reinterpret_cast<float4*>(splats));
+    return hipGetLastError();
+}
+
+hipError_t launch_rect_area(hipStream_t st, int64_t n, const uint16_t* rect, uint32_t* rec_counts)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_rect_area, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n,
+                       reinterpret_cast<const ushort4*>(rect), rec_counts);
+    return hipGetLastError();
+}
+
+hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
+                                const uint32_t* offsets, const uint32_t* rec_offsets, int tiles_x, int64_t P,
+                                uint64_t* keys, uint32_t* vals, float* splats, float* pair_grad)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_emit_pairs_cb, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n,
+                       reinterpret_cast<const ushort4*>(proj.rect), proj.depth,
+                       reinterpret_cast<const float2*>(proj.mean2d), reinterpret_cast<const float4*>(proj.conic_opacity),
+                       proj.rgb, cfg, offsets, rec_offsets, tiles_x, (uint32_t)P, keys, vals,
+                       reinterpret_cast<float4*>(splats),
+                       reinterpret_cast<float4*>(pair_grad));
     return hipGetLastError();
 }
 

@@ -26,16 +26,83 @@ struct CfgDev {
     float jclamp;
     float power_min;  // exponents below this cannot reach alpha_min for opacity <= 1 (conservative)
     int score_mode;
+    int compact_box;  // pairs from the ellipse-tile test instead of the 3-sigma square
+    float cb_beta;
 };
+
+// ---- Compact Box (FastGS Sec. 4.4 and its supplement) ------------------------------------------
+// Support of a Gaussian: (p - mu_2D)^T Sigma_2D^-1 (p - mu_2D) <= Q, Q = beta * 2 ln(sigma / tau_alpha)
+// with tau_alpha = alpha_min.  These three functions decide integers (pair counts, which keys exist),
+// so their fp32 operation order is fixed: plain IEEE operations as written, fused multiply-adds only
+// where spelled out.
+
+// ln(x) for x > 0: x = m 2^e, m in [sqrt(1/2), sqrt(2)); s = (m-1)/(m+1); z = s^2;
+// ln m = 2 s (1 + z/3 + z^2/5 + z^3/7 + z^4/9) by Horner with fmaf; ln x = fmaf(e, ln 2, ln m).
+__device__ __forceinline__ float log_c(float x)
+{
+    int e;
+    float m = frexpf(x, &e);
+    if (m < 0x1.6a09e6p-1f) { m = m + m; e = e - 1; }
+    const float s = (m - 1.0f) / (m + 1.0f);
+    const float z = s * s;
+    float p = 0x1.c71c72p-4f;
+    p = __builtin_fmaf(p, z, 0x1.24924ap-3f);
+    p = __builtin_fmaf(p, z, 0x1.99999ap-3f);
+    p = __builtin_fmaf(p, z, 0x1.555556p-2f);
+    p = __builtin_fmaf(p, z, 1.0f);
+    const float lnm = (s + s) * p;
+    return __builtin_fmaf((float)e, 0x1.62e43p-1f, lnm);
+}
+
+// Q of a Gaussian of opacity sigma; 0 when it can never reach alpha_min.
+__device__ __forceinline__ float cb_threshold(float sigma, const CfgDev& cfg)
+{
+    const float ratio = sigma / cfg.alpha_min;
+    if (!(ratio > 1.0f)) return 0.0f;
+    return cfg.cb_beta * (2.0f * log_c(ratio));
+}
+
+// Does the closed rectangle of tile (tx, ty) meet the ellipse?  The quadratic form is convex with its
+// minimum at mu_2D: the minimum over the rectangle is 0 when mu_2D is inside, and otherwise lies on the
+// vertical and/or horizontal edge that faces mu_2D, where it is a 1-D quadratic with a clamped minimiser.
+__device__ __forceinline__ bool cb_tile_hit(float mx, float my, float A, float B, float C, float Q, int tx, int ty)
+{
+    const float X0 = (float)(tx * TILE), X1 = (float)(tx * TILE + TILE);
+    const float Y0 = (float)(ty * TILE), Y1 = (float)(ty * TILE + TILE);
+    const float dxl = X0 - mx, dxr = X1 - mx, dyt = Y0 - my, dyb = Y1 - my;
+    const bool in_x = dxl <= 0.0f && dxr >= 0.0f;
+    const bool in_y = dyt <= 0.0f && dyb >= 0.0f;
+    if (in_x && in_y) return true;
+    const float B2 = B + B;
+    bool have = false;
+    float qmin = 0.0f;
+    if (!in_x) {
+        const float ex = dxl > 0.0f ? dxl : dxr;
+        float dys = -(B * ex) / C;
+        dys = fminf(fmaxf(dys, dyt), dyb);
+        qmin = __builtin_fmaf(ex, __builtin_fmaf(B2, dys, A * ex), (C * dys) * dys);
+        have = true;
+    }
+    if (!in_y) {
+        const float ey = dyt > 0.0f ? dyt : dyb;
+        float dxs = -(B * ey) / A;
+        dxs = fminf(fmaxf(dxs, dxl), dxr);
+        const float q = __builtin_fmaf(dxs, __builtin_fmaf(B2, ey, A * dxs), (C * ey) * ey);
+        if (!have || q < qmin) qmin = q;
+    }
+    return qmin <= Q;
+}
 
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) ------------------------
 hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                              const CfgDev& cfg, const fs_projected& out);
-// pair_grad: [P] records of PAIR_REC floats (see render.hip); offsets/touched as in fs_bins/fs_projected
+// pair_grad: records of PAIR_REC floats (see render.hip); Gaussian i owns records
+// [rec_offsets[i], rec_offsets[i] + rec_counts[i]); touched as in fs_projected (0 = not visible)
 constexpr int PAIR_REC = 12;
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                                  const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
-                                 const uint32_t* offsets, const float* pair_grad, const fs_grads& out);
+                                 const uint32_t* rec_counts, const uint32_t* rec_offsets, const float* pair_grad,
+                                 const fs_grads& out);
 
 // exclusive scan of n uint32 values; total (uint64) written to *total_dev. tmp: >= scan_tmp_bytes(n).
 size_t scan_tmp_bytes(int64_t n);
@@ -46,6 +113,14 @@ hipError_t launch_exclusive_scan(hipStream_t st, const uint32_t* in, uint32_t* o
 constexpr int SPLAT_REC = 16;
 hipError_t launch_emit_pairs(hipStream_t st, int64_t n, const fs_projected& proj, const uint32_t* offsets,
                              int tiles_x, uint64_t* keys, uint32_t* vals, float* splats);
+// Compact Box: rec_counts[i] = tiles in Gaussian i's box (the candidates of the ellipse test)
+hipError_t launch_rect_area(hipStream_t st, int64_t n, const uint16_t* rect, uint32_t* rec_counts);
+// Compact Box emission: one key per candidate tile that meets the ellipse, at offsets[i] + its rank among
+// the Gaussian's hits; the gradient record of every candidate that misses (rec_offsets[i] + row-major
+// place in the box) is zeroed, since no render workgroup will ever write it.
+hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
+                                const uint32_t* offsets, const uint32_t* rec_offsets, int tiles_x, int64_t P,
+                                uint64_t* keys, uint32_t* vals, float* splats, float* pair_grad);
 
 constexpr int RADIX_BLOCK_KEYS = 2048;  // keys ranked by one workgroup per pass
 constexpr int RADIX_BITS = 9;            // widest digit

@@ -63,11 +63,14 @@ struct Splat {
     float s00, s01, s02, s11, s12, s22;  // Sigma_3D (symmetric)
     float a, b, c, det;
     float mx, my, radius;
+    float Q;             // Compact Box threshold
     int x0, y0, x1, y1;
 };
 
+// `sigma` (the opacity) only matters with the Compact Box, whose box depends on it.  With the Compact
+// Box, s.visible still has to be and-ed with "some tile of the box meets the ellipse" by the caller.
 __device__ __forceinline__ void project(const float* __restrict__ means, const float* __restrict__ scales,
-                                        const float* __restrict__ quats, int64_t i, const CamDev& cam,
+                                        const float* __restrict__ quats, float sigma, int64_t i, const CamDev& cam,
                                         const CfgDev& cfg, Splat& s)
 {
     s.visible = false;
@@ -138,19 +141,30 @@ __device__ __forceinline__ void project(const float* __restrict__ means, const f
     s.det = s.a * s.c - s.b * s.b;
     if (!(s.det > 0.0f)) return;
 
-    const float mid = 0.5f * (s.a + s.c);
-    const float hd = 0.5f * (s.a - s.c);
-    const float lam = mid + sqrtf(hd * hd + s.b * s.b);
-    s.radius = ceilf(3.0f * sqrtf(lam));
     s.mx = cam.fx * s.txz + cam.cx;
     s.my = cam.fy * s.tyz + cam.cy;
-    if (!(s.radius < 1e6f) || !(fabsf(s.mx) < 1e7f) || !(fabsf(s.my) < 1e7f)) return;
+    float hx, hy;   // half-widths of the box round mu_2D
+    if (!cfg.compact_box) {
+        const float mid = 0.5f * (s.a + s.c);
+        const float hd = 0.5f * (s.a - s.c);
+        const float lam = mid + sqrtf(hd * hd + s.b * s.b);
+        s.radius = ceilf(3.0f * sqrtf(lam));
+        hx = hy = s.radius;
+    } else {
+        // the ellipse q <= Q spans sqrt(Q Sigma_xx) horizontally and sqrt(Q Sigma_yy) vertically
+        s.Q = cb_threshold(sigma, cfg);
+        if (!(s.Q > 0.0f)) return;
+        hx = sqrtf(s.Q * s.a);
+        hy = sqrtf(s.Q * s.c);
+        s.radius = ceilf(hx > hy ? hx : hy);
+    }
+    if (!(hx < 1e6f) || !(hy < 1e6f) || !(fabsf(s.mx) < 1e7f) || !(fabsf(s.my) < 1e7f)) return;
 
     const float it = 1.0f / (float)TILE;
-    const float fx0 = floorf((s.mx - s.radius) * it);
-    const float fy0 = floorf((s.my - s.radius) * it);
-    const float fx1 = floorf((s.mx + s.radius) * it) + 1.0f;
-    const float fy1 = floorf((s.my + s.radius) * it) + 1.0f;
+    const float fx0 = floorf((s.mx - hx) * it);
+    const float fy0 = floorf((s.my - hy) * it);
+    const float fx1 = floorf((s.mx + hx) * it) + 1.0f;
+    const float fy1 = floorf((s.my + hy) * it) + 1.0f;
     const float TXf = (float)cam.tiles_x, TYf = (float)cam.tiles_y;
     s.x0 = (int)fminf(fmaxf(fx0, 0.0f), TXf);
     s.y0 = (int)fminf(fmaxf(fy0, 0.0f), TYf);
@@ -188,7 +202,19 @@ __global__ __launch_bounds__(256) void k_preprocess(int64_t n, const float* __re
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     Splat s;
-    project(means, scales, quats, i, cam, cfg, s);
+    project(means, scales, quats, opac[i], i, cam, cfg, s);
+    uint32_t hits = 0;
+    if (s.visible) {
+        if (!cfg.compact_box) {
+            hits = (uint32_t)((s.x1 - s.x0) * (s.y1 - s.y0));
+        } else {
+            const float idet = 1.0f / s.det;
+            const float A = s.c * idet, B = -s.b * idet, C = s.a * idet;
+            for (int ty = s.y0; ty < s.y1; ty++)
+                for (int tx = s.x0; tx < s.x1; tx++) hits += cb_tile_hit(s.mx, s.my, A, B, C, s.Q, tx, ty) ? 1u : 0u;
+            s.visible = hits > 0;
+        }
+    }
     float2 m2 = make_float2(0.f, 0.f);
     float4 co = make_float4(0.f, 0.f, 0.f, 0.f);
     float col[3] = {0.f, 0.f, 0.f};
@@ -202,7 +228,7 @@ __global__ __launch_bounds__(256) void k_preprocess(int64_t n, const float* __re
         m2 = make_float2(s.mx, s.my);
         dep = s.tz;
         rc = make_ushort4((unsigned short)s.x0, (unsigned short)s.y0, (unsigned short)s.x1, (unsigned short)s.y1);
-        tt = (uint32_t)((s.x1 - s.x0) * (s.y1 - s.y0));
+        tt = hits;
         float d[3], len;
         view_dir(means, i, cam, d, len);
         constexpr int K = (DEG + 1) * (DEG + 1);
@@ -269,8 +295,9 @@ __device__ __forceinline__ void sh_dir_grad(float x, float y, float z, const flo
 template <int DEG>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(
     int64_t n, const float* __restrict__ means, const float* __restrict__ scales, const float* __restrict__ quats,
-    const float* __restrict__ sh, CamDev cam, CfgDev cfg, const uint8_t* __restrict__ clamped,
-    const uint32_t* __restrict__ touched, const uint32_t* __restrict__ offsets,
+    const float* __restrict__ opac, const float* __restrict__ sh, CamDev cam, CfgDev cfg,
+    const uint8_t* __restrict__ clamped, const uint32_t* __restrict__ touched,
+    const uint32_t* __restrict__ rec_counts, const uint32_t* __restrict__ offsets,
     const float4* __restrict__ pair_grad, float* __restrict__ d_means, float* __restrict__ d_scales,
     float* __restrict__ d_quats, float* __restrict__ d_sh, float* __restrict__ d_opac,
     float* __restrict__ d_mean2d, float* __restrict__ d_conic /* may be null */,
@@ -294,7 +321,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     float rc = 0.f;
     {
         const uint32_t off = in_range ? offsets[i] : 0u;
-        const uint32_t cnt = in_range ? touched[i] : 0u;
+        const uint32_t cnt = in_range && touched[i] ? rec_counts[i] : 0u;
         uint32_t lo_all = cnt ? off : 0xffffffffu, hi_all = cnt ? off + cnt : 0u;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -365,7 +392,10 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
 
     Splat s;
     s.visible = false;
-    if (in_range) project(means, scales, quats, i, cam, cfg, s);
+    if (in_range) {
+        project(means, scales, quats, opac[i], i, cam, cfg, s);
+        s.visible = s.visible && touched[i] > 0;   // Compact Box: a box none of whose tiles meets the ellipse
+    }
     if (in_range && !s.visible) {
         for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
         *reinterpret_cast<float4*>(d_quats + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -527,14 +557,16 @@ hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussi
 
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                                  const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
-                                 const uint32_t* offsets, const float* pair_grad, const fs_grads& o)
+                                 const uint32_t* rec_counts, const uint32_t* rec_offsets, const float* pair_grad,
+                                 const fs_grads& o)
 {
     if (n == 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
 #define FS_LAUNCH(D)                                                                                      \
-    hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.sh, cam, cfg, \
-                       clamped, touched, offsets, reinterpret_cast<const float4*>(pair_grad), o.dmeans, o.dscales,  \
-                       o.dquats, o.dsh, o.dopacities, o.dmean2d, o.dconic, o.drgb)
+    hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.opacities, g.sh, \
+                       cam, cfg, clamped, touched, rec_counts, rec_offsets,                                       \
+                       reinterpret_cast<const float4*>(pair_grad), o.dmeans, o.dscales, o.dquats, o.dsh,          \
+                       o.dopacities, o.dmean2d, o.dconic, o.drgb)
     switch (deg) {
         case 0: FS_LAUNCH(0); break;
         case 1: FS_LAUNCH(1); break;

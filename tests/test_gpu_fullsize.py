@@ -4,7 +4,7 @@ routines on disjoint tile subsets to keep the wall time of the test suite reason
 import numpy as np
 import pytest
 
-from oracle import Oracle
+from oracle import Config, Oracle
 from paper_2511_04283_amd import scenes
 from gpu_common import assert_grads_close, gpu_pipeline
 
@@ -75,6 +75,22 @@ def test_config3_full_the_benchmark_workload(ctx, orc32):
     g = gpu_pipeline(ctx, sc, cam, target=tgt)
     r = _oracle_full(orc32, sc, cam, tgt)
     assert r["bins"].num_pairs == 1357789
+    _check(g, r)
+
+
+def test_config3_full_compact_box():
+    """The benchmark workload with the Compact Box: fewer pairs, everything else to the same bar."""
+    from paper_2511_04283_amd import binding as B
+    sc = scenes.make_scene(3)
+    cam = sc.cameras[0]
+    tgt = scenes.target_image(3, 0, cam)
+    cfg = B.default_config()
+    cfg.compact_box = 1
+    c = B.Context("cuda:0", cfg)
+    g = gpu_pipeline(c, sc, cam, target=tgt)
+    c.close()
+    r = _oracle_full(Oracle(np.float32, Config(compact_box=True)), sc, cam, tgt)
+    assert 0 < r["bins"].num_pairs < 1357789
     _check(g, r)
 
 
