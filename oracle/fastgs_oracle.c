@@ -181,3 +181,102 @@ void orc_tile_ranges(uint64_t P, const uint64_t *keys_sorted, int num_tiles, uin
         if (i + 1 == P || (uint32_t)(keys_sorted[i + 1] >> 32) != t) ranges[2 * t + 1] = (uint32_t)(i + 1);
     }
 }
+
+/* ------------------------------------------------------------------------------------- */
+/* Photometric loss of Sec. 4.3 / Sec. 4.5:  E = (1 - lambda) L1 + lambda (1 - SSIM).
+ * The paper cites the structural-similarity index without restating it; the reading taken is
+ * the usual one for Gaussian-splatting losses: per channel, local statistics under an 11x11
+ * Gaussian window (standard deviation 1.5 px, normalised to sum 1, the outer product of two
+ * 11-tap windows), the image continued by zeros outside its border, C1 = 0.01^2, C2 = 0.03^2
+ * (dynamic range 1), and the mean of the SSIM map over all channels and pixels.
+ * Everything here is double precision and written as the plain 121-tap definition.            */
+
+#define SSIM_R 5
+static void ssim_window(double w[2 * SSIM_R + 1])
+{
+    double s = 0;
+    for (int k = -SSIM_R; k <= SSIM_R; k++) { w[k + SSIM_R] = exp(-(double)(k * k) / (2.0 * 1.5 * 1.5)); s += w[k + SSIM_R]; }
+    for (int k = 0; k <= 2 * SSIM_R; k++) w[k] /= s;
+}
+
+/* out(v,u) = sum_{i,j} w_i w_j in(v+i, u+j), terms outside the plane dropped */
+static void window_sum(int H, int W, const double *in, const double w[2 * SSIM_R + 1], double *out)
+{
+    for (int v = 0; v < H; v++)
+        for (int u = 0; u < W; u++) {
+            double s = 0;
+            for (int i = -SSIM_R; i <= SSIM_R; i++) {
+                if (v + i < 0 || v + i >= H) continue;
+                for (int j = -SSIM_R; j <= SSIM_R; j++) {
+                    if (u + j < 0 || u + j >= W) continue;
+                    s += w[i + SSIM_R] * w[j + SSIM_R] * in[(size_t)(v + i) * W + (u + j)];
+                }
+            }
+            out[(size_t)v * W + u] = s;
+        }
+}
+
+/* SSIM map [C,H,W] of x against y, its mean, and (if grad != NULL) d mean / d x.
+ * With mu1 = <x>, mu2 = <y>, e11 = <x^2>, e22 = <y^2>, e12 = <x y> (window sums):
+ *   s1 = e11 - mu1^2, s2 = e22 - mu2^2, s12 = e12 - mu1 mu2,
+ *   ssim = (2 mu1 mu2 + C1)(2 s12 + C2) / ((mu1^2 + mu2^2 + C1)(s1 + s2 + C2)).
+ * The gradient follows from the chain rule through (mu1, e11, e12), each a window sum of x, x^2, x y. */
+double orc_ssim(int C, int H, int W, const double *x, const double *y, double *map, double *grad)
+{
+    const double C1 = 0.01 * 0.01, C2 = 0.03 * 0.03;
+    double w[2 * SSIM_R + 1];
+    ssim_window(w);
+    size_t n = (size_t)H * W;
+    double *t = malloc(sizeof(double) * n * 9);
+    double *xx = t, *yy = t + n, *xy = t + 2 * n, *mu1 = t + 3 * n, *mu2 = t + 4 * n, *e11 = t + 5 * n,
+           *e22 = t + 6 * n, *e12 = t + 7 * n, *tmp = t + 8 * n;
+    double total = 0;
+    for (int c = 0; c < C; c++) {
+        const double *xc = x + c * n, *yc = y + c * n;
+        for (size_t p = 0; p < n; p++) { xx[p] = xc[p] * xc[p]; yy[p] = yc[p] * yc[p]; xy[p] = xc[p] * yc[p]; }
+        window_sum(H, W, xc, w, mu1);
+        window_sum(H, W, yc, w, mu2);
+        window_sum(H, W, xx, w, e11);
+        window_sum(H, W, yy, w, e22);
+        window_sum(H, W, xy, w, e12);
+        /* reuse xx, yy, xy for the three derivative maps */
+        for (size_t p = 0; p < n; p++) {
+            double m1 = mu1[p], m2 = mu2[p];
+            double s1 = e11[p] - m1 * m1, s2 = e22[p] - m2 * m2, s12 = e12[p] - m1 * m2;
+            double A = 2 * m1 * m2 + C1, B = 2 * s12 + C2, Cq = m1 * m1 + m2 * m2 + C1, D = s1 + s2 + C2;
+            double s = (A * B) / (Cq * D);
+            if (map) map[c * n + p] = s;
+            total += s;
+            /* d ssim / d mu1, / d e11, / d e12 with the other window sums held fixed */
+            xx[p] = (2 * m2 * (B - A) - s * 2 * m1 * (D - Cq)) / (Cq * D);
+            yy[p] = -s / D;
+            xy[p] = 2 * A / (Cq * D);
+        }
+        if (grad) {
+            double inv = 1.0 / ((double)C * (double)n);
+            window_sum(H, W, xx, w, tmp);
+            for (size_t p = 0; p < n; p++) grad[c * n + p] = tmp[p] * inv;
+            window_sum(H, W, yy, w, tmp);
+            for (size_t p = 0; p < n; p++) grad[c * n + p] += 2 * xc[p] * tmp[p] * inv;
+            window_sum(H, W, xy, w, tmp);
+            for (size_t p = 0; p < n; p++) grad[c * n + p] += yc[p] * tmp[p] * inv;
+        }
+    }
+    free(t);
+    return total / ((double)C * (double)n);
+}
+
+/* VCP pruning score (Sec. 4.3): s_p = N( sum_j count_i^j * E_photo^j ), N = min-max normalisation
+ * over the Gaussians (all zeros when every sum is equal).  counts: [K,n] row-major.            */
+void orc_prune_score(int K, int64_t n, const int32_t *counts, const double *E, double *raw, double *score)
+{
+    double lo = 0, hi = 0;
+    for (int64_t i = 0; i < n; i++) {
+        double s = 0;
+        for (int j = 0; j < K; j++) s += (double)counts[(size_t)j * n + i] * E[j];
+        raw[i] = s;
+        if (i == 0 || s < lo) lo = s;
+        if (i == 0 || s > hi) hi = s;
+    }
+    for (int64_t i = 0; i < n; i++) score[i] = hi > lo ? (raw[i] - lo) / (hi - lo) : 0.0;
+}
