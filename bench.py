@@ -20,7 +20,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Algorithmic work per unit (DESIGN.md section 7): flops per examined list entry ("evaluation")
+# Algorithmic work per unit: flops per examined list entry ("evaluation")
 # and per blended (Gaussian, pixel) pair, for the forward and backward compositing kernels.
 FWD_FLOPS_PER_EVAL = 11     # dx, dy, q (2 mul + 2 fma + mul), -0.5*q
 FWD_FLOPS_PER_BLEND = 26    # exp (mul, rint, sub, 5 fma, ldexp) 14; alpha 2; T 2; w 1; colour 3 fma 6; + min
