@@ -340,3 +340,58 @@ class Oracle:
         g["conic"] = d2[1]
         g["rgb"] = d2[3]
         return g
+
+
+# ---- photometric loss (Sec. 4.3, Sec. 4.5) and pruning score (Sec. 4.3) --------------------------
+def ssim(image, target, want_grad=False, threads=1):
+    """Mean SSIM of `image` against `target` ([C,H,W]), the SSIM map, and d mean / d image (or None).
+    Double precision whatever the inputs' type.  threads > 1 runs the channels side by side (test
+    harness convenience; each channel is the same single-threaded routine)."""
+    L = lib()
+    L.orc_ssim.restype = ctypes.c_double
+    x = np.ascontiguousarray(image, dtype=np.float64)
+    y = np.ascontiguousarray(target, dtype=np.float64)
+    C, H, W = x.shape
+    smap = np.zeros((C, H, W))
+    grad = np.zeros((C, H, W)) if want_grad else None
+    if threads <= 1 or C == 1:
+        mean = float(L.orc_ssim(ctypes.c_int(C), ctypes.c_int(H), ctypes.c_int(W), _p(x), _p(y), _p(smap), _p(grad)))
+        return mean, smap, grad
+    import threading
+    means = [0.0] * C
+
+    def work(c):
+        g = grad[c:c + 1] if want_grad else None
+        means[c] = float(L.orc_ssim(ctypes.c_int(1), ctypes.c_int(H), ctypes.c_int(W), _p(x[c:c + 1]), _p(y[c:c + 1]),
+                                    _p(smap[c:c + 1]), _p(g)))
+    ts = [threading.Thread(target=work, args=(c,)) for c in range(C)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    if want_grad:
+        grad /= C
+    return float(sum(means) / C), smap, grad
+
+
+def photometric(image, target, lam=0.2, want_grad=True, threads=1):
+    """E = (1 - lam) * L1 + lam * (1 - SSIM) over the whole image, and dE / d image."""
+    x = np.ascontiguousarray(image, dtype=np.float64)
+    y = np.ascontiguousarray(target, dtype=np.float64)
+    l1 = float(np.abs(x - y).mean())
+    s, _, g = ssim(x, y, want_grad=want_grad, threads=threads)
+    out = dict(L1=l1, ssim=s, E=(1.0 - lam) * l1 + lam * (1.0 - s))
+    if want_grad:
+        out["grad"] = (1.0 - lam) * np.sign(x - y) / x.size - lam * g
+    return out
+
+
+def prune_score(counts, E):
+    """s_p = N(sum_j counts[j, i] * E[j]) with N the min-max normalisation over the Gaussians;
+    returns (raw sums, s_p)."""
+    L = lib()
+    c = np.ascontiguousarray(counts, dtype=np.int32)
+    K, n = c.shape
+    e = np.ascontiguousarray(E, dtype=np.float64)
+    raw = np.zeros(n)
+    sp = np.zeros(n)
+    L.orc_prune_score(ctypes.c_int(K), ctypes.c_int64(n), _p(c), _p(e), _p(raw), _p(sp))
+    return raw, sp
