@@ -11,6 +11,9 @@
  *   fs_error_mask        per-pixel L1 error map and high-error mask             (Sec. 4.2, first three equations)
  *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
  *                        one view per call                                      (Sec. 4.2, Eq. for s_d)
+ *   fs_photo_loss        E = (1-lambda) L1 + lambda (1 - SSIM) and dE/dC        (Sec. 4.3 E_photo; Sec. 4.5 Eq. for L)
+ *   fs_prune_score_accumulate / fs_prune_score_normalize
+ *                        s_p = N(sum over views of count * E_photo)             (Sec. 4.3, Eq. for s_p)
  *
  * General rules
  *   - Every pointer inside the structs below is a DEVICE pointer (HIP, the ctx's device) owned
@@ -186,6 +189,28 @@ int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bi
                         const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
                         int32_t *counts);
 
+/* Photometric loss of one view (Sec. 4.3: E_photo; Sec. 4.5: the training loss has the same form):
+ *   E = (1 - lambda) * L1 + lambda * (1 - SSIM),  L1 = mean |image - target| over the 3*H*W values.
+ * SSIM (the paper cites the index without restating it): per channel, local means / variances /
+ * covariance under an 11x11 Gaussian window (standard deviation 1.5 px, normalised to sum 1), the
+ * images continued by zeros beyond their border, C1 = 0.01^2, C2 = 0.03^2; mean of the SSIM map over
+ * channels and pixels.  image, target: [3,H,W] planar.  dL_dimage [3,H,W] (may be NULL) receives
+ * dE/d image, OVERWRITTEN.  out3 (device pointer to three doubles, may be NULL) receives
+ * {L1, SSIM, E}.  The ctx keeps 9*H*W floats of scratch when the gradient is requested.
+ * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP. */
+int fs_photo_loss(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
+                  float lambda, float *dL_dimage, double *out3);
+
+/* Pruning score (Sec. 4.3, Eq. for s_p).  Per view j, after fs_score_accumulate has filled that view's
+ * own counts_view [n] (zeroed before the call) and fs_photo_loss has left E^j on the device:
+ *   acc[i] += counts_view[i] * (*E)          acc: [n] doubles, caller-owned, zeroed before the first view.
+ * E points at ONE device double (e.g. out3 + 2 of fs_photo_loss). */
+int fs_prune_score_accumulate(fs_ctx *ctx, const int32_t *counts_view, int64_t n, const double *E, double *acc);
+
+/* s_p[i] = (acc[i] - min acc) / (max acc - min acc): the min-max normalisation N over the Gaussians;
+ * all zeros when max = min.  s_p: [n] floats. */
+int fs_prune_score_normalize(fs_ctx *ctx, const double *acc, int64_t n, float *s_p);
+
 /* ---- measurement helpers (no part of the method) ------------------------------------------
  * Per-kernel timing with HIP events recorded on the ctx stream around the launches of the
  * selected kernel groups.  fs_profile_enable(mask) clears the accumulated times and selects the
@@ -200,7 +225,7 @@ enum {
     FS_K_RANGES,         /* fill + k_tile_ranges                          */
     FS_K_RENDER_FWD,     /* k_render_fwd                                  */
     FS_K_L1,             /* k_l1_grad (+ final reduction)                 */
-    FS_K_FILL,           /* zeroing of the gradient accumulators          */
+    FS_K_PHOTO,          /* the kernels of fs_photo_loss                  */
     FS_K_RENDER_BWD,     /* k_render_bwd                                  */
     FS_K_PREPROCESS_BWD, /* k_preprocess_bwd                              */
     FS_K_ERR_MASK,       /* the kernels of fs_error_mask                  */

@@ -23,8 +23,9 @@ _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
            "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
+           "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_profile_enable", "fs_profile_read")
-KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "fill",
+KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
                  "render_bwd", "preprocess_bwd", "error_mask", "score")
 
 
@@ -94,6 +95,9 @@ def load_library() -> ctypes.CDLL:
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
+    lib.fs_photo_loss.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
+    lib.fs_prune_score_accumulate.argtypes = [vp, vp, i64, vp, vp]
+    lib.fs_prune_score_normalize.argtypes = [vp, vp, i64, vp]
     lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
     for name in EXPORTS:
@@ -340,6 +344,33 @@ class Context:
         self._check(self.lib.fs_error_mask(self.handle, _ptr(image), _ptr(target), H, W, int(rule), float(k), _ptr(mask),
                                            _ptr(threshold_out)), "fs_error_mask")
         return mask, threshold_out
+
+    def fs_photo_loss(self, image, target, lam=0.2, dL_dimage=None, out3=None, want_grad=True):
+        """Returns (out3, dL_dimage): out3 = device doubles {L1, SSIM, E}; dL_dimage is None if not wanted."""
+        _, H, W = image.shape
+        if out3 is None:
+            out3 = torch.zeros(3, dtype=torch.float64, device=self.device)
+        if dL_dimage is None and want_grad:
+            dL_dimage = torch.empty_like(image)
+        self._check(self.lib.fs_photo_loss(self.handle, _ptr(image), _ptr(target), H, W, float(lam),
+                                           _ptr(dL_dimage) if dL_dimage is not None else None, _ptr(out3)), "fs_photo_loss")
+        return out3, dL_dimage
+
+    def fs_prune_score_accumulate(self, counts_view, E, acc):
+        n = int(counts_view.shape[0])
+        _chk(counts_view, torch.int32, (n,), "counts_view")
+        _chk(acc, torch.float64, (n,), "acc")
+        assert E.dtype == torch.float64 and E.numel() >= 1
+        self._check(self.lib.fs_prune_score_accumulate(self.handle, _ptr(counts_view), n, _ptr(E), _ptr(acc)),
+                    "fs_prune_score_accumulate")
+        return acc
+
+    def fs_prune_score_normalize(self, acc, s_p=None):
+        n = int(acc.shape[0])
+        if s_p is None:
+            s_p = torch.empty(n, dtype=torch.float32, device=self.device)
+        self._check(self.lib.fs_prune_score_normalize(self.handle, _ptr(acc), n, _ptr(s_p)), "fs_prune_score_normalize")
+        return s_p
 
     def fs_score_accumulate(self, proj: Projected, bins: Bins, cam: fs_camera, final_T, n_contrib, mask, counts):
         _chk(counts, torch.int32, (int(proj.depth.shape[0]),), "counts")

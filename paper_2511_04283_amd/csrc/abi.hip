@@ -35,6 +35,7 @@ struct fs_ctx {
     ScratchBuf rec_counts;    // uint32 [n] Compact Box: tiles in each Gaussian's box
     ScratchBuf rec_offsets;   // uint32 [n] Compact Box: exclusive prefix sum of rec_counts
     ScratchBuf err_map;       // float  [H*W]
+    ScratchBuf ssim_maps;     // float  [3, 3*H*W] derivative maps of the SSIM term
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: scan totals [2] (pairs, backward records)
     uint64_t* total_host = nullptr;  // pinned host copy
@@ -95,7 +96,7 @@ int ensure(fs_ctx* ctx, ScratchBuf& b, size_t bytes, const char* what)
     } while (0)
 
 const char* const kGroupNames[FS_K_COUNT] = {"preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges",
-                                             "render_fwd", "l1_grad", "fill", "render_bwd", "preprocess_bwd",
+                                             "render_fwd", "l1_grad", "photo_loss", "render_bwd", "preprocess_bwd",
                                              "error_mask", "score"};
 
 hipEvent_t prof_event(fs_ctx* ctx)
@@ -225,7 +226,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
                          &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
-                         &ctx->err_map, &ctx->partial};
+                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -461,6 +462,44 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                         static_cast<const float*>(bins->splats), n_contrib, mask, counts),
            "k_score");
+    return FS_OK;
+}
+
+int fs_photo_loss(fs_ctx* ctx, const float* image, const float* target, int32_t height, int32_t width, float lambda,
+                  float* dL_dimage, double* out3)
+{
+    if (!ctx) return FS_EINVAL;
+    if (!image || !target || height <= 0 || width <= 0 || !(lambda >= 0.f && lambda <= 1.f) || (!dL_dimage && !out3))
+        return fail(ctx, FS_EINVAL, "fs_photo_loss: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    const size_t nb = (size_t)photo_blocks(height, width);
+    FS_TRY(ensure(ctx, ctx->partial, (2 * nb > (size_t)4 * mask_partials() ? 2 * nb : (size_t)4 * mask_partials()) * sizeof(double),
+                  "partials"));
+    if (dL_dimage)
+        FS_TRY(ensure(ctx, ctx->ssim_maps, (size_t)9 * height * width * sizeof(float), "SSIM derivative maps"));
+    ProfScope prof(ctx, FS_K_PHOTO);
+    FS_HIP(launch_photo_loss(ctx->stream, image, target, height, width, lambda, static_cast<float*>(ctx->ssim_maps.ptr),
+                             static_cast<double*>(ctx->partial.ptr), dL_dimage, out3),
+           "k_ssim_*");
+    return FS_OK;
+}
+
+int fs_prune_score_accumulate(fs_ctx* ctx, const int32_t* counts_view, int64_t n, const double* E, double* acc)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!counts_view || !E || !acc))) return fail(ctx, FS_EINVAL, "fs_prune_score_accumulate: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_prune_accumulate(ctx->stream, counts_view, n, E, acc), "k_prune_accumulate");
+    return FS_OK;
+}
+
+int fs_prune_score_normalize(fs_ctx* ctx, const double* acc, int64_t n, float* s_p)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!acc || !s_p))) return fail(ctx, FS_EINVAL, "fs_prune_score_normalize: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
+    FS_HIP(launch_prune_normalize(ctx->stream, acc, n, static_cast<double*>(ctx->partial.ptr), s_p), "k_prune_normalize");
     return FS_OK;
 }
 

@@ -156,6 +156,15 @@ hipError_t launch_error_mask(hipStream_t st, const float* image, const float* ta
                              float k, float* err, double* partial, uint8_t* mask, float* thr_out);
 int mask_partials();
 
+// Photometric loss (1-lambda) L1 + lambda (1 - SSIM).  dmaps: 3 * 3*H*W floats (only touched when dL != null);
+// partial: >= 2 * photo_blocks(H, W) doubles; dL (may be null): dE/d image; out3 (may be null): {L1, SSIM, E}.
+int photo_blocks(int H, int W);
+hipError_t launch_photo_loss(hipStream_t st, const float* image, const float* target, int H, int W, float lambda,
+                             float* dmaps, double* partial, float* dL, double* out3);
+// acc[i] += counts[i] * *E;  then out = min-max normalised acc (partial: >= 2*mask_partials() + 2 doubles)
+hipError_t launch_prune_accumulate(hipStream_t st, const int32_t* counts, int64_t n, const double* E, double* acc);
+hipError_t launch_prune_normalize(hipStream_t st, const double* acc, int64_t n, double* partial, float* out);
+
 hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t count);
 
 }  // namespace fs

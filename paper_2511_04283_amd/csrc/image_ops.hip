@@ -1,5 +1,7 @@
-// Image-space helpers of the hot path (gfx950): L1 term with its gradient, and the per-pixel
-// error map / threshold / high-error mask of FastGS Sec. 4.2 (first three equations).
+// Image-space helpers of the hot path (gfx950): L1 term with its gradient, the per-pixel
+// error map / threshold / high-error mask of FastGS Sec. 4.2 (first three equations), the
+// photometric loss E = (1 - lambda) L1 + lambda (1 - SSIM) of Sec. 4.3 / Sec. 4.5 with its
+// gradient, and the pruning score of Sec. 4.3.
 //
 // Reductions over the image run in double precision in a fixed tree (per-thread strided sums,
 // wavefront shuffle tree, per-workgroup partials, one final workgroup), so results do not depend
@@ -161,6 +163,228 @@ __global__ __launch_bounds__(256) void k_err_mask(const float* __restrict__ err,
     if (i < pixels) mask[i] = err[i] > *thr;
 }
 
+// ---- photometric loss: (1 - lambda) L1 + lambda (1 - SSIM) ---------------------------------------
+// SSIM per channel under an 11x11 Gaussian window (sigma 1.5, sum 1, separable), image continued by
+// zeros, C1 = 0.01^2, C2 = 0.03^2; its mean over channels and pixels.  With the window sums
+// mu1 = <x>, mu2 = <y>, e11 = <x^2>, e22 = <y^2>, e12 = <x y>:
+//   ssim = (2 mu1 mu2 + C1)(2 (e12 - mu1 mu2) + C2) / ((mu1^2 + mu2^2 + C1)(e11 - mu1^2 + e22 - mu2^2 + C2)).
+// Gradient with respect to x: the three maps d ssim/d mu1, d ssim/d e11, d ssim/d e12 are window-summed
+// again (the window is symmetric) and combined as  g = <d_mu1> + 2 x <d_e11> + y <d_e12>.
+//
+// One workgroup produces a 32x16 block of one channel: the (32+10)x(16+10) input region goes to LDS,
+// a horizontal 11-tap pass (one lane: 4 neighbouring columns of one row, sliding over 14 inputs) leaves
+// NQ row-filtered planes in LDS, and a vertical pass (one lane: 2 neighbouring rows of one column) finishes.
+constexpr int SS_R = 5, SS_TAPS = 2 * SS_R + 1;
+constexpr int SS_TW = 32, SS_TH = 16;
+constexpr int SS_IW = SS_TW + 2 * SS_R, SS_IH = SS_TH + 2 * SS_R;   // 42 x 26
+constexpr int SS_IP = SS_IW + 2;                                     // padded LDS row
+
+struct SsimWin { float w[SS_TAPS]; };
+
+// zero-continued load of the block's input region of one plane
+__device__ __forceinline__ void ss_load(const float* __restrict__ plane, int H, int W, int x0, int y0,
+                                        float (*dst)[SS_IP])
+{
+    for (int e = threadIdx.x; e < SS_IH * SS_IW; e += 256) {
+        const int r = e / SS_IW, c = e - r * SS_IW;
+        const int gy = y0 + r - SS_R, gx = x0 + c - SS_R;
+        dst[r][c] = (gy >= 0 && gy < H && gx >= 0 && gx < W) ? plane[(size_t)gy * W + gx] : 0.0f;
+    }
+}
+
+// vertical pass for the two outputs of this lane: rows r0, r0+1 of column c of one row-filtered plane
+__device__ __forceinline__ void ss_vertical(const float (*h)[SS_TW], int r0, int c, const SsimWin& win, float& o0,
+                                            float& o1)
+{
+    float col[SS_TAPS + 1];
+#pragma unroll
+    for (int i = 0; i < SS_TAPS + 1; i++) col[i] = h[r0 + i][c];
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS_TAPS; k++) {
+        a = __builtin_fmaf(win.w[k], col[k], a);
+        b = __builtin_fmaf(win.w[k], col[k + 1], b);
+    }
+    o0 = a; o1 = b;
+}
+
+__global__ __launch_bounds__(256) void k_ssim_fwd(const float* __restrict__ image, const float* __restrict__ target,
+                                                  int H, int W, SsimWin win, float* __restrict__ dmaps,
+                                                  double* __restrict__ partial, int nblocks)
+{
+    __shared__ float s_in[2][SS_IH][SS_IP];
+    __shared__ float s_h[5][SS_IH][SS_TW];
+    __shared__ double smem[4];
+    const int x0 = blockIdx.x * SS_TW, y0 = blockIdx.y * SS_TH;
+    const size_t plane = (size_t)blockIdx.z * H * W;
+    ss_load(image + plane, H, W, x0, y0, s_in[0]);
+    ss_load(target + plane, H, W, x0, y0, s_in[1]);
+    __syncthreads();
+    if (threadIdx.x < SS_IH * (SS_TW / 4)) {
+        const int r = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+        float xv[SS_TAPS + 3], yv[SS_TAPS + 3], xx[SS_TAPS + 3], yy[SS_TAPS + 3], xy[SS_TAPS + 3];
+#pragma unroll
+        for (int i = 0; i < SS_TAPS + 3; i++) {
+            xv[i] = s_in[0][r][c0 + i];
+            yv[i] = s_in[1][r][c0 + i];
+            xx[i] = xv[i] * xv[i];
+            yy[i] = yv[i] * yv[i];
+            xy[i] = xv[i] * yv[i];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            float m1 = 0.f, m2 = 0.f, e11 = 0.f, e22 = 0.f, e12 = 0.f;
+#pragma unroll
+            for (int k = 0; k < SS_TAPS; k++) {
+                const float wk = win.w[k];
+                m1 = __builtin_fmaf(wk, xv[j + k], m1);
+                m2 = __builtin_fmaf(wk, yv[j + k], m2);
+                e11 = __builtin_fmaf(wk, xx[j + k], e11);
+                e22 = __builtin_fmaf(wk, yy[j + k], e22);
+                e12 = __builtin_fmaf(wk, xy[j + k], e12);
+            }
+            s_h[0][r][c0 + j] = m1; s_h[1][r][c0 + j] = m2; s_h[2][r][c0 + j] = e11;
+            s_h[3][r][c0 + j] = e22; s_h[4][r][c0 + j] = e12;
+        }
+    }
+    __syncthreads();
+    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * 2;
+    float q[5][2];
+#pragma unroll
+    for (int k = 0; k < 5; k++) ss_vertical(s_h[k], r0, c, win, q[k][0], q[k][1]);
+    const float C1 = 0.01f * 0.01f, C2 = 0.03f * 0.03f;
+    double ssum = 0.0, lsum = 0.0;
+#pragma unroll
+    for (int o = 0; o < 2; o++) {
+        const int gy = y0 + r0 + o, gx = x0 + c;
+        if (gy < H && gx < W) {
+            const float m1 = q[0][o], m2 = q[1][o];
+            const float s1 = q[2][o] - m1 * m1, s2 = q[3][o] - m2 * m2, s12 = q[4][o] - m1 * m2;
+            const float A = 2.f * m1 * m2 + C1, B = 2.f * s12 + C2, Cq = m1 * m1 + m2 * m2 + C1, D = s1 + s2 + C2;
+            const float inv = 1.0f / (Cq * D);
+            const float sv = A * B * inv;
+            ssum += (double)sv;
+            lsum += (double)fabsf(s_in[0][r0 + o + SS_R][c + SS_R] - s_in[1][r0 + o + SS_R][c + SS_R]);
+            if (dmaps) {
+                const size_t n3 = (size_t)3 * H * W, p = plane + (size_t)gy * W + gx;
+                dmaps[p] = (2.f * m2 * (B - A) - sv * 2.f * m1 * (D - Cq)) * inv;
+                dmaps[n3 + p] = -sv / D;
+                dmaps[2 * n3 + p] = 2.f * A * inv;
+            }
+        }
+    }
+    ssum = block_reduce<RED_SUM>(ssum, smem);
+    lsum = block_reduce<RED_SUM>(lsum, smem);
+    if (threadIdx.x == 0) {
+        const int b = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        partial[b] = ssum;
+        partial[nblocks + b] = lsum;
+    }
+}
+
+// out3 = {L1, SSIM, (1 - lambda) L1 + lambda (1 - SSIM)}: one workgroup adds the partials in a fixed order
+__global__ __launch_bounds__(RED_THREADS) void k_photo_final(const double* __restrict__ partial, int nblocks,
+                                                            double count, double lambda, double* __restrict__ out3)
+{
+    __shared__ double smem[4];
+    double s = 0.0, l = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += RED_THREADS) { s += partial[i]; l += partial[nblocks + i]; }
+    s = block_reduce<RED_SUM>(s, smem);
+    l = block_reduce<RED_SUM>(l, smem);
+    if (threadIdx.x == 0) {
+        const double ssim = s / count, l1 = l / count;
+        out3[0] = l1;
+        out3[1] = ssim;
+        out3[2] = (1.0 - lambda) * l1 + lambda * (1.0 - ssim);
+    }
+}
+
+// dE/dx = c_l1 sign(x - y) - c_ss (<d_mu1> + 2 x <d_e11> + y <d_e12>),  c_l1 = (1-lambda)/N, c_ss = lambda/N
+__global__ __launch_bounds__(256) void k_ssim_bwd(const float* __restrict__ image, const float* __restrict__ target,
+                                                  int H, int W, SsimWin win, const float* __restrict__ dmaps,
+                                                  float c_l1, float c_ss, float* __restrict__ dL)
+{
+    __shared__ float s_in[3][SS_IH][SS_IP];
+    __shared__ float s_h[3][SS_IH][SS_TW];
+    const int x0 = blockIdx.x * SS_TW, y0 = blockIdx.y * SS_TH;
+    const size_t plane = (size_t)blockIdx.z * H * W, n3 = (size_t)3 * H * W;
+#pragma unroll
+    for (int k = 0; k < 3; k++) ss_load(dmaps + k * n3 + plane, H, W, x0, y0, s_in[k]);
+    __syncthreads();
+    if (threadIdx.x < SS_IH * (SS_TW / 4)) {
+        const int r = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+#pragma unroll
+        for (int k = 0; k < 3; k++) {
+            float v[SS_TAPS + 3];
+#pragma unroll
+            for (int i = 0; i < SS_TAPS + 3; i++) v[i] = s_in[k][r][c0 + i];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                float a = 0.f;
+#pragma unroll
+                for (int t = 0; t < SS_TAPS; t++) a = __builtin_fmaf(win.w[t], v[j + t], a);
+                s_h[k][r][c0 + j] = a;
+            }
+        }
+    }
+    __syncthreads();
+    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * 2;
+    float q[3][2];
+#pragma unroll
+    for (int k = 0; k < 3; k++) ss_vertical(s_h[k], r0, c, win, q[k][0], q[k][1]);
+#pragma unroll
+    for (int o = 0; o < 2; o++) {
+        const int gy = y0 + r0 + o, gx = x0 + c;
+        if (gy < H && gx < W) {
+            const size_t p = plane + (size_t)gy * W + gx;
+            const float x = image[p], y = target[p];
+            const float g = q[0][o] + 2.f * x * q[1][o] + y * q[2][o];
+            const float d = x - y;
+            const float sg = d > 0.f ? c_l1 : (d < 0.f ? -c_l1 : 0.f);
+            dL[p] = sg - c_ss * g;
+        }
+    }
+}
+
+// ---- pruning score (Sec. 4.3): s_p = N(sum_j count_i^j E^j) -------------------------------------
+__global__ __launch_bounds__(256) void k_prune_accumulate(const int32_t* __restrict__ counts, int64_t n,
+                                                          const double* __restrict__ E, double* __restrict__ acc)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) acc[i] = acc[i] + (double)counts[i] * *E;
+}
+
+__global__ __launch_bounds__(RED_THREADS) void k_minmax_f64(const double* __restrict__ v, int64_t n,
+                                                           double* __restrict__ partial)
+{
+    __shared__ double smem[4];
+    double lo = 1.0e300, hi = -1.0e300;
+    for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < n; i += (int64_t)RED_BLOCKS * RED_THREADS) {
+        lo = v[i] < lo ? v[i] : lo;
+        hi = v[i] > hi ? v[i] : hi;
+    }
+    lo = block_reduce<RED_MIN>(lo, smem);
+    hi = block_reduce<RED_MAX>(hi, smem);
+    if (threadIdx.x == 0) { partial[blockIdx.x] = lo; partial[RED_BLOCKS + blockIdx.x] = hi; }
+}
+
+__global__ __launch_bounds__(RED_THREADS) void k_minmax_final(double* __restrict__ partial)
+{
+    __shared__ double smem[4];
+    const double lo = final_reduce<RED_MIN>(partial, smem);
+    const double hi = final_reduce<RED_MAX>(partial + RED_BLOCKS, smem);
+    if (threadIdx.x == 0) { partial[2 * RED_BLOCKS] = lo; partial[2 * RED_BLOCKS + 1] = hi; }
+}
+
+__global__ __launch_bounds__(256) void k_prune_normalize(const double* __restrict__ acc, int64_t n,
+                                                         const double* __restrict__ lohi, float* __restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const double lo = lohi[0], hi = lohi[1];
+    out[i] = hi > lo ? (float)((acc[i] - lo) / (hi - lo)) : 0.0f;
+}
+
 }  // namespace
 
 int l1_partials() { return RED_BLOCKS; }
@@ -185,6 +409,43 @@ hipError_t launch_error_mask(hipStream_t st, const float* image, const float* ta
         hipLaunchKernelGGL(k_err_var, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, err, pixels, partial);
     hipLaunchKernelGGL(k_err_threshold, dim3(1), dim3(RED_THREADS), 0, st, partial, pixels, rule, k, thr);
     hipLaunchKernelGGL(k_err_mask, dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0, st, err, pixels, thr, mask);
+    return hipGetLastError();
+}
+
+int photo_blocks(int H, int W) { return ((W + SS_TW - 1) / SS_TW) * ((H + SS_TH - 1) / SS_TH) * 3; }
+
+hipError_t launch_photo_loss(hipStream_t st, const float* image, const float* target, int H, int W, float lambda,
+                             float* dmaps, double* partial, float* dL, double* out3)
+{
+    SsimWin win;
+    double w[SS_TAPS], sum = 0.0;
+    for (int k = 0; k < SS_TAPS; k++) { w[k] = exp(-(double)((k - SS_R) * (k - SS_R)) / (2.0 * 1.5 * 1.5)); sum += w[k]; }
+    for (int k = 0; k < SS_TAPS; k++) win.w[k] = (float)(w[k] / sum);
+    const dim3 grid((unsigned)((W + SS_TW - 1) / SS_TW), (unsigned)((H + SS_TH - 1) / SS_TH), 3);
+    const int nb = photo_blocks(H, W);
+    const double count = 3.0 * (double)H * (double)W;
+    hipLaunchKernelGGL(k_ssim_fwd, grid, dim3(256), 0, st, image, target, H, W, win, dL ? dmaps : nullptr, partial, nb);
+    if (out3) hipLaunchKernelGGL(k_photo_final, dim3(1), dim3(RED_THREADS), 0, st, partial, nb, count, (double)lambda, out3);
+    if (dL)
+        hipLaunchKernelGGL(k_ssim_bwd, grid, dim3(256), 0, st, image, target, H, W, win, dmaps,
+                           (float)((1.0 - (double)lambda) / count), (float)((double)lambda / count), dL);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_accumulate(hipStream_t st, const int32_t* counts, int64_t n, const double* E, double* acc)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_prune_accumulate, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, E, acc);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_normalize(hipStream_t st, const double* acc, int64_t n, double* partial, float* out)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_minmax_f64, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, acc, n, partial);
+    hipLaunchKernelGGL(k_minmax_final, dim3(1), dim3(RED_THREADS), 0, st, partial);
+    hipLaunchKernelGGL(k_prune_normalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, acc, n,
+                       partial + 2 * RED_BLOCKS, out);
     return hipGetLastError();
 }
 
