@@ -171,96 +171,127 @@ __global__ __launch_bounds__(256) void k_err_mask(const float* __restrict__ err,
 // Gradient with respect to x: the three maps d ssim/d mu1, d ssim/d e11, d ssim/d e12 are window-summed
 // again (the window is symmetric) and combined as  g = <d_mu1> + 2 x <d_e11> + y <d_e12>.
 //
-// One workgroup produces a 32x16 block of one channel: the (32+10)x(16+10) input region goes to LDS,
+// One workgroup produces a 32x32 block of one channel: the (32+10)x(32+10) input region goes to LDS,
 // a horizontal 11-tap pass (one lane: 4 neighbouring columns of one row, sliding over 14 inputs) leaves
-// NQ row-filtered planes in LDS, and a vertical pass (one lane: 2 neighbouring rows of one column) finishes.
+// NQ row-filtered planes in LDS, and a vertical pass (one lane: 4 neighbouring rows of one column) finishes.
 constexpr int SS_R = 5, SS_TAPS = 2 * SS_R + 1;
 constexpr int SS_TW = 32, SS_TH = 16;
-constexpr int SS_IW = SS_TW + 2 * SS_R, SS_IH = SS_TH + 2 * SS_R;   // 42 x 26
+constexpr int SS_VO = SS_TW * SS_TH / 256;                         // outputs (neighbouring rows of one column) per lane
+constexpr int SS_IW = SS_TW + 2 * SS_R, SS_IH = SS_TH + 2 * SS_R;   // 42 x 42
 constexpr int SS_IP = SS_IW + 2;                                     // padded LDS row
 
 struct SsimWin { float w[SS_TAPS]; };
 
-// zero-continued load of the block's input region of one plane
-__device__ __forceinline__ void ss_load(const float* __restrict__ plane, int H, int W, int x0, int y0,
-                                        float (*dst)[SS_IP])
+// zero-continued load of the block's input region of NP planes: every global load is issued before the
+// first LDS write, so that their latencies overlap
+template <int NP>
+__device__ __forceinline__ void ss_load(const float* const (&base)[NP], int H, int W, int x0, int y0,
+                                        float (*dst)[SS_IH][SS_IP])
 {
-    for (int e = threadIdx.x; e < SS_IH * SS_IW; e += 256) {
+    constexpr int IT = (SS_IH * SS_IW + 255) / 256;
+    float v[NP][IT];
+#pragma unroll
+    for (int it = 0; it < IT; it++) {
+        const int e = threadIdx.x + 256 * it;
         const int r = e / SS_IW, c = e - r * SS_IW;
         const int gy = y0 + r - SS_R, gx = x0 + c - SS_R;
-        dst[r][c] = (gy >= 0 && gy < H && gx >= 0 && gx < W) ? plane[(size_t)gy * W + gx] : 0.0f;
+        const bool in = e < SS_IH * SS_IW && gy >= 0 && gy < H && gx >= 0 && gx < W;
+        const size_t off = in ? (size_t)gy * W + gx : 0;
+#pragma unroll
+        for (int p = 0; p < NP; p++) {
+            const float t = base[p][off];   // (off = 0 is always a valid address)
+            v[p][it] = in ? t : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < IT; it++) {
+        const int e = threadIdx.x + 256 * it;
+        const int r = e / SS_IW, c = e - r * SS_IW;
+        if (e < SS_IH * SS_IW) {
+#pragma unroll
+            for (int p = 0; p < NP; p++) dst[p][r][c] = v[p][it];
+        }
     }
 }
 
-// vertical pass for the two outputs of this lane: rows r0, r0+1 of column c of one row-filtered plane
-__device__ __forceinline__ void ss_vertical(const float (*h)[SS_TW], int r0, int c, const SsimWin& win, float& o0,
-                                            float& o1)
+// vertical pass for the SS_VO outputs of this lane: rows r0 .. r0+SS_VO-1 of column c of one row-filtered plane
+__device__ __forceinline__ void ss_vertical(const float (*h)[SS_TW], int r0, int c, const SsimWin& win,
+                                            float out[SS_VO])
 {
-    float col[SS_TAPS + 1];
+    float col[SS_TAPS + SS_VO - 1];
 #pragma unroll
-    for (int i = 0; i < SS_TAPS + 1; i++) col[i] = h[r0 + i][c];
-    float a = 0.f, b = 0.f;
+    for (int i = 0; i < SS_TAPS + SS_VO - 1; i++) col[i] = h[r0 + i][c];
 #pragma unroll
-    for (int k = 0; k < SS_TAPS; k++) {
-        a = __builtin_fmaf(win.w[k], col[k], a);
-        b = __builtin_fmaf(win.w[k], col[k + 1], b);
+    for (int o = 0; o < SS_VO; o++) {
+        float a = 0.f;
+#pragma unroll
+        for (int k = 0; k < SS_TAPS; k++) a = __builtin_fmaf(win.w[k], col[k + o], a);
+        out[o] = a;
     }
-    o0 = a; o1 = b;
 }
 
 __global__ __launch_bounds__(256) void k_ssim_fwd(const float* __restrict__ image, const float* __restrict__ target,
                                                   int H, int W, SsimWin win, float* __restrict__ dmaps,
                                                   double* __restrict__ partial, int nblocks)
 {
-    __shared__ float s_in[2][SS_IH][SS_IP];
-    __shared__ float s_h[5][SS_IH][SS_TW];
+    __shared__ __attribute__((aligned(16))) float s_in[2][SS_IH][SS_IP];
+    __shared__ __attribute__((aligned(16))) float s_h[4][SS_IH][SS_TW];
     __shared__ double smem[4];
     const int x0 = blockIdx.x * SS_TW, y0 = blockIdx.y * SS_TH;
     const size_t plane = (size_t)blockIdx.z * H * W;
-    ss_load(image + plane, H, W, x0, y0, s_in[0]);
-    ss_load(target + plane, H, W, x0, y0, s_in[1]);
+    const float* const src[2] = {image + plane, target + plane};
+    ss_load<2>(src, H, W, x0, y0, s_in);
     __syncthreads();
-    if (threadIdx.x < SS_IH * (SS_TW / 4)) {
-        const int r = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
-        float xv[SS_TAPS + 3], yv[SS_TAPS + 3], xx[SS_TAPS + 3], yy[SS_TAPS + 3], xy[SS_TAPS + 3];
+    for (int u = threadIdx.x; u < SS_IH * (SS_TW / 4); u += 256) {
+        const int r = u >> 3, c0 = (u & 7) * 4;
+        // 16-byte LDS accesses: a lane's 16 inputs are four aligned float4s, and 8 neighbouring lanes cover
+        // all banks (a 4-byte access pattern with stride 4 would hit every fourth bank only)
+        // (only the sum e11 + e22 enters the index, so x^2 + y^2 is filtered as one plane)
+        float xv[16], yv[16], sq[SS_TAPS + 3], xy[SS_TAPS + 3];
 #pragma unroll
-        for (int i = 0; i < SS_TAPS + 3; i++) {
-            xv[i] = s_in[0][r][c0 + i];
-            yv[i] = s_in[1][r][c0 + i];
-            xx[i] = xv[i] * xv[i];
-            yy[i] = yv[i] * yv[i];
-            xy[i] = xv[i] * yv[i];
+        for (int i = 0; i < 4; i++) {
+            const float4 a = *reinterpret_cast<const float4*>(&s_in[0][r][c0 + 4 * i]);
+            const float4 b = *reinterpret_cast<const float4*>(&s_in[1][r][c0 + 4 * i]);
+            xv[4 * i] = a.x; xv[4 * i + 1] = a.y; xv[4 * i + 2] = a.z; xv[4 * i + 3] = a.w;
+            yv[4 * i] = b.x; yv[4 * i + 1] = b.y; yv[4 * i + 2] = b.z; yv[4 * i + 3] = b.w;
         }
 #pragma unroll
+        for (int i = 0; i < SS_TAPS + 3; i++) {
+            sq[i] = __builtin_fmaf(xv[i], xv[i], yv[i] * yv[i]);
+            xy[i] = xv[i] * yv[i];
+        }
+        float o[4][4];
+#pragma unroll
         for (int j = 0; j < 4; j++) {
-            float m1 = 0.f, m2 = 0.f, e11 = 0.f, e22 = 0.f, e12 = 0.f;
+            float m1 = 0.f, m2 = 0.f, esq = 0.f, e12 = 0.f;
 #pragma unroll
             for (int k = 0; k < SS_TAPS; k++) {
                 const float wk = win.w[k];
                 m1 = __builtin_fmaf(wk, xv[j + k], m1);
                 m2 = __builtin_fmaf(wk, yv[j + k], m2);
-                e11 = __builtin_fmaf(wk, xx[j + k], e11);
-                e22 = __builtin_fmaf(wk, yy[j + k], e22);
+                esq = __builtin_fmaf(wk, sq[j + k], esq);
                 e12 = __builtin_fmaf(wk, xy[j + k], e12);
             }
-            s_h[0][r][c0 + j] = m1; s_h[1][r][c0 + j] = m2; s_h[2][r][c0 + j] = e11;
-            s_h[3][r][c0 + j] = e22; s_h[4][r][c0 + j] = e12;
+            o[0][j] = m1; o[1][j] = m2; o[2][j] = esq; o[3][j] = e12;
         }
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            *reinterpret_cast<float4*>(&s_h[k][r][c0]) = make_float4(o[k][0], o[k][1], o[k][2], o[k][3]);
     }
     __syncthreads();
-    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * 2;
-    float q[5][2];
+    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * SS_VO;
+    float q[4][SS_VO];
 #pragma unroll
-    for (int k = 0; k < 5; k++) ss_vertical(s_h[k], r0, c, win, q[k][0], q[k][1]);
+    for (int k = 0; k < 4; k++) ss_vertical(s_h[k], r0, c, win, q[k]);
     const float C1 = 0.01f * 0.01f, C2 = 0.03f * 0.03f;
     double ssum = 0.0, lsum = 0.0;
 #pragma unroll
-    for (int o = 0; o < 2; o++) {
+    for (int o = 0; o < SS_VO; o++) {
         const int gy = y0 + r0 + o, gx = x0 + c;
         if (gy < H && gx < W) {
             const float m1 = q[0][o], m2 = q[1][o];
-            const float s1 = q[2][o] - m1 * m1, s2 = q[3][o] - m2 * m2, s12 = q[4][o] - m1 * m2;
-            const float A = 2.f * m1 * m2 + C1, B = 2.f * s12 + C2, Cq = m1 * m1 + m2 * m2 + C1, D = s1 + s2 + C2;
+            const float mm = m1 * m1 + m2 * m2, s12 = q[3][o] - m1 * m2;
+            const float A = 2.f * m1 * m2 + C1, B = 2.f * s12 + C2, Cq = mm + C1, D = (q[2][o] - mm) + C2;
             const float inv = 1.0f / (Cq * D);
             const float sv = A * B * inv;
             ssum += (double)sv;
@@ -287,8 +318,19 @@ __global__ __launch_bounds__(RED_THREADS) void k_photo_final(const double* __res
                                                             double count, double lambda, double* __restrict__ out3)
 {
     __shared__ double smem[4];
+    // 2 x 8 loads in flight per lane and round; the order of the additions is fixed
     double s = 0.0, l = 0.0;
-    for (int i = threadIdx.x; i < nblocks; i += RED_THREADS) { s += partial[i]; l += partial[nblocks + i]; }
+    for (int i0 = threadIdx.x; i0 < nblocks; i0 += 8 * RED_THREADS) {
+        double a[8], b[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int i = i0 + k * RED_THREADS;
+            a[k] = i < nblocks ? partial[i] : 0.0;
+            b[k] = i < nblocks ? partial[nblocks + i] : 0.0;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) { s += a[k]; l += b[k]; }
+    }
     s = block_reduce<RED_SUM>(s, smem);
     l = block_reduce<RED_SUM>(l, smem);
     if (threadIdx.x == 0) {
@@ -304,36 +346,40 @@ __global__ __launch_bounds__(256) void k_ssim_bwd(const float* __restrict__ imag
                                                   int H, int W, SsimWin win, const float* __restrict__ dmaps,
                                                   float c_l1, float c_ss, float* __restrict__ dL)
 {
-    __shared__ float s_in[3][SS_IH][SS_IP];
-    __shared__ float s_h[3][SS_IH][SS_TW];
+    __shared__ __attribute__((aligned(16))) float s_in[3][SS_IH][SS_IP];
+    __shared__ __attribute__((aligned(16))) float s_h[3][SS_IH][SS_TW];
     const int x0 = blockIdx.x * SS_TW, y0 = blockIdx.y * SS_TH;
     const size_t plane = (size_t)blockIdx.z * H * W, n3 = (size_t)3 * H * W;
-#pragma unroll
-    for (int k = 0; k < 3; k++) ss_load(dmaps + k * n3 + plane, H, W, x0, y0, s_in[k]);
+    const float* const src[3] = {dmaps + plane, dmaps + n3 + plane, dmaps + 2 * n3 + plane};
+    ss_load<3>(src, H, W, x0, y0, s_in);
     __syncthreads();
-    if (threadIdx.x < SS_IH * (SS_TW / 4)) {
-        const int r = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+    for (int u = threadIdx.x; u < SS_IH * (SS_TW / 4); u += 256) {
+        const int r = u >> 3, c0 = (u & 7) * 4;
 #pragma unroll
         for (int k = 0; k < 3; k++) {
-            float v[SS_TAPS + 3];
+            float v[16], o[4];
 #pragma unroll
-            for (int i = 0; i < SS_TAPS + 3; i++) v[i] = s_in[k][r][c0 + i];
+            for (int i = 0; i < 4; i++) {
+                const float4 a = *reinterpret_cast<const float4*>(&s_in[k][r][c0 + 4 * i]);
+                v[4 * i] = a.x; v[4 * i + 1] = a.y; v[4 * i + 2] = a.z; v[4 * i + 3] = a.w;
+            }
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 float a = 0.f;
 #pragma unroll
                 for (int t = 0; t < SS_TAPS; t++) a = __builtin_fmaf(win.w[t], v[j + t], a);
-                s_h[k][r][c0 + j] = a;
+                o[j] = a;
             }
+            *reinterpret_cast<float4*>(&s_h[k][r][c0]) = make_float4(o[0], o[1], o[2], o[3]);
         }
     }
     __syncthreads();
-    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * 2;
-    float q[3][2];
+    const int c = threadIdx.x & 31, r0 = (threadIdx.x >> 5) * SS_VO;
+    float q[3][SS_VO];
 #pragma unroll
-    for (int k = 0; k < 3; k++) ss_vertical(s_h[k], r0, c, win, q[k][0], q[k][1]);
+    for (int k = 0; k < 3; k++) ss_vertical(s_h[k], r0, c, win, q[k]);
 #pragma unroll
-    for (int o = 0; o < 2; o++) {
+    for (int o = 0; o < SS_VO; o++) {
         const int gy = y0 + r0 + o, gx = x0 + c;
         if (gy < H && gx < W) {
             const size_t p = plane + (size_t)gy * W + gx;
