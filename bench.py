@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--compact-box", action="store_true",
                     help="pairs from the Compact Box (ellipse-tile test, Sec. 4.4) instead of the 3-sigma square")
     ap.add_argument("--cb-beta", type=float, default=1.0)
+    ap.add_argument("--abs-grad", action="store_true",
+                    help="also accumulate the absolute positional gradient in the backward pass (split criterion)")
     ap.add_argument("--photo-loss", action="store_true",
                     help="train on (1-0.2) L1 + 0.2 (1-SSIM) (fs_photo_loss) instead of the L1 term alone (fs_l1_grad)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -75,6 +77,8 @@ def main() -> int:
     loss = torch.zeros(1, dtype=torch.float64, device=dev)
     out3 = torch.zeros(3, dtype=torch.float64, device=dev)
     grads = dict(means=e(n, 3), scales=e(n, 3), quats=e(n, 4), opacities=e(n), sh=e(n, K, 3), mean2d=e(n, 2))
+    if args.abs_grad:
+        grads["mean2d_abs"] = e(n, 2)
     mask, thr = e(H, W, dt=torch.uint8), e(1)
     counts = torch.zeros(n, dtype=torch.int32, device=dev)
     state = {}

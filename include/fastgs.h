@@ -14,6 +14,9 @@
  *   fs_photo_loss        E = (1-lambda) L1 + lambda (1 - SSIM) and dE/dC        (Sec. 4.3 E_photo; Sec. 4.5 Eq. for L)
  *   fs_prune_score_accumulate / fs_prune_score_normalize
  *                        s_p = N(sum over views of count * E_photo)             (Sec. 4.3, Eq. for s_p)
+ *   fs_densify_accumulate / fs_select / fs_compact / fs_gather_rows
+ *                        gradient statistics, clone / split / prune masks, index lists and row copies
+ *                                                                               (Sec. 4.2, 4.3, supplement)
  *
  * General rules
  *   - Every pointer inside the structs below is a DEVICE pointer (HIP, the ctx's device) owned
@@ -129,6 +132,9 @@ typedef struct {
     float *dmean2d;    /* [n,2] dL/dmu_2D (the screen-space positional gradient used by densification) */
     float *dconic;     /* [n,3] dL/d(a,b,c) of conic_opacity, b counted with its factor 2; may be NULL */
     float *drgb;       /* [n,3] dL/d rgb; may be NULL                                                   */
+    float *dmean2d_abs; /* [n,2] absolute positional gradient: sum over pixels of |that pixel's contribution to
+                          dL/dmu_2D|, component-wise (the quantity FastGS thresholds for splitting; supplement,
+                          "Implementation Details").  May be NULL: then it is not computed.                    */
 } fs_grads;
 
 typedef struct fs_ctx fs_ctx;
@@ -210,6 +216,42 @@ int fs_prune_score_accumulate(fs_ctx *ctx, const int32_t *counts_view, int64_t n
 /* s_p[i] = (acc[i] - min acc) / (max acc - min acc): the min-max normalisation N over the Gaussians;
  * all zeros when max = min.  s_p: [n] floats. */
 int fs_prune_score_normalize(fs_ctx *ctx, const double *acc, int64_t n, float *s_p);
+
+/* ---- densification / pruning decisions (Sec. 4.2 VCD, Sec. 4.3 VCP, supplement "Implementation Details") ----
+ * The paper keeps the gradient tests of vanilla 3DGS (plain positional gradient for cloning, the absolute
+ * one for splitting) and adds: densify only where s_d = counts / K exceeds tau_d (5 in the paper); prune
+ * where opacity < 0.1 or s_p > 0.9.  The gradient thresholds and the size limit are the caller's.        */
+typedef struct {
+    float tau_grad;    /* clone: mean over iterations of |dL/dmu_2D| (Euclidean norm, pixels) >= tau_grad     */
+    float tau_abs;     /* split: the same mean of the absolute positional gradient >= tau_abs                 */
+    float tau_d;       /* both: s_d = counts / K > tau_d                                                      */
+    float size_limit;  /* clone if the largest scale <= size_limit, split if it is larger                     */
+    float min_opacity; /* prune if opacity < min_opacity                                                      */
+    float tau_p;       /* prune if s_p > tau_p                                                                */
+    int32_t K;         /* number of views behind `counts`                                                     */
+} fs_select_params;
+
+/* After each fs_render_bwd of a training view: for every Gaussian visible in that view (tiles_touched > 0)
+ *   grad_accum[i] += |dmean2d[i]|,  abs_accum[i] += |dmean2d_abs[i]|,  denom[i] += 1.
+ * dmean2d_abs and abs_accum may both be NULL.  Accumulators are caller-owned and zeroed by the caller. */
+int fs_densify_accumulate(fs_ctx *ctx, const float *dmean2d, const float *dmean2d_abs, const uint32_t *tiles_touched,
+                          int64_t n, float *grad_accum, float *abs_accum, uint32_t *denom);
+
+/* The three masks ([n] uint8, 0/1).  abs_accum may be NULL (then nothing is split); s_p may be NULL (then
+ * only the opacity test prunes).  scales [n,3], opacities [n]: the scene's activated values.
+ * Divisions and comparisons are fp32: mean = accum / max(denom, 1), s_d = counts / K. */
+int fs_select(fs_ctx *ctx, int64_t n, const float *grad_accum, const float *abs_accum, const uint32_t *denom,
+              const int32_t *counts, const float *scales, const float *opacities, const float *s_p,
+              const fs_select_params *params, uint8_t *clone, uint8_t *split, uint8_t *prune);
+
+/* Stream compaction: indices[0..count) = ascending positions i with mask[i] != 0.  indices needs room for n
+ * entries.  *count_host (host pointer) is set on return; the call synchronises the stream for that. */
+int fs_compact(fs_ctx *ctx, const uint8_t *mask, int64_t n, uint32_t *indices, int64_t *count_host);
+
+/* dst[r, 0..row_floats) = src[indices[r], 0..row_floats) for r < count: the copy that clone / prune-keep /
+ * split-parent selection apply to each per-Gaussian array.  src and dst must not overlap. */
+int fs_gather_rows(fs_ctx *ctx, const float *src, int64_t row_floats, const uint32_t *indices, int64_t count,
+                   float *dst);
 
 /* ---- measurement helpers (no part of the method) ------------------------------------------
  * Per-kernel timing with HIP events recorded on the ctx stream around the launches of the

@@ -235,13 +235,14 @@ class Oracle:
     def render_bwd(self, proj: Projected, bins: Bins, cam, dL_dimage, tile_list=None):
         n, dt = proj.depth.shape[0], self.dtype
         d_mean2d = np.zeros((n, 2)); d_conic = np.zeros((n, 3)); d_op = np.zeros(n); d_rgb = np.zeros((n, 3))
+        d_abs = np.zeros((n, 2))
         tl, ntl = self._tl(tile_list)
         self._f("orc_render_bwd")(
             _p(proj.mean2d), _p(proj.conic_opacity), _p(proj.rgb), _p(bins.gauss_sorted), _p(bins.tile_ranges),
             ctypes.c_int(cam.width), ctypes.c_int(cam.height), _p(self.cfg.array(dt)),
             ctypes.c_int(self.cfg.tile), _p(tl), ctypes.c_int(ntl), _p(self._a(dL_dimage)),
-            _p(d_mean2d), _p(d_conic), _p(d_op), _p(d_rgb))
-        return d_mean2d, d_conic, d_op, d_rgb
+            _p(d_mean2d), _p(d_conic), _p(d_op), _p(d_rgb), _p(d_abs))
+        return d_mean2d, d_conic, d_op, d_rgb, d_abs
 
     # -- a9 --------------------------------------------------------------------------
     def preprocess_bwd(self, sc, cam, d_mean2d, d_conic, d_opacity, d_rgb):
@@ -322,8 +323,8 @@ class Oracle:
 
     def backward_mt(self, sc, cam, proj, bins, dL_dimage, tile_list=None, threads=8):
         d2 = self.render_bwd_mt(proj, bins, cam, dL_dimage, tile_list, threads)
-        g = self.preprocess_bwd(sc, cam, *d2)
-        g["mean2d"], g["conic"], g["rgb"] = d2[0], d2[1], d2[3]
+        g = self.preprocess_bwd(sc, cam, *d2[:4])
+        g["mean2d"], g["conic"], g["rgb"], g["mean2d_abs"] = d2[0], d2[1], d2[3], d2[4]
         return g
 
     # -- whole path (used by finite differences and by the timed CPU baseline) ---------
@@ -335,10 +336,11 @@ class Oracle:
 
     def backward(self, sc, cam, proj, bins, dL_dimage, tile_list=None):
         d2 = self.render_bwd(proj, bins, cam, dL_dimage, tile_list)
-        g = self.preprocess_bwd(sc, cam, *d2)
+        g = self.preprocess_bwd(sc, cam, *d2[:4])
         g["mean2d"] = d2[0]
         g["conic"] = d2[1]
         g["rgb"] = d2[3]
+        g["mean2d_abs"] = d2[4]
         return g
 
 
@@ -395,3 +397,40 @@ def prune_score(counts, E):
     sp = np.zeros(n)
     L.orc_prune_score(ctypes.c_int(K), ctypes.c_int64(n), _p(c), _p(e), _p(raw), _p(sp))
     return raw, sp
+
+
+# ---- densification / pruning decisions (Sec. 4.2, Sec. 4.3, supplement "Implementation Details") ---
+def densify_accumulate(dmean2d, dmean2d_abs, tiles_touched, grad_accum, abs_accum, denom):
+    """Per training view: add the Euclidean norms of the positional gradient (and of the absolute one) of
+    every Gaussian visible in the view to the running sums; count the view.  In place, in the arrays' type."""
+    vis = np.asarray(tiles_touched) > 0
+    dt = grad_accum.dtype
+    g = np.asarray(dmean2d, dt)
+    grad_accum[vis] = grad_accum[vis] + np.sqrt(g[vis, 0] * g[vis, 0] + g[vis, 1] * g[vis, 1])
+    if dmean2d_abs is not None:
+        a = np.asarray(dmean2d_abs, dt)
+        abs_accum[vis] = abs_accum[vis] + np.sqrt(a[vis, 0] * a[vis, 0] + a[vis, 1] * a[vis, 1])
+    denom[vis] += 1
+
+
+def densify_prune_masks(grad_norm, grad_abs_norm, denom, counts, K, max_scale, opacity, s_p, *, tau_grad, tau_abs,
+                        tau_d=5.0, size_limit, min_opacity=0.1, tau_p=0.9, dtype=np.float64):
+    """The selection rules as the paper states them, per Gaussian:
+      clone  : mean positional-gradient norm >= tau_grad, largest scale <= size_limit, and s_d > tau_d
+      split  : mean ABSOLUTE positional-gradient norm >= tau_abs, largest scale > size_limit, and s_d > tau_d
+      prune  : opacity < min_opacity, or s_p > tau_p
+    grad_norm / grad_abs_norm are sums over `denom` iterations of the per-iteration norms; s_d = counts / K.
+    The gradient thresholds and the size limit follow vanilla 3DGS ("we follow 3DGS ... gradient for
+    cloning, ... absolute gradient ... for splitting"); their values are the caller's.  All divisions and
+    comparisons are made in `dtype` (IEEE, correctly rounded).  Returns uint8 masks."""
+    f = lambda v: np.asarray(v, dtype=dtype)
+    d = np.maximum(f(denom), dtype(1))
+    g = f(grad_norm) / d
+    ga = f(grad_abs_norm) / d
+    s_d = f(counts) / dtype(K)
+    important = s_d > dtype(tau_d)
+    big = f(max_scale) > dtype(size_limit)
+    clone = (g >= dtype(tau_grad)) & ~big & important
+    split = (ga >= dtype(tau_abs)) & big & important
+    prune = (f(opacity) < dtype(min_opacity)) | (f(s_p) > dtype(tau_p))
+    return clone.astype(np.uint8), split.astype(np.uint8), prune.astype(np.uint8)

@@ -459,7 +459,7 @@ void FN(orc_render_bwd)(const REAL *mean2d, const REAL *conic_opacity, const REA
                         const uint32_t *gauss_sorted, const uint32_t *ranges, int width, int height,
                         const REAL *cfg, int tile, const int32_t *tile_list, int n_tiles_listed,
                         const REAL *dL_dimage, double *d_mean2d, double *d_conic, double *d_opacity,
-                        double *d_rgb)
+                        double *d_rgb, double *d_mean2d_abs /* may be NULL */)
 {
     int TX = (width + tile - 1) / tile, TY = (height + tile - 1) / tile;
     int ntl = tile_list ? n_tiles_listed : TX * TY;
@@ -512,8 +512,17 @@ void FN(orc_render_bwd)(const REAL *mean2d, const REAL *conic_opacity, const REA
                     d_conic[3 * g + 1] += (double)(dL_dq * (REAL)2 * dx * dy);
                     d_conic[3 * g + 2] += (double)(dL_dq * dy * dy);
                     /* d = p - mu  =>  dq/dmu = -(2 a dx + 2 b dy, 2 b dx + 2 c dy) */
-                    d_mean2d[2 * g + 0] += (double)(-dL_dq * ((REAL)2 * ca * dx + (REAL)2 * cb * dy));
-                    d_mean2d[2 * g + 1] += (double)(-dL_dq * ((REAL)2 * cb * dx + (REAL)2 * cc * dy));
+                    REAL gmx = -dL_dq * ((REAL)2 * ca * dx + (REAL)2 * cb * dy);
+                    REAL gmy = -dL_dq * ((REAL)2 * cb * dx + (REAL)2 * cc * dy);
+                    d_mean2d[2 * g + 0] += (double)gmx;
+                    d_mean2d[2 * g + 1] += (double)gmy;
+                    /* absolute positional gradient (the supplement's implementation details adopt it for
+                     * splitting): every pixel's contribution enters with its magnitude, component-wise,
+                     * so that contributions of opposite sign do not cancel */
+                    if (d_mean2d_abs) {
+                        d_mean2d_abs[2 * g + 0] += (double)FABS(gmx);
+                        d_mean2d_abs[2 * g + 1] += (double)FABS(gmy);
+                    }
                 }
             }
     }

@@ -24,6 +24,7 @@ _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
            "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
+           "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_profile_enable", "fs_profile_read")
 KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
                  "render_bwd", "preprocess_bwd", "error_mask", "score")
@@ -61,10 +62,16 @@ class fs_bins(ctypes.Structure):
                 ("tile_order", ctypes.c_void_p), ("splats", ctypes.c_void_p)]
 
 
+class fs_select_params(ctypes.Structure):
+    _fields_ = [("tau_grad", ctypes.c_float), ("tau_abs", ctypes.c_float), ("tau_d", ctypes.c_float),
+                ("size_limit", ctypes.c_float), ("min_opacity", ctypes.c_float), ("tau_p", ctypes.c_float),
+                ("K", ctypes.c_int32)]
+
+
 class fs_grads(ctypes.Structure):
     _fields_ = [("dmeans", ctypes.c_void_p), ("dscales", ctypes.c_void_p), ("dquats", ctypes.c_void_p),
                 ("dopacities", ctypes.c_void_p), ("dsh", ctypes.c_void_p), ("dmean2d", ctypes.c_void_p),
-                ("dconic", ctypes.c_void_p), ("drgb", ctypes.c_void_p)]
+                ("dconic", ctypes.c_void_p), ("drgb", ctypes.c_void_p), ("dmean2d_abs", ctypes.c_void_p)]
 
 
 _lib = None
@@ -98,6 +105,10 @@ def load_library() -> ctypes.CDLL:
     lib.fs_photo_loss.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     lib.fs_prune_score_accumulate.argtypes = [vp, vp, i64, vp, vp]
     lib.fs_prune_score_normalize.argtypes = [vp, vp, i64, vp]
+    lib.fs_densify_accumulate.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.fs_select.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, P(fs_select_params), vp, vp, vp]
+    lib.fs_compact.argtypes = [vp, vp, i64, vp, P(i64)]
+    lib.fs_gather_rows.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
     for name in EXPORTS:
@@ -316,7 +327,7 @@ class Context:
         return dL_dimage
 
     def fs_render_bwd(self, g: Gaussians, cam: fs_camera, proj: Projected, bins: Bins, final_T, n_contrib, dL_dimage,
-                      out: dict | None = None, want_2d: bool = False) -> dict:
+                      out: dict | None = None, want_2d: bool = False, want_abs: bool = False) -> dict:
         n, K, dev = g.n, (g.sh_degree + 1) ** 2, self.device
         if out is None:
             e = lambda *s: torch.empty(s, dtype=torch.float32, device=dev)
@@ -324,11 +335,14 @@ class Context:
             if want_2d:
                 out["conic"] = e(n, 3)
                 out["rgb"] = e(n, 3)
+            if want_abs:
+                out["mean2d_abs"] = e(n, 2)
         gr = fs_grads()
         gr.dmeans, gr.dscales, gr.dquats = out["means"].data_ptr(), out["scales"].data_ptr(), out["quats"].data_ptr()
         gr.dopacities, gr.dsh, gr.dmean2d = out["opacities"].data_ptr(), out["sh"].data_ptr(), out["mean2d"].data_ptr()
         gr.dconic = out["conic"].data_ptr() if "conic" in out else None
         gr.drgb = out["rgb"].data_ptr() if "rgb" in out else None
+        gr.dmean2d_abs = out["mean2d_abs"].data_ptr() if "mean2d_abs" in out else None
         gs, ps = g.struct(), proj.struct()
         self._check(self.lib.fs_render_bwd(self.handle, ctypes.byref(gs), ctypes.byref(cam), ctypes.byref(ps),
                                            ctypes.byref(bins.struct), _ptr(final_T), _ptr(n_contrib), _ptr(dL_dimage),
@@ -371,6 +385,36 @@ class Context:
             s_p = torch.empty(n, dtype=torch.float32, device=self.device)
         self._check(self.lib.fs_prune_score_normalize(self.handle, _ptr(acc), n, _ptr(s_p)), "fs_prune_score_normalize")
         return s_p
+
+    def fs_densify_accumulate(self, dmean2d, dmean2d_abs, tiles_touched, grad_accum, abs_accum, denom):
+        n = int(dmean2d.shape[0])
+        self._check(self.lib.fs_densify_accumulate(self.handle, _ptr(dmean2d), _ptr(dmean2d_abs), _ptr(tiles_touched), n,
+                                                   _ptr(grad_accum), _ptr(abs_accum), _ptr(denom)), "fs_densify_accumulate")
+
+    def fs_select(self, grad_accum, abs_accum, denom, counts, scales, opacities, s_p, params: fs_select_params):
+        n = int(grad_accum.shape[0])
+        m = [torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(3)]
+        self._check(self.lib.fs_select(self.handle, n, _ptr(grad_accum), _ptr(abs_accum), _ptr(denom), _ptr(counts),
+                                       _ptr(scales), _ptr(opacities), _ptr(s_p), ctypes.byref(params), _ptr(m[0]),
+                                       _ptr(m[1]), _ptr(m[2])), "fs_select")
+        return tuple(m)
+
+    def fs_compact(self, mask):
+        """Returns the int32 tensor of selected positions (ascending)."""
+        n = int(mask.shape[0])
+        _chk(mask, torch.uint8, (n,), "mask")
+        idx = torch.empty(max(n, 1), dtype=torch.int32, device=self.device)
+        cnt = ctypes.c_int64(0)
+        self._check(self.lib.fs_compact(self.handle, _ptr(mask), n, _ptr(idx), ctypes.byref(cnt)), "fs_compact")
+        return idx[:cnt.value]
+
+    def fs_gather_rows(self, src, indices):
+        _chk(src, torch.float32, None, "src")
+        count = int(indices.shape[0])
+        row = int(src.numel() // max(1, src.shape[0]))
+        dst = torch.empty((count,) + tuple(src.shape[1:]), dtype=torch.float32, device=self.device)
+        self._check(self.lib.fs_gather_rows(self.handle, _ptr(src), row, _ptr(indices), count, _ptr(dst)), "fs_gather_rows")
+        return dst
 
     def fs_score_accumulate(self, proj: Projected, bins: Bins, cam: fs_camera, final_T, n_contrib, mask, counts):
         _chk(counts, torch.int32, (int(proj.depth.shape[0]),), "counts")

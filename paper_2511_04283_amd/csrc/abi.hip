@@ -414,7 +414,8 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     if (bins->num_pairs > 0) {
         ProfScope prof(ctx, FS_K_RENDER_BWD);
         FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
-                                 static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad),
+                                 static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad,
+                                 out->dmean2d_abs != nullptr),
                "k_render_bwd");
     }
     // a9: per-Gaussian sum of its records, then the chain through the projection
@@ -500,6 +501,63 @@ int fs_prune_score_normalize(fs_ctx* ctx, const double* acc, int64_t n, float* s
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
     FS_HIP(launch_prune_normalize(ctx->stream, acc, n, static_cast<double*>(ctx->partial.ptr), s_p), "k_prune_normalize");
+    return FS_OK;
+}
+
+int fs_densify_accumulate(fs_ctx* ctx, const float* dmean2d, const float* dmean2d_abs, const uint32_t* tiles_touched,
+                          int64_t n, float* grad_accum, float* abs_accum, uint32_t* denom)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!dmean2d || !tiles_touched || !grad_accum || !denom)) || ((dmean2d_abs != nullptr) != (abs_accum != nullptr)))
+        return fail(ctx, FS_EINVAL, "fs_densify_accumulate: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_densify_accumulate(ctx->stream, n, dmean2d, dmean2d_abs, tiles_touched, grad_accum, abs_accum, denom),
+           "k_densify_accumulate");
+    return FS_OK;
+}
+
+int fs_select(fs_ctx* ctx, int64_t n, const float* grad_accum, const float* abs_accum, const uint32_t* denom,
+              const int32_t* counts, const float* scales, const float* opacities, const float* s_p,
+              const fs_select_params* params, uint8_t* clone, uint8_t* split, uint8_t* prune)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || !params || params->K <= 0 ||
+        (n > 0 && (!grad_accum || !denom || !counts || !scales || !opacities || !clone || !split || !prune)))
+        return fail(ctx, FS_EINVAL, "fs_select: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_select(ctx->stream, n, grad_accum, abs_accum, denom, counts, scales, opacities, s_p, *params, clone,
+                         split, prune),
+           "k_select");
+    return FS_OK;
+}
+
+int fs_compact(fs_ctx* ctx, const uint8_t* mask, int64_t n, uint32_t* indices, int64_t* count_host)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || !count_host || (n > 0 && (!mask || !indices))) return fail(ctx, FS_EINVAL, "fs_compact: bad arguments");
+    if (n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_compact: n does not fit 31 bits");
+    *count_host = 0;
+    if (n == 0) return FS_OK;
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_TRY(ensure(ctx, ctx->rec_counts, (size_t)n * sizeof(uint32_t), "compaction positions"));
+    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
+    FS_HIP(launch_compact(ctx->stream, n, mask, static_cast<uint32_t*>(ctx->rec_counts.ptr), ctx->scan_tmp.ptr,
+                          ctx->total_dev, indices),
+           "compaction");
+    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, ctx->stream),
+           "hipMemcpyAsync");
+    FS_HIP(hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");
+    *count_host = (int64_t)ctx->total_host[0];
+    return FS_OK;
+}
+
+int fs_gather_rows(fs_ctx* ctx, const float* src, int64_t row_floats, const uint32_t* indices, int64_t count, float* dst)
+{
+    if (!ctx) return FS_EINVAL;
+    if (count < 0 || row_floats <= 0 || row_floats > 4096 || (count > 0 && (!src || !indices || !dst)))
+        return fail(ctx, FS_EINVAL, "fs_gather_rows: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_gather_rows(ctx->stream, src, (int)row_floats, indices, count, dst), "k_gather_rows");
     return FS_OK;
 }
 

@@ -141,7 +141,7 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad);
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                         const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,
@@ -164,6 +164,18 @@ hipError_t launch_photo_loss(hipStream_t st, const float* image, const float* ta
 // acc[i] += counts[i] * *E;  then out = min-max normalised acc (partial: >= 2*mask_partials() + 2 doubles)
 hipError_t launch_prune_accumulate(hipStream_t st, const int32_t* counts, int64_t n, const double* E, double* acc);
 hipError_t launch_prune_normalize(hipStream_t st, const double* acc, int64_t n, double* partial, float* out);
+
+// densification / pruning decisions and index plumbing (densify.hip)
+hipError_t launch_densify_accumulate(hipStream_t st, int64_t n, const float* dmean2d, const float* dabs,
+                                     const uint32_t* touched, float* grad_accum, float* abs_accum, uint32_t* denom);
+hipError_t launch_select(hipStream_t st, int64_t n, const float* grad_accum, const float* abs_accum,
+                         const uint32_t* denom, const int32_t* counts, const float* scales, const float* opac,
+                         const float* s_p, const fs_select_params& prm, uint8_t* clone, uint8_t* split, uint8_t* prune);
+// positions: uint32 [n] scratch; total_dev receives the number of selected elements
+hipError_t launch_compact(hipStream_t st, int64_t n, const uint8_t* mask, uint32_t* positions, void* scan_tmp,
+                          uint64_t* total_dev, uint32_t* indices);
+hipError_t launch_gather_rows(hipStream_t st, const float* src, int row_floats, const uint32_t* indices,
+                              int64_t count, float* dst);
 
 hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t count);
 

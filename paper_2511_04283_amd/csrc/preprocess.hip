@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     const float4* __restrict__ pair_grad, float* __restrict__ d_means, float* __restrict__ d_scales,
     float* __restrict__ d_quats, float* __restrict__ d_sh, float* __restrict__ d_opac,
     float* __restrict__ d_mean2d, float* __restrict__ d_conic /* may be null */,
-    float* __restrict__ d_rgb /* may be null */)
+    float* __restrict__ d_rgb /* may be null */, float* __restrict__ d_abs /* may be null */)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     constexpr int K = (DEG + 1) * (DEG + 1);
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     // The 64 Gaussians of a wavefront own one contiguous run of records.  The wavefront streams that
     // run through LDS in chunks with coalesced 16-byte loads; each lane then adds up its own records.
     float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb = ra;
-    float rc = 0.f;
+    float rc = 0.f, rabs_x = 0.f, rabs_y = 0.f;
     {
         const uint32_t off = in_range ? offsets[i] : 0u;
         const uint32_t cnt = in_range && touched[i] ? rec_counts[i] : 0u;
@@ -338,10 +338,11 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
             const uint32_t r0 = max(off, cs), r1 = min(off + cnt, cs + nrec);
             for (uint32_t r = r0; r < r1; r++) {
                 const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1];
-                const float c = buf[(r - cs) * 3 + 2].x;
+                const float4 c4 = buf[(r - cs) * 3 + 2];
                 ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
                 rb.x += b.x; rb.y += b.y; rb.z += b.z; rb.w += b.w;
-                rc += c;
+                rc += c4.x;
+                rabs_x += c4.y; rabs_y += c4.z;   // (only meaningful when the records carry them)
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -404,6 +405,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         d_mean2d[2 * i] = 0.f; d_mean2d[2 * i + 1] = 0.f;
         if (d_conic) for (int k = 0; k < 3; k++) d_conic[3 * i + k] = 0.f;
         if (d_rgb) for (int k = 0; k < 3; k++) d_rgb[3 * i + k] = 0.f;
+        if (d_abs) { d_abs[2 * i] = 0.f; d_abs[2 * i + 1] = 0.f; }
     }
     if (in_range && s.visible) {
         const float g_rgb3[3] = {ra.x, ra.y, ra.z};
@@ -413,6 +415,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         d_mean2d[2 * i] = g_m2[0]; d_mean2d[2 * i + 1] = g_m2[1];
         if (d_conic) { d_conic[3 * i] = g_conic3[0]; d_conic[3 * i + 1] = g_conic3[1]; d_conic[3 * i + 2] = g_conic3[2]; }
         if (d_rgb) { d_rgb[3 * i] = g_rgb3[0]; d_rgb[3 * i + 1] = g_rgb3[1]; d_rgb[3 * i + 2] = g_rgb3[2]; }
+        if (d_abs) { d_abs[2 * i] = rabs_x; d_abs[2 * i + 1] = rabs_y; }
         // ---- colour -> SH coefficients and, through the view direction, the mean ----
         float d[3], len;
         view_dir(means, i, cam, d, len);
@@ -566,7 +569,7 @@ hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_ga
     hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.opacities, g.sh, \
                        cam, cfg, clamped, touched, rec_counts, rec_offsets,                                       \
                        reinterpret_cast<const float4*>(pair_grad), o.dmeans, o.dscales, o.dquats, o.dsh,          \
-                       o.dopacities, o.dmean2d, o.dconic, o.drgb)
+                       o.dopacities, o.dmean2d, o.dconic, o.drgb, o.dmean2d_abs)
     switch (deg) {
         case 0: FS_LAUNCH(0); break;
         case 1: FS_LAUNCH(1); break;

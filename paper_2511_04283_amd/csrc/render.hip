@@ -310,6 +310,17 @@ __device__ __forceinline__ void row_reduce9(const float v[9], int lane, float& p
     ninth = r8;
 }
 
+// Two more values: afterwards the even lanes of the row hold the total of a, the odd lanes that of b.
+__device__ __forceinline__ float row_reduce2(float a, float b, int lane)
+{
+    constexpr int XOR1 = 0xB1, XOR2 = 0x4E, ROR4 = 0x124, ROR8 = 0x128;
+    float r = fold<XOR1>(lane & 1, a, b);
+    r = r + dpp_get<XOR2>(r);
+    r = r + dpp_get<ROR4>(r);
+    r = r + dpp_get<ROR8>(r);
+    return r;
+}
+
 // Backward of the compositing.  Walks each sub-tile's list back to front from the furthest blended
 // Gaussian; per Gaussian, 9 partial sums over the 16 pixels of a sub-tile are formed across the
 // row's lanes and combined across the sub-tiles in LDS.  The 9 sums: dL/drgb (3), dL/dsigma, and with
@@ -321,6 +332,11 @@ __device__ __forceinline__ void row_reduce9(const float v[9], int lane, float& p
 // plain store (rgb 3, sigma, conic 3, mu_2D 2), every pair of the tile is written exactly once (zeros
 // for the ones nothing blended), and the per-Gaussian sum over its contiguous records is left to the
 // projection's backward kernel.  No global atomics, and the result does not depend on scheduling.
+//
+// ABS adds the absolute positional gradient (used by FastGS for the split decision): per pixel the
+// magnitudes |dL/dmu_x|, |dL/dmu_y| of its own contribution, summed like the other values and stored
+// in the record's floats 9 and 10.
+template <bool ABS>
 __global__ __launch_bounds__(256) void k_render_bwd(
     CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
     const uint32_t* __restrict__ gauss_sorted,
@@ -330,7 +346,8 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     __shared__ Stage s;
     __shared__ float4 s_rgb[BATCH];
     __shared__ uint32_t s_id[BATCH];
-    __shared__ float s_acc[BATCH][9];
+    constexpr int NV = ABS ? 11 : 9;
+    __shared__ float s_acc[BATCH][NV];
     __shared__ int s_max;
 
     const int tile = (int)tile_order[blockIdx.x];  // longest lists first
@@ -367,7 +384,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         const int m = min(BATCH, total - start);
         __syncthreads();  // the previous batch's flush has read s_acc / s_id
 #pragma unroll
-        for (int k = 0; k < 9; k++) s_acc[threadIdx.x][k] = 0.f;
+        for (int k = 0; k < NV; k++) s_acc[threadIdx.x][k] = 0.f;
         const int mine = stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         const int longest = wave_max_of_rows(mine);
         for (int it = 0; it < longest; it++) {
@@ -417,8 +434,18 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             row_reduce9(v, lane, packed, ninth);
             // lanes 0..7 of a row hold the totals of values 0..7, lane 8 adds the ninth
             const int li = lane & 15;
-            if (li < 9 && ((act_mask >> (lane & 48)) & 0xffffull) != 0)
+            if (ABS) {
+                // |dq/dmu . g| per pixel: (2a dx + 2b dy, 2b dx + 2c dy) scaled by |g|  (co.y holds 2b)
+                const float ag = fabsf(gq);
+                const float ax = ag * fabsf(__builtin_fmaf(co.y, dy, 2.0f * co.x * dx));
+                const float ay = ag * fabsf(__builtin_fmaf(co.y, dx, 2.0f * co.z * dy));
+                const float r2 = row_reduce2(ax, ay, lane);
+                // lane 10 (even) holds the total of ax -> slot 9, lane 9 (odd) that of ay -> slot 10
+                if (li < 11 && ((act_mask >> (lane & 48)) & 0xffffull) != 0)
+                    atomicAdd(&s_acc[j][li < 9 ? li : 19 - li], li < 8 ? packed : (li == 8 ? ninth : r2));
+            } else if (li < 9 && ((act_mask >> (lane & 48)) & 0xffffull) != 0) {
                 atomicAdd(&s_acc[j][li], li < 8 ? packed : ninth);
+            }
         }
         __syncthreads();
         if ((int)threadIdx.x < m) {
@@ -428,7 +455,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             rec[0] = make_float4(a[0], a[1], a[2], a[3]);
             // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
             rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
-            rec[2].x = -(co.y * a[7] + 2.0f * co.z * a[8]);
+            rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
         }
     }
     // pairs behind the furthest blended Gaussian of the tile received nothing
@@ -441,7 +468,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
         rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
         rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rec[2].x = 0.f;
+        rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 }
 
@@ -525,13 +552,20 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad)
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_render_bwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
-                       reinterpret_cast<float4*>(pair_grad));
+    if (abs_grad)
+        hipLaunchKernelGGL(k_render_bwd<true>, dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
+                           reinterpret_cast<float4*>(pair_grad));
+    else
+        hipLaunchKernelGGL(k_render_bwd<false>, dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
+                           reinterpret_cast<float4*>(pair_grad));
     return hipGetLastError();
 }
 

@@ -3,7 +3,8 @@ output back as numpy, next to the fp32 oracle's outputs for the same seeded inpu
 import numpy as np
 
 
-def gpu_pipeline(ctx, sc, cam, target=None, dL=None, mask_rule=0, mask_k=1.0, want_bwd=True, want_score=True):
+def gpu_pipeline(ctx, sc, cam, target=None, dL=None, mask_rule=0, mask_k=1.0, want_bwd=True, want_score=True,
+                 want_abs=False):
     import torch
     from paper_2511_04283_amd import binding as B
     g = B.Gaussians.from_scene(sc, ctx.device)
@@ -29,7 +30,7 @@ def gpu_pipeline(ctx, sc, cam, target=None, dL=None, mask_rule=0, mask_k=1.0, wa
         else:
             dLt = torch.from_numpy(np.ascontiguousarray(dL, dtype=np.float32)).to(ctx.device)
         if want_bwd:
-            gr = ctx.fs_render_bwd(g, fcam, proj, bins, final_T, n_contrib, dLt, want_2d=True)
+            gr = ctx.fs_render_bwd(g, fcam, proj, bins, final_T, n_contrib, dLt, want_2d=True, want_abs=want_abs)
             out["grads"] = {k: v.cpu().numpy() for k, v in gr.items()}
         if want_score and target is not None:
             mask, thr = ctx.fs_error_mask(image, tgt, rule=mask_rule, k=mask_k)

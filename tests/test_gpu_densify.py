@@ -1,0 +1,104 @@
+"""GPU parity for the densification / pruning row: absolute positional gradient (floating point, the
+gradient tolerance), gradient statistics (fp32 norms), selection masks, compaction and row gathers
+(bit-exact)."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Config, Oracle
+from paper_2511_04283_amd import scenes
+from gpu_common import assert_grads_close, gpu_pipeline
+from test_gpu_parity import check_all, oracle_pipeline
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2511_04283_amd import binding as B
+    c = B.Context("cuda:0")
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("deg,cb", [(0, False), (3, False), (1, True)])
+def test_absolute_gradient_tiny_scenes(deg, cb):
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.compact_box = int(cb)
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(500 + deg, 9000, 203, 117, sh_degree=deg, log_scale=(-2.6, 0.8), spread=1.4)
+    cam = sc.cameras[0]
+    tgt = np.random.default_rng(deg).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    g = gpu_pipeline(c, sc, cam, target=tgt, want_abs=True)
+    r = oracle_pipeline(Oracle(np.float32, Config(compact_box=cb)), sc, cam, target=tgt)
+    assert "mean2d_abs" in g["grads"] and np.abs(r["grads"]["mean2d_abs"]).max() > 0
+    check_all(g, r, sc)                      # every other output too: the ABS kernel variant is a full backward
+    ga, gm = g["grads"]["mean2d_abs"], g["grads"]["mean2d"]
+    assert (ga >= np.abs(gm) * (1 - 1e-4) - 1e-9).all() and (ga > 1.2 * np.abs(gm)).any()
+    c.close()
+
+
+def test_absolute_gradient_config3_full(ctx):
+    sc = scenes.make_scene(3)
+    cam = sc.cameras[0]
+    tgt = scenes.target_image(3, 0, cam)
+    g = gpu_pipeline(ctx, sc, cam, target=tgt, want_abs=True, want_score=False)
+    o = Oracle(np.float32)
+    proj = o.preprocess(sc, cam)
+    bins = o.bin_sort(proj, cam)
+    img, fT, nc = o.render_fwd_mt(proj, bins, cam, threads=14)
+    _, dL = o.l1(img, tgt)
+    ref = o.backward_mt(sc, cam, proj, bins, dL, threads=14)
+    assert_grads_close(g["grads"], ref)
+    assert np.abs(ref["mean2d_abs"]).max() > 0
+
+
+def test_statistics_masks_compaction_and_gather(ctx):
+    import torch
+    from paper_2511_04283_amd import binding as B
+    dev = ctx.device
+    rng = np.random.default_rng(9)
+    n, iters, K = 50_003, 3, 10
+    grad = np.zeros(n, np.float32); gabs = np.zeros(n, np.float32); den = np.zeros(n, np.uint32)
+    t_grad = torch.zeros(n, device=dev); t_abs = torch.zeros(n, device=dev)
+    t_den = torch.zeros(n, dtype=torch.int32, device=dev)
+    for it in range(iters):
+        d2 = rng.normal(0, 3e-4, (n, 2)).astype(np.float32)
+        da = (np.abs(d2) + np.abs(rng.normal(0, 3e-4, (n, 2)))).astype(np.float32)
+        tt = (rng.uniform(size=n) < 0.7).astype(np.uint32) * rng.integers(1, 9, n).astype(np.uint32)
+        oracle.densify_accumulate(d2, da, tt, grad, gabs, den)
+        ctx.fs_densify_accumulate(torch.from_numpy(d2).to(dev), torch.from_numpy(da).to(dev),
+                                  torch.from_numpy(tt.view(np.int32)).to(dev), t_grad, t_abs, t_den)
+    assert np.array_equal(t_den.cpu().numpy().view(np.uint32), den)
+    # fp32 sqrt and adds are correctly rounded on both sides; a*a + b*b is evaluated unfused on both
+    assert np.array_equal(t_grad.cpu().numpy(), grad) and np.array_equal(t_abs.cpu().numpy(), gabs)
+
+    counts = rng.integers(0, 120, n).astype(np.int32)
+    scales = np.exp(rng.normal(-3.0, 1.0, (n, 3))).astype(np.float32)
+    opac = rng.uniform(0, 1, n).astype(np.float32)
+    s_p = rng.uniform(0, 1, n).astype(np.float32)
+    prm = B.fs_select_params(tau_grad=2e-4, tau_abs=4e-4, tau_d=5.0, size_limit=0.05, min_opacity=0.1, tau_p=0.9, K=K)
+    # plant exact boundary values
+    counts[:10] = 50; opac[10:20] = np.float32(0.1); s_p[20:30] = np.float32(0.9)
+    want = oracle.densify_prune_masks(grad, gabs, den, counts, K, scales.max(1), opac, s_p, tau_grad=2e-4, tau_abs=4e-4,
+                                      tau_d=5.0, size_limit=0.05, min_opacity=0.1, tau_p=0.9, dtype=np.float32)
+    got = ctx.fs_select(t_grad, t_abs, t_den, torch.from_numpy(counts).to(dev), torch.from_numpy(scales).to(dev),
+                        torch.from_numpy(opac).to(dev), torch.from_numpy(s_p).to(dev), prm)
+    for name, a, b in zip(("clone", "split", "prune"), got, want):
+        assert np.array_equal(a.cpu().numpy(), b), name
+        assert 0 < b.sum() < n, name
+    assert not (want[0] & want[1]).any()
+
+    # compaction == flatnonzero; gather == fancy indexing (the "keep" list of pruning, the clone list)
+    keep = (1 - want[2]).astype(np.uint8)
+    idx = ctx.fs_compact(torch.from_numpy(keep).to(dev))
+    assert np.array_equal(idx.cpu().numpy(), np.flatnonzero(keep).astype(np.int32))
+    sh = rng.normal(size=(n, 16, 3)).astype(np.float32)
+    for arr in (sh, scales, opac):
+        out = ctx.fs_gather_rows(torch.from_numpy(arr).to(dev), idx)
+        assert np.array_equal(out.cpu().numpy(), arr[np.flatnonzero(keep)])
+    # edge cases: nothing / everything selected, n = 1
+    assert ctx.fs_compact(torch.zeros(777, dtype=torch.uint8, device=dev)).numel() == 0
+    assert np.array_equal(ctx.fs_compact(torch.ones(777, dtype=torch.uint8, device=dev)).cpu().numpy(), np.arange(777))
+    assert ctx.fs_compact(torch.ones(1, dtype=torch.uint8, device=dev)).cpu().numpy().tolist() == [0]

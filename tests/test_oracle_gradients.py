@@ -109,7 +109,7 @@ def test_screen_space_gradients_by_finite_differences(orc64):
     proj = o.preprocess(sc, cam)
     bins = o.bin_sort(proj, cam)
     w = np.random.default_rng(2).normal(size=(3, cam.height, cam.width))
-    d_mean2d, d_conic, d_op, d_rgb = o.render_bwd(proj, bins, cam, w)
+    d_mean2d, d_conic, d_op, d_rgb, _ = o.render_bwd(proj, bins, cam, w)
     nc0 = o.render_fwd(proj, bins, cam)[2]
 
     def f():
@@ -146,6 +146,6 @@ def test_alpha_cap_blocks_gradient(orc64):
     proj = orc64.preprocess(sc, cam)
     bins = orc64.bin_sort(proj, cam)
     w = np.zeros((3, 16, 16)); w[:, 8, 8] = 1.0            # only the pixel centred on the mean: G = 1
-    d_mean2d, d_conic, d_op, d_rgb = orc64.render_bwd(proj, bins, cam, w)
+    d_mean2d, d_conic, d_op, d_rgb, d_abs = orc64.render_bwd(proj, bins, cam, w)
     assert d_op[0] == 0 and not d_conic.any() and not d_mean2d.any()
     assert np.allclose(d_rgb[0], 0.99)
