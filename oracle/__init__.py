@@ -434,3 +434,38 @@ def densify_prune_masks(grad_norm, grad_abs_norm, denom, counts, K, max_scale, o
     split = (ga >= dtype(tau_abs)) & big & important
     prune = (f(opacity) < dtype(min_opacity)) | (f(s_p) > dtype(tau_p))
     return clone.astype(np.uint8), split.astype(np.uint8), prune.astype(np.uint8)
+
+
+# ---- optimiser (Sec. 5.1: Adam; supplement "Implementation Details": the 32/64 schedule) -------------
+def adam_step(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-15, grad_scale=1.0):
+    """One Adam update (Kingma & Ba, Algorithm 1, with bias correction), in place, in the arrays' type:
+         g = grad_scale * grad;  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+         param -= lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),   t = step >= 1."""
+    dt = param.dtype.type
+    g = np.asarray(grad, param.dtype) * dt(grad_scale)
+    m[...] = dt(beta1) * m + dt(1 - beta1) * g
+    v[...] = dt(beta2) * v + dt(1 - beta2) * (g * g)
+    mhat = m / dt(1 - beta1 ** step)
+    vhat = v / dt(1 - beta2 ** step)
+    param[...] = param - dt(lr) * mhat / (np.sqrt(vhat) + dt(eps))
+
+
+def adam_interval(iteration):
+    """Iterations between optimiser updates: every iteration before 15 000, every 32 iterations from 15 000 to
+    20 000, every 64 afterwards; gradients of the iterations in between are summed."""
+    return 1 if iteration < 15000 else (32 if iteration < 20000 else 64)
+
+
+def activate(raw_scales, raw_quats, raw_opac):
+    """Stored -> used parameters, as in vanilla 3DGS (which the paper keeps): s = exp(raw), q = raw / |raw|,
+    sigma = 1 / (1 + exp(-raw))."""
+    q = raw_quats / np.sqrt((raw_quats * raw_quats).sum(1, keepdims=True))
+    return np.exp(raw_scales), q, 1.0 / (1.0 + np.exp(-raw_opac))
+
+
+def activate_bwd(raw_scales, raw_quats, raw_opac, d_scales, d_quats, d_opac):
+    """Chain rule through `activate`."""
+    s, q, o = activate(raw_scales, raw_quats, raw_opac)
+    nrm = np.sqrt((raw_quats * raw_quats).sum(1, keepdims=True))
+    d_raw_q = (d_quats - q * (q * d_quats).sum(1, keepdims=True)) / nrm
+    return d_scales * s, d_raw_q, d_opac * o * (1.0 - o)
