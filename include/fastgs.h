@@ -14,6 +14,9 @@
  *   fs_photo_loss        E = (1-lambda) L1 + lambda (1 - SSIM) and dE/dC        (Sec. 4.3 E_photo; Sec. 4.5 Eq. for L)
  *   fs_prune_score_accumulate / fs_prune_score_normalize
  *                        s_p = N(sum over views of count * E_photo)             (Sec. 4.3, Eq. for s_p)
+ *   fs_adam_step / fs_grad_accumulate / fs_adam_interval / fs_activate / fs_activate_bwd
+ *                        fused Adam update with the 32/64 schedule, parameter activations
+ *                                                                               (Sec. 5.1, supplement)
  *   fs_densify_accumulate / fs_select / fs_compact / fs_gather_rows
  *                        gradient statistics, clone / split / prune masks, index lists and row copies
  *                                                                               (Sec. 4.2, 4.3, supplement)
@@ -252,6 +255,36 @@ int fs_compact(fs_ctx *ctx, const uint8_t *mask, int64_t n, uint32_t *indices, i
  * split-parent selection apply to each per-Gaussian array.  src and dst must not overlap. */
 int fs_gather_rows(fs_ctx *ctx, const float *src, int64_t row_floats, const uint32_t *indices, int64_t count,
                    float *dst);
+
+/* ---- optimiser (Sec. 5.1: all methods train with Adam; supplement "Implementation Details": the update
+ * schedule of the accelerated baseline) ---------------------------------------------------------------- */
+
+/* One Adam update (Kingma & Ba, Algorithm 1, with bias correction) of `count` parameters, in place:
+ *   g = grad_scale * grad;  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   param -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps),   step >= 1.
+ * If zero_grad != 0 the gradient array is cleared in the same pass.  All four arrays: `count` floats,
+ * 16-byte aligned (FS_EINVAL otherwise). */
+int fs_adam_step(fs_ctx *ctx, float *param, float *grad, float *m, float *v, int64_t count, float lr, float beta1,
+                 float beta2, float eps, int32_t step, float grad_scale, int32_t zero_grad);
+
+/* acc += grad (count floats, 16-byte aligned): the sum of the gradients of the iterations between two
+ * optimiser updates. */
+int fs_grad_accumulate(fs_ctx *ctx, float *acc, const float *grad, int64_t count);
+
+/* Iterations between optimiser updates at training iteration `iteration`: 1 before 15 000, 32 from 15 000
+ * to 20 000, 64 afterwards.  Host-only helper. */
+int32_t fs_adam_interval(int32_t iteration);
+
+/* Stored -> used parameters of vanilla 3DGS (which the paper's pipeline keeps): scale = exp(raw),
+ * quaternion = raw / |raw|, opacity = 1 / (1 + exp(-raw)).  raw_quats and quats 16-byte aligned. */
+int fs_activate(fs_ctx *ctx, int64_t n, const float *raw_scales, const float *raw_quats, const float *raw_opacities,
+                float *scales, float *quats, float *opacities);
+
+/* Chain rule through fs_activate: gradients w.r.t. the used parameters -> w.r.t. the stored ones.  The outputs
+ * may alias the corresponding inputs (d_raw_scales == d_scales, ...). */
+int fs_activate_bwd(fs_ctx *ctx, int64_t n, const float *raw_scales, const float *raw_quats,
+                    const float *raw_opacities, const float *d_scales, const float *d_quats, const float *d_opacities,
+                    float *d_raw_scales, float *d_raw_quats, float *d_raw_opacities);
 
 /* ---- measurement helpers (no part of the method) ------------------------------------------
  * Per-kernel timing with HIP events recorded on the ctx stream around the launches of the

@@ -25,6 +25,7 @@ EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_
            "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
+           "fs_adam_step", "fs_grad_accumulate", "fs_adam_interval", "fs_activate", "fs_activate_bwd",
            "fs_profile_enable", "fs_profile_read")
 KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
                  "render_bwd", "preprocess_bwd", "error_mask", "score")
@@ -109,11 +110,17 @@ def load_library() -> ctypes.CDLL:
     lib.fs_select.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, P(fs_select_params), vp, vp, vp]
     lib.fs_compact.argtypes = [vp, vp, i64, vp, P(i64)]
     lib.fs_gather_rows.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.fs_adam_step.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, i32, f32, i32]
+    lib.fs_grad_accumulate.argtypes = [vp, vp, vp, i64]
+    lib.fs_adam_interval.argtypes = [i32]
+    lib.fs_activate.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.fs_activate_bwd.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
     for name in EXPORTS:
-        if name not in ("fs_default_config", "fs_destroy", "fs_last_error"):
+        if name not in ("fs_default_config", "fs_destroy", "fs_last_error", "fs_adam_interval"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.fs_adam_interval.restype = ctypes.c_int32
     _lib = lib
     return lib
 
@@ -385,6 +392,38 @@ class Context:
             s_p = torch.empty(n, dtype=torch.float32, device=self.device)
         self._check(self.lib.fs_prune_score_normalize(self.handle, _ptr(acc), n, _ptr(s_p)), "fs_prune_score_normalize")
         return s_p
+
+    def fs_adam_step(self, param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-15, grad_scale=1.0,
+                     zero_grad=False):
+        for t, nm in ((param, "param"), (grad, "grad"), (m, "m"), (v, "v")):
+            _chk(t, torch.float32, None, nm)
+            assert t.numel() == param.numel()
+        self._check(self.lib.fs_adam_step(self.handle, _ptr(param), _ptr(grad), _ptr(m), _ptr(v), param.numel(), float(lr),
+                                          float(beta1), float(beta2), float(eps), int(step), float(grad_scale),
+                                          int(bool(zero_grad))), "fs_adam_step")
+
+    def fs_grad_accumulate(self, acc, grad):
+        _chk(acc, torch.float32, None, "acc"); _chk(grad, torch.float32, None, "grad")
+        assert acc.numel() == grad.numel()
+        self._check(self.lib.fs_grad_accumulate(self.handle, _ptr(acc), _ptr(grad), acc.numel()), "fs_grad_accumulate")
+
+    def fs_adam_interval(self, iteration):
+        return int(self.lib.fs_adam_interval(int(iteration)))
+
+    def fs_activate(self, raw_scales, raw_quats, raw_opacities):
+        n = int(raw_opacities.shape[0])
+        s, q, o = torch.empty_like(raw_scales), torch.empty_like(raw_quats), torch.empty_like(raw_opacities)
+        self._check(self.lib.fs_activate(self.handle, n, _ptr(raw_scales), _ptr(raw_quats), _ptr(raw_opacities), _ptr(s),
+                                         _ptr(q), _ptr(o)), "fs_activate")
+        return s, q, o
+
+    def fs_activate_bwd(self, raw_scales, raw_quats, raw_opacities, d_scales, d_quats, d_opacities, in_place=True):
+        n = int(raw_opacities.shape[0])
+        outs = (d_scales, d_quats, d_opacities) if in_place else tuple(torch.empty_like(t) for t in (d_scales, d_quats, d_opacities))
+        self._check(self.lib.fs_activate_bwd(self.handle, n, _ptr(raw_scales), _ptr(raw_quats), _ptr(raw_opacities),
+                                             _ptr(d_scales), _ptr(d_quats), _ptr(d_opacities), _ptr(outs[0]), _ptr(outs[1]),
+                                             _ptr(outs[2])), "fs_activate_bwd")
+        return outs
 
     def fs_densify_accumulate(self, dmean2d, dmean2d_abs, tiles_touched, grad_accum, abs_accum, denom):
         n = int(dmean2d.shape[0])

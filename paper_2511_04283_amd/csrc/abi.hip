@@ -561,6 +561,64 @@ int fs_gather_rows(fs_ctx* ctx, const float* src, int64_t row_floats, const uint
     return FS_OK;
 }
 
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int fs_adam_step(fs_ctx* ctx, float* param, float* grad, float* m, float* v, int64_t count, float lr, float beta1,
+                 float beta2, float eps, int32_t step, float grad_scale, int32_t zero_grad)
+{
+    if (!ctx) return FS_EINVAL;
+    if (count < 0 || step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) ||
+        (count > 0 && (!param || !grad || !m || !v)))
+        return fail(ctx, FS_EINVAL, "fs_adam_step: bad arguments");
+    if (!aligned16(param) || !aligned16(grad) || !aligned16(m) || !aligned16(v))
+        return fail(ctx, FS_EINVAL, "fs_adam_step: arrays must be 16-byte aligned");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_adam(ctx->stream, param, grad, m, v, count, lr, beta1, beta2, eps, step, grad_scale, zero_grad != 0),
+           "k_adam");
+    return FS_OK;
+}
+
+int fs_grad_accumulate(fs_ctx* ctx, float* acc, const float* grad, int64_t count)
+{
+    if (!ctx) return FS_EINVAL;
+    if (count < 0 || (count > 0 && (!acc || !grad)) || !aligned16(acc) || !aligned16(grad))
+        return fail(ctx, FS_EINVAL, "fs_grad_accumulate: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_grad_accumulate(ctx->stream, acc, grad, count), "k_grad_accumulate");
+    return FS_OK;
+}
+
+int32_t fs_adam_interval(int32_t iteration) { return iteration < 15000 ? 1 : (iteration < 20000 ? 32 : 64); }
+
+int fs_activate(fs_ctx* ctx, int64_t n, const float* raw_scales, const float* raw_quats, const float* raw_opacities,
+                float* scales, float* quats, float* opacities)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!raw_scales || !raw_quats || !raw_opacities || !scales || !quats || !opacities)) ||
+        !aligned16(raw_quats) || !aligned16(quats))
+        return fail(ctx, FS_EINVAL, "fs_activate: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_activate(ctx->stream, n, raw_scales, raw_quats, raw_opacities, scales, quats, opacities), "k_activate");
+    return FS_OK;
+}
+
+int fs_activate_bwd(fs_ctx* ctx, int64_t n, const float* raw_scales, const float* raw_quats, const float* raw_opacities,
+                    const float* d_scales, const float* d_quats, const float* d_opacities, float* d_raw_scales,
+                    float* d_raw_quats, float* d_raw_opacities)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 ||
+        (n > 0 && (!raw_scales || !raw_quats || !raw_opacities || !d_scales || !d_quats || !d_opacities ||
+                   !d_raw_scales || !d_raw_quats || !d_raw_opacities)) ||
+        !aligned16(raw_quats) || !aligned16(d_quats) || !aligned16(d_raw_quats))
+        return fail(ctx, FS_EINVAL, "fs_activate_bwd: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_activate_bwd(ctx->stream, n, raw_scales, raw_quats, raw_opacities, d_scales, d_quats, d_opacities,
+                               d_raw_scales, d_raw_quats, d_raw_opacities),
+           "k_activate_bwd");
+    return FS_OK;
+}
+
 static int prof_collect(fs_ctx* ctx)
 {
     FS_HIP(hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");

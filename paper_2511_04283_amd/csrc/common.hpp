@@ -177,6 +177,16 @@ hipError_t launch_compact(hipStream_t st, int64_t n, const uint8_t* mask, uint32
 hipError_t launch_gather_rows(hipStream_t st, const float* src, int row_floats, const uint32_t* indices,
                               int64_t count, float* dst);
 
+// optimiser and activations (optimizer.hip)
+hipError_t launch_adam(hipStream_t st, float* p, float* g, float* m, float* v, int64_t count, float lr, float beta1,
+                       float beta2, float eps, int step, float grad_scale, bool zero_grad);
+hipError_t launch_grad_accumulate(hipStream_t st, float* acc, const float* g, int64_t count);
+hipError_t launch_activate(hipStream_t st, int64_t n, const float* raw_s, const float* raw_q, const float* raw_o,
+                           float* s, float* q, float* o);
+hipError_t launch_activate_bwd(hipStream_t st, int64_t n, const float* raw_s, const float* raw_q, const float* raw_o,
+                               const float* d_s, const float* d_q, const float* d_o, float* d_raw_s, float* d_raw_q,
+                               float* d_raw_o);
+
 hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t count);
 
 }  // namespace fs
