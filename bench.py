@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--cb-beta", type=float, default=1.0)
     ap.add_argument("--abs-grad", action="store_true",
                     help="also accumulate the absolute positional gradient in the backward pass (split criterion)")
+    ap.add_argument("--train-iteration", action="store_true",
+                    help="time a whole training iteration: activations + the hot path + chain rule + Adam on every group")
     ap.add_argument("--photo-loss", action="store_true",
                     help="train on (1-0.2) L1 + 0.2 (1-SSIM) (fs_photo_loss) instead of the L1 term alone (fs_l1_grad)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,7 +85,18 @@ def main() -> int:
     counts = torch.zeros(n, dtype=torch.int32, device=dev)
     state = {}
 
+    if args.train_iteration:
+        raw = dict(scales=torch.log(g.scales), quats=g.quats.clone(), opac=torch.logit(g.opacities.clamp(1e-4, 1 - 1e-4)))
+        params = dict(means=g.means, sh=g.sh, scales=raw["scales"], quats=raw["quats"], opacities=raw["opac"])
+        adam_m = {k: torch.zeros_like(v) for k, v in params.items()}
+        adam_v = {k: torch.zeros_like(v) for k, v in params.items()}
+        state["it"] = 0
+
     def step():
+        if args.train_iteration:
+            state["it"] += 1
+            s_, q_, o_ = ctx.fs_activate(raw["scales"], raw["quats"], raw["opac"])
+            g.scales, g.quats, g.opacities = s_, q_, o_
         ctx.fs_preprocess(g, fcam, proj)
         bins = ctx.fs_bin_sort(proj, fcam)
         ctx.fs_render_fwd(proj, bins, fcam, image, final_T, n_contrib)
@@ -92,6 +105,10 @@ def main() -> int:
         else:
             ctx.fs_l1_grad(image, target, dL, loss)
         ctx.fs_render_bwd(g, fcam, proj, bins, final_T, n_contrib, dL, grads)
+        if args.train_iteration:
+            ctx.fs_activate_bwd(raw["scales"], raw["quats"], raw["opac"], grads["scales"], grads["quats"], grads["opacities"])
+            for k in params:
+                ctx.fs_adam_step(params[k], grads[k], adam_m[k], adam_v[k], state["it"], 1e-5)
         ctx.fs_error_mask(image, target, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
         counts.zero_()
         ctx.fs_score_accumulate(proj, bins, fcam, final_T, n_contrib, mask, counts)
@@ -172,8 +189,9 @@ def main() -> int:
         "config": {"workload": sc.name + (f"+compact_box(beta={args.cb_beta:g})" if args.compact_box else ""),
                    "gaussians": n, "sh_degree": sc.sh_degree, "image": [W, H],
                    "pairs": int(P), "max_tile_list": int(tile_len.max().item()),
-                   "step": "preprocess+bin_sort+render_fwd+" + ("photo_loss" if args.photo_loss else "l1_grad") +
-                           "+render_bwd+error_mask+score_accumulate"},
+                   "step": ("activate+" if args.train_iteration else "") + "preprocess+bin_sort+render_fwd+" +
+                           ("photo_loss" if args.photo_loss else "l1_grad") + "+render_bwd+" +
+                           ("activate_bwd+adam+" if args.train_iteration else "") + "error_mask+score_accumulate"},
         "roofline": roofline,
         "kernels_ms": {k: round(v, 4) for k, v in kernels_ms.items()},
         "gaussian_pixel_evals_per_s": round((evals_fwd_bound + evals_bwd) / (ms_per_step * 1e-3), 1),
@@ -183,7 +201,7 @@ def main() -> int:
         "loss": float(out3[2].item()) if args.photo_loss else float(loss.item()),
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.train_iteration:   # (the oracle leg times the hot path on the untouched scene)
         from oracle import Config, Oracle
         o = Oracle(np.float32, Config(compact_box=args.compact_box, cb_beta=args.cb_beta))
         c0 = time.perf_counter()
