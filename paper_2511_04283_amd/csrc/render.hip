@@ -227,7 +227,9 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
         const int m = min(BATCH, total - start);
         const int mine = stage_batch<true, 0>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, splats,
                                               range.x + start, m);
-        const int longest = wave_max_of_rows(mine);
+        // a row whose 16 pixels have all finished does not lengthen the wavefront's loop
+        const bool row_alive = ((__ballot(!done) >> (threadIdx.x & 48)) & 0xffffull) != 0;
+        const int longest = wave_max_of_rows(row_alive ? mine : 0);
         // Straight-line body with selects: lanes past their list's end (or finished) read a stale
         // slot and discard the result; only two wave-uniform branches per iteration.
         for (int k = 0; k < longest; k++) {
@@ -386,7 +388,9 @@ __global__ __launch_bounds__(256) void k_render_bwd(
 #pragma unroll
         for (int k = 0; k < NV; k++) s_acc[threadIdx.x][k] = 0.f;
         const int mine = stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
-        const int longest = wave_max_of_rows(mine);
+        // a row none of whose pixels reaches into this batch does not lengthen the wavefront's loop
+        const bool row_walks = ((__ballot(start < last) >> (lane & 48)) & 0xffffull) != 0;
+        const int longest = wave_max_of_rows(row_walks ? mine : 0);
         for (int it = 0; it < longest; it++) {
             const int k = mine - 1 - it;      // every row walks its own list from the back
             const int j = s.list[sub][k & (BATCH - 1)];
@@ -511,8 +515,12 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
         s_cnt[threadIdx.x] = 0;
         const int mine = stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats,
                                                range.x + start, m);
-        if (__ballot(start < last) != 0) {
-            const int longest = wave_max_of_rows(mine);
+        // a row none of whose pixels is still walking (no mask pixel, or all past their last Gaussian)
+        // has nothing to count in this batch
+        const uint64_t walking = __ballot(start < last);
+        if (walking != 0) {
+            const bool row_walks = ((walking >> (lane & 48)) & 0xffffull) != 0;
+            const int longest = wave_max_of_rows(row_walks ? mine : 0);
             for (int k = 0; k < longest; k++) {
                 const int j = s.list[sub][k];
                 const float2 xy = s.xy[j];
