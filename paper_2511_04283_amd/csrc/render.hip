@@ -49,9 +49,9 @@ struct Pixel {
     float px, py;
 };
 
-__device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
+__device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile, int thread)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = thread >> 6, lane = thread & 63;
     const int tx = tile % cam.tiles_x, ty = tile / cam.tiles_x;
     const int row = lane >> 4;  // 4x4 sub-tile (row & 1, row >> 1) of the quadrant
     Pixel p;
@@ -63,12 +63,18 @@ __device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
     return p;
 }
 
+__device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
+{
+    return pixel_of_thread(cam, tile, (int)threadIdx.x);
+}
+
 // LDS image of one batch of a tile's list, shared by the three kernels.
 struct Stage {
     float2 xy[BATCH];          // mu_2D
     float4 co[BATCH];          // (a, 2b, c, sigma)
     uint64_t bits[16][4];      // per sub-tile, per staging wavefront: which of its 64 slots the sub-tile visits
     uint8_t list[16][BATCH];   // per sub-tile (index wave*4 + row): batch slots to visit, in list order
+    int len[16];               // length of each sub-tile's list
 };
 
 template <int CTRL>
@@ -185,6 +191,7 @@ __device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_
         b16 &= b16 - 1u;
     }
     const int mine = __shfl((int)inc, (lane & 48) | 15, 64);
+    if (i == 15) s.len[st] = (int)inc;
     __syncthreads();
     return mine;
 }
@@ -508,6 +515,67 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     __syncthreads();
     const int total = s_max;
     float T = 1.0f;
+
+    // The walking pixels (mask pixels with at least one blended Gaussian) are usually a small part of the
+    // tile.  When at most half of it walks, they are packed into the first lanes of the workgroup: lane c
+    // takes over the c-th walking pixel, with that pixel's own sub-tile list, so that one or two wavefronts
+    // run the loop instead of four mostly idle ones.  The per-pixel arithmetic is the same either way.
+    __shared__ int s_wave_cnt[4];
+    __shared__ uint8_t s_walker[256];
+    const bool walks = last > 0;
+    const uint64_t wb = __ballot(walks);
+    if (lane == 0) s_wave_cnt[threadIdx.x >> 6] = __popcll(wb);
+    __syncthreads();
+    int before = 0, nwalk = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        before += w < (int)(threadIdx.x >> 6) ? s_wave_cnt[w] : 0;
+        nwalk += s_wave_cnt[w];
+    }
+    if (walks) s_walker[before + __popcll(wb & ((1ull << lane) - 1ull))] = (uint8_t)threadIdx.x;
+    __syncthreads();
+
+    if (nwalk <= 128) {
+        // Which wavefront takes the first 64 walkers rotates with the workgroup index: wavefront w of every
+        // workgroup runs on the same SIMD of its CU, and the walk is the expensive part.
+        const int c = (int)((((threadIdx.x >> 6) - blockIdx.x) & 3u) * 64u) + lane;
+        const bool on = c < nwalk;
+        const int me = on ? (int)s_walker[c] : 0;
+        const Pixel pw = pixel_of_thread(cam, tile, me);
+        const int my_sub = (me >> 6) * 4 + ((me & 63) >> 4);
+        const int my_last = on ? (int)n_contrib[(size_t)pw.y * cam.width + pw.x] : 0;
+        const bool wave_on = (c - lane) < nwalk;   // uniform per wavefront
+        for (int start = 0; start < total; start += BATCH) {
+            const int m = min(BATCH, total - start);
+            __syncthreads();  // the previous batch's flush has read s_cnt / s_id
+            s_cnt[threadIdx.x] = 0;
+            stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
+            if (wave_on) {
+                const int len = start < my_last ? s.len[my_sub] : 0;
+                for (int k = 0; __ballot(k < len) != 0; k++) {
+                    const int j = s.list[my_sub][k & (BATCH - 1)];
+                    const float2 xy = s.xy[j];
+                    const float4 co = s.co[j];
+                    const float dx = pw.px - xy.x, dy = pw.py - xy.y;
+                    const float u = __builtin_fmaf(co.y, dy, co.x * dx);
+                    const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+                    const float power = -0.5f * q;
+                    bool act = (k < len) & (start + j < my_last) & !(power > 0.0f) & !(power < cfg.power_min);
+                    if (__ballot(act) == 0) continue;
+                    const float alpha = fminf(cfg.alpha_max, co.w * exp_c(power));
+                    act = act & (alpha >= cfg.alpha_min);
+                    const float w = alpha * T;
+                    const bool hit = act & (cfg.score_mode == FS_SCORE_ALPHA || w > cfg.alpha_min);
+                    T = act ? T * (1.0f - alpha) : T;
+                    if (hit) atomicAdd(&s_cnt[j], 1);
+                }
+            }
+            __syncthreads();
+            if ((int)threadIdx.x < m && s_cnt[threadIdx.x] != 0)
+                atomicAdd(&counts[s_id[threadIdx.x]], s_cnt[threadIdx.x]);
+        }
+        return;
+    }
 
     for (int start = 0; start < total; start += BATCH) {
         const int m = min(BATCH, total - start);
