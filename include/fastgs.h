@@ -53,6 +53,7 @@ typedef enum {
 
 enum { FS_SCORE_WEIGHT = 0, FS_SCORE_ALPHA = 1 };
 enum { FS_MASK_MEAN_STD = 0, FS_MASK_MINMAX_TAU = 1 };
+enum { FS_SORT_AUTO = 0, FS_SORT_RADIX = 1 };
 
 /* Conventions the paper leaves open; fs_default_config fills in the documented defaults. */
 typedef struct {
@@ -69,6 +70,9 @@ typedef struct {
                             exists iff the tile's closed rectangle meets the ellipse
                             (p-mu_2D)^T Sigma_2D^-1 (p-mu_2D) <= cb_beta * 2 ln(sigma / alpha_min)  (0)          */
     float cb_beta;       /* Compact Box threshold scale beta in (0, 1]; 1 keeps every pixel with alpha >= alpha_min (1) */
+    int32_t sort_mode;   /* how fs_bin_sort orders the pairs; the result is the same either way.  FS_SORT_AUTO: per-tile
+                            segments sorted in LDS while no tile's list exceeds 8192 entries, else the global radix sort;
+                            FS_SORT_RADIX: always the global stable LSD radix sort on tile << 32 | depth bits (0)   */
 } fs_config;
 
 /* Pinhole camera: x_cam = R x_world + t (the paper's viewing transformation W);
@@ -158,8 +162,10 @@ const char *fs_last_error(const fs_ctx *ctx);
  * radius ceil(3 sqrt(lambda_max)), tile rectangle, SH colour.  Errors: FS_EINVAL, FS_EHIP. */
 int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_projected *out);
 
-/* Steps a2-a5: exclusive scan of tiles_touched, one 64-bit key per (Gaussian, tile) pair, stable
- * LSD radix sort by key, per-tile ranges.  n = number of Gaussians in `proj`.  Also packs the
+/* Steps a2-a5: exclusive scan of tiles_touched, one 64-bit key per (Gaussian, tile) pair, the keys in
+ * ascending order (ties by Gaussian index) and per-tile ranges.  The order is that of a stable sort of
+ * index-ordered keys; it is computed per tile (count, place, sort each tile's segment in LDS) or by a global
+ * LSD radix sort (cfg.sort_mode; the result is identical).  n = number of Gaussians in `proj`.  Also packs the
  * projected splats into bins->splats; later calls that take `bins` must be given the same `proj`.
  * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (P >= 2^32). */
 int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int64_t n, fs_bins *out);
@@ -295,9 +301,9 @@ int fs_activate_bwd(fs_ctx *ctx, int64_t n, const float *raw_scales, const float
 enum {
     FS_K_PREPROCESS = 0, /* k_preprocess                                  */
     FS_K_SCAN,           /* the three kernels of the tiles_touched scan   */
-    FS_K_EMIT,           /* k_emit_pairs                                  */
-    FS_K_RADIX_SORT,     /* all passes: histogram, scan, scatter          */
-    FS_K_RANGES,         /* fill + k_tile_ranges                          */
+    FS_K_EMIT,           /* k_emit_pairs, or the per-tile counting kernels */
+    FS_K_RADIX_SORT,     /* the ordering: radix passes, or placement + per-tile sort */
+    FS_K_RANGES,         /* k_tile_ranges + k_tile_order (radix mode only) */
     FS_K_RENDER_FWD,     /* k_render_fwd                                  */
     FS_K_L1,             /* k_l1_grad (+ final reduction)                 */
     FS_K_PHOTO,          /* the kernels of fs_photo_loss                  */

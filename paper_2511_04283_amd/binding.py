@@ -18,6 +18,7 @@ LIB_PATH = os.environ.get("FASTGS_HIP_LIB") or os.path.join(_PKG, "libfastgs_hip
 
 FS_OK = 0
 FS_SCORE_WEIGHT, FS_SCORE_ALPHA = 0, 1
+FS_SORT_AUTO, FS_SORT_RADIX = 0, 1
 FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
@@ -35,7 +36,7 @@ class fs_config(ctypes.Structure):
     _fields_ = [("tile", ctypes.c_int32), ("z_near", ctypes.c_float), ("lowpass", ctypes.c_float),
                 ("alpha_min", ctypes.c_float), ("alpha_max", ctypes.c_float), ("T_min", ctypes.c_float),
                 ("bg", ctypes.c_float * 3), ("jclamp", ctypes.c_float), ("score_mode", ctypes.c_int32),
-                ("compact_box", ctypes.c_int32), ("cb_beta", ctypes.c_float)]
+                ("compact_box", ctypes.c_int32), ("cb_beta", ctypes.c_float), ("sort_mode", ctypes.c_int32)]
 
 
 class fs_camera(ctypes.Structure):

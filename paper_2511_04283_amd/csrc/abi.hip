@@ -37,7 +37,7 @@ struct fs_ctx {
     ScratchBuf err_map;       // float  [H*W]
     ScratchBuf ssim_maps;     // float  [3, 3*H*W] derivative maps of the SSIM term
     ScratchBuf partial;       // double reduction partials
-    uint64_t* total_dev = nullptr;   // device: scan totals [2] (pairs, backward records)
+    uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
 
     // per-group event timing (measurement only)
@@ -189,6 +189,7 @@ void fs_default_config(fs_config* cfg)
     cfg->score_mode = FS_SCORE_WEIGHT;
     cfg->compact_box = 0;
     cfg->cb_beta = 1.0f;
+    cfg->sort_mode = FS_SORT_AUTO;
 }
 
 int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
@@ -200,7 +201,7 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     if (c.tile != TILE || !(c.alpha_min > 0.f) || !(c.alpha_min < c.alpha_max) || !(c.alpha_max < 1.f) ||
         !(c.T_min > 0.f) || !(c.T_min < 1.f) || !(c.lowpass >= 0.f) ||
         (c.score_mode != FS_SCORE_WEIGHT && c.score_mode != FS_SCORE_ALPHA) ||
-        (c.compact_box != 0 && c.compact_box != 1) || (c.compact_box && !(c.cb_beta > 0.f && c.cb_beta <= 1.f)))
+        (c.compact_box != 0 && c.compact_box != 1) || (c.sort_mode != FS_SORT_AUTO && c.sort_mode != FS_SORT_RADIX) || (c.compact_box && !(c.cb_beta > 0.f && c.cb_beta <= 1.f)))
         return FS_EINVAL;
     if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return FS_EHIP; }
     fs_ctx* ctx = new (std::nothrow) fs_ctx();
@@ -209,8 +210,8 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->cfg = c;
     ctx->err[0] = 0;
-    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 2 * sizeof(uint64_t)) != hipSuccess ||
-        hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), 2 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 4 * sizeof(uint64_t)) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), 4 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         fs_destroy(ctx);
         return FS_EHIP;
@@ -265,7 +266,13 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     hipStream_t st = ctx->stream;
     const int tiles = cd.tiles_x * cd.tiles_y;
 
-    FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * 3 * sizeof(uint32_t), "tile ranges and order"));
+    // ranges [T,2] | tile_order [T] | tile totals [T] | per-tile counters [TILE_COPIES,T]
+    FS_TRY(ensure(ctx, ctx->ranges, (size_t)tiles * (4 + TILE_COPIES) * sizeof(uint32_t), "tile ranges and order"));
+    uint32_t* const ranges_p = static_cast<uint32_t*>(ctx->ranges.ptr);
+    uint32_t* const order_p = ranges_p + 2 * (size_t)tiles;
+    uint32_t* const ttotal_p = ranges_p + 3 * (size_t)tiles;
+    uint32_t* const tcount_p = ranges_p + 4 * (size_t)tiles;
+    const bool bucketed = ctx->cfg.sort_mode == FS_SORT_AUTO && tiles <= TILE_LDS_MAX_TILES;
     FS_TRY(ensure(ctx, ctx->offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "offsets"));
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
     FS_TRY(ensure(ctx, ctx->splats, (size_t)(n > 0 ? n : 1) * SPLAT_REC * sizeof(float), "splats"));
@@ -290,13 +297,26 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
                    "scan");
         }
     }
-    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, (cb ? 2 : 1) * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
+    // tile-bucketed ordering, first half: pairs per tile, ranges, longest list (needs no P-sized memory,
+    // so it is enqueued ahead of the read-back)
+    if (bucketed) {
+        ProfScope prof(ctx, FS_K_EMIT);
+        fs_projected none = {};
+        FS_HIP(launch_tile_count(st, n, proj ? *proj : none, cf, cd.tiles_x, tiles, tcount_p, ttotal_p,
+                                 reinterpret_cast<uint2*>(ranges_p), order_p, ctx->total_dev + 2),
+               "k_tile_pairs (count)");
+    }
+    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
            "hipMemcpyAsync");
     FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
     const uint64_t P = ctx->total_host[0];
     const uint64_t NR = cb ? ctx->total_host[1] : P;
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
     if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
+    if (bucketed && ctx->total_host[2] != P)
+        return fail(ctx, FS_EINVAL, "fs_bin_sort: tiles_touched does not match rect (proj from another configuration?)");
+    const uint64_t max_len = bucketed ? ctx->total_host[3] : 0;
+    const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_MAX;
     if (cb) FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(NR ? NR : 1) * PAIR_REC * sizeof(float), "pair gradients"));
 
     const int64_t nb = radix_num_blocks((int64_t)P);
@@ -310,33 +330,43 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     uint64_t* keys[2] = {static_cast<uint64_t*>(ctx->keys[0].ptr), static_cast<uint64_t*>(ctx->keys[1].ptr)};
     uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};
     int res = 0;
-    if (P > 0) {
-        // a3
-        {
-            ProfScope prof(ctx, FS_K_EMIT);
-            if (cb)
-                FS_HIP(launch_emit_pairs_cb(st, n, *proj, cf, static_cast<const uint32_t*>(ctx->offsets.ptr),
-                                            static_cast<const uint32_t*>(ctx->rec_offsets.ptr), cd.tiles_x, (int64_t)P,
-                                            keys[0], vals[0], static_cast<float*>(ctx->splats.ptr),
-                                            static_cast<float*>(ctx->pair_grad.ptr)),
-                       "k_emit_pairs_cb");
-            else
-                FS_HIP(launch_emit_pairs(st, n, *proj, static_cast<const uint32_t*>(ctx->offsets.ptr), cd.tiles_x,
-                                         keys[0], vals[0], static_cast<float*>(ctx->splats.ptr)),
-                       "k_emit_pairs");
-        }
-        // a4: 32 depth bits + the tile bits are live
+    if (lds_sort) {
+        // second half: placement into the tiles' segments (keys[1] serves as the bucket array) and the
+        // per-tile LDS sort; ranges are already in place
         ProfScope prof(ctx, FS_K_RADIX_SORT);
-        FS_HIP(launch_radix_sort(st, (int64_t)P, 32 + tile_bits(tiles), keys, vals, static_cast<uint32_t*>(ctx->hist.ptr),
-                                 ctx->scan_tmp.ptr, ctx->total_dev, &res),
-               "radix sort");
-    }
-    // a5
-    {
+        fs_projected none = {};
+        FS_HIP(launch_tile_scatter_sort(st, n, proj ? *proj : none, cf,
+                                        cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr)
+                                           : static_cast<const uint32_t*>(ctx->offsets.ptr),
+                                        cd.tiles_x, tiles, (int64_t)P, (int)max_len, reinterpret_cast<const uint2*>(ranges_p),
+                                        tcount_p, order_p, keys[1], keys[0], vals[0], static_cast<float*>(ctx->splats.ptr),
+                                        static_cast<float*>(ctx->pair_grad.ptr)),
+               "tile-bucketed ordering");
+    } else {
+        if (P > 0) {
+            // a3
+            {
+                ProfScope prof(ctx, FS_K_EMIT);
+                if (cb)
+                    FS_HIP(launch_emit_pairs_cb(st, n, *proj, cf, static_cast<const uint32_t*>(ctx->offsets.ptr),
+                                                static_cast<const uint32_t*>(ctx->rec_offsets.ptr), cd.tiles_x, (int64_t)P,
+                                                keys[0], vals[0], static_cast<float*>(ctx->splats.ptr),
+                                                static_cast<float*>(ctx->pair_grad.ptr)),
+                           "k_emit_pairs_cb");
+                else
+                    FS_HIP(launch_emit_pairs(st, n, *proj, static_cast<const uint32_t*>(ctx->offsets.ptr), cd.tiles_x,
+                                             keys[0], vals[0], static_cast<float*>(ctx->splats.ptr)),
+                           "k_emit_pairs");
+            }
+            // a4: 32 depth bits + the tile bits are live
+            ProfScope prof(ctx, FS_K_RADIX_SORT);
+            FS_HIP(launch_radix_sort(st, (int64_t)P, 32 + tile_bits(tiles), keys, vals, static_cast<uint32_t*>(ctx->hist.ptr),
+                                     ctx->scan_tmp.ptr, ctx->total_dev, &res),
+                   "radix sort");
+        }
+        // a5
         ProfScope prof(ctx, FS_K_RANGES);
-        FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, static_cast<uint32_t*>(ctx->ranges.ptr),
-                                  static_cast<uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles),
-               "k_tile_ranges");
+        FS_HIP(launch_tile_ranges(st, (int64_t)P, keys[res], tiles, ranges_p, order_p), "k_tile_ranges");
     }
     out->num_pairs = (int64_t)P;
     out->keys_sorted = keys[res];

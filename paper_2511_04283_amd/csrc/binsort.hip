@@ -287,6 +287,245 @@ __global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4*
     }
 }
 
+// ---- tile-bucketed ordering ----------------------------------------------------------------
+// The order wanted is (tile, depth, Gaussian index): instead of one global sort on 45 live key bits, the
+// pairs are (1) counted per tile, (2) placed into their tile's segment in arrival order, and (3) every
+// tile's segment is sorted in LDS on the 64-bit word depth_bits << 32 | Gaussian index.  Those words are
+// unique within a tile, so the result does not depend on the arrival order and equals what a stable global
+// sort of index-ordered keys gives.  The per-tile ranges fall out of step (1).
+
+// Steps (1) and (2) are launched as TILE_COPIES workgroups, each keeping its own counter per tile in LDS
+// (so num_tiles * 4 bytes must fit there) and walking the same Gaussians in both steps; step (1) ends by
+// writing its counters as one row of a [TILE_COPIES, num_tiles] table, which k_tile_sum turns into each
+// workgroup's start within every tile's segment, and step (2) starts from that row.  Global atomics reach
+// about 45 G/s on this chip whatever the contention; LDS atomics are an order of magnitude cheaper.
+//
+// Steps (1) and (2) walk the candidate tiles of 64 consecutive Gaussians per wavefront the way k_emit_pairs
+// does.  SCATTER = false: count[tile] += 1 per pair.  SCATTER = true: slot = first[tile] + counter[tile]++
+// (k_tile_sum has turned each copy's counter into that copy's start within the tile's segment),
+// bucket[slot] = depth_bits << 32 | index; also packs the splat records and, with
+// the Compact Box, zeroes the gradient records of the candidates that are no pairs.
+template <bool CB, bool SCATTER>
+__global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, const ushort4* __restrict__ rect,
+                                                    const float* __restrict__ depth,
+                                                    const float2* __restrict__ mean2d,
+                                                    const float4* __restrict__ conic_opacity,
+                                                    const float* __restrict__ rgb, CfgDev cfg,
+                                                    const uint32_t* __restrict__ rec_offsets, int tiles_x,
+                                                    int num_tiles, uint32_t* __restrict__ tile_counter,
+                                                    const uint2* __restrict__ ranges, uint32_t P,
+                                                    uint64_t* __restrict__ bucket, float4* __restrict__ splats,
+                                                    float4* __restrict__ pair_grad)
+{
+    extern __shared__ uint32_t s_tile[];   // this workgroup's counter per tile
+    uint32_t* const my_row = tile_counter + (size_t)blockIdx.x * num_tiles;
+    for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) s_tile[t] = SCATTER ? my_row[t] : 0u;
+    __syncthreads();
+    const uint32_t lane = lane_id();
+    // (every wavefront of the workgroup walks its own 64 Gaussians per round; no barrier inside the rounds)
+    for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i - lane < n;
+         i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
+    const bool valid = i < n;
+    const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
+    const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
+    const uint32_t cnt = w * h;
+    const uint32_t roff = (SCATTER && valid) ? rec_offsets[i] : 0u;
+    const uint32_t dbits = (SCATTER && cnt) ? __float_as_uint(depth[i]) : 0u;
+    float mx = 0.f, my = 0.f, A = 1.f, B = 0.f, C = 1.f, Q = 0.f;
+    if (cnt && (CB || SCATTER)) {
+        const float2 m = mean2d[i];
+        const float4 co = conic_opacity[i];
+        if (CB) { mx = m.x; my = m.y; A = co.x; B = co.y; C = co.z; Q = cb_threshold(co.w, cfg); }
+        if (SCATTER) {
+            float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
+            rec[0] = make_float4(m.x, m.y, co.x, co.y);
+            rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
+            rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(roff), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
+                                 __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
+        }
+    }
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    const uint32_t excl = inc - cnt;
+    const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
+    const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
+    for (uint32_t j0 = 0; j0 < total; j0 += 64) {
+        const bool live = j0 + lane < total;
+        const uint32_t j = min(j0 + lane, total - 1);
+        uint32_t s = 0;
+#pragma unroll
+        for (uint32_t step = 32; step >= 1; step >>= 1) {
+            const uint32_t t = s + step;
+            const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
+            s = e <= j ? t : s;
+        }
+        const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);
+        const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
+        const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
+        uint32_t row = (uint32_t)((float)k / (float)ow);
+        while (row * ow > k) row--;
+        while ((row + 1) * ow <= k) row++;
+        const uint32_t col = k - row * ow;
+        const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
+        bool hit = live;
+        if (CB) {
+            const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
+            const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
+            const float oQ = __shfl(Q, (int)s, 64);
+            hit = live && cb_tile_hit(omx, omy, oA, oB, oC, oQ, (int)tx, (int)ty);
+        }
+        const uint32_t tile = ty * (uint32_t)tiles_x + tx;
+        if (!SCATTER) {
+            if (hit) atomicAdd(&s_tile[tile], 1u);
+        } else {
+            const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
+            const uint32_t oroff = (uint32_t)__shfl((int)roff, (int)s, 64);
+            if (hit) {
+                const uint32_t slot = ranges[tile].x + atomicAdd(&s_tile[tile], 1u);
+                if (slot < P) bucket[slot] = ((uint64_t)od << 32) | (uint32_t)(i - lane + s);
+            } else if (CB && live) {
+                float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
+                const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                g[0] = z; g[1] = z; g[2] = z;
+            }
+        }
+    }
+    }
+    if (!SCATTER) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) my_row[t] = s_tile[t];
+    }
+}
+
+// Per tile: its count summed over the workgroups' rows -> tile_total; each row's counter is replaced by the
+// number of the tile's pairs in the rows before it (where that workgroup's pairs start within the tile's
+// segment).  A workgroup takes 64 tiles; its wavefront g takes rows [64 g, 64 g + 64) of each.
+__global__ __launch_bounds__(64 * (TILE_COPIES / 64)) void k_tile_sum(uint32_t* __restrict__ count, int num_tiles,
+                                                                     uint32_t* __restrict__ tile_total)
+{
+    constexpr int GROUPS = TILE_COPIES / 64;
+    __shared__ uint32_t gsum[GROUPS][64];
+    const int g = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 64 + lane;
+    uint32_t part[64];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < 64; k++) {
+        part[k] = t < num_tiles ? count[(size_t)(g * 64 + k) * num_tiles + t] : 0u;
+        sum += part[k];
+    }
+    gsum[g][lane] = sum;
+    __syncthreads();
+    uint32_t run = 0, all = 0;
+#pragma unroll
+    for (int q = 0; q < GROUPS; q++) {
+        run += q < g ? gsum[q][lane] : 0u;
+        all += gsum[q][lane];
+    }
+    if (t >= num_tiles) return;
+#pragma unroll
+    for (int k = 0; k < 64; k++) {
+        count[(size_t)(g * 64 + k) * num_tiles + t] = run;
+        run += part[k];
+    }
+    if (g == 0) tile_total[t] = all;
+}
+
+// One workgroup: exclusive scan of the tile totals -> ranges [first, last); totals[0] = sum,
+// totals[1] = longest list; and the order in which the render kernels take the tiles (longest list first,
+// bucketed by length / 8, as k_tile_order).  Thread t owns the consecutive tiles [t*per, t*per + per).
+__global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__ tile_total, int num_tiles,
+                                                    uint2* __restrict__ ranges, uint32_t* __restrict__ order,
+                                                    uint64_t* __restrict__ totals)
+{
+    constexpr int NB = 512;
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t max_s;
+    __shared__ uint32_t cnt[NB];
+    for (int b = threadIdx.x; b < NB; b += 1024) cnt[b] = 0;
+    if (threadIdx.x == 0) max_s = 0;
+    __syncthreads();
+    constexpr int PER_MAX = (TILE_LDS_MAX_TILES + 1023) / 1024;   // this path is only taken up to that many tiles
+    const int per = (num_tiles + 1023) / 1024;
+    const int t0 = threadIdx.x * per;
+    auto bucket = [](uint32_t len) { return (int)(NB - 1 - min(len >> 3, (uint32_t)NB - 1)); };
+    uint32_t c[PER_MAX];   // this thread's tile totals, read once
+    uint32_t v = 0, mymax = 0;
+#pragma unroll
+    for (int q = 0; q < PER_MAX; q++) {
+        const bool in = q < per && t0 + q < num_tiles;
+        c[q] = in ? tile_total[t0 + q] : 0u;
+        v += c[q];
+        mymax = max(mymax, c[q]);
+        if (in) atomicAdd(&cnt[bucket(c[q])], 1u);
+    }
+    const uint32_t inc = wave_inclusive_scan(v);
+    if (lane_id() == 63) wsum[threadIdx.x >> 6] = inc;
+    if (mymax) atomicMax(&max_s, mymax);
+    __syncthreads();
+    uint32_t run = inc - v;
+    for (int w = 0; w < (int)(threadIdx.x >> 6); w++) run += wsum[w];
+#pragma unroll
+    for (int q = 0; q < PER_MAX; q++) {
+        if (q < per && t0 + q < num_tiles) ranges[t0 + q] = c[q] ? make_uint2(run, run + c[q]) : make_uint2(0u, 0u);
+        run += c[q];
+    }
+    if (threadIdx.x == 1023) { totals[0] = run; totals[1] = max_s; }
+    // tile order: exclusive prefix over the 512 length buckets by one wavefront, then a counting placement
+    if (threadIdx.x < 64) {
+        uint32_t b8[8], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 8; q++) { b8[q] = cnt[threadIdx.x * 8 + q]; sum += b8[q]; }
+        uint32_t pre = wave_inclusive_scan(sum) - sum;
+#pragma unroll
+        for (int q = 0; q < 8; q++) { cnt[threadIdx.x * 8 + q] = pre; pre += b8[q]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER_MAX; q++)
+        if (q < per && t0 + q < num_tiles) order[atomicAdd(&cnt[bucket(c[q])], 1u)] = (uint32_t)(t0 + q);
+}
+
+// Step (3): one workgroup sorts one tile's segment in LDS (bitonic network on the 64-bit words, padded to
+// a power of two with all-ones words) and writes the final keys tile << 32 | depth_bits and the Gaussian
+// indices.  Thread t does compare-exchange t (+256, ...) of a step.  (Replacing the workgroup barrier by a
+// wavefront-level one for the steps at distance <= 64, which stay inside one wavefront's 128 words, and a
+// register/shuffle variant of those steps, were both measured slower.)
+// Handles the tiles whose length is in (len_lo, CAP]; the others are left to another launch.
+template <int CAP>
+__global__ __launch_bounds__(256) void k_tile_sort(const uint2* __restrict__ ranges,
+                                                   const uint32_t* __restrict__ tile_order,
+                                                   const uint64_t* __restrict__ bucket, int len_lo,
+                                                   uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
+{
+    __shared__ uint64_t k[CAP];
+    const uint32_t tile = tile_order[blockIdx.x];
+    const uint2 r = ranges[tile];
+    const int n = (int)(r.y - r.x);
+    if (n <= len_lo || n > CAP) return;   // (uniform over the workgroup)
+    int N = 2;
+    while (N < n) N <<= 1;
+    for (int i = threadIdx.x; i < N; i += 256) k[i] = i < n ? bucket[r.x + i] : ~0ull;
+    __syncthreads();
+    for (int k2 = 2; k2 <= N; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (N >> 1); t += 256) {
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int hi = lo | j;
+                const bool up = (lo & k2) == 0;
+                const uint64_t a = k[lo], b = k[hi];
+                if ((a > b) == up) { k[lo] = b; k[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const uint64_t v = k[i];
+        keys_out[r.x + i] = ((uint64_t)tile << 32) | (v >> 32);
+        vals_out[r.x + i] = (uint32_t)v;
+    }
+}
+
 // ---- radix sort -------------------------------------------------------------------------
 // One pass ranks RADIX_BLOCK_KEYS keys per workgroup on a digit of up to RADIX_BITS bits (the live key
 // bits are split into the fewest such digits, of equal width).  Wave w of the workgroup owns the
@@ -473,6 +712,59 @@ hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& p
                        proj.rgb, cfg, offsets, rec_offsets, tiles_x, (uint32_t)P, keys, vals,
                        reinterpret_cast<float4*>(splats),
                        reinterpret_cast<float4*>(pair_grad));
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
+                             int num_tiles, uint32_t* tile_count, uint32_t* tile_total, uint2* ranges,
+                             uint32_t* tile_order, uint64_t* totals)
+{
+    {
+        const dim3 grid(TILE_COPIES), block(TILE_PAIR_THREADS);
+        const size_t lds = (size_t)num_tiles * sizeof(uint32_t);
+        const ushort4* rect = reinterpret_cast<const ushort4*>(proj.rect);
+        const float2* m2 = reinterpret_cast<const float2*>(proj.mean2d);
+        const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
+        if (cfg.compact_box)
+            hipLaunchKernelGGL((k_tile_pairs<true, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
+                               nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr);
+        else
+            hipLaunchKernelGGL((k_tile_pairs<false, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb,
+                               cfg, nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr);
+    }
+    hipLaunchKernelGGL(k_tile_sum, dim3((unsigned)((num_tiles + 63) / 64)), dim3(64 * (TILE_COPIES / 64)), 0, st, tile_count,
+                       num_tiles, tile_total);
+    hipLaunchKernelGGL(k_tile_scan, dim3(1), dim3(1024), 0, st, tile_total, num_tiles, ranges, tile_order, totals);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
+                                    const uint32_t* rec_offsets, int tiles_x, int num_tiles, int64_t P, int max_len,
+                                    const uint2* ranges, uint32_t* cursor, const uint32_t* tile_order, uint64_t* bucket,
+                                    uint64_t* keys_out, uint32_t* vals_out, float* splats, float* pair_grad)
+{
+    if (n > 0) {
+        const dim3 grid(TILE_COPIES), block(TILE_PAIR_THREADS);
+        const size_t lds = (size_t)num_tiles * sizeof(uint32_t);
+        const ushort4* rect = reinterpret_cast<const ushort4*>(proj.rect);
+        const float2* m2 = reinterpret_cast<const float2*>(proj.mean2d);
+        const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
+        if (cfg.compact_box)
+            hipLaunchKernelGGL((k_tile_pairs<true, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
+                               rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
+                               reinterpret_cast<float4*>(pair_grad));
+        else
+            hipLaunchKernelGGL((k_tile_pairs<false, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
+                               rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
+                               reinterpret_cast<float4*>(pair_grad));
+    }
+    if (P > 0) {
+        hipLaunchKernelGGL(k_tile_sort<TILE_SORT_SMALL>, dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket, 0,
+                           keys_out, vals_out);
+        if (max_len > TILE_SORT_SMALL)
+            hipLaunchKernelGGL(k_tile_sort<TILE_SORT_MAX>, dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket,
+                               TILE_SORT_SMALL, keys_out, vals_out);
+    }
     return hipGetLastError();
 }
 

@@ -28,7 +28,7 @@ def test_default_config_and_struct_layouts_match_header():
     c = B.default_config()
     assert c.tile == 16 and c.score_mode == 0
     assert abs(c.alpha_min - 1 / 255) < 1e-9 and abs(c.alpha_max - 0.99) < 1e-7 and abs(c.T_min - 1e-4) < 1e-10
-    assert ctypes.sizeof(B.fs_config) == 52 and ctypes.sizeof(B.fs_camera) == 72
+    assert ctypes.sizeof(B.fs_config) == 56 and ctypes.sizeof(B.fs_camera) == 72
     assert ctypes.sizeof(B.fs_gaussians) == 56 and ctypes.sizeof(B.fs_projected) == 56
     assert ctypes.sizeof(B.fs_bins) == 80 and ctypes.sizeof(B.fs_grads) == 72 and ctypes.sizeof(B.fs_select_params) == 28
 

@@ -194,3 +194,36 @@ def test_error_codes(ctx):
     p = B.fs_projected()
     assert lib.fs_preprocess(ctx.handle, ctypes.byref(g), ctypes.byref(cam), ctypes.byref(p)) == -1
     assert b"fs_preprocess" in lib.fs_last_error(ctx.handle)
+
+
+@pytest.mark.parametrize("n,W,H,mode,lo,hi", [
+    (3000, 203, 117, 1, 0, 2048),          # forced global radix sort
+    (3000, 203, 117, 0, 0, 2048),          # per-tile LDS sort, 16 KB variant
+    (40000, 70, 50, 0, 2049, 8192),        # lists that need the 64 KB variant
+    (40000, 70, 50, 1, 2049, 8192),
+    (90000, 40, 33, 0, 8193, 10 ** 9),     # lists beyond LDS: automatic fall-back to the radix sort
+])
+def test_pair_order_is_the_same_whichever_way_it_is_computed(orc32, n, W, H, mode, lo, hi):
+    """Keys, order and ranges bit-exact for both orderings of fs_bin_sort, at list lengths that reach
+    each of its code paths; image and n_contrib as well."""
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.sort_mode = mode
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(900 + n % 97, n, W, H, sh_degree=0, log_scale=(-3.2, 0.7), spread=1.1)
+    sc.means[5:400:5, 2] = sc.means[5, 2]                  # equal depths: ties broken by index
+    cam = sc.cameras[0]
+    g = gpu_pipeline(c, sc, cam)
+    p_o = orc32.preprocess(sc, cam)
+    b_o = orc32.bin_sort(p_o, cam)
+    L = b_o.tile_ranges[:, 1].astype(np.int64) - b_o.tile_ranges[:, 0]
+    assert lo <= L.max() <= hi, int(L.max())
+    assert g["num_pairs"] == b_o.num_pairs
+    assert np.array_equal(g["keys_sorted"], b_o.keys_sorted)
+    assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted)
+    assert np.array_equal(g["tile_ranges"], b_o.tile_ranges)
+    if n <= 40000:
+        img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
+        assert np.array_equal(g["n_contrib"], nc)
+        assert np.abs(g["image"] - img).max() <= 1e-4
+    c.close()
