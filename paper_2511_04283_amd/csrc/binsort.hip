@@ -319,7 +319,8 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
 {
     extern __shared__ uint32_t s_tile[];   // this workgroup's counter per tile
     uint32_t* const my_row = tile_counter + (size_t)blockIdx.x * num_tiles;
-    for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) s_tile[t] = SCATTER ? my_row[t] : 0u;
+    // placement: the counter starts at the absolute position of this workgroup's first pair of the tile
+    for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) s_tile[t] = SCATTER ? ranges[t].x + my_row[t] : 0u;
     __syncthreads();
     const uint32_t lane = lane_id();
     // (every wavefront of the workgroup walks its own 64 Gaussians per round; no barrier inside the rounds)
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
             const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
             const uint32_t oroff = (uint32_t)__shfl((int)roff, (int)s, 64);
             if (hit) {
-                const uint32_t slot = ranges[tile].x + atomicAdd(&s_tile[tile], 1u);
+                const uint32_t slot = atomicAdd(&s_tile[tile], 1u);
                 if (slot < P) bucket[slot] = ((uint64_t)od << 32) | (uint32_t)(i - lane + s);
             } else if (CB && live) {
                 float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
