@@ -552,22 +552,30 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
             stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
             if (wave_on) {
                 const int len = start < my_last ? s.len[my_sub] : 0;
-                for (int k = 0; __ballot(k < len) != 0; k++) {
-                    const int j = s.list[my_sub][k & (BATCH - 1)];
-                    const float2 xy = s.xy[j];
-                    const float4 co = s.co[j];
-                    const float dx = pw.px - xy.x, dy = pw.py - xy.y;
-                    const float u = __builtin_fmaf(co.y, dy, co.x * dx);
-                    const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
-                    const float power = -0.5f * q;
-                    bool act = (k < len) & (start + j < my_last) & !(power > 0.0f) & !(power < cfg.power_min);
-                    if (__ballot(act) == 0) continue;
-                    const float alpha = fminf(cfg.alpha_max, co.w * exp_c(power));
-                    act = act & (alpha >= cfg.alpha_min);
-                    const float w = alpha * T;
-                    const bool hit = act & (cfg.score_mode == FS_SCORE_ALPHA || w > cfg.alpha_min);
-                    T = act ? T * (1.0f - alpha) : T;
-                    if (hit) atomicAdd(&s_cnt[j], 1);
+                // two list entries per trip: their alphas are independent, only the transmittance chains
+                for (int k = 0; __ballot(k < len) != 0; k += 2) {
+                    const int j0 = s.list[my_sub][k & (BATCH - 1)], j1 = s.list[my_sub][(k + 1) & (BATCH - 1)];
+                    const float2 xy0 = s.xy[j0], xy1 = s.xy[j1];
+                    const float4 co0 = s.co[j0], co1 = s.co[j1];
+                    const float dx0 = pw.px - xy0.x, dy0 = pw.py - xy0.y;
+                    const float dx1 = pw.px - xy1.x, dy1 = pw.py - xy1.y;
+                    const float q0 = __builtin_fmaf(dx0, __builtin_fmaf(co0.y, dy0, co0.x * dx0), (co0.z * dy0) * dy0);
+                    const float q1 = __builtin_fmaf(dx1, __builtin_fmaf(co1.y, dy1, co1.x * dx1), (co1.z * dy1) * dy1);
+                    const float power0 = -0.5f * q0, power1 = -0.5f * q1;
+                    bool act0 = (k < len) & (start + j0 < my_last) & !(power0 > 0.0f) & !(power0 < cfg.power_min);
+                    bool act1 = (k + 1 < len) & (start + j1 < my_last) & !(power1 > 0.0f) & !(power1 < cfg.power_min);
+                    if (__ballot(act0 | act1) == 0) continue;
+                    // (an inactive entry's exponent may be anything: clamp it so that exp_c stays in range)
+                    const float alpha0 = fminf(cfg.alpha_max, co0.w * exp_c(act0 ? power0 : 0.0f));
+                    const float alpha1 = fminf(cfg.alpha_max, co1.w * exp_c(act1 ? power1 : 0.0f));
+                    act0 = act0 & (alpha0 >= cfg.alpha_min);
+                    act1 = act1 & (alpha1 >= cfg.alpha_min);
+                    const bool hit0 = act0 & (cfg.score_mode == FS_SCORE_ALPHA || alpha0 * T > cfg.alpha_min);
+                    T = act0 ? T * (1.0f - alpha0) : T;
+                    const bool hit1 = act1 & (cfg.score_mode == FS_SCORE_ALPHA || alpha1 * T > cfg.alpha_min);
+                    T = act1 ? T * (1.0f - alpha1) : T;
+                    if (hit0) atomicAdd(&s_cnt[j0], 1);
+                    if (hit1) atomicAdd(&s_cnt[j1], 1);
                 }
             }
             __syncthreads();
