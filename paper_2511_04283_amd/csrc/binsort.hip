@@ -326,70 +326,71 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
     // (every wavefront of the workgroup walks its own 64 Gaussians per round; no barrier inside the rounds)
     for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i - lane < n;
          i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
-    const bool valid = i < n;
-    const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
-    const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
-    const uint32_t cnt = w * h;
-    const uint32_t roff = (SCATTER && valid) ? rec_offsets[i] : 0u;
-    const uint32_t dbits = (SCATTER && cnt) ? __float_as_uint(depth[i]) : 0u;
-    float mx = 0.f, my = 0.f, A = 1.f, B = 0.f, C = 1.f, Q = 0.f;
-    if (cnt && (CB || SCATTER)) {
-        const float2 m = mean2d[i];
-        const float4 co = conic_opacity[i];
-        if (CB) { mx = m.x; my = m.y; A = co.x; B = co.y; C = co.z; Q = cb_threshold(co.w, cfg); }
-        if (SCATTER) {
-            float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
-            rec[0] = make_float4(m.x, m.y, co.x, co.y);
-            rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
-            rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(roff), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
-                                 __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
-        }
-    }
-    const uint32_t inc = wave_inclusive_scan(cnt);
-    const uint32_t excl = inc - cnt;
-    const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
-    const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
-    for (uint32_t j0 = 0; j0 < total; j0 += 64) {
-        const bool live = j0 + lane < total;
-        const uint32_t j = min(j0 + lane, total - 1);
-        uint32_t s = 0;
-#pragma unroll
-        for (uint32_t step = 32; step >= 1; step >>= 1) {
-            const uint32_t t = s + step;
-            const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
-            s = e <= j ? t : s;
-        }
-        const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);
-        const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
-        const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
-        uint32_t row = (uint32_t)((float)k / (float)ow);
-        while (row * ow > k) row--;
-        while ((row + 1) * ow <= k) row++;
-        const uint32_t col = k - row * ow;
-        const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
-        bool hit = live;
-        if (CB) {
-            const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
-            const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
-            const float oQ = __shfl(Q, (int)s, 64);
-            hit = live && cb_tile_hit(omx, omy, oA, oB, oC, oQ, (int)tx, (int)ty);
-        }
-        const uint32_t tile = ty * (uint32_t)tiles_x + tx;
-        if (!SCATTER) {
-            if (hit) atomicAdd(&s_tile[tile], 1u);
-        } else {
-            const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
-            const uint32_t oroff = (uint32_t)__shfl((int)roff, (int)s, 64);
-            if (hit) {
-                const uint32_t slot = atomicAdd(&s_tile[tile], 1u);
-                if (slot < P) bucket[slot] = ((uint64_t)od << 32) | (uint32_t)(i - lane + s);
-            } else if (CB && live) {
-                float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
-                const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-                g[0] = z; g[1] = z; g[2] = z;
+        const bool valid = i < n;
+        const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
+        const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
+        const uint32_t cnt = w * h;
+        const uint32_t roff = (SCATTER && valid) ? rec_offsets[i] : 0u;
+        const uint32_t dbits = (SCATTER && cnt) ? __float_as_uint(depth[i]) : 0u;
+        float mx = 0.f, my = 0.f, A = 1.f, B = 0.f, C = 1.f, Q = 0.f;
+        if (cnt && (CB || SCATTER)) {
+            const float2 m = mean2d[i];
+            const float4 co = conic_opacity[i];
+            if (CB) { mx = m.x; my = m.y; A = co.x; B = co.y; C = co.z; Q = cb_threshold(co.w, cfg); }
+            if (SCATTER) {
+                float4* rec = splats + (size_t)i * (SPLAT_REC / 4);
+                rec[0] = make_float4(m.x, m.y, co.x, co.y);
+                rec[1] = make_float4(co.z, co.w, rgb[3 * i], rgb[3 * i + 1]);
+                rec[2] = make_float4(rgb[3 * i + 2], __uint_as_float(roff), __uint_as_float((uint32_t)r.x | (uint32_t)r.y << 16),
+                                     __uint_as_float((uint32_t)r.z | (uint32_t)r.w << 16));
             }
         }
-    }
+        const uint32_t inc = wave_inclusive_scan(cnt);
+        const uint32_t excl = inc - cnt;
+        const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
+        const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
+        for (uint32_t j0 = 0; j0 < total; j0 += 64) {
+            const bool live = j0 + lane < total;
+            const uint32_t j = min(j0 + lane, total - 1);
+            uint32_t s = 0;
+#pragma unroll
+            for (uint32_t step = 32; step >= 1; step >>= 1) {
+                const uint32_t t = s + step;
+                const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
+                s = e <= j ? t : s;
+            }
+            const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);
+            const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
+            const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
+            uint32_t row = (uint32_t)((float)k / (float)ow);
+            while (row * ow > k) row--;
+            while ((row + 1) * ow <= k) row++;
+            const uint32_t col = k - row * ow;
+            const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
+            bool hit = live;
+            if (CB) {
+                const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
+                const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
+                const float oQ = __shfl(Q, (int)s, 64);
+                hit = live && cb_tile_hit(omx, omy, oA, oB, oC, oQ, (int)tx, (int)ty);
+            }
+            const uint32_t tile = ty * (uint32_t)tiles_x + tx;
+            hit = hit && tile < (uint32_t)num_tiles;   // (always true for a rect made for this camera)
+            if (!SCATTER) {
+                if (hit) atomicAdd(&s_tile[tile], 1u);
+            } else {
+                const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
+                const uint32_t oroff = (uint32_t)__shfl((int)roff, (int)s, 64);
+                if (hit) {
+                    const uint32_t slot = atomicAdd(&s_tile[tile], 1u);
+                    if (slot < P) bucket[slot] = ((uint64_t)od << 32) | (uint32_t)(i - lane + s);
+                } else if (CB && live) {
+                    float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
+                    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                    g[0] = z; g[1] = z; g[2] = z;
+                }
+            }
+        }
     }
     if (!SCATTER) {
         __syncthreads();

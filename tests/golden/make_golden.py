@@ -11,7 +11,7 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
-from oracle import Oracle  # noqa: E402
+from oracle import Config, Oracle  # noqa: E402
 from paper_2511_04283_amd import scenes  # noqa: E402
 
 
@@ -19,10 +19,10 @@ def sha(a):
     return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()[:32]
 
 
-def digest(cfg, n=None):
+def digest(cfg, n=None, compact_box=False):
     sc = scenes.make_scene(cfg, n)
     cam = sc.cameras[0]
-    o = Oracle(np.float32)
+    o = Oracle(np.float32, Config(compact_box=compact_box))
     proj, bins, img, fT, nc = o.forward(sc, cam)
     tgt = scenes.target_image(cfg, 0, cam)
     mask, thr, _ = o.error_mask(img, tgt, rule=0, k=1.0)
@@ -38,7 +38,8 @@ def digest(cfg, n=None):
 
 
 if __name__ == "__main__":
-    out = {"cfg1": digest(1), "cfg2_n20000": digest(2, 20000)}
+    out = {"cfg1": digest(1), "cfg2_n20000": digest(2, 20000), "cfg1_compact_box": digest(1, None, True),
+           "cfg2_n20000_compact_box": digest(2, 20000, True)}
     with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "oracle_digest.json"), "w") as f:
         json.dump(out, f, indent=1, sort_keys=True)
     print(json.dumps(out, indent=1, sort_keys=True))

@@ -15,7 +15,8 @@ def test_oracle_digest_reproduces():
     with open(os.path.join(HERE, "golden", "oracle_digest.json")) as f:
         want = json.load(f)
     import pytest
-    for key, args in (("cfg1", (1,)), ("cfg2_n20000", (2, 20000))):
+    for key, args in (("cfg1", (1,)), ("cfg2_n20000", (2, 20000)), ("cfg1_compact_box", (1, None, True)),
+                      ("cfg2_n20000_compact_box", (2, 20000, True))):
         got = mg.digest(*args)
         if got["inputs"] != want[key]["inputs"]:
             pytest.skip("numpy on this host draws different inputs (libm/SIMD differences in the generator)")
