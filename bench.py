@@ -138,6 +138,25 @@ def main() -> int:
     timed = ctx.fs_profile_read()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # the training iteration alone (no mask / score pass): preprocess, bin_sort, render_fwd, loss, render_bwd
+    def train_iter():
+        ctx.fs_preprocess(g, fcam, proj)
+        b_ = ctx.fs_bin_sort(proj, fcam)
+        ctx.fs_render_fwd(proj, b_, fcam, image, final_T, n_contrib)
+        if args.photo_loss:
+            ctx.fs_photo_loss(image, target, 0.2, dL, out3)
+        else:
+            ctx.fs_l1_grad(image, target, dL, loss)
+        ctx.fs_render_bwd(g, fcam, proj, b_, final_T, n_contrib, dL, grads)
+    ctx.fs_profile_enable(())
+    train_iter()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        train_iter()
+    torch.cuda.synchronize()
+    fwd_bwd_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+
     # untimed: per-kernel breakdown of the same steps
     ctx.fs_profile_enable(None)
     for _ in range(max(3, args.steps // 2)):
@@ -198,9 +217,14 @@ def main() -> int:
         "render_fwd": {"avg_launch_ms": round(fwd_ms, 4),
                        "achieved_tflops": round(fwd_flops / (fwd_ms * 1e-3) / 1e12, 3) if fwd_ms > 0 else 0.0},
         "work": {"evals_fwd_upper_bound": evals_fwd_bound, "evals_bwd": evals_bwd, "blends": blends},
+        "fwd_bwd_only": {"ms": round(fwd_bwd_ms, 4), "iters_per_s": round(1e3 / fwd_bwd_ms, 2),
+                         "calls": "preprocess+bin_sort+render_fwd+loss+render_bwd (no mask, no score pass)"},
         "loss": float(out3[2].item()) if args.photo_loss else float(loss.item()),
     }
 
+    copy_gbs, fma_tf = ctx.fs_measure_peaks(1 << 30)
+    out["measured_peaks"] = {"copy_GBps": round(copy_gbs, 1), "fp32_fma_TFLOPs_unpacked": round(fma_tf, 2),
+                             "note": "1 GiB device copy (read + write) and chains of independent v_fma_f32, same process"}
     if not args.no_cpu_baseline and not args.train_iteration:   # (the oracle leg times the hot path on the untouched scene)
         from oracle import Config, Oracle
         o = Oracle(np.float32, Config(compact_box=args.compact_box, cb_beta=args.cb_beta))

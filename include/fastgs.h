@@ -316,6 +316,12 @@ enum {
 int fs_profile_enable(fs_ctx *ctx, uint32_t group_mask);
 int fs_profile_read(fs_ctx *ctx, int32_t group, const char **name, double *total_ms, int64_t *launches);
 
+/* Two reference measurements on the ctx's device and stream, for the roofline figures: a streaming copy of
+ * `copy_bytes` (device scratch, read + written once: *copy_gbs = 2 * copy_bytes / time) and chains of
+ * independent fp32 fused multiply-adds, 2 flops each, without packed-fp32 instructions (*fma_tflops).
+ * Either output may be NULL.  Synchronises the stream.  Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP. */
+int fs_measure_peaks(fs_ctx *ctx, int64_t copy_bytes, double *copy_gbs, double *fma_tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_adam_step", "fs_grad_accumulate", "fs_adam_interval", "fs_activate", "fs_activate_bwd",
-           "fs_profile_enable", "fs_profile_read")
+           "fs_profile_enable", "fs_profile_read", "fs_measure_peaks")
 KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
                  "render_bwd", "preprocess_bwd", "error_mask", "score")
 
@@ -116,6 +116,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_adam_interval.argtypes = [i32]
     lib.fs_activate.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp]
     lib.fs_activate_bwd.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.fs_measure_peaks.argtypes = [vp, i64, P(ctypes.c_double), P(ctypes.c_double)]
     lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
     for name in EXPORTS:
@@ -393,6 +394,12 @@ class Context:
             s_p = torch.empty(n, dtype=torch.float32, device=self.device)
         self._check(self.lib.fs_prune_score_normalize(self.handle, _ptr(acc), n, _ptr(s_p)), "fs_prune_score_normalize")
         return s_p
+
+    def fs_measure_peaks(self, copy_bytes=1 << 30):
+        """(streaming-copy GB/s, plain fp32 FMA TFLOP/s) measured on this context's device."""
+        c, f = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        self._check(self.lib.fs_measure_peaks(self.handle, int(copy_bytes), ctypes.byref(c), ctypes.byref(f)), "fs_measure_peaks")
+        return c.value, f.value
 
     def fs_adam_step(self, param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-15, grad_scale=1.0,
                      zero_grad=False):

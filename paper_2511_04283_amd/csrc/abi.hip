@@ -649,6 +649,59 @@ int fs_activate_bwd(fs_ctx* ctx, int64_t n, const float* raw_scales, const float
     return FS_OK;
 }
 
+int fs_measure_peaks(fs_ctx* ctx, int64_t copy_bytes, double* copy_gbs, double* fma_tflops)
+{
+    if (!ctx) return FS_EINVAL;
+    if (copy_bytes < 0 || copy_bytes > ((int64_t)1 << 33)) return fail(ctx, FS_EINVAL, "fs_measure_peaks: bad size");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    hipStream_t st = ctx->stream;
+    hipEvent_t a = nullptr, b = nullptr;
+    FS_HIP(hipEventCreate(&a), "hipEventCreate");
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return hip_fail(ctx, hipGetLastError(), "hipEventCreate"); }
+    int rc = FS_OK;
+    float ms = 0.f;
+    if (copy_gbs && copy_bytes >= 16) {
+        const int64_t bytes = copy_bytes / 16 * 16;
+        void *src = nullptr, *dst = nullptr;
+        if (hipMalloc(&src, (size_t)bytes) != hipSuccess || hipMalloc(&dst, (size_t)bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            if (src) (void)hipFree(src);
+            rc = fail(ctx, FS_ENOMEM, "fs_measure_peaks: allocation failed%s");
+        } else {
+            hipError_t e = launch_fill_u32(st, static_cast<uint32_t*>(src), 0x3f800000u, bytes / 4);
+            for (int r = 0; r < 3 && e == hipSuccess; r++) {   // the third run is the timed one
+                if (r == 2) e = hipEventRecord(a, st);
+                if (e == hipSuccess) e = launch_copy(st, src, dst, bytes);
+            }
+            if (e == hipSuccess) e = hipEventRecord(b, st);
+            if (e == hipSuccess) e = hipEventSynchronize(b);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+            if (e != hipSuccess) rc = hip_fail(ctx, e, "fs_measure_peaks (copy)");
+            else *copy_gbs = 2.0 * (double)bytes / ((double)ms * 1e-3) / 1e9;
+            (void)hipStreamSynchronize(st);
+            (void)hipFree(src);
+            (void)hipFree(dst);
+        }
+    }
+    if (rc == FS_OK && fma_tflops) {
+        const int blocks = 256 * 32, iters = 4096;
+        FS_TRY(ensure(ctx, ctx->err_map, (size_t)blocks * 256 * sizeof(float), "fma output"));
+        hipError_t e = hipSuccess;
+        for (int r = 0; r < 2 && e == hipSuccess; r++) {
+            if (r == 1) e = hipEventRecord(a, st);
+            if (e == hipSuccess) e = launch_fma_chain(st, static_cast<float*>(ctx->err_map.ptr), blocks, iters);
+        }
+        if (e == hipSuccess) e = hipEventRecord(b, st);
+        if (e == hipSuccess) e = hipEventSynchronize(b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e != hipSuccess) rc = hip_fail(ctx, e, "fs_measure_peaks (fma)");
+        else *fma_tflops = 2.0 * 8.0 * (double)iters * (double)blocks * 256.0 / ((double)ms * 1e-3) / 1e12;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    return rc;
+}
+
 static int prof_collect(fs_ctx* ctx)
 {
     FS_HIP(hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");

@@ -205,6 +205,11 @@ hipError_t launch_activate_bwd(hipStream_t st, int64_t n, const float* raw_s, co
                                const float* d_s, const float* d_q, const float* d_o, float* d_raw_s, float* d_raw_q,
                                float* d_raw_o);
 
+// reference measurements: streaming copy of `bytes` (multiple of 16), and 8 fma chains x iters per lane on
+// blocks x 256 lanes (out: blocks * 256 floats)
+hipError_t launch_copy(hipStream_t st, const void* src, void* dst, int64_t bytes);
+hipError_t launch_fma_chain(hipStream_t st, float* out, int blocks, int iters);
+
 hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t count);
 
 }  // namespace fs

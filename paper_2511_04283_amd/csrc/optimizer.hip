@@ -109,6 +109,26 @@ __global__ __launch_bounds__(256) void k_activate_bwd(int64_t n, const float* __
     d_raw_o[i] = d_o[i] * sg * (1.0f - sg);
 }
 
+// ---- reference measurements ------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_copy(const float4* __restrict__ src, float4* __restrict__ dst, int64_t nvec)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+}
+
+// 8 independent chains of fused multiply-adds per lane; the result is stored so that nothing is optimised away
+__global__ __launch_bounds__(256) void k_fma_chain(float* __restrict__ out, int iters, float a, float b)
+{
+    float x0 = (float)threadIdx.x, x1 = x0 + 1.f, x2 = x0 + 2.f, x3 = x0 + 3.f, x4 = x0 + 4.f, x5 = x0 + 5.f,
+          x6 = x0 + 6.f, x7 = x0 + 7.f;
+    for (int i = 0; i < iters; i++) {
+        x0 = __builtin_fmaf(x0, a, b); x1 = __builtin_fmaf(x1, a, b); x2 = __builtin_fmaf(x2, a, b);
+        x3 = __builtin_fmaf(x3, a, b); x4 = __builtin_fmaf(x4, a, b); x5 = __builtin_fmaf(x5, a, b);
+        x6 = __builtin_fmaf(x6, a, b); x7 = __builtin_fmaf(x7, a, b);
+    }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
+}
+
 int stream_blocks(int64_t work_items)
 {
     const int64_t b = (work_items + 255) / 256;
@@ -154,6 +174,21 @@ hipError_t launch_activate_bwd(hipStream_t st, int64_t n, const float* raw_s, co
     hipLaunchKernelGGL(k_activate_bwd, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, raw_s,
                        reinterpret_cast<const float4*>(raw_q), raw_o, d_s, reinterpret_cast<const float4*>(d_q), d_o,
                        d_raw_s, reinterpret_cast<float4*>(d_raw_q), d_raw_o);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(hipStream_t st, const void* src, void* dst, int64_t bytes)
+{
+    const int64_t nvec = bytes / 16;
+    if (nvec <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_copy, dim3(stream_blocks(nvec)), dim3(256), 0, st, static_cast<const float4*>(src),
+                       static_cast<float4*>(dst), nvec);
+    return hipGetLastError();
+}
+
+hipError_t launch_fma_chain(hipStream_t st, float* out, int blocks, int iters)
+{
+    hipLaunchKernelGGL(k_fma_chain, dim3(blocks), dim3(256), 0, st, out, iters, 0.999f, 0.001f);
     return hipGetLastError();
 }
 
