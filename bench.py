@@ -157,6 +157,32 @@ def main() -> int:
     torch.cuda.synchronize()
     fwd_bwd_ms = (time.perf_counter() - t2) * 1e3 / args.steps
 
+    # the multi-view score pass of VCD (Sec. 4.2): K views x (preprocess, bin_sort, render_fwd, error_mask,
+    # score_accumulate), counts summed over the views -- for workloads that come with several cameras
+    score_pass = None
+    if len(sc.cameras) > 1:
+        cams = [B.make_camera(c) for c in sc.cameras]
+        tgts = [torch.from_numpy(scenes.target_image(args.config, v, c)).to(dev) for v, c in enumerate(sc.cameras)]
+
+        def views():
+            counts.zero_()
+            for fc, tg in zip(cams, tgts):
+                ctx.fs_preprocess(g, fc, proj)
+                b_ = ctx.fs_bin_sort(proj, fc)
+                ctx.fs_render_fwd(proj, b_, fc, image, final_T, n_contrib)
+                ctx.fs_error_mask(image, tg, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+                ctx.fs_score_accumulate(proj, b_, fc, final_T, n_contrib, mask, counts)
+        views()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        reps = max(1, args.steps // 4)
+        for _ in range(reps):
+            views()
+        torch.cuda.synchronize()
+        sp_ms = (time.perf_counter() - t3) * 1e3 / reps
+        score_pass = {"views": len(cams), "ms": round(sp_ms, 4), "ms_per_view": round(sp_ms / len(cams), 4),
+                      "gaussians_with_s_d_above_5": int((counts.to(torch.float32) / len(cams) > 5.0).sum().item())}
+
     # untimed: per-kernel breakdown of the same steps
     ctx.fs_profile_enable(None)
     for _ in range(max(3, args.steps // 2)):
@@ -220,6 +246,7 @@ def main() -> int:
         "fwd_bwd_only": {"ms": round(fwd_bwd_ms, 4), "iters_per_s": round(1e3 / fwd_bwd_ms, 2),
                          "calls": "preprocess+bin_sort+render_fwd+loss+render_bwd (no mask, no score pass)"},
         "loss": float(out3[2].item()) if args.photo_loss else float(loss.item()),
+        "score_pass": score_pass,
     }
 
     copy_gbs, fma_tf = ctx.fs_measure_peaks(1 << 30)
