@@ -40,6 +40,7 @@ def main() -> int:
     ap.add_argument("--compact-box", action="store_true",
                     help="pairs from the Compact Box (ellipse-tile test, Sec. 4.4) instead of the 3-sigma square")
     ap.add_argument("--cb-beta", type=float, default=1.0)
+    ap.add_argument("--radix-sort", action="store_true", help="order the pairs with the global radix sort (sort_mode)")
     ap.add_argument("--abs-grad", action="store_true",
                     help="also accumulate the absolute positional gradient in the backward pass (split criterion)")
     ap.add_argument("--train-iteration", action="store_true",
@@ -65,6 +66,7 @@ def main() -> int:
     cfg0 = B.default_config()
     cfg0.compact_box = 1 if args.compact_box else 0
     cfg0.cb_beta = args.cb_beta
+    cfg0.sort_mode = B.FS_SORT_RADIX if args.radix_sort else B.FS_SORT_AUTO
     ctx = B.Context(dev, cfg0)
     g = B.Gaussians.from_scene(sc, dev)
     fcam = B.make_camera(cam)
