@@ -227,3 +227,21 @@ def test_pair_order_is_the_same_whichever_way_it_is_computed(orc32, n, W, H, mod
         assert np.array_equal(g["n_contrib"], nc)
         assert np.abs(g["image"] - img).max() <= 1e-4
     c.close()
+
+
+def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
+    """2016 x 2000 px = 126 x 125 = 15 750 tiles: beyond the per-tile LDS counters of the tile-bucketed
+    ordering, so fs_bin_sort takes the radix path by itself; results as everywhere else."""
+    sc = scenes.tiny_scene(31, 4000, 2016, 2000, sh_degree=0, log_scale=(-2.5, 0.8), spread=1.0)
+    cam = sc.cameras[0]
+    g = gpu_pipeline(ctx, sc, cam)
+    p_o = orc32.preprocess(sc, cam)
+    b_o = orc32.bin_sort(p_o, cam)
+    assert b_o.tile_ranges.shape[0] == 126 * 125 and b_o.num_pairs > 10000
+    assert g["num_pairs"] == b_o.num_pairs
+    assert np.array_equal(g["keys_sorted"], b_o.keys_sorted)
+    assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted)
+    assert np.array_equal(g["tile_ranges"], b_o.tile_ranges)
+    img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
+    assert np.array_equal(g["n_contrib"], nc)
+    assert np.abs(g["image"] - img).max() <= 1e-4
