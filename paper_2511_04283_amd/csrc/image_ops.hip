@@ -64,6 +64,9 @@ __device__ __forceinline__ double final_reduce(const double* partial, double* sm
     return block_reduce<OP>(v, smem);
 }
 
+// VEC = 4: 16-byte accesses (count a multiple of 4, arrays 16-byte aligned); VEC = 1 otherwise.  The sum is
+// accumulated per thread in element order either way.
+template <int VEC>
 __global__ __launch_bounds__(RED_THREADS) void k_l1_grad(const float* __restrict__ image,
                                                         const float* __restrict__ target, int64_t count,
                                                         float scale, float* __restrict__ dL,
@@ -71,10 +74,24 @@ __global__ __launch_bounds__(RED_THREADS) void k_l1_grad(const float* __restrict
 {
     __shared__ double smem[4];
     double s = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < count; i += (int64_t)RED_BLOCKS * RED_THREADS) {
-        const float d = image[i] - target[i];
-        s += (double)fabsf(d);
-        dL[i] = d > 0.f ? scale : (d < 0.f ? -scale : 0.f);
+    const int64_t stride = (int64_t)RED_BLOCKS * RED_THREADS;
+    if (VEC == 4) {
+        const float4* a4 = reinterpret_cast<const float4*>(image);
+        const float4* b4 = reinterpret_cast<const float4*>(target);
+        float4* d4 = reinterpret_cast<float4*>(dL);
+        for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < (count >> 2); i += stride) {
+            const float4 a = a4[i], b = b4[i];
+            const float d0 = a.x - b.x, d1 = a.y - b.y, d2 = a.z - b.z, d3 = a.w - b.w;
+            s += (double)fabsf(d0); s += (double)fabsf(d1); s += (double)fabsf(d2); s += (double)fabsf(d3);
+            d4[i] = make_float4(d0 > 0.f ? scale : (d0 < 0.f ? -scale : 0.f), d1 > 0.f ? scale : (d1 < 0.f ? -scale : 0.f),
+                                d2 > 0.f ? scale : (d2 < 0.f ? -scale : 0.f), d3 > 0.f ? scale : (d3 < 0.f ? -scale : 0.f));
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < count; i += stride) {
+            const float d = image[i] - target[i];
+            s += (double)fabsf(d);
+            dL[i] = d > 0.f ? scale : (d < 0.f ? -scale : 0.f);
+        }
     }
     s = block_reduce<RED_SUM>(s, smem);
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
@@ -89,21 +106,41 @@ __global__ __launch_bounds__(RED_THREADS) void k_l1_final(const double* __restri
 }
 
 // e = ((|d0| + |d1|) + |d2|) / 3 per pixel; partial sums / minima / maxima per workgroup.
+// VEC = 4: four neighbouring pixels per thread with 16-byte accesses (pixels a multiple of 4, arrays aligned).
+template <int VEC>
 __global__ __launch_bounds__(RED_THREADS) void k_err_map(const float* __restrict__ image,
                                                         const float* __restrict__ target, int64_t pixels,
                                                         float* __restrict__ err, double* __restrict__ partial)
 {
     __shared__ double smem[4];
     double s = 0.0, lo = 1.0e300, hi = -1.0e300;
-    for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < pixels; i += (int64_t)RED_BLOCKS * RED_THREADS) {
-        const float d0 = fabsf(image[i] - target[i]);
-        const float d1 = fabsf(image[pixels + i] - target[pixels + i]);
-        const float d2 = fabsf(image[2 * pixels + i] - target[2 * pixels + i]);
-        const float e = ((d0 + d1) + d2) / 3.0f;
-        err[i] = e;
+    const int64_t stride = (int64_t)RED_BLOCKS * RED_THREADS;
+    auto one = [&](float i0, float i1, float i2, float t0, float t1, float t2) {
+        const float e = ((fabsf(i0 - t0) + fabsf(i1 - t1)) + fabsf(i2 - t2)) / 3.0f;
         s += (double)e;
         lo = (double)e < lo ? (double)e : lo;
         hi = (double)e > hi ? (double)e : hi;
+        return e;
+    };
+    if (VEC == 4) {
+        const int64_t q = pixels >> 2;
+        const float4* a4 = reinterpret_cast<const float4*>(image);
+        const float4* b4 = reinterpret_cast<const float4*>(target);
+        float4* e4 = reinterpret_cast<float4*>(err);
+        for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < q; i += stride) {
+            const float4 a0 = a4[i], a1 = a4[q + i], a2 = a4[2 * q + i];
+            const float4 b0 = b4[i], b1 = b4[q + i], b2 = b4[2 * q + i];
+            float4 e;
+            e.x = one(a0.x, a1.x, a2.x, b0.x, b1.x, b2.x);
+            e.y = one(a0.y, a1.y, a2.y, b0.y, b1.y, b2.y);
+            e.z = one(a0.z, a1.z, a2.z, b0.z, b1.z, b2.z);
+            e.w = one(a0.w, a1.w, a2.w, b0.w, b1.w, b2.w);
+            e4[i] = e;
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < pixels; i += stride)
+            err[i] = one(image[i], image[pixels + i], image[2 * pixels + i], target[i], target[pixels + i],
+                         target[2 * pixels + i]);
     }
     s = block_reduce<RED_SUM>(s, smem);
     lo = block_reduce<RED_MIN>(lo, smem);
@@ -441,7 +478,12 @@ hipError_t launch_l1_grad(hipStream_t st, const float* image, const float* targe
 {
     if (count <= 0) return hipSuccess;
     const float scale = 1.0f / (float)count;
-    hipLaunchKernelGGL(k_l1_grad, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, count, scale, dL, partial);
+    const bool vec = count % 4 == 0 && ((reinterpret_cast<uintptr_t>(image) | reinterpret_cast<uintptr_t>(target) |
+                                         reinterpret_cast<uintptr_t>(dL)) & 15u) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_l1_grad<4>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, count, scale, dL, partial);
+    else
+        hipLaunchKernelGGL(k_l1_grad<1>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, count, scale, dL, partial);
     if (loss_out) hipLaunchKernelGGL(k_l1_final, dim3(1), dim3(RED_THREADS), 0, st, partial, count, loss_out);
     return hipGetLastError();
 }
@@ -450,7 +492,12 @@ hipError_t launch_error_mask(hipStream_t st, const float* image, const float* ta
                              float k, float* err, double* partial, uint8_t* mask, float* thr)
 {
     if (pixels <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_err_map, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, pixels, err, partial);
+    const bool vec = pixels % 4 == 0 && ((reinterpret_cast<uintptr_t>(image) | reinterpret_cast<uintptr_t>(target) |
+                                          reinterpret_cast<uintptr_t>(err)) & 15u) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_err_map<4>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, pixels, err, partial);
+    else
+        hipLaunchKernelGGL(k_err_map<1>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, pixels, err, partial);
     if (rule == FS_MASK_MEAN_STD)
         hipLaunchKernelGGL(k_err_var, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, err, pixels, partial);
     hipLaunchKernelGGL(k_err_threshold, dim3(1), dim3(RED_THREADS), 0, st, partial, pixels, rule, k, thr);
