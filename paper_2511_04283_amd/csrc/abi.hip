@@ -26,10 +26,10 @@ struct fs_ctx {
 
     ScratchBuf offsets;       // uint32 [n]
     ScratchBuf scan_tmp;      // uint64 block sums for the scans
-    ScratchBuf keys[2];       // uint64 [P] ping-pong
+    ScratchBuf keys[2];       // uint64 [P]: final keys and the tiles' unsorted segments, or the radix ping-pong pair
     ScratchBuf vals[2];       // uint32 [P] ping-pong
-    ScratchBuf hist;          // uint32 [256 * radix blocks]
-    ScratchBuf ranges;        // uint32 [tiles, 2]
+    ScratchBuf hist;          // uint32 [RADIX_DIGITS * radix blocks] (radix mode)
+    ScratchBuf ranges;        // uint32: ranges [T,2] | tile order [T] | tile totals [T] | counters [TILE_COPIES,T]
     ScratchBuf pair_grad;     // float  [P, PAIR_REC] per-pair partial gradients of the backward pass
     ScratchBuf splats;        // float  [n, SPLAT_REC] packed projected splats (written by fs_bin_sort)
     ScratchBuf rec_counts;    // uint32 [n] Compact Box: tiles in each Gaussian's box

@@ -1,9 +1,11 @@
-// Gaussian-tile pair binning on gfx950: exclusive scan, key emission, stable LSD radix sort,
-// per-tile ranges.  All integer work; results are unique and reproducible bit for bit.
+// Gaussian-tile pair binning on gfx950: exclusive scans, the pairs of every Gaussian, their order
+// (tile, depth, index) and the per-tile ranges.  All integer work; results are unique and reproducible
+// bit for bit.
 //
-// FastGS Sec. 3 blends "Gaussians sorted by depth" per pixel; Sec. 4.4 names the Gaussian-tile
-// pairs the 3-sigma rule produces.  A pair's key is tile_id << 32 | bits(depth): one global sort
-// yields, for every tile, its Gaussians front to back.
+// FastGS Sec. 3 blends "Gaussians sorted by depth" per pixel; Sec. 4.4 names the Gaussian-tile pairs that
+// the 3-sigma rule (or the Compact Box) produces.  A pair's key is tile_id << 32 | bits(depth).  Two ways
+// to the same order live here: the tile-bucketed one (count per tile, place, sort each tile's segment in
+// LDS), used whenever the lists are short enough, and a global stable LSD radix sort of index-ordered keys.
 #include "common.hpp"
 
 namespace fs {
