@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--compact-box", action="store_true",
                     help="pairs from the Compact Box (ellipse-tile test, Sec. 4.4) instead of the 3-sigma square")
     ap.add_argument("--cb-beta", type=float, default=1.0)
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="fs_render_fwd + fs_l1_grad + fs_error_mask instead of fs_render_fwd_loss + fs_error_mask_fused")
     ap.add_argument("--radix-sort", action="store_true", help="order the pairs with the global radix sort (sort_mode)")
     ap.add_argument("--abs-grad", action="store_true",
                     help="also accumulate the absolute positional gradient in the backward pass (split criterion)")
@@ -94,6 +96,9 @@ def main() -> int:
         adam_v = {k: torch.zeros_like(v) for k, v in params.items()}
         state["it"] = 0
 
+    # the L1 term and the error map are fused into the forward kernel unless asked otherwise (same outputs)
+    fused = not (args.separate_calls or args.photo_loss)
+
     def step():
         if args.train_iteration:
             state["it"] += 1
@@ -101,17 +106,23 @@ def main() -> int:
             g.scales, g.quats, g.opacities = s_, q_, o_
         ctx.fs_preprocess(g, fcam, proj)
         bins = ctx.fs_bin_sort(proj, fcam)
-        ctx.fs_render_fwd(proj, bins, fcam, image, final_T, n_contrib)
-        if args.photo_loss:
-            ctx.fs_photo_loss(image, target, 0.2, dL, out3)
+        if fused:
+            ctx.fs_render_fwd_loss(proj, bins, fcam, target, image, final_T, n_contrib, dL, loss)
         else:
-            ctx.fs_l1_grad(image, target, dL, loss)
+            ctx.fs_render_fwd(proj, bins, fcam, image, final_T, n_contrib)
+            if args.photo_loss:
+                ctx.fs_photo_loss(image, target, 0.2, dL, out3)
+            else:
+                ctx.fs_l1_grad(image, target, dL, loss)
         ctx.fs_render_bwd(g, fcam, proj, bins, final_T, n_contrib, dL, grads)
         if args.train_iteration:
             ctx.fs_activate_bwd(raw["scales"], raw["quats"], raw["opac"], grads["scales"], grads["quats"], grads["opacities"])
             for k in params:
                 ctx.fs_adam_step(params[k], grads[k], adam_m[k], adam_v[k], state["it"], 1e-5)
-        ctx.fs_error_mask(image, target, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+        if fused:
+            ctx.fs_error_mask_fused(H, W, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+        else:
+            ctx.fs_error_mask(image, target, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
         counts.zero_()
         ctx.fs_score_accumulate(proj, bins, fcam, final_T, n_contrib, mask, counts)
         state["bins"] = bins
@@ -144,11 +155,14 @@ def main() -> int:
     def train_iter():
         ctx.fs_preprocess(g, fcam, proj)
         b_ = ctx.fs_bin_sort(proj, fcam)
-        ctx.fs_render_fwd(proj, b_, fcam, image, final_T, n_contrib)
-        if args.photo_loss:
-            ctx.fs_photo_loss(image, target, 0.2, dL, out3)
+        if fused:
+            ctx.fs_render_fwd_loss(proj, b_, fcam, target, image, final_T, n_contrib, dL, loss)
         else:
-            ctx.fs_l1_grad(image, target, dL, loss)
+            ctx.fs_render_fwd(proj, b_, fcam, image, final_T, n_contrib)
+            if args.photo_loss:
+                ctx.fs_photo_loss(image, target, 0.2, dL, out3)
+            else:
+                ctx.fs_l1_grad(image, target, dL, loss)
         ctx.fs_render_bwd(g, fcam, proj, b_, final_T, n_contrib, dL, grads)
     ctx.fs_profile_enable(())
     train_iter()
@@ -236,9 +250,11 @@ def main() -> int:
         "config": {"workload": sc.name + (f"+compact_box(beta={args.cb_beta:g})" if args.compact_box else ""),
                    "gaussians": n, "sh_degree": sc.sh_degree, "image": [W, H],
                    "pairs": int(P), "max_tile_list": int(tile_len.max().item()),
-                   "step": ("activate+" if args.train_iteration else "") + "preprocess+bin_sort+render_fwd+" +
-                           ("photo_loss" if args.photo_loss else "l1_grad") + "+render_bwd+" +
-                           ("activate_bwd+adam+" if args.train_iteration else "") + "error_mask+score_accumulate"},
+                   "step": ("activate+" if args.train_iteration else "") + "preprocess+bin_sort+" +
+                           ("render_fwd_loss(render_fwd+l1_grad+error map fused)" if fused else
+                            "render_fwd+" + ("photo_loss" if args.photo_loss else "l1_grad")) + "+render_bwd+" +
+                           ("activate_bwd+adam+" if args.train_iteration else "") +
+                           ("error_mask_fused" if fused else "error_mask") + "+score_accumulate"},
         "roofline": roofline,
         "kernels_ms": {k: round(v, 4) for k, v in kernels_ms.items()},
         "gaussian_pixel_evals_per_s": round((evals_fwd_bound + evals_bwd) / (ms_per_step * 1e-3), 1),

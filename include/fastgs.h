@@ -7,6 +7,8 @@
  *   fs_bin_sort          Gaussian-tile pairs, ordered by (tile, depth)          (Sec. 3, "sorted by depth")
  *   fs_render_fwd        front-to-back alpha compositing                        (Eqs. (4), (5))
  *   fs_l1_grad           L1 term of the training loss and dL/dC                 (Sec. 4.5)
+ *   fs_render_fwd_loss / fs_error_mask_fused
+ *                        the forward pass with the L1 term and the error map fused into it
  *   fs_render_bwd        gradient of a loss w.r.t. every Gaussian parameter     (chain rule of Eqs. (2)-(5))
  *   fs_error_mask        per-pixel L1 error map and high-error mask             (Sec. 4.2, first three equations)
  *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
@@ -175,6 +177,22 @@ int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int
  * All three are fully overwritten. */
 int fs_render_fwd(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
                   float *image, float *final_T, uint32_t *n_contrib);
+
+/* Steps a6 + a7 in one pass, and the first pass of a10: fs_render_fwd with, fused into the epilogue of its kernel,
+ * dL_dimage = sign(image - target) / (3 H W) (may be NULL), the L1 loss (loss_out: device pointer to one double, may be
+ * NULL) and the per-pixel error map of fs_error_mask, which the ctx keeps for a following fs_error_mask_fused.
+ * Saves reading the finished image twice more.  Same outputs as the separate calls (the two fp64 sums are formed in
+ * a different order).  target: [3,H,W]. */
+int fs_render_fwd_loss(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
+                       const float *target, float *image, float *final_T, uint32_t *n_contrib, float *dL_dimage,
+                       double *loss_out);
+
+/* Step a10 from the error map that the last fs_render_fwd_loss on this ctx left behind (same rule / k / outputs as
+ * fs_error_mask).  FS_EINVAL if no such map of H x W pixels is pending: fs_l1_grad, fs_error_mask, fs_photo_loss,
+ * fs_prune_score_normalize and fs_measure_peaks reuse that scratch and discard it; it may be used any number of
+ * times until then. */
+int fs_error_mask_fused(fs_ctx *ctx, int32_t height, int32_t width, int32_t rule, float k, uint8_t *mask,
+                        float *threshold_out);
 
 /* Step a7: loss = mean |image - target| over 3*H*W values; dL_dimage = sign(image-target)/(3HW).
  * loss_out (device pointer to one double) may be NULL. */

@@ -23,7 +23,7 @@ FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
+           "fs_render_fwd", "fs_render_fwd_loss", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_adam_step", "fs_grad_accumulate", "fs_adam_interval", "fs_activate", "fs_activate_bwd",
@@ -101,6 +101,8 @@ def load_library() -> ctypes.CDLL:
     lib.fs_bin_sort.argtypes = [vp, P(fs_projected), P(fs_camera), i64, P(fs_bins)]
     lib.fs_render_fwd.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp]
     lib.fs_l1_grad.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.fs_render_fwd_loss.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp, vp, vp]
+    lib.fs_error_mask_fused.argtypes = [vp, i32, i32, i32, f32, vp, vp]
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
@@ -325,6 +327,33 @@ class Context:
         self._check(self.lib.fs_render_fwd(self.handle, ctypes.byref(ps), ctypes.byref(bins.struct), ctypes.byref(cam),
                                            _ptr(image), _ptr(final_T), _ptr(n_contrib)), "fs_render_fwd")
         return image, final_T, n_contrib
+
+    def fs_render_fwd_loss(self, proj: Projected, bins: Bins, cam: fs_camera, target, image=None, final_T=None,
+                           n_contrib=None, dL_dimage=None, loss_out=None, want_grad=True):
+        H, W, dev = cam.height, cam.width, self.device
+        _chk(target, torch.float32, (3, H, W), "target")
+        if image is None:
+            image = torch.empty((3, H, W), dtype=torch.float32, device=dev)
+        if final_T is None:
+            final_T = torch.empty((H, W), dtype=torch.float32, device=dev)
+        if n_contrib is None:
+            n_contrib = torch.empty((H, W), dtype=torch.int32, device=dev)
+        if dL_dimage is None and want_grad:
+            dL_dimage = torch.empty((3, H, W), dtype=torch.float32, device=dev)
+        ps = proj.struct()
+        self._check(self.lib.fs_render_fwd_loss(self.handle, ctypes.byref(ps), ctypes.byref(bins.struct), ctypes.byref(cam),
+                                                _ptr(target), _ptr(image), _ptr(final_T), _ptr(n_contrib), _ptr(dL_dimage),
+                                                _ptr(loss_out)), "fs_render_fwd_loss")
+        return image, final_T, n_contrib, dL_dimage
+
+    def fs_error_mask_fused(self, H, W, rule=FS_MASK_MEAN_STD, k=1.0, mask=None, threshold_out=None):
+        if mask is None:
+            mask = torch.empty((H, W), dtype=torch.uint8, device=self.device)
+        if threshold_out is None:
+            threshold_out = torch.empty(1, dtype=torch.float32, device=self.device)
+        self._check(self.lib.fs_error_mask_fused(self.handle, int(H), int(W), int(rule), float(k), _ptr(mask),
+                                                 _ptr(threshold_out)), "fs_error_mask_fused")
+        return mask, threshold_out
 
     def fs_l1_grad(self, image, target, dL_dimage=None, loss_out=None):
         _, H, W = image.shape

@@ -39,6 +39,8 @@ struct fs_ctx {
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
+    ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
+    int64_t fused_pixels = 0;        // > 0: err_map / partial hold the error map of the last fs_render_fwd_loss
 
     // per-group event timing (measurement only)
     uint32_t prof_mask = 0;
@@ -227,7 +229,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
                          &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
-                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial};
+                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -398,12 +400,62 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     return FS_OK;
 }
 
+int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, const fs_camera* cam, const float* target,
+                       float* image, float* final_T, uint32_t* n_contrib, float* dL_dimage, double* loss_out)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !bins->tile_order || !image || !final_T || !n_contrib || !target)
+        return fail(ctx, FS_EINVAL, "fs_render_fwd_loss: bad arguments");
+    if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
+        return fail(ctx, FS_EINVAL, "fs_render_fwd_loss: null array");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    const int tiles = cd.tiles_x * cd.tiles_y;
+    const int64_t pixels = (int64_t)cd.width * cd.height;
+    ctx->fused_pixels = 0;
+    FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
+    FS_TRY(ensure(ctx, ctx->partial, (size_t)fused_partials() * sizeof(double), "partials"));
+    FS_TRY(ensure(ctx, ctx->tile_partial, (size_t)4 * tiles * sizeof(double), "tile partials"));
+    {
+        ProfScope prof(ctx, FS_K_RENDER_FWD);
+        FS_HIP(launch_render_fwd_fused(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order,
+                                       bins->gauss_sorted, static_cast<const float*>(bins->splats), image, final_T, n_contrib,
+                                       target, dL_dimage, static_cast<float*>(ctx->err_map.ptr),
+                                       static_cast<double*>(ctx->tile_partial.ptr)),
+               "k_render_fwd");
+    }
+    ProfScope prof(ctx, FS_K_L1);
+    FS_HIP(launch_fold_tile_partials(ctx->stream, static_cast<const double*>(ctx->tile_partial.ptr), tiles, 3 * pixels,
+                                     static_cast<double*>(ctx->partial.ptr), loss_out),
+           "k_fold_tile_partials");
+    ctx->fused_pixels = pixels;
+    return FS_OK;
+}
+
+int fs_error_mask_fused(fs_ctx* ctx, int32_t height, int32_t width, int32_t rule, float k, uint8_t* mask, float* threshold_out)
+{
+    if (!ctx) return FS_EINVAL;
+    if (!mask || height <= 0 || width <= 0 || (rule != FS_MASK_MEAN_STD && rule != FS_MASK_MINMAX_TAU))
+        return fail(ctx, FS_EINVAL, "fs_error_mask_fused: bad arguments");
+    const int64_t pixels = (int64_t)height * width;
+    if (ctx->fused_pixels != pixels)
+        return fail(ctx, FS_EINVAL, "fs_error_mask_fused: no error map of this size from fs_render_fwd_loss is pending");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    float* err = static_cast<float*>(ctx->err_map.ptr);
+    float* thr = threshold_out ? threshold_out : err + pixels;
+    ProfScope prof(ctx, FS_K_ERR_MASK);
+    FS_HIP(launch_error_mask_from_map(ctx->stream, pixels, rule, k, err, static_cast<double*>(ctx->partial.ptr), mask, thr),
+           "k_err_*");
+    return FS_OK;
+}
+
 int fs_l1_grad(fs_ctx* ctx, const float* image, const float* target, int32_t height, int32_t width, float* dL_dimage,
                double* loss_out)
 {
     if (!ctx) return FS_EINVAL;
     if (!image || !target || !dL_dimage || height <= 0 || width <= 0)
         return fail(ctx, FS_EINVAL, "fs_l1_grad: bad arguments");
+    ctx->fused_pixels = 0;   // (the scratch that the fused forward pass leaves its error map in is reused here)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
     ProfScope prof(ctx, FS_K_L1);
@@ -464,6 +516,7 @@ int fs_error_mask(fs_ctx* ctx, const float* image, const float* target, int32_t 
     if (!image || !target || !mask || height <= 0 || width <= 0 ||
         (rule != FS_MASK_MEAN_STD && rule != FS_MASK_MINMAX_TAU))
         return fail(ctx, FS_EINVAL, "fs_error_mask: bad arguments");
+    ctx->fused_pixels = 0;   // (the scratch that the fused forward pass leaves its error map in is reused here)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     const int64_t pixels = (int64_t)height * width;
     FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
@@ -502,6 +555,7 @@ int fs_photo_loss(fs_ctx* ctx, const float* image, const float* target, int32_t 
     if (!ctx) return FS_EINVAL;
     if (!image || !target || height <= 0 || width <= 0 || !(lambda >= 0.f && lambda <= 1.f) || (!dL_dimage && !out3))
         return fail(ctx, FS_EINVAL, "fs_photo_loss: bad arguments");
+    ctx->fused_pixels = 0;   // (the scratch that the fused forward pass leaves its error map in is reused here)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     const size_t nb = (size_t)photo_blocks(height, width);
     FS_TRY(ensure(ctx, ctx->partial, (2 * nb > (size_t)4 * mask_partials() ? 2 * nb : (size_t)4 * mask_partials()) * sizeof(double),
@@ -528,6 +582,7 @@ int fs_prune_score_normalize(fs_ctx* ctx, const double* acc, int64_t n, float* s
 {
     if (!ctx) return FS_EINVAL;
     if (n < 0 || (n > 0 && (!acc || !s_p))) return fail(ctx, FS_EINVAL, "fs_prune_score_normalize: bad arguments");
+    ctx->fused_pixels = 0;   // (the scratch that the fused forward pass leaves its error map in is reused here)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     FS_TRY(ensure(ctx, ctx->partial, (size_t)4 * mask_partials() * sizeof(double), "partials"));
     FS_HIP(launch_prune_normalize(ctx->stream, acc, n, static_cast<double*>(ctx->partial.ptr), s_p), "k_prune_normalize");
@@ -653,6 +708,7 @@ int fs_measure_peaks(fs_ctx* ctx, int64_t copy_bytes, double* copy_gbs, double* 
 {
     if (!ctx) return FS_EINVAL;
     if (copy_bytes < 0 || copy_bytes > ((int64_t)1 << 33)) return fail(ctx, FS_EINVAL, "fs_measure_peaks: bad size");
+    ctx->fused_pixels = 0;   // (the scratch that the fused forward pass leaves its error map in is reused here)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
     hipEvent_t a = nullptr, b = nullptr;

@@ -93,6 +93,49 @@ __device__ __forceinline__ bool cb_tile_hit(float mx, float my, float A, float B
     return qmin <= Q;
 }
 
+// ---- workgroup reductions in double precision (fixed tree: results do not depend on scheduling) ----------
+constexpr int RED_BLOCKS = 1024;  // partial sums per reduction (a multiple of RED_THREADS)
+constexpr int RED_THREADS = 256;
+
+__device__ __forceinline__ double shfl_down_f64(double v, int d)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __shfl_down((int)(b & 0xffffffffll), d, 64);
+    const int hi = __shfl_down((int)(b >> 32), d, 64);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+enum RedOp { RED_SUM, RED_MIN, RED_MAX };
+
+template <RedOp OP>
+__device__ __forceinline__ double red_combine(double a, double b)
+{
+    if (OP == RED_SUM) return a + b;
+    if (OP == RED_MIN) return a < b ? a : b;
+    return a > b ? a : b;
+}
+
+// Reduces one value per thread over the workgroup; the result is valid in thread 0.
+template <RedOp OP>
+__device__ __forceinline__ double block_reduce(double v, double* smem /*[4]*/)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = red_combine<OP>(v, shfl_down_f64(v, d));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) v = red_combine<OP>(red_combine<OP>(smem[0], smem[1]), red_combine<OP>(smem[2], smem[3]));
+    return v;
+}
+
+template <RedOp OP>
+__device__ __forceinline__ double red_identity()
+{
+    if (OP == RED_SUM) return 0.0;
+    if (OP == RED_MIN) return 1.0e300;
+    return -1.0e300;
+}
+
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) ------------------------
 hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                              const CfgDev& cfg, const fs_projected& out);
@@ -156,6 +199,19 @@ hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_so
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
                              uint32_t* n_contrib);
+
+// forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
+// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null
+hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
+                                   const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
+                                   float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
+                                   float* err, double* tile_partial);
+// partial: >= fused_partials() doubles
+int fused_partials();
+hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,
+                                     double* partial, double* loss_out);
+hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, float k, const float* err,
+                                      double* partial, uint8_t* mask, float* thr);
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,

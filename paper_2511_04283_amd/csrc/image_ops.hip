@@ -12,48 +12,6 @@ namespace fs {
 
 namespace {
 
-constexpr int RED_BLOCKS = 1024;  // partial sums per reduction (a multiple of RED_THREADS)
-constexpr int RED_THREADS = 256;
-
-__device__ __forceinline__ double shfl_down_f64(double v, int d)
-{
-    const long long b = __double_as_longlong(v);
-    const int lo = __shfl_down((int)(b & 0xffffffffll), d, 64);
-    const int hi = __shfl_down((int)(b >> 32), d, 64);
-    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
-}
-
-enum RedOp { RED_SUM, RED_MIN, RED_MAX };
-
-template <RedOp OP>
-__device__ __forceinline__ double red_combine(double a, double b)
-{
-    if (OP == RED_SUM) return a + b;
-    if (OP == RED_MIN) return a < b ? a : b;
-    return a > b ? a : b;
-}
-
-// Reduces one value per thread over the workgroup; the result is valid in thread 0.
-template <RedOp OP>
-__device__ __forceinline__ double block_reduce(double v, double* smem /*[4]*/)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = red_combine<OP>(v, shfl_down_f64(v, d));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
-    __syncthreads();
-    if (threadIdx.x == 0) v = red_combine<OP>(red_combine<OP>(smem[0], smem[1]), red_combine<OP>(smem[2], smem[3]));
-    return v;
-}
-
-template <RedOp OP>
-__device__ __forceinline__ double red_identity()
-{
-    if (OP == RED_SUM) return 0.0;
-    if (OP == RED_MIN) return 1.0e300;
-    return -1.0e300;
-}
-
 // final reduction of RED_BLOCKS partials by one workgroup (thread i takes partials i, i+256, ... in order)
 template <RedOp OP>
 __device__ __forceinline__ double final_reduce(const double* partial, double* smem)
@@ -150,6 +108,39 @@ __global__ __launch_bounds__(RED_THREADS) void k_err_map(const float* __restrict
         partial[RED_BLOCKS + blockIdx.x] = lo;
         partial[2 * RED_BLOCKS + blockIdx.x] = hi;
     }
+}
+
+// Folds the per-tile partials that the fused forward kernel leaves ([4][tiles]: sum |d|, sum / min / max of e)
+// into the RED_BLOCKS-wide layout the final kernels read: partial[0..] = sum e, [RED_BLOCKS..] = min,
+// [2 RED_BLOCKS..] = max, and the L1 sums at [4 RED_BLOCKS..].  Thread b adds tiles b, b + RED_BLOCKS, ... in order.
+__global__ __launch_bounds__(RED_THREADS) void k_fold_tile_partials(const double* __restrict__ tile_partial, int tiles,
+                                                                   double* __restrict__ partial)
+{
+    const int b = blockIdx.x * RED_THREADS + threadIdx.x;   // < RED_BLOCKS
+    double l1 = 0.0, s = 0.0, lo = 1.0e300, hi = -1.0e300;
+    for (int t0 = b; t0 < tiles; t0 += 4 * RED_BLOCKS) {   // 16 loads in flight per round, added in a fixed order
+        double v[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int t = t0 + u * RED_BLOCKS;
+            const bool in = t < tiles;
+            v[u][0] = in ? tile_partial[t] : 0.0;
+            v[u][1] = in ? tile_partial[(size_t)tiles + t] : 0.0;
+            v[u][2] = in ? tile_partial[2 * (size_t)tiles + t] : 1.0e300;
+            v[u][3] = in ? tile_partial[3 * (size_t)tiles + t] : -1.0e300;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            l1 += v[u][0];
+            s += v[u][1];
+            lo = v[u][2] < lo ? v[u][2] : lo;
+            hi = v[u][3] > hi ? v[u][3] : hi;
+        }
+    }
+    partial[b] = s;
+    partial[RED_BLOCKS + b] = lo;
+    partial[2 * RED_BLOCKS + b] = hi;
+    partial[4 * RED_BLOCKS + b] = l1;
 }
 
 // second pass of the two-pass variance: partial sums of (e - mean)^2
@@ -472,6 +463,7 @@ __global__ __launch_bounds__(256) void k_prune_normalize(const double* __restric
 
 int l1_partials() { return RED_BLOCKS; }
 int mask_partials() { return RED_BLOCKS; }
+int fused_partials() { return 5 * RED_BLOCKS; }
 
 hipError_t launch_l1_grad(hipStream_t st, const float* image, const float* target, int64_t count, float* dL,
                           double* partial, double* loss_out)
@@ -539,6 +531,29 @@ hipError_t launch_prune_normalize(hipStream_t st, const double* acc, int64_t n, 
     hipLaunchKernelGGL(k_minmax_final, dim3(1), dim3(RED_THREADS), 0, st, partial);
     hipLaunchKernelGGL(k_prune_normalize, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, acc, n,
                        partial + 2 * RED_BLOCKS, out);
+    return hipGetLastError();
+}
+
+// After the fused forward kernel: fold its per-tile partials, optionally finish the L1 loss.
+hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,
+                                     double* partial, double* loss_out)
+{
+    hipLaunchKernelGGL(k_fold_tile_partials, dim3(RED_BLOCKS / RED_THREADS), dim3(RED_THREADS), 0, st, tile_partial, tiles,
+                       partial);
+    if (loss_out)
+        hipLaunchKernelGGL(k_l1_final, dim3(1), dim3(RED_THREADS), 0, st, partial + 4 * RED_BLOCKS, count, loss_out);
+    return hipGetLastError();
+}
+
+// fs_error_mask without its first pass: the error map and its partial sums are already in place
+hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, float k, const float* err,
+                                      double* partial, uint8_t* mask, float* thr)
+{
+    if (pixels <= 0) return hipSuccess;
+    if (rule == FS_MASK_MEAN_STD)
+        hipLaunchKernelGGL(k_err_var, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, err, pixels, partial);
+    hipLaunchKernelGGL(k_err_threshold, dim3(1), dim3(RED_THREADS), 0, st, partial, pixels, rule, k, thr);
+    hipLaunchKernelGGL(k_err_mask, dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0, st, err, pixels, thr, mask);
     return hipGetLastError();
 }
 

@@ -204,11 +204,19 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
     return max(max(a, b), max(c, d));
 }
 
+// FUSED: the epilogue also does, per pixel, what the L1 term (FastGS Sec. 4.5) and the error map of the
+// multi-view score (Sec. 4.2) need from the finished colour -- dL/dC = sign(C - target) * scale, the error
+// e = ((|d0| + |d1|) + |d2|) / 3 -- and leaves this tile's partial sums (sum of |d|, sum / min / max of e)
+// at tile_partial[q * num_tiles + tile], so that the image is not read again for them.
+template <bool FUSED>
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                     const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
                                                     const float4* __restrict__ splats, float* __restrict__ image,
-                                                    float* __restrict__ final_T, uint32_t* __restrict__ n_contrib)
+                                                    float* __restrict__ final_T, uint32_t* __restrict__ n_contrib,
+                                                    const float* __restrict__ target, float scale,
+                                                    float* __restrict__ dL, float* __restrict__ err,
+                                                    double* __restrict__ tile_partial)
 {
     __shared__ Stage s;
     __shared__ float4 s_rgb[BATCH];
@@ -266,14 +274,55 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             last = blend ? (uint32_t)(start + j + 1) : last;
         }
     }
+    double l1 = 0.0, esum = 0.0, emin = 1.0e300, emax = -1.0e300;
     if (p.inside) {
         const size_t hw = (size_t)cam.width * cam.height;
         const size_t pix = (size_t)p.y * cam.width + p.x;
-        image[pix] = __builtin_fmaf(T, cfg.bg[0], C0);
-        image[hw + pix] = __builtin_fmaf(T, cfg.bg[1], C1);
-        image[2 * hw + pix] = __builtin_fmaf(T, cfg.bg[2], C2);
+        const float c0 = __builtin_fmaf(T, cfg.bg[0], C0), c1 = __builtin_fmaf(T, cfg.bg[1], C1);
+        const float c2 = __builtin_fmaf(T, cfg.bg[2], C2);
+        image[pix] = c0;
+        image[hw + pix] = c1;
+        image[2 * hw + pix] = c2;
         final_T[pix] = T;
         n_contrib[pix] = last;
+        if (FUSED) {
+            const float d0 = c0 - target[pix], d1 = c1 - target[hw + pix], d2 = c2 - target[2 * hw + pix];
+            if (dL) {
+                dL[pix] = d0 > 0.f ? scale : (d0 < 0.f ? -scale : 0.f);
+                dL[hw + pix] = d1 > 0.f ? scale : (d1 < 0.f ? -scale : 0.f);
+                dL[2 * hw + pix] = d2 > 0.f ? scale : (d2 < 0.f ? -scale : 0.f);
+            }
+            const float e = ((fabsf(d0) + fabsf(d1)) + fabsf(d2)) / 3.0f;
+            err[pix] = e;
+            l1 = ((double)fabsf(d0) + (double)fabsf(d1)) + (double)fabsf(d2);
+            esum = emin = emax = (double)e;
+        }
+    }
+    if (FUSED) {
+        // per-wavefront partials by shuffles (sums in double, extrema of the fp32 errors in float: exact), combined
+        // across the four wavefronts through LDS with a single barrier
+        float fmin_e = (float)emin == (float)emin && emin < 1.0e299 ? (float)emin : 3.0e38f;
+        float fmax_e = emax > -1.0e299 ? (float)emax : -3.0e38f;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            l1 += shfl_down_f64(l1, d);
+            esum += shfl_down_f64(esum, d);
+            fmin_e = fminf(fmin_e, __shfl_down(fmin_e, d, 64));
+            fmax_e = fmaxf(fmax_e, __shfl_down(fmax_e, d, 64));
+        }
+        __shared__ double s_part[4][4];
+        if ((threadIdx.x & 63) == 0) {
+            double* w = s_part[threadIdx.x >> 6];
+            w[0] = l1; w[1] = esum; w[2] = (double)fmin_e; w[3] = (double)fmax_e;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const size_t nt = (size_t)cam.tiles_x * cam.tiles_y;
+            tile_partial[tile] = (s_part[0][0] + s_part[1][0]) + (s_part[2][0] + s_part[3][0]);
+            tile_partial[nt + tile] = (s_part[0][1] + s_part[1][1]) + (s_part[2][1] + s_part[3][1]);
+            tile_partial[2 * nt + tile] = fmin(fmin(s_part[0][2], s_part[1][2]), fmin(s_part[2][2], s_part[3][2]));
+            tile_partial[3 * nt + tile] = fmax(fmax(s_part[0][3], s_part[1][3]), fmax(s_part[2][3], s_part[3][3]));
+        }
     }
 }
 
@@ -629,8 +678,23 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_render_fwd, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib);
+    hipLaunchKernelGGL(k_render_fwd<false>, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
+                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib,
+                       nullptr, 0.f, nullptr, nullptr, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
+                                   const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
+                                   float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
+                                   float* err, double* tile_partial)
+{
+    const int tiles = cam.tiles_x * cam.tiles_y;
+    if (tiles == 0) return hipSuccess;
+    const float scale = 1.0f / (float)((int64_t)3 * cam.width * cam.height);
+    hipLaunchKernelGGL(k_render_fwd<true>, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
+                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib,
+                       target, scale, dL, err, tile_partial);
     return hipGetLastError();
 }
 

@@ -245,3 +245,40 @@ def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
     img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
     assert np.array_equal(g["n_contrib"], nc)
     assert np.abs(g["image"] - img).max() <= 1e-4
+
+
+@pytest.mark.parametrize("W,H,rule,k", [(203, 117, 0, 1.0), (128, 96, 1, 0.35)])
+def test_fused_forward_gives_what_the_separate_calls_give(ctx, orc32, W, H, rule, k):
+    """fs_render_fwd_loss + fs_error_mask_fused against fs_render_fwd + fs_l1_grad + fs_error_mask (bit-exact
+    image, n_contrib, dL, mask, threshold; the loss to rounding) and against the oracle."""
+    import torch
+    from paper_2511_04283_amd import binding as B
+    sc = scenes.tiny_scene(700 + W, 4000, W, H, sh_degree=1, log_scale=(-2.6, 0.7), spread=1.2)
+    cam = sc.cameras[0]
+    tgt_np = np.random.default_rng(W).uniform(0, 1, (3, H, W)).astype(np.float32)
+    g = B.Gaussians.from_scene(sc, ctx.device)
+    fcam = B.make_camera(cam)
+    tgt = torch.from_numpy(tgt_np).to(ctx.device)
+    proj = ctx.fs_preprocess(g, fcam)
+    bins = ctx.fs_bin_sort(proj, fcam)
+    img_a, T_a, nc_a = ctx.fs_render_fwd(proj, bins, fcam)
+    loss_a = torch.zeros(1, dtype=torch.float64, device=ctx.device)
+    dL_a = ctx.fs_l1_grad(img_a, tgt, loss_out=loss_a)
+    mask_a, thr_a = ctx.fs_error_mask(img_a, tgt, rule, k)
+    loss_b = torch.zeros(1, dtype=torch.float64, device=ctx.device)
+    img_b, T_b, nc_b, dL_b = ctx.fs_render_fwd_loss(proj, bins, fcam, tgt, loss_out=loss_b)
+    mask_b, thr_b = ctx.fs_error_mask_fused(H, W, rule, k)
+    mask_c, thr_c = ctx.fs_error_mask_fused(H, W, rule, k)           # the map may be used again
+    for a, b in ((img_a, img_b), (T_a, T_b), (nc_a, nc_b), (dL_a, dL_b), (mask_a, mask_b), (mask_b, mask_c)):
+        assert torch.equal(a, b)
+    assert thr_a.item() == thr_b.item() == thr_c.item()
+    assert loss_b.item() == pytest.approx(loss_a.item(), rel=1e-12)
+    img_o = orc32.forward(sc, cam)[2]
+    l_o, dL_o = orc32.l1(img_o, tgt_np)
+    m_o, thr_o, _ = orc32.error_mask(img_o, tgt_np, rule=rule, k=k)
+    assert loss_b.item() == pytest.approx(l_o, rel=1e-6) and np.array_equal(dL_b.cpu().numpy(), dL_o)
+    assert np.array_equal(mask_b.cpu().numpy(), m_o) and 0.01 < m_o.mean() < 0.9
+    # another call that uses the same scratch discards the pending map
+    ctx.fs_l1_grad(img_a, tgt)
+    with pytest.raises(RuntimeError):
+        ctx.fs_error_mask_fused(H, W, rule, k)
