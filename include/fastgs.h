@@ -2,7 +2,8 @@
  * fastgs.h -- C ABI of the MI355X (gfx950) FastGS rasterizer hot path.
  *
  * What it computes (paper: FastGS, Sec. 3 "Background: 3D Gaussian Splatting", Sec. 4.2
- * "Multi-view Consistent Densification", Sec. 4.4 "Compact Box" for the 3-sigma rule):
+ * "Multi-view Consistent Densification", Sec. 4.3 "Multi-view Consistent Pruning", Sec. 4.4 "Compact Box",
+ * Sec. 4.5 "Optimization", and the supplement's "Details of Compact Box" and "Implementation Details"):
  *   fs_preprocess        projection of every Gaussian to a screen-space splat   (Eqs. (2), (3))
  *   fs_bin_sort          Gaussian-tile pairs, ordered by (tile, depth)          (Sec. 3, "sorted by depth")
  *   fs_render_fwd        front-to-back alpha compositing                        (Eqs. (4), (5))
@@ -28,9 +29,10 @@
  *     by the caller unless marked "ctx-owned"; structs themselves live in host memory.
  *   - Arrays are dense, row-major, 4-byte aligned (16-byte for [n,4] float arrays); fp32 unless
  *     stated.  Nothing is freed or reallocated on the caller's behalf.
- *   - Work is enqueued on the stream given to fs_create.  fs_bin_sort reads one 8-byte value
- *     back (the pair count) and therefore synchronises that stream; all other calls return as
- *     soon as the work is enqueued.
+ *   - Work is enqueued on the stream given to fs_create.  fs_bin_sort reads 32 bytes back (the
+ *     pair count and what it needs to choose its path), fs_compact 8 bytes (the count), and
+ *     fs_measure_peaks / fs_profile_read wait for their measurements: these synchronise that
+ *     stream; all other calls return as soon as the work is enqueued.
  *   - Every call returns FS_OK (0) or a negative fs_status and never throws or aborts;
  *     fs_last_error gives a message for the last failure on that ctx.
  *   - n = 0 Gaussians and P = 0 pairs are valid (the image is the background).
