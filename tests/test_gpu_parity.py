@@ -247,6 +247,53 @@ def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
     assert np.abs(g["image"] - img).max() <= 1e-4
 
 
+@pytest.mark.parametrize("compact_box", [0, 1])
+def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_box):
+    """A context keeps its scratch buffers from call to call and grows them when a call needs more. One
+    context therefore goes through: a first call, a much larger scene (buffers grow), smaller ones (buffers
+    larger than needed), long lists after short ones and short after long (the two LDS sort variants), a
+    scene without pairs, and another tile grid. Keys, order, ranges and n_contrib bit-exact every time."""
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.compact_box = compact_box
+    cfg.cb_beta = 0.7
+    c = B.Context("cuda:0", cfg)
+    o = Oracle(np.float32, Config(compact_box=compact_box, cb_beta=0.7)) if compact_box else orc32
+    cases = [(700, 2000, 203, 117, (-3.2, 0.7)),    # short lists
+             (701, 30000, 203, 117, (-3.2, 0.7)),   # many more pairs: buffers grow
+             (702, 9000, 203, 117, (-3.2, 0.7)),    # fewer again
+             (703, 40000, 70, 50, (-3.2, 0.7)),     # lists beyond 2048 after short ones
+             (704, 40000, 70, 50, (-3.2, 0.7)),     # ... and again
+             (705, 1500, 70, 50, (-3.2, 0.7)),      # short after long
+             (706, 0, 70, 50, (-3.2, 0.7)),         # nothing to order
+             (707, 5000, 333, 219, (-3.0, 0.6))]    # another tile grid
+    seen_long = False
+    for seed, n, W, H, ls in cases:
+        if n == 0:
+            cam = scenes.Camera(W, H, 60.0, 60.0, W / 2.0, H / 2.0)
+            sc = scenes.Scene("empty", 0, np.zeros((0, 3), np.float32), np.zeros((0, 3), np.float32),
+                              np.zeros((0, 4), np.float32), np.zeros(0, np.float32), np.zeros((0, 1, 3), np.float32), [cam], 0)
+        else:
+            sc = scenes.tiny_scene(seed, n, W, H, sh_degree=0, log_scale=ls, spread=1.1)
+            cam = sc.cameras[0]
+        g = gpu_pipeline(c, sc, cam)
+        p_o = o.preprocess(sc, cam)
+        b_o = o.bin_sort(p_o, cam)
+        L = b_o.tile_ranges[:, 1].astype(np.int64) - b_o.tile_ranges[:, 0]
+        seen_long |= bool(L.max() > 2048)
+        assert L.max() <= 8192
+        assert g["num_pairs"] == b_o.num_pairs, (seed, n)
+        assert np.array_equal(g["keys_sorted"], b_o.keys_sorted), (seed, n)
+        assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted), (seed, n)
+        assert np.array_equal(g["tile_ranges"], b_o.tile_ranges), (seed, n)
+        if n <= 9000:
+            img, fT, nc = o.render_fwd_mt(p_o, b_o, cam, threads=8)
+            assert np.array_equal(g["n_contrib"], nc), (seed, n)
+            assert np.abs(g["image"] - img).max() <= 1e-4
+    assert seen_long
+    c.close()
+
+
 @pytest.mark.parametrize("W,H,rule,k", [(203, 117, 0, 1.0), (128, 96, 1, 0.35)])
 def test_fused_forward_gives_what_the_separate_calls_give(ctx, orc32, W, H, rule, k):
     """fs_render_fwd_loss + fs_error_mask_fused against fs_render_fwd + fs_l1_grad + fs_error_mask (bit-exact
