@@ -165,6 +165,7 @@ def main() -> int:
                 ctx.fs_l1_grad(image, target, dL, loss)
         ctx.fs_render_bwd(g, fcam, proj, b_, final_T, n_contrib, dL, grads)
     ctx.fs_profile_enable(())
+    ctx.fs_set_score_record(False)    # no count pass follows these forward passes
     train_iter()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -172,6 +173,7 @@ def main() -> int:
         train_iter()
     torch.cuda.synchronize()
     fwd_bwd_ms = (time.perf_counter() - t2) * 1e3 / args.steps
+    ctx.fs_set_score_record(True)
 
     # the multi-view score pass of VCD (Sec. 4.2): K views x (preprocess, bin_sort, render_fwd, error_mask,
     # score_accumulate), counts summed over the views -- for workloads that come with several cameras
@@ -185,8 +187,12 @@ def main() -> int:
             for fc, tg in zip(cams, tgts):
                 ctx.fs_preprocess(g, fc, proj)
                 b_ = ctx.fs_bin_sort(proj, fc)
-                ctx.fs_render_fwd(proj, b_, fc, image, final_T, n_contrib)
-                ctx.fs_error_mask(image, tg, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+                if fused:
+                    ctx.fs_render_fwd_loss(proj, b_, fc, tg, image, final_T, n_contrib, want_grad=False)
+                    ctx.fs_error_mask_fused(fc.height, fc.width, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
+                else:
+                    ctx.fs_render_fwd(proj, b_, fc, image, final_T, n_contrib)
+                    ctx.fs_error_mask(image, tg, B.FS_MASK_MEAN_STD, 1.0, mask, thr)
                 ctx.fs_score_accumulate(proj, b_, fc, final_T, n_contrib, mask, counts)
         views()
         torch.cuda.synchronize()

@@ -196,6 +196,14 @@ int fs_render_fwd_loss(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bin
 int fs_error_mask_fused(fs_ctx *ctx, int32_t height, int32_t width, int32_t rule, float k, uint8_t *mask,
                         float *threshold_out);
 
+/* Whether fs_render_fwd_loss also records, for every pair, at which pixels of its tile the multi-view score
+ * (Sec. 4.2) counts the pair's Gaussian: 32 bytes per pair of ctx scratch.  On by default.  When the latest forward
+ * pass on the ctx over `bins` was such a call, fs_score_accumulate takes its counts from that record (one population
+ * count per pair against the tile's mask) instead of walking the tile lists a second time; it then reads neither
+ * final_T nor n_contrib, and the counts are the same.  The record costs the forward kernel some time: turn it off
+ * for forward passes that no count pass follows (plain training iterations). */
+int fs_set_score_record(fs_ctx *ctx, int32_t on);
+
 /* Step a7: loss = mean |image - target| over 3*H*W values; dL_dimage = sign(image-target)/(3HW).
  * loss_out (device pointer to one double) may be NULL. */
 int fs_l1_grad(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
@@ -219,7 +227,9 @@ int fs_error_mask(fs_ctx *ctx, const float *image, const float *target, int32_t 
 
 /* Step a11: for one view, counts[i] += number of pixels p with mask[p] = 1 at which Gaussian i
  * is blended by the forward pass (and, in FS_SCORE_WEIGHT mode, with alpha_i T_i > alpha_min).
- * counts [n] int32 is ACCUMULATED: zero it before the first view; s_d = counts / K. */
+ * counts [n] int32 is ACCUMULATED: zero it before the first view; s_d = counts / K.
+ * final_T / n_contrib: those of the latest forward pass over `bins` (see fs_set_score_record for when they are not
+ * read). */
 int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
                         const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
                         int32_t *counts);

@@ -23,7 +23,7 @@ FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_render_fwd_loss", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
+           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_adam_step", "fs_grad_accumulate", "fs_adam_interval", "fs_activate", "fs_activate_bwd",
@@ -103,6 +103,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_l1_grad.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.fs_render_fwd_loss.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp, vp, vp]
     lib.fs_error_mask_fused.argtypes = [vp, i32, i32, i32, f32, vp, vp]
+    lib.fs_set_score_record.argtypes = [vp, i32]
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
@@ -345,6 +346,9 @@ class Context:
                                                 _ptr(target), _ptr(image), _ptr(final_T), _ptr(n_contrib), _ptr(dL_dimage),
                                                 _ptr(loss_out)), "fs_render_fwd_loss")
         return image, final_T, n_contrib, dL_dimage
+
+    def fs_set_score_record(self, on: bool):
+        self._check(self.lib.fs_set_score_record(self.handle, 1 if on else 0), "fs_set_score_record")
 
     def fs_error_mask_fused(self, H, W, rule=FS_MASK_MEAN_STD, k=1.0, mask=None, threshold_out=None):
         if mask is None:

@@ -40,6 +40,11 @@ struct fs_ctx {
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
     ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
+    ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES]: per pair, the pixels of its tile at which the score counts it
+    bool record_bits = true;         // fs_render_fwd_loss fills pair_bits (fs_set_score_record)
+    int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
+    const void* bits_order = nullptr;  // ... with this gauss_sorted, on this many tiles; -1: they describe nothing
+    int bits_tiles = 0;
     int64_t fused_pixels = 0;        // > 0: err_map / partial hold the error map of the last fs_render_fwd_loss
 
     // per-group event timing (measurement only)
@@ -229,7 +234,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
                          &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
-                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial};
+                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial, &ctx->pair_bits};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -264,6 +269,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     if (!out || n < 0 || !make_cam(cam, cd)) return fail(ctx, FS_EINVAL, "fs_bin_sort: bad arguments");
     if (n > 0 && !proj_ok(proj)) return fail(ctx, FS_EINVAL, "fs_bin_sort: null array");
     if (n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: n does not fit 31 bits");
+    ctx->bits_pairs = -1;
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
     const int tiles = cd.tiles_x * cd.tiles_y;
@@ -393,6 +399,7 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    ctx->bits_pairs = -1;   // (what a fused forward pass recorded for the count pass no longer describes the latest one)
     ProfScope prof(ctx, FS_K_RENDER_FWD);
     FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                              static_cast<const float*>(bins->splats), image, final_T, n_contrib),
@@ -413,22 +420,38 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
     const int tiles = cd.tiles_x * cd.tiles_y;
     const int64_t pixels = (int64_t)cd.width * cd.height;
     ctx->fused_pixels = 0;
+    ctx->bits_pairs = -1;
+    const bool bits = ctx->record_bits && bins->num_pairs > 0;
     FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
     FS_TRY(ensure(ctx, ctx->partial, (size_t)fused_partials() * sizeof(double), "partials"));
     FS_TRY(ensure(ctx, ctx->tile_partial, (size_t)4 * tiles * sizeof(double), "tile partials"));
+    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, (size_t)bins->num_pairs * PAIR_BITS_BYTES, "score bits"));
     {
         ProfScope prof(ctx, FS_K_RENDER_FWD);
         FS_HIP(launch_render_fwd_fused(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order,
                                        bins->gauss_sorted, static_cast<const float*>(bins->splats), image, final_T, n_contrib,
                                        target, dL_dimage, static_cast<float*>(ctx->err_map.ptr),
-                                       static_cast<double*>(ctx->tile_partial.ptr)),
+                                       static_cast<double*>(ctx->tile_partial.ptr), bits ? ctx->pair_bits.ptr : nullptr),
                "k_render_fwd");
+    }
+    if (bits) {
+        ctx->bits_pairs = bins->num_pairs;
+        ctx->bits_order = bins->gauss_sorted;
+        ctx->bits_tiles = tiles;
     }
     ProfScope prof(ctx, FS_K_L1);
     FS_HIP(launch_fold_tile_partials(ctx->stream, static_cast<const double*>(ctx->tile_partial.ptr), tiles, 3 * pixels,
                                      static_cast<double*>(ctx->partial.ptr), loss_out),
            "k_fold_tile_partials");
     ctx->fused_pixels = pixels;
+    return FS_OK;
+}
+
+int fs_set_score_record(fs_ctx* ctx, int32_t on)
+{
+    if (!ctx) return FS_EINVAL;
+    ctx->record_bits = on != 0;
+    if (!ctx->record_bits) ctx->bits_pairs = -1;
     return FS_OK;
 }
 
@@ -543,6 +566,13 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
         return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_SCORE);
+    if (ctx->bits_pairs == bins->num_pairs && ctx->bits_order == bins->gauss_sorted &&
+        ctx->bits_tiles == cd.tiles_x * cd.tiles_y) {
+        // the latest forward pass over these bins recorded where each pair is counted: no second walk
+        FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, bins->gauss_sorted, ctx->pair_bits.ptr, mask, counts),
+               "k_score_bits");
+        return FS_OK;
+    }
     FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                         static_cast<const float*>(bins->splats), n_contrib, mask, counts),
            "k_score");

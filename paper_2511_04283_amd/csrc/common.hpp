@@ -201,11 +201,16 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
                              uint32_t* n_contrib);
 
 // forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
-// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null
+// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null; pair_bits: null, or PAIR_BITS_BYTES per pair,
+// which receive the pixels of its tile at which the multi-view score counts the pair's Gaussian
+constexpr int PAIR_BITS_BYTES = 32;
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial);
+                                   float* err, double* tile_partial, void* pair_bits);
+// the count pass from those bits: counts[g] += |bits(pair) & mask(tile)| over the pairs of every tile
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* gauss_sorted,
+                             const void* pair_bits, const uint8_t* mask, int32_t* counts);
 // partial: >= fused_partials() doubles
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,

@@ -43,6 +43,20 @@ __device__ __forceinline__ float exp_c(float x)
     return __builtin_ldexpf(p, (int)n);
 }
 
+// 16-byte streaming (non-temporal) store / load
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void nt_store(const uint4& v, uint4* dst)
+{
+    u32x4 t;
+    t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(dst));
+}
+__device__ __forceinline__ uint4 nt_load(const uint4* src)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 struct Pixel {
     int x, y;
     bool inside;
@@ -208,7 +222,13 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 // multi-view score (Sec. 4.2) need from the finished colour -- dL/dC = sign(C - target) * scale, the error
 // e = ((|d0| + |d1|) + |d2|) / 3 -- and leaves this tile's partial sums (sum of |d|, sum / min / max of e)
 // at tile_partial[q * num_tiles + tile], so that the image is not read again for them.
-template <bool FUSED>
+//
+// BITS: the kernel also records, for every pair of the tile's list (by its position in the sorted order), at which
+// of the tile's 256 pixels the Gaussian is counted by the multi-view score (Sec. 4.2): where it is blended and, in
+// FS_SCORE_WEIGHT mode, alpha T > alpha_min.  32 bytes per pair: 16 sub-tiles (index wave*4 + row) x 16 bits (lane
+// within the row), zeros for pairs the loop never reached.  With these the count pass is a population count per
+// pair instead of a second walk over the lists (k_score_bits).
+template <bool FUSED, bool BITS>
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                     const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
@@ -216,10 +236,11 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib,
                                                     const float* __restrict__ target, float scale,
                                                     float* __restrict__ dL, float* __restrict__ err,
-                                                    double* __restrict__ tile_partial)
+                                                    double* __restrict__ tile_partial, uint4* __restrict__ pair_bits)
 {
     __shared__ Stage s;
     __shared__ float4 s_rgb[BATCH];
+    __shared__ __align__(16) uint16_t s_pb[BITS ? BATCH : 1][16];  // this batch's bits, [slot][sub-tile]
 
     const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const int sub = (threadIdx.x >> 6) * 4 + ((threadIdx.x & 63) >> 4);  // this lane's sub-tile list
@@ -237,9 +258,37 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
     s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
 
+    // BITS: row t of s_pb is zeroed and written out by thread t alone; the other wavefronts set bits in it between
+    // a batch's staging barriers and the barrier at the top of the next batch
+    const float hit_above = cfg.score_mode == FS_SCORE_ALPHA ? 0.0f : cfg.alpha_min;
+    int pending = -1, pending_m = 0;  // the batch whose bits are in s_pb and not yet in memory (uniform)
+    int reached = 0;                  // list positions below this one have been staged (uniform)
+    auto write_bits = [&](int first, int count) {
+        if ((int)threadIdx.x < count) {
+            const uint4* row = reinterpret_cast<const uint4*>(s_pb[threadIdx.x]);
+            uint4* dst = pair_bits + ((size_t)range.x + first + threadIdx.x) * 2;
+            // (streaming stores: the record is read once, by the count pass, and should not displace the step's
+            // other arrays from the caches)
+            nt_store(row[0], dst);
+            nt_store(row[1], dst + 1);
+        }
+    };
     for (int start = 0; start < total; start += BATCH) {
-        if (__syncthreads_count(!done) == 0) break;
+        const int alive = __syncthreads_count(!done);
+        if (BITS && pending >= 0) {
+            write_bits(pending, pending_m);
+            pending = -1;
+        }
+        if (alive == 0) break;
         const int m = min(BATCH, total - start);
+        if (BITS) {
+            uint4* row = reinterpret_cast<uint4*>(s_pb[threadIdx.x]);
+            row[0] = make_uint4(0u, 0u, 0u, 0u);
+            row[1] = make_uint4(0u, 0u, 0u, 0u);
+            pending = start;
+            pending_m = m;
+            reached = start + m;
+        }
         const int mine = stage_batch<true, 0>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, splats,
                                               range.x + start, m);
         // a row whose 16 pixels have all finished does not lengthen the wavefront's loop
@@ -270,8 +319,29 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             C0 = __builtin_fmaf(col.x, w, C0);
             C1 = __builtin_fmaf(col.y, w, C1);
             C2 = __builtin_fmaf(col.z, w, C2);
+            if (BITS) {
+                // (kept behind the colour update: scheduled ahead of it, the LDS store below would sit between the
+                // colour's LDS read and the wait for it, and every iteration would wait for the store as well)
+                asm volatile("" : "+v"(C0), "+v"(C1), "+v"(C2) : : "memory");
+                // w is alpha T with the transmittance in front of this Gaussian where it is blended (> 0 then), else 0:
+                // one comparison against alpha_min (FS_SCORE_WEIGHT) or 0 (FS_SCORE_ALPHA) decides
+                const uint64_t hb = __builtin_amdgcn_ballot_w64(w > hit_above);
+                // the row's first lane stores the row's 16 bits (past the end of the row's list j is stale)
+                if ((threadIdx.x & 15) == 0 && k < mine) s_pb[j][sub] = (uint16_t)(hb >> (threadIdx.x & 48));
+            }
             T = blend ? Tn : T;
             last = blend ? (uint32_t)(start + j + 1) : last;
+        }
+    }
+    if (BITS) {
+        if (pending >= 0) {
+            __syncthreads();
+            write_bits(pending, pending_m);
+        }
+        // pairs the loop never reached (every pixel had finished) are blended nowhere
+        for (uint32_t pos = range.x + reached + threadIdx.x; pos < range.y; pos += 256) {
+            nt_store(make_uint4(0u, 0u, 0u, 0u), pair_bits + (size_t)pos * 2);
+            nt_store(make_uint4(0u, 0u, 0u, 0u), pair_bits + (size_t)pos * 2 + 1);
         }
     }
     double l1 = 0.0, esum = 0.0, emin = 1.0e300, emax = -1.0e300;
@@ -310,7 +380,9 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             fmin_e = fminf(fmin_e, __shfl_down(fmin_e, d, 64));
             fmax_e = fmaxf(fmax_e, __shfl_down(fmax_e, d, 64));
         }
-        __shared__ double s_part[4][4];
+        // (the staging masks serve as the 4 x 4 doubles of scratch: they are only live inside stage_batch, between
+        // its two barriers, and every wavefront has left its last stage_batch before any of them gets here)
+        double (*s_part)[4] = reinterpret_cast<double (*)[4]>(&s.bits[0][0]);
         if ((threadIdx.x & 63) == 0) {
             double* w = s_part[threadIdx.x >> 6];
             w[0] = l1; w[1] = esum; w[2] = (double)fmin_e; w[3] = (double)fmax_e;
@@ -670,6 +742,45 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     }
 }
 
+// Count pass from the bits a k_render_fwd<., true> launch left: per tile, the mask of its 256 pixels in the same
+// layout as a pair's bits, then one population count per pair of the tile's list.  Tiles without mask pixels
+// read nothing else.
+__global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges,
+                                                    const uint32_t* __restrict__ gauss_sorted,
+                                                    const uint4* __restrict__ pair_bits,
+                                                    const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
+{
+    __shared__ __align__(16) uint16_t s_m[16];
+    const int tile = (int)blockIdx.x;
+    const Pixel p = pixel_of_thread(cam, tile);
+    const int lane = threadIdx.x & 63;
+    const uint2 range = ranges[tile];
+    const bool on = p.inside && mask[(size_t)p.y * cam.width + p.x] != 0;
+    // the first 256 pairs' bits are requested before the tile's mask is known, so that the two latencies overlap
+    uint32_t pos = range.x + threadIdx.x;
+    uint4 a = make_uint4(0u, 0u, 0u, 0u), c = a;
+    uint32_t g = 0;
+    if (pos < range.y) {
+        a = nt_load(pair_bits + (size_t)pos * 2);
+        c = nt_load(pair_bits + (size_t)pos * 2 + 1);
+        g = gauss_sorted[pos];
+    }
+    const uint64_t b = __ballot(on);
+    if ((lane & 15) == 0) s_m[(threadIdx.x >> 6) * 4 + (lane >> 4)] = (uint16_t)((b >> (lane & 48)) & 0xffffull);
+    if (__syncthreads_or(on) == 0) return;
+    const uint4 m0 = reinterpret_cast<const uint4*>(s_m)[0], m1 = reinterpret_cast<const uint4*>(s_m)[1];
+    for (;;) {
+        const int n = __popc(a.x & m0.x) + __popc(a.y & m0.y) + __popc(a.z & m0.z) + __popc(a.w & m0.w) +
+                      __popc(c.x & m1.x) + __popc(c.y & m1.y) + __popc(c.z & m1.z) + __popc(c.w & m1.w);
+        if (n != 0) atomicAdd(&counts[g], n);   // (all zeros for a thread past the end of the list)
+        pos += 256;
+        if (pos >= range.y) break;
+        a = nt_load(pair_bits + (size_t)pos * 2);
+        c = nt_load(pair_bits + (size_t)pos * 2 + 1);
+        g = gauss_sorted[pos];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
@@ -678,23 +789,41 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_render_fwd<false>, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib,
-                       nullptr, 0.f, nullptr, nullptr, nullptr);
+    hipLaunchKernelGGL((k_render_fwd<false, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
+                       reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                       reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr, nullptr,
+                       nullptr, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial)
+                                   float* err, double* tile_partial, void* pair_bits)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     const float scale = 1.0f / (float)((int64_t)3 * cam.width * cam.height);
-    hipLaunchKernelGGL(k_render_fwd<true>, dim3(tiles), dim3(256), 0, st, cam, cfg, reinterpret_cast<const uint2*>(ranges),
-                       tile_order, gauss_sorted, reinterpret_cast<const float4*>(splats), image, final_T, n_contrib,
-                       target, scale, dL, err, tile_partial);
+    if (pair_bits)
+        hipLaunchKernelGGL((k_render_fwd<true, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
+                           tile_partial, static_cast<uint4*>(pair_bits));
+    else
+        hipLaunchKernelGGL((k_render_fwd<true, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
+                           tile_partial, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* gauss_sorted,
+                             const void* pair_bits, const uint8_t* mask, int32_t* counts)
+{
+    const int tiles = cam.tiles_x * cam.tiles_y;
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_score_bits, dim3(tiles), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges), gauss_sorted,
+                       static_cast<const uint4*>(pair_bits), mask, counts);
     return hipGetLastError();
 }
 

@@ -112,8 +112,9 @@ class Trainer:
             fcam = B.make_camera(cam)
             proj = ctx.fs_preprocess(g, fcam)
             bins = ctx.fs_bin_sort(proj, fcam)
-            image, fT, nc = ctx.fs_render_fwd(proj, bins, fcam)
-            mask, _ = ctx.fs_error_mask(image, target, c.mask_rule, c.mask_k)
+            # forward pass with the error map and the per-pair record of counted pixels fused into it
+            image, fT, nc, _ = ctx.fs_render_fwd_loss(proj, bins, fcam, target, want_grad=False)
+            mask, _ = ctx.fs_error_mask_fused(cam.height, cam.width, c.mask_rule, c.mask_k)
             view = torch.zeros(n, dtype=torch.int32, device=dev)
             ctx.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, view)
             out3, _ = ctx.fs_photo_loss(image, target, c.lam, want_grad=False)
