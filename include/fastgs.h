@@ -196,12 +196,12 @@ int fs_render_fwd_loss(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bin
 int fs_error_mask_fused(fs_ctx *ctx, int32_t height, int32_t width, int32_t rule, float k, uint8_t *mask,
                         float *threshold_out);
 
-/* Whether fs_render_fwd_loss also records, for every pair, at which pixels of its tile the multi-view score
- * (Sec. 4.2) counts the pair's Gaussian: 32 bytes per pair of ctx scratch.  On by default.  When the latest forward
- * pass on the ctx over `bins` was such a call, fs_score_accumulate takes its counts from that record (one population
- * count per pair against the tile's mask) instead of walking the tile lists a second time; it then reads neither
- * final_T nor n_contrib, and the counts are the same.  The record costs the forward kernel some time: turn it off
- * for forward passes that no count pass follows (plain training iterations). */
+/* Whether the forward passes (fs_render_fwd, fs_render_fwd_loss) also record, for every pair, at which pixels of its
+ * tile the multi-view score (Sec. 4.2) counts the pair's Gaussian: 32 bytes per pair of ctx scratch.  On by default.
+ * When the latest forward pass on the ctx over `bins` made such a record, fs_score_accumulate takes its counts from it
+ * (one population count per pair against the tile's mask) instead of walking the tile lists a second time; it then
+ * reads neither final_T nor n_contrib, and the counts are the same.  The record costs the forward kernel some time
+ * (about a tenth): turn it off for forward passes that no count pass follows (plain training iterations). */
 int fs_set_score_record(fs_ctx *ctx, int32_t on);
 
 /* Step a7: loss = mean |image - target| over 3*H*W values; dL_dimage = sign(image-target)/(3HW).

@@ -41,7 +41,7 @@ struct fs_ctx {
     uint64_t* total_host = nullptr;  // pinned host copy
     ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
     ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES]: per pair, the pixels of its tile at which the score counts it
-    bool record_bits = true;         // fs_render_fwd_loss fills pair_bits (fs_set_score_record)
+    bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
     int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
     const void* bits_order = nullptr;  // ... with this gauss_sorted, on this many tiles; -1: they describe nothing
     int bits_tiles = 0;
@@ -176,6 +176,14 @@ int tile_bits(int tiles)
 bool proj_ok(const fs_projected* p)
 {
     return p && p->mean2d && p->depth && p->conic_opacity && p->rgb && p->rect && p->tiles_touched && p->clamped;
+}
+
+// the record in ctx->pair_bits now describes the forward pass over these bins
+void note_bits(fs_ctx* ctx, const fs_bins* bins, int tiles)
+{
+    ctx->bits_pairs = bins->num_pairs;
+    ctx->bits_order = bins->gauss_sorted;
+    ctx->bits_tiles = tiles;
 }
 
 }  // namespace
@@ -399,11 +407,15 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
-    ctx->bits_pairs = -1;   // (what a fused forward pass recorded for the count pass no longer describes the latest one)
+    ctx->bits_pairs = -1;   // (what an earlier forward pass recorded for the count pass does not describe this one)
+    const bool bits = ctx->record_bits && bins->num_pairs > 0;
+    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, (size_t)bins->num_pairs * PAIR_BITS_BYTES, "score bits"));
     ProfScope prof(ctx, FS_K_RENDER_FWD);
     FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
-                             static_cast<const float*>(bins->splats), image, final_T, n_contrib),
+                             static_cast<const float*>(bins->splats), image, final_T, n_contrib,
+                             bits ? ctx->pair_bits.ptr : nullptr),
            "k_render_fwd");
+    if (bits) note_bits(ctx, bins, cd.tiles_x * cd.tiles_y);
     return FS_OK;
 }
 
@@ -434,11 +446,7 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
                                        static_cast<double*>(ctx->tile_partial.ptr), bits ? ctx->pair_bits.ptr : nullptr),
                "k_render_fwd");
     }
-    if (bits) {
-        ctx->bits_pairs = bins->num_pairs;
-        ctx->bits_order = bins->gauss_sorted;
-        ctx->bits_tiles = tiles;
-    }
+    if (bits) note_bits(ctx, bins, tiles);
     ProfScope prof(ctx, FS_K_L1);
     FS_HIP(launch_fold_tile_partials(ctx->stream, static_cast<const double*>(ctx->tile_partial.ptr), tiles, 3 * pixels,
                                      static_cast<double*>(ctx->partial.ptr), loss_out),

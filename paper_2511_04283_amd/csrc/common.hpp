@@ -196,14 +196,15 @@ hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t
 hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
                               uint32_t* ranges, uint32_t* tile_order);
 
+// pair_bits: null, or PAIR_BITS_BYTES per pair, which receive the pixels of its tile at which the multi-view score
+// counts the pair's Gaussian (see launch_score_bits)
+constexpr int PAIR_BITS_BYTES = 32;
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib);
+                             uint32_t* n_contrib, void* pair_bits);
 
 // forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
-// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null; pair_bits: null, or PAIR_BITS_BYTES per pair,
-// which receive the pixels of its tile at which the multi-view score counts the pair's Gaussian
-constexpr int PAIR_BITS_BYTES = 32;
+// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null; pair_bits as for launch_render_fwd
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,

@@ -785,14 +785,20 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib)
+                             uint32_t* n_contrib, void* pair_bits)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL((k_render_fwd<false, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
-                       reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
-                       reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr, nullptr,
-                       nullptr, nullptr);
+    if (pair_bits)
+        hipLaunchKernelGGL((k_render_fwd<false, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
+                           nullptr, nullptr, static_cast<uint4*>(pair_bits));
+    else
+        hipLaunchKernelGGL((k_render_fwd<false, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
+                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
+                           reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
+                           nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 

@@ -37,6 +37,7 @@ class TrainConfig:
 class Trainer:
     def __init__(self, ctx: B.Context, means, scales, quats, opacities, sh, sh_degree: int, cfg: TrainConfig | None = None):
         self.ctx, self.cfg, self.sh_degree = ctx, cfg or TrainConfig(), int(sh_degree)
+        ctx.fs_set_score_record(False)   # training iterations are not followed by a count pass; score_views turns it on
         f = lambda t: t.detach().to(ctx.device, torch.float32).contiguous().clone()
         op = f(opacities).clamp(1e-4, 1 - 1e-4)
         self.p = dict(means=f(means), sh=f(sh), raw_scales=torch.log(f(scales)), raw_quats=f(quats),
@@ -108,6 +109,7 @@ class Trainer:
         n, dev = self.n, ctx.device
         counts = torch.zeros(n, dtype=torch.int32, device=dev)
         acc = torch.zeros(n, dtype=torch.float64, device=dev)
+        ctx.fs_set_score_record(True)   # (off during the training iterations, which no count pass follows)
         for cam, target in zip(cams, targets):
             fcam = B.make_camera(cam)
             proj = ctx.fs_preprocess(g, fcam)
@@ -120,6 +122,7 @@ class Trainer:
             out3, _ = ctx.fs_photo_loss(image, target, c.lam, want_grad=False)
             ctx.fs_prune_score_accumulate(view, out3[2:3], acc)
             counts += view   # (memory plumbing: a plain integer add of two device arrays)
+        ctx.fs_set_score_record(False)
         return counts, ctx.fs_prune_score_normalize(acc)
 
     # -- densify by cloning, prune; Adam state of the survivors is kept, clones start at zero ------

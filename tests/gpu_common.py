@@ -39,6 +39,17 @@ def gpu_pipeline(ctx, sc, cam, target=None, dL=None, mask_rule=0, mask_k=1.0, wa
             out["mask"] = mask.cpu().numpy()
             out["thr"] = np.float32(thr.item())
             out["counts"] = counts.cpu().numpy()
+            # the count pass has two implementations: from the record the forward pass left (above, the default)
+            # and by a second walk over the tile lists (when no record is kept); both must give the same counts
+            ctx.fs_set_score_record(False)
+            try:
+                image2, final_T2, n_contrib2 = ctx.fs_render_fwd(proj, bins, fcam)
+                walked = torch.zeros(sc.n, dtype=torch.int32, device=ctx.device)
+                ctx.fs_score_accumulate(proj, bins, fcam, final_T2, n_contrib2, mask, walked)
+            finally:
+                ctx.fs_set_score_record(True)
+            assert torch.equal(image2, image) and torch.equal(n_contrib2, n_contrib)
+            assert torch.equal(walked, counts), "count pass: record and walk disagree"
     return out
 
 

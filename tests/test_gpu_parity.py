@@ -334,8 +334,8 @@ def test_fused_forward_gives_what_the_separate_calls_give(ctx, orc32, W, H, rule
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("case", ["transparent", "opaque", "long_lists"])
 def test_counts_from_the_forward_record_equal_the_walk_and_the_oracle(orc32, mode, case):
-    """fs_score_accumulate after fs_render_fwd_loss (counts from the per-pair record of the forward pass) against
-    fs_score_accumulate after fs_render_fwd (second walk over the lists) and the oracle, bit-exact, in both score
+    """fs_score_accumulate from the per-pair record of the forward pass (either forward entry point) against
+    fs_score_accumulate without a record (second walk over the lists) and the oracle, bit-exact, in both score
     modes; scenes: mostly transparent, opaque enough that pixels finish early and the tail of the lists is never
     reached, and lists of several batches.  Also: the record follows the latest forward pass, not an earlier one."""
     import torch
@@ -378,17 +378,23 @@ def test_counts_from_the_forward_record_equal_the_walk_and_the_oracle(orc32, mod
     c.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, cnt_rec)
     c.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, cnt_rec)          # accumulates; the record stays usable
     assert np.array_equal(cnt_rec.cpu().numpy(), 2 * ref)
-    # (2) a plain forward pass afterwards: the record is not used any more, the lists are walked
+    # (2) the plain forward pass keeps the record as well
     img2, fT2, nc2 = c.fs_render_fwd(proj, bins, fcam)
-    cnt_walk = torch.zeros(sc.n, dtype=torch.int32, device=c.device)
-    c.fs_score_accumulate(proj, bins, fcam, fT2, nc2, mask, cnt_walk)
-    assert np.array_equal(cnt_walk.cpu().numpy(), ref)
-    # (3) record off: the fused forward pass gives the same image, the count pass walks
+    assert torch.equal(img2, img) and torch.equal(nc2, nc)
+    cnt_plain = torch.zeros(sc.n, dtype=torch.int32, device=c.device)
+    c.fs_score_accumulate(proj, bins, fcam, fT2, nc2, mask, cnt_plain)
+    assert np.array_equal(cnt_plain.cpu().numpy(), ref)
+    # (3) record off: both forward passes give the same image, the count pass walks the lists
     c.fs_set_score_record(False)
     img3, fT3, nc3, dL3 = c.fs_render_fwd_loss(proj, bins, fcam, tgt)
     assert torch.equal(img3, img) and torch.equal(nc3, nc) and torch.equal(dL3, dL)
     cnt_off = torch.zeros(sc.n, dtype=torch.int32, device=c.device)
     c.fs_score_accumulate(proj, bins, fcam, fT3, nc3, mask, cnt_off)
+    assert np.array_equal(cnt_off.cpu().numpy(), ref)
+    img4, fT4, nc4 = c.fs_render_fwd(proj, bins, fcam)
+    assert torch.equal(img4, img) and torch.equal(nc4, nc)
+    cnt_off.zero_()
+    c.fs_score_accumulate(proj, bins, fcam, fT4, nc4, mask, cnt_off)
     assert np.array_equal(cnt_off.cpu().numpy(), ref)
     # (4) record on again, another mask (every pixel): counts = blended pixels per Gaussian
     c.fs_set_score_record(True)
