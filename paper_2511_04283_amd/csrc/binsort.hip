@@ -491,43 +491,106 @@ __global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__
 
 // Step (3): one workgroup sorts one tile's segment in LDS (bitonic network on the 64-bit words, padded to
 // a power of two with all-ones words) and writes the final keys tile << 32 | depth_bits and the Gaussian
-// indices.  Thread t does compare-exchange t (+256, ...) of a step.  (Replacing the workgroup barrier by a
-// wavefront-level one for the steps at distance <= 64, which stay inside one wavefront's 128 words, and a
-// register/shuffle variant of those steps, were both measured slower.)
+// indices.  The network is bound by LDS traffic (every step reads and writes every word), so the steps at
+// distances 4, 2, 1 of a stage -- which stay inside aligned groups of 8 words -- are done in registers: a thread
+// loads a group, runs the three steps (all of the stages 2, 4, 8 at the start) and stores it back, which makes 21
+// passes over LDS of the 36 steps of a 256-word sort; long lists use groups of 16 words (distances 8 .. 1).
+// Groups are 16 bytes further apart in LDS than their size so that the 16-byte accesses of neighbouring lanes fall
+// into different banks.  Steps at larger distances: thread t does compare-exchange t (+256, ...).  (Replacing the workgroup barrier by a wavefront-level one for the steps at
+// distance <= 64, a register/shuffle variant of those steps, and giving short lists to single wavefronts were
+// all measured slower.)
 // Handles the tiles whose length is in (len_lo, CAP]; the others are left to another launch.
+__device__ __forceinline__ void cmpx(uint64_t& a, uint64_t& b, bool up)
+{
+    const bool sw = (a > b) == up;
+    const uint64_t x = sw ? b : a, y = sw ? a : b;
+    a = x;
+    b = y;
+}
+
+// The sort proper, with G (8 or 16) words per register group; k holds N + 2 N / G words.
+template <int G>
+__device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_t tile, uint32_t first,
+                                              const uint64_t* __restrict__ bucket, uint64_t* __restrict__ keys_out,
+                                              uint32_t* __restrict__ vals_out)
+{
+    constexpr int LG = G == 8 ? 3 : 4;
+    static_assert(G == 8 || G == 16, "group of 8 or 16 words");
+    auto at = [](int e) { return e + ((e >> LG) << 1); };   // word e of the sequence -> its place in k
+    for (int i = threadIdx.x; i < N; i += 256) k[at(i)] = i < n ? bucket[first + i] : ~0ull;
+    __syncthreads();
+    // one group through registers: FIRST = the complete stages 2 .. G, otherwise the steps at distances
+    // G/2 .. 1 of a later stage, whose direction `up` is the same for the whole group
+    auto local = [&](int g, bool first_stages, bool up) {
+        uint4* q = reinterpret_cast<uint4*>(&k[(G + 2) * g]);
+        uint64_t v[G];
+#pragma unroll
+        for (int h = 0; h < G / 2; h++) {
+            const uint4 w = q[h];
+            v[2 * h] = ((uint64_t)w.y << 32) | w.x;
+            v[2 * h + 1] = ((uint64_t)w.w << 32) | w.z;
+        }
+        if (first_stages) {
+#pragma unroll
+            for (int k2 = 2; k2 < G; k2 <<= 1)
+#pragma unroll
+                for (int j = k2 >> 1; j > 0; j >>= 1)
+#pragma unroll
+                    for (int e = 0; e < G; e++)
+                        if ((e & j) == 0) cmpx(v[e], v[e | j], (e & k2) == 0);
+        }
+#pragma unroll
+        for (int j = G / 2; j > 0; j >>= 1)
+#pragma unroll
+            for (int e = 0; e < G; e++)
+                if ((e & j) == 0) cmpx(v[e], v[e | j], up);
+#pragma unroll
+        for (int h = 0; h < G / 2; h++)
+            q[h] = make_uint4((uint32_t)v[2 * h], (uint32_t)(v[2 * h] >> 32), (uint32_t)v[2 * h + 1],
+                              (uint32_t)(v[2 * h + 1] >> 32));
+    };
+    for (int g = threadIdx.x; g < (N >> LG); g += 256) local(g, true, ((G * g) & G) == 0);
+    __syncthreads();
+    for (int k2 = 2 * G; k2 <= N; k2 <<= 1) {
+        for (int j = k2 >> 1; j >= G; j >>= 1) {
+            for (int t = threadIdx.x; t < (N >> 1); t += 256) {
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int hi = lo | j;
+                const bool up = (lo & k2) == 0;
+                const uint64_t a = k[at(lo)], b = k[at(hi)];
+                if ((a > b) == up) { k[at(lo)] = b; k[at(hi)] = a; }
+            }
+            __syncthreads();
+        }
+        for (int g = threadIdx.x; g < (N >> LG); g += 256) local(g, false, ((G * g) & k2) == 0);
+        __syncthreads();
+    }
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const uint64_t v = k[at(i)];
+        keys_out[first + i] = ((uint64_t)tile << 32) | (v >> 32);
+        vals_out[first + i] = (uint32_t)v;
+    }
+}
+
 template <int CAP>
 __global__ __launch_bounds__(256) void k_tile_sort(const uint2* __restrict__ ranges,
                                                    const uint32_t* __restrict__ tile_order,
                                                    const uint64_t* __restrict__ bucket, int len_lo,
                                                    uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
 {
-    __shared__ uint64_t k[CAP];
+    __shared__ __align__(16) uint64_t k[CAP + CAP / 4];
     const uint32_t tile = tile_order[blockIdx.x];
     const uint2 r = ranges[tile];
     const int n = (int)(r.y - r.x);
     if (n <= len_lo || n > CAP) return;   // (uniform over the workgroup)
-    int N = 2;
+    int N = 16;
     while (N < n) N <<= 1;
-    for (int i = threadIdx.x; i < N; i += 256) k[i] = i < n ? bucket[r.x + i] : ~0ull;
-    __syncthreads();
-    for (int k2 = 2; k2 <= N; k2 <<= 1) {
-        for (int j = k2 >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < (N >> 1); t += 256) {
-                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int hi = lo | j;
-                const bool up = (lo & k2) == 0;
-                const uint64_t a = k[lo], b = k[hi];
-                if ((a > b) == up) { k[lo] = b; k[hi] = a; }
-            }
-            __syncthreads();
-        }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < n; i += 256) {
-        const uint64_t v = k[i];
-        keys_out[r.x + i] = ((uint64_t)tile << 32) | (v >> 32);
-        vals_out[r.x + i] = (uint32_t)v;
-    }
+    // groups of 16 words make fewer passes over LDS but leave N / 16 threads busy in the register phases:
+    // measured better from 1024 words on
+    if (N <= TILE_SORT_GROUP16_FROM / 2)
+        tile_sort_lds<8>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
+    else
+        tile_sort_lds<16>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
 }
 
 // ---- radix sort -------------------------------------------------------------------------

@@ -173,6 +173,7 @@ hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& p
 constexpr int TILE_COPIES = 256;        // workgroups of the counting / placement kernels, each with its own counters (a multiple of 64)
 constexpr int TILE_PAIR_THREADS = 1024;
 constexpr int TILE_LDS_MAX_TILES = 15360;  // their per-tile counters live in LDS (60 KB)
+constexpr int TILE_SORT_GROUP16_FROM = 1024;  // padded list length from which a thread merges 16 words in registers, not 8
 constexpr int TILE_SORT_SMALL = 2048;  // longest list one workgroup sorts with 16 KB of LDS
 constexpr int TILE_SORT_MAX = 8192;    // ... with 64 KB
 hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
