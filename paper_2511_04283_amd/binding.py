@@ -240,6 +240,9 @@ class Bins:
     def copy_ranges(self):
         return self._copy(self.struct.tile_ranges, 2 * self.num_tiles, torch.int32).view(self.num_tiles, 2)
 
+    def copy_order(self):
+        return self._copy(self.struct.tile_order, self.num_tiles, torch.int32)
+
 
 class Context:
     """Owns one fs_ctx bound to a torch device and (by default) torch's current stream on it."""

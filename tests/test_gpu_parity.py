@@ -247,6 +247,28 @@ def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
     assert np.abs(g["image"] - img).max() <= 1e-4
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("n,W,H", [(3000, 203, 117), (60000, 640, 400), (500, 1600, 1064)])
+def test_tile_order_is_a_permutation_with_the_longest_lists_first(n, W, H, mode):
+    """bins.tile_order (the order in which the render kernels take the tiles) holds every tile once, and list
+    lengths, in units of 8 entries capped at 511 units, never increase along it -- from both orderings."""
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.sort_mode = mode
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(40 + n % 7, n, W, H, sh_degree=0, log_scale=(-3.0, 0.8), spread=1.1)
+    g = B.Gaussians.from_scene(sc, c.device)
+    fcam = B.make_camera(sc.cameras[0])
+    bins = c.fs_bin_sort(c.fs_preprocess(g, fcam), fcam)
+    order = bins.copy_order().cpu().numpy().astype(np.int64)
+    r = bins.copy_ranges().cpu().numpy().view(np.uint32).astype(np.int64)
+    T = ((W + 15) // 16) * ((H + 15) // 16)
+    assert order.shape == (T,) and np.array_equal(np.sort(order), np.arange(T))
+    units = np.minimum((r[:, 1] - r[:, 0])[order] >> 3, 511)
+    assert (np.diff(units) <= 0).all() and units[0] > 0
+    c.close()
+
+
 @pytest.mark.parametrize("compact_box", [0, 1])
 def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_box):
     """A context keeps its scratch buffers from call to call and grows them when a call needs more. One
