@@ -119,12 +119,15 @@ typedef struct {
     const uint64_t *keys_sorted;  /* [P] tile_id << 32 | bits(depth), ascending; ties by Gaussian index */
     const uint32_t *gauss_sorted; /* [P] Gaussian index of each entry                                 */
     const uint32_t *tile_ranges;  /* [tiles,2] first,last(+1) entry of each tile; 0,0 if empty; tile_id = ty*TX+tx */
-    const uint32_t *pair_offsets; /* [n] exclusive prefix sum of tiles_touched: Gaussian i's pairs were emitted from
-                                     pair_offsets[i] on, rows then columns of rect, before the sort             */
+    const uint32_t *pair_offsets; /* radix ordering: [n] exclusive prefix sum of tiles_touched (Gaussian i's pairs were
+                                     emitted from pair_offsets[i] on, rows then columns of rect, before the sort);
+                                     NULL when the pairs were ordered per tile, which emits nothing in index order */
     int64_t num_records;          /* backward scratch records: P, or with the Compact Box the sum of rect areas  */
     const uint32_t *record_offsets; /* [n] Gaussian i's backward records start here; the record of tile (tx,ty) is
-                                     record_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0).  Equals pair_offsets
-                                     without the Compact Box.                                                   */
+                                     record_offsets[i] + (ty - y0)*(x1 - x0) + (tx - x0).  The places of different
+                                     Gaussians are disjoint and lie within num_records; they are in index order
+                                     only after the radix ordering (then equal to pair_offsets without the Compact
+                                     Box), and may differ from call to call otherwise.                          */
     const uint32_t *record_counts;  /* [n] records per Gaussian (rect area); NULL = proj->tiles_touched           */
     const uint32_t *tile_order;   /* [tiles] the tiles by decreasing list length: the order the render kernels take them in */
     const void *splats;           /* [n] 64-byte records (opaque): fs_bin_sort's copy of mean2d, conic_opacity, rgb,

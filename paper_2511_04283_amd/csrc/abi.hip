@@ -39,6 +39,8 @@ struct fs_ctx {
     ScratchBuf partial;       // double reduction partials
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
+    uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
+    bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
     ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
     ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES]: per pair, the pixels of its tile at which the score counts it
     bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
@@ -225,7 +227,9 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->cfg = c;
     ctx->err[0] = 0;
-    if (hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 4 * sizeof(uint64_t)) != hipSuccess ||
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->alloc_dev), 2 * sizeof(uint64_t)) != hipSuccess ||
+        hipMemset(ctx->alloc_dev, 0, 2 * sizeof(uint64_t)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 4 * sizeof(uint64_t)) != hipSuccess ||
         hipHostMalloc(reinterpret_cast<void**>(&ctx->total_host), 4 * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         fs_destroy(ctx);
@@ -246,6 +250,7 @@ void fs_destroy(fs_ctx* ctx)
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
+    if (ctx->alloc_dev) (void)hipFree(ctx->alloc_dev);
     if (ctx->total_host) (void)hipHostFree(ctx->total_host);
     for (auto& v : ctx->prof_pending)
         for (auto& pr : v) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
@@ -293,18 +298,22 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
     FS_TRY(ensure(ctx, ctx->splats, (size_t)(n > 0 ? n : 1) * SPLAT_REC * sizeof(float), "splats"));
 
-    // a2: offsets and the pair count P (the one host read-back of the path).  With the Compact Box the
-    // backward records are indexed by candidate tile, so the boxes' areas get a prefix sum of their own.
+    // a2: where each Gaussian's pairs / backward records start, and the pair count P (the one host read-back of
+    // the path).  With the Compact Box the records are indexed by candidate tile, so the boxes' areas get
+    // offsets of their own.  The radix path emits its keys in index order from exclusive prefix sums; the
+    // tile-bucketed path only needs disjoint places for the records and gets them from its counting kernel.
     const bool cb = ctx->cfg.compact_box != 0;
     const CfgDev cf = make_cfg(ctx->cfg);
-    {
+    if (cb) {
+        FS_TRY(ensure(ctx, ctx->rec_counts, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record counts"));
+        FS_TRY(ensure(ctx, ctx->rec_offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record offsets"));
+    }
+    auto prefix_sums = [&]() -> int {
         ProfScope prof(ctx, FS_K_SCAN);
         FS_HIP(launch_exclusive_scan(st, proj ? proj->tiles_touched : nullptr, static_cast<uint32_t*>(ctx->offsets.ptr),
                                      n, ctx->scan_tmp.ptr, ctx->total_dev),
                "scan");
         if (cb) {
-            FS_TRY(ensure(ctx, ctx->rec_counts, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record counts"));
-            FS_TRY(ensure(ctx, ctx->rec_offsets, (size_t)(n > 0 ? n : 1) * sizeof(uint32_t), "record offsets"));
             FS_HIP(launch_rect_area(st, n, proj ? proj->rect : nullptr, static_cast<uint32_t*>(ctx->rec_counts.ptr)),
                    "k_rect_area");
             FS_HIP(launch_exclusive_scan(st, static_cast<const uint32_t*>(ctx->rec_counts.ptr),
@@ -312,25 +321,34 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
                                          ctx->total_dev + 1),
                    "scan");
         }
-    }
-    // tile-bucketed ordering, first half: pairs per tile, ranges, longest list (needs no P-sized memory,
-    // so it is enqueued ahead of the read-back)
+        return FS_OK;
+    };
     if (bucketed) {
+        // first half: pairs per tile, ranges, longest list, record places (needs no P-sized memory, so it is
+        // enqueued ahead of the read-back)
         ProfScope prof(ctx, FS_K_EMIT);
         fs_projected none = {};
+        if (ctx->alloc_dirty) FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(ctx->alloc_dev), 0u, 4), "k_fill_u32");
+        ctx->alloc_dirty = true;
         FS_HIP(launch_tile_count(st, n, proj ? *proj : none, cf, cd.tiles_x, tiles, tcount_p, ttotal_p,
-                                 reinterpret_cast<uint2*>(ranges_p), order_p, ctx->total_dev + 2),
+                                 reinterpret_cast<uint2*>(ranges_p), order_p, ctx->total_dev,
+                                 static_cast<uint32_t*>(cb ? ctx->rec_offsets.ptr : ctx->offsets.ptr),
+                                 cb ? static_cast<uint32_t*>(ctx->rec_counts.ptr) : nullptr, ctx->alloc_dev),
                "k_tile_pairs (count)");
+        ctx->alloc_dirty = false;
+    } else {
+        FS_TRY(prefix_sums());
     }
     FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
            "hipMemcpyAsync");
     FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
-    const uint64_t P = ctx->total_host[0];
-    const uint64_t NR = cb ? ctx->total_host[1] : P;
+    // bucketed: {sum of tiles_touched, records, pairs counted per tile, longest list}; else {pairs, records (CB)}
+    const uint64_t P = bucketed ? ctx->total_host[2] : ctx->total_host[0];
+    const uint64_t NR = cb || bucketed ? ctx->total_host[1] : P;
+    if (bucketed && (ctx->total_host[0] != P || (!cb && NR != P)))
+        return fail(ctx, FS_EINVAL, "fs_bin_sort: tiles_touched does not match rect (proj from another configuration?)");
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
     if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
-    if (bucketed && ctx->total_host[2] != P)
-        return fail(ctx, FS_EINVAL, "fs_bin_sort: tiles_touched does not match rect (proj from another configuration?)");
     const uint64_t max_len = bucketed ? ctx->total_host[3] : 0;
     const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_MAX;
     if (cb) FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(NR ? NR : 1) * PAIR_REC * sizeof(float), "pair gradients"));
@@ -359,6 +377,8 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
                                         static_cast<float*>(ctx->pair_grad.ptr)),
                "tile-bucketed ordering");
     } else {
+        // (lists too long for the per-tile sort: the radix path's prefix sums have not been made yet)
+        if (bucketed) FS_TRY(prefix_sums());
         if (P > 0) {
             // a3
             {
@@ -388,9 +408,9 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->keys_sorted = keys[res];
     out->gauss_sorted = vals[res];
     out->tile_ranges = static_cast<const uint32_t*>(ctx->ranges.ptr);
-    out->pair_offsets = static_cast<const uint32_t*>(ctx->offsets.ptr);
+    out->pair_offsets = lds_sort ? nullptr : static_cast<const uint32_t*>(ctx->offsets.ptr);
     out->num_records = (int64_t)NR;
-    out->record_offsets = cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr) : out->pair_offsets;
+    out->record_offsets = static_cast<const uint32_t*>(cb ? ctx->rec_offsets.ptr : ctx->offsets.ptr);
     out->record_counts = cb ? static_cast<const uint32_t*>(ctx->rec_counts.ptr) : nullptr;
     out->splats = ctx->splats.ptr;
     out->tile_order = static_cast<const uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles;

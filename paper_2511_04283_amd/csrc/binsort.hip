@@ -307,6 +307,21 @@ __global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4*
 // (k_tile_sum has turned each copy's counter into that copy's start within the tile's segment),
 // bucket[slot] = depth_bits << 32 | index; also packs the splat records and, with
 // the Compact Box, zeroes the gradient records of the candidates that are no pairs.
+//
+// Step (1) also hands every Gaussian the place of its backward records (one per tile of its rectangle): a
+// workgroup first adds up the records of all its Gaussians and reserves them with one add on a global counter
+// (adds on one address take about 10 ns each, so one per wavefront and round would cost more than the prefix sum
+// it replaces); inside the reservation the wavefronts, their rounds and the 64 Gaussians of a round follow each
+// other.  The places are disjoint, each Gaussian's are contiguous and so are those of 64 consecutive Gaussians,
+// which is all their users need -- no prefix sum over the Gaussians.  A second counter receives the sum of
+// tiles_touched, which the host compares with the number of pairs counted per tile.
+struct RecAlloc {
+    const uint32_t* tiles_touched;   // [n]
+    uint32_t* rec_offsets;           // [n] out: first record of each Gaussian
+    uint32_t* rec_counts;            // [n] out (may be null): records of each Gaussian = area of its rectangle
+    unsigned long long* counters;    // [2]: records handed out, sum of tiles_touched
+};
+
 template <bool CB, bool SCATTER>
 __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, const ushort4* __restrict__ rect,
                                                     const float* __restrict__ depth,
@@ -317,7 +332,7 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
                                                     int num_tiles, uint32_t* __restrict__ tile_counter,
                                                     const uint2* __restrict__ ranges, uint32_t P,
                                                     uint64_t* __restrict__ bucket, float4* __restrict__ splats,
-                                                    float4* __restrict__ pair_grad)
+                                                    float4* __restrict__ pair_grad, RecAlloc ra)
 {
     extern __shared__ uint32_t s_tile[];   // this workgroup's counter per tile
     uint32_t* const my_row = tile_counter + (size_t)blockIdx.x * num_tiles;
@@ -325,6 +340,38 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
     for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) s_tile[t] = SCATTER ? ranges[t].x + my_row[t] : 0u;
     __syncthreads();
     const uint32_t lane = lane_id();
+    uint32_t rec_next = 0;   // (counting) where the records of this wavefront's next round start
+    if (!SCATTER) {
+        __shared__ uint32_t s_wave_recs[TILE_PAIR_THREADS / 64];
+        __shared__ uint32_t s_tt[TILE_PAIR_THREADS / 64];
+        __shared__ uint32_t s_base[2];
+        uint32_t recs = 0, tt = 0;
+        for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i < n;
+             i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
+            const ushort4 r = rect[i];
+            recs += (r.z > r.x ? (uint32_t)(r.z - r.x) : 0u) * (r.w > r.y ? (uint32_t)(r.w - r.y) : 0u);
+            tt += ra.tiles_touched[i];
+        }
+        recs = wave_inclusive_scan(recs);
+        tt = wave_inclusive_scan(tt);
+        if (lane == 63) { s_wave_recs[threadIdx.x >> 6] = recs; s_tt[threadIdx.x >> 6] = tt; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long all = 0, all_tt = 0;
+            for (int w = 0; w < TILE_PAIR_THREADS / 64; w++) { all += s_wave_recs[w]; all_tt += s_tt[w]; }
+            unsigned long long b = 0;
+            if (all | all_tt) {
+                b = atomicAdd(&ra.counters[0], all);
+                atomicAdd(&ra.counters[1], all_tt);
+            }
+            // (a reservation that reaches beyond 32 bits is never used: the host rejects the call on the total)
+            s_base[0] = (uint32_t)b;
+            s_base[1] = (b + all) >> 32 ? 1u : 0u;
+        }
+        __syncthreads();
+        rec_next = s_base[1] ? 0u : s_base[0];
+        for (int w = 0; w < (int)(threadIdx.x >> 6); w++) rec_next += s_base[1] ? 0u : s_wave_recs[w];
+    }
     // (every wavefront of the workgroup walks its own 64 Gaussians per round; no barrier inside the rounds)
     for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i - lane < n;
          i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
@@ -351,6 +398,13 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
         const uint32_t excl = inc - cnt;
         const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
         const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
+        if (!SCATTER) {
+            if (valid) {
+                ra.rec_offsets[i] = rec_next + excl;
+                if (ra.rec_counts) ra.rec_counts[i] = cnt;
+            }
+            rec_next += total;
+        }
         for (uint32_t j0 = 0; j0 < total; j0 += 64) {
             const bool live = j0 + lane < total;
             const uint32_t j = min(j0 + lane, total - 1);
@@ -434,12 +488,13 @@ __global__ __launch_bounds__(64 * (TILE_COPIES / 64)) void k_tile_sum(uint32_t* 
     if (g == 0) tile_total[t] = all;
 }
 
-// One workgroup: exclusive scan of the tile totals -> ranges [first, last); totals[0] = sum,
-// totals[1] = longest list; and the order in which the render kernels take the tiles (longest list first,
-// bucketed by length / 8, as k_tile_order).  Thread t owns the consecutive tiles [t*per, t*per + per).
+// One workgroup: exclusive scan of the tile totals -> ranges [first, last); totals[2] = sum,
+// totals[3] = longest list (totals[0..1] come from the counting kernel's two counters); and the order in which
+// the render kernels take the tiles (longest list first, bucketed by length / 8, as k_tile_order).  Thread t owns the consecutive tiles [t*per, t*per + per).
 __global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__ tile_total, int num_tiles,
                                                     uint2* __restrict__ ranges, uint32_t* __restrict__ order,
-                                                    uint64_t* __restrict__ totals)
+                                                    uint64_t* __restrict__ totals,
+                                                    unsigned long long* __restrict__ counters)
 {
     constexpr int NB = 512;
     __shared__ uint32_t wsum[16];
@@ -473,7 +528,16 @@ __global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__
         if (q < per && t0 + q < num_tiles) ranges[t0 + q] = c[q] ? make_uint2(run, run + c[q]) : make_uint2(0u, 0u);
         run += c[q];
     }
-    if (threadIdx.x == 1023) { totals[0] = run; totals[1] = max_s; }
+    if (threadIdx.x == 1023) {
+        // totals: sum of tiles_touched, backward records, pairs counted per tile, longest list; the two counters of
+        // the counting kernel start the next call at zero
+        totals[0] = counters[1];
+        totals[1] = counters[0];
+        totals[2] = run;
+        totals[3] = max_s;
+        counters[0] = 0ull;
+        counters[1] = 0ull;
+    }
     // tile order: exclusive prefix over the 512 length buckets by one wavefront, then a counting placement
     if (threadIdx.x < 64) {
         uint32_t b8[8], sum = 0;
@@ -784,8 +848,10 @@ hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& p
 
 hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
                              int num_tiles, uint32_t* tile_count, uint32_t* tile_total, uint2* ranges,
-                             uint32_t* tile_order, uint64_t* totals)
+                             uint32_t* tile_order, uint64_t* totals, uint32_t* rec_offsets, uint32_t* rec_counts,
+                             uint64_t* counters)
 {
+    const RecAlloc ra = {proj.tiles_touched, rec_offsets, rec_counts, reinterpret_cast<unsigned long long*>(counters)};
     {
         const dim3 grid(TILE_COPIES), block(TILE_PAIR_THREADS);
         const size_t lds = (size_t)num_tiles * sizeof(uint32_t);
@@ -794,14 +860,15 @@ hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj
         const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
         if (cfg.compact_box)
             hipLaunchKernelGGL((k_tile_pairs<true, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
-                               nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr);
+                               nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr, ra);
         else
             hipLaunchKernelGGL((k_tile_pairs<false, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb,
-                               cfg, nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr);
+                               cfg, nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr, ra);
     }
     hipLaunchKernelGGL(k_tile_sum, dim3((unsigned)((num_tiles + 63) / 64)), dim3(64 * (TILE_COPIES / 64)), 0, st, tile_count,
                        num_tiles, tile_total);
-    hipLaunchKernelGGL(k_tile_scan, dim3(1), dim3(1024), 0, st, tile_total, num_tiles, ranges, tile_order, totals);
+    hipLaunchKernelGGL(k_tile_scan, dim3(1), dim3(1024), 0, st, tile_total, num_tiles, ranges, tile_order, totals,
+                       reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError();
 }
 
@@ -819,11 +886,11 @@ hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projecte
         if (cfg.compact_box)
             hipLaunchKernelGGL((k_tile_pairs<true, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
                                rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
-                               reinterpret_cast<float4*>(pair_grad));
+                               reinterpret_cast<float4*>(pair_grad), RecAlloc{});
         else
             hipLaunchKernelGGL((k_tile_pairs<false, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
                                rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
-                               reinterpret_cast<float4*>(pair_grad));
+                               reinterpret_cast<float4*>(pair_grad), RecAlloc{});
     }
     if (P > 0) {
         hipLaunchKernelGGL(k_tile_sort<TILE_SORT_SMALL>, dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket, 0,

@@ -168,8 +168,11 @@ hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& p
 // Tile-bucketed ordering (used when no tile's list is longer than TILE_SORT_MAX; otherwise the global
 // radix sort below): per-tile counts and ranges, then placement into the tiles' segments and an LDS sort
 // of every segment.  ranges/tile_order/tile_total: [num_tiles]; tile_count: [TILE_COPIES, num_tiles], turned by
-// launch_tile_count into each copy's start within its tile (the `cursor` of launch_tile_scatter_sort);
-// totals: {sum, longest list}.
+// launch_tile_count into each copy's start within its tile (the `cursor` of launch_tile_scatter_sort).
+// launch_tile_count also gives every Gaussian the place of its backward records (rec_offsets [n]: disjoint,
+// contiguous per Gaussian, not ordered by index; rec_counts [n], may be null: the area of its rectangle) from
+// `counters` (two uint64 that are zero at the start and are left zero), and writes
+// totals [4] = {sum of proj.tiles_touched, records handed out, pairs counted per tile, longest list}.
 constexpr int TILE_COPIES = 256;        // workgroups of the counting / placement kernels, each with its own counters (a multiple of 64)
 constexpr int TILE_PAIR_THREADS = 1024;
 constexpr int TILE_LDS_MAX_TILES = 15360;  // their per-tile counters live in LDS (60 KB)
@@ -178,7 +181,8 @@ constexpr int TILE_SORT_SMALL = 2048;  // longest list one workgroup sorts with 
 constexpr int TILE_SORT_MAX = 8192;    // ... with 64 KB
 hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
                              int num_tiles, uint32_t* tile_count, uint32_t* tile_total, uint2* ranges,
-                             uint32_t* tile_order, uint64_t* totals);
+                             uint32_t* tile_order, uint64_t* totals, uint32_t* rec_offsets, uint32_t* rec_counts,
+                             uint64_t* counters);
 hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
                                     const uint32_t* rec_offsets, int tiles_x, int num_tiles, int64_t P, int max_len,
                                     const uint2* ranges, uint32_t* cursor, const uint32_t* tile_order, uint64_t* bucket,
