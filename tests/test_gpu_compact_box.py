@@ -99,3 +99,24 @@ def test_bad_beta_is_rejected():
         cfg.cb_beta = beta
         h = ctypes.c_void_p()
         assert lib.fs_create(ctypes.byref(h), 0, None, ctypes.byref(cfg)) == -1
+
+
+@pytest.mark.parametrize("compact_box", [0, 1])
+def test_lists_too_long_for_the_per_tile_sort_whole_path(compact_box):
+    """Lists beyond 8192 entries: fs_bin_sort starts on the per-tile ordering, finds the longest list on the host
+    and falls back to the radix sort, making the prefix sums it had skipped.  The whole path (ranges, image,
+    gradients through the per-pair records, counts) against the oracle, with and without the Compact Box."""
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.compact_box = compact_box
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(77, 60000, 40, 33, sh_degree=0, log_scale=(-3.2, 0.7), spread=1.1)
+    cam = sc.cameras[0]
+    tgt = np.random.default_rng(3).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    o = Oracle(np.float32, Config(compact_box=bool(compact_box)))
+    r = oracle_pipeline(o, sc, cam, target=tgt)
+    L = r["bins"].tile_ranges[:, 1].astype(np.int64) - r["bins"].tile_ranges[:, 0]
+    assert L.max() > 8192
+    g = gpu_pipeline(c, sc, cam, target=tgt)
+    check_all(g, r, sc)
+    c.close()
