@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--radix-sort", action="store_true", help="order the pairs with the global radix sort (sort_mode)")
     ap.add_argument("--abs-grad", action="store_true",
                     help="also accumulate the absolute positional gradient in the backward pass (split criterion)")
+    ap.add_argument("--per-splat-bwd", action="store_true",
+                    help="run the backward pass in its per-splat-parallel mapping (fs_set_backward_mode), for comparison")
     ap.add_argument("--train-iteration", action="store_true",
                     help="time a whole training iteration: activations + the hot path + chain rule + Adam on every group")
     ap.add_argument("--photo-loss", action="store_true",
@@ -70,6 +72,8 @@ def main() -> int:
     cfg0.cb_beta = args.cb_beta
     cfg0.sort_mode = B.FS_SORT_RADIX if args.radix_sort else B.FS_SORT_AUTO
     ctx = B.Context(dev, cfg0)
+    if args.per_splat_bwd:
+        ctx.fs_set_backward_mode(B.FS_BWD_PER_SPLAT)
     g = B.Gaussians.from_scene(sc, dev)
     fcam = B.make_camera(cam)
     target = torch.from_numpy(target_np).to(dev)
@@ -238,11 +242,12 @@ def main() -> int:
     dominant = max(kernels_ms, key=kernels_ms.get)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_cfg{args.config}.json")
-    if os.path.exists(tpath) and not args.compact_box:
+    if os.path.exists(tpath) and not args.compact_box and not args.per_splat_bwd:
         with open(tpath) as f:
             traffic = json.load(f).get("render_bwd_bytes_per_launch")
     achieved = bwd_flops / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
-    roofline = {"kernel": "k_render_bwd", "bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_TFLOPS,
+    roofline = {"kernel": "k_render_bwd_splat" if args.per_splat_bwd else "k_render_bwd", "bound": "alu",
+                "achieved": round(achieved, 3), "peak": PEAK_FP32_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(bwd_ms, 4), "flops_per_launch": bwd_flops,
                 "dominant_group_by_time": dominant}

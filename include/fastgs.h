@@ -221,6 +221,16 @@ int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, cons
                   const fs_bins *bins, const float *final_T, const uint32_t *n_contrib,
                   const float *dL_dimage, fs_grads *out);
 
+/* How fs_render_bwd maps the backward of the compositing onto the GPU (same inputs, outputs and tolerances):
+ * FS_BWD_PER_PIXEL (default): a lane per pixel walks its sub-tile's list back to front; a Gaussian's sums over the
+ *   pixels are reduced across lanes.
+ * FS_BWD_PER_SPLAT: a lane per list entry, the pixels of an 8x8 block pass by one after the other; the quantities
+ *   carried along a pixel's list become scans over the lanes, the sums need no reduction.  This is the mapping of
+ *   the paper's baseline (Sec. 5.3 and the supplement: per-splat parallel backpropagation); on this chip and on
+ *   lists as sparse as the benchmark's it is the slower of the two, and it is kept for comparison. */
+enum { FS_BWD_PER_PIXEL = 0, FS_BWD_PER_SPLAT = 1 };
+int fs_set_backward_mode(fs_ctx *ctx, int32_t mode);
+
 /* Step a10: e = mean over channels of |image - target|; threshold t = mean(e) + k*std(e)
  * (FS_MASK_MEAN_STD; population std, fp64 accumulation) or min(e) + k*(max(e)-min(e))
  * (FS_MASK_MINMAX_TAU, i.e. min-max normalised e > k); mask = e > t (uint8 0/1, [H,W]).

@@ -43,6 +43,7 @@ struct fs_ctx {
     bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
     ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
     ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES]: per pair, the pixels of its tile at which the score counts it
+    bool per_splat_bwd = false;      // fs_set_backward_mode
     bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
     int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
     const void* bits_order = nullptr;  // ... with this gauss_sorted, on this many tiles; -1: they describe nothing
@@ -475,6 +476,14 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
     return FS_OK;
 }
 
+int fs_set_backward_mode(fs_ctx* ctx, int32_t mode)
+{
+    if (!ctx) return FS_EINVAL;
+    if (mode != FS_BWD_PER_PIXEL && mode != FS_BWD_PER_SPLAT) return fail(ctx, FS_EINVAL, "fs_set_backward_mode: unknown mode");
+    ctx->per_splat_bwd = mode == FS_BWD_PER_SPLAT;
+    return FS_OK;
+}
+
 int fs_set_score_record(fs_ctx* ctx, int32_t on)
 {
     if (!ctx) return FS_EINVAL;
@@ -548,7 +557,7 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
         ProfScope prof(ctx, FS_K_RENDER_BWD);
         FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                                  static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad,
-                                 out->dmean2d_abs != nullptr),
+                                 out->dmean2d_abs != nullptr, ctx->per_splat_bwd),
                "k_render_bwd");
     }
     // a9: per-Gaussian sum of its records, then the chain through the projection

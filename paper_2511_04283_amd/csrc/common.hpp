@@ -226,7 +226,8 @@ hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, 
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad);
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad,
+                             bool per_splat);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                         const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,

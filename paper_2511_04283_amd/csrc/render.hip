@@ -604,6 +604,232 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     }
 }
 
+// ---- per-splat-parallel backward (the mapping of Taming-3DGS that the paper's baseline uses) -------------
+// Alternative to k_render_bwd with the same inputs, outputs and record layout; kept for comparison.
+// A wavefront owns one 8x8 quadrant of the tile.  Per batch it forms the quadrant's list (the staged entries
+// whose box meets any of its four sub-tiles), takes it in chunks of 64 entries from the back, one entry per
+// lane (lane 0 = the entry furthest back), and passes the quadrant's 64 pixels by one after the other.  For a
+// pixel p every lane evaluates its own Gaussian; what the per-pixel kernel carries from entry to entry becomes
+// two scans over the lanes:
+//   T in front of entry l    = T_behind_chunk / prod_{k <= l} (1 - alpha_k)
+//   S behind entry l         = the maps  S -> alpha_k (dC . c_k) + (1 - alpha_k) S  of the entries k < l applied,
+//                              furthest first, to S_behind_chunk, where S = dC . (colour composited behind),
+//                              which is all that dL/dalpha = T (dC . c - S) needs.
+// The 9 (11) sums of a Gaussian over the pixels are then plain per-lane accumulators: no reduction across
+// lanes.  Pixel p's state (T, S behind the part of the list already done) lives in lane p and is fetched with
+// readlane.  The four quadrants' sums of a Gaussian meet in LDS as in k_render_bwd.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_from(float identity, float v)
+{
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+
+// Inclusive scan over the lanes of the composition of the maps S -> b + m S, lane 0 applied first:
+// afterwards (m, b) of lane l is the composition of the maps of lanes 0 .. l.
+__device__ __forceinline__ void wave_scan_affine(float& m, float& b)
+{
+#define FS_AFFINE_STEP(CTRL, ROW_MASK)                                  \
+    {                                                                   \
+        const float mo = dpp_from<CTRL, ROW_MASK>(1.0f, m);             \
+        const float bo = dpp_from<CTRL, ROW_MASK>(0.0f, b);             \
+        b = __builtin_fmaf(m, bo, b);                                   \
+        m = m * mo;                                                     \
+    }
+    FS_AFFINE_STEP(0x111, 0xF)   // row_shr:1
+    FS_AFFINE_STEP(0x112, 0xF)   // row_shr:2
+    FS_AFFINE_STEP(0x114, 0xF)   // row_shr:4
+    FS_AFFINE_STEP(0x118, 0xF)   // row_shr:8
+    FS_AFFINE_STEP(0x142, 0xA)   // row_bcast:15 into rows 1 and 3
+    FS_AFFINE_STEP(0x143, 0xC)   // row_bcast:31 into rows 2 and 3
+#undef FS_AFFINE_STEP
+}
+
+template <bool ABS>
+__global__ __launch_bounds__(256) void k_render_bwd_splat(
+    CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
+    const uint32_t* __restrict__ gauss_sorted,
+    const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
+    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
+{
+    __shared__ Stage s;
+    __shared__ float4 s_rgb[BATCH];
+    __shared__ uint32_t s_id[BATCH];
+    constexpr int NV = ABS ? 11 : 9;
+    __shared__ float s_acc[BATCH][NV];
+    __shared__ uint8_t s_qlist[4][BATCH];   // per quadrant: the batch slots on its list, in list order
+    __shared__ int s_max;
+
+    const int tile = (int)tile_order[blockIdx.x];
+    const Pixel p = pixel_of_thread(cam, tile);
+    const uint2 range = ranges[tile];
+    const size_t hw = (size_t)cam.width * cam.height;
+    const size_t pix = (size_t)p.y * cam.width + p.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+
+    // this lane's pixel: constants and the state behind the part of the list already done
+    const int last = p.inside ? (int)n_contrib[pix] : 0;
+    float T_st = p.inside ? final_T[pix] : 0.f;
+    float dC0 = 0.f, dC1 = 0.f, dC2 = 0.f;
+    if (p.inside) {
+        dC0 = dL_dimage[pix];
+        dC1 = dL_dimage[hw + pix];
+        dC2 = dL_dimage[2 * hw + pix];
+    }
+    float S_st = __builtin_fmaf(dC2, cfg.bg[2], __builtin_fmaf(dC1, cfg.bg[1], dC0 * cfg.bg[0]));
+
+    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
+    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (threadIdx.x == 0) s_max = 0;
+    __syncthreads();
+    atomicMax(&s_max, last);
+    __syncthreads();
+    const int total = s_max;
+    // the furthest position any pixel of this quadrant reaches (uniform in the wavefront)
+    int wave_last = last;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) wave_last = max(wave_last, __shfl_xor(wave_last, d, 64));
+
+    for (int start = ((total - 1) / BATCH) * BATCH; start >= 0 && total > 0; start -= BATCH) {
+        const int m = min(BATCH, total - start);
+        __syncthreads();  // the previous batch's flush has read s_acc / s_id, its walk s_qlist
+#pragma unroll
+        for (int k = 0; k < NV; k++) s_acc[threadIdx.x][k] = 0.f;
+        stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
+        // the quadrant's list: lane l looks at slots 4 l .. 4 l + 3 of the union of its four sub-tiles' masks
+        uint32_t b4 = 0;
+        {
+            const int word = lane >> 4, shift = (lane & 15) * 4;
+            uint64_t u = 0;
+#pragma unroll
+            for (int r = 0; r < 4; r++) u |= s.bits[wave * 4 + r][word];
+            b4 = (uint32_t)(u >> shift) & 0xFu;
+        }
+        const int cnt = __popc(b4);
+        int inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += o;
+        }
+        const int qlen = __shfl(inc, 63, 64);
+        {
+            int pos = inc - cnt;
+            uint32_t b = b4;
+            while (b) {
+                s_qlist[wave][pos++] = (uint8_t)(4 * lane + __builtin_ctz(b));
+                b &= b - 1u;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        if (start < wave_last) {
+            for (int c_end = qlen; c_end > 0; c_end -= 64) {
+                // lane 0 takes the entry furthest back of the chunk
+                const int idx = c_end - 1 - lane;
+                const bool have = idx >= 0;
+                const int j = have ? (int)s_qlist[wave][idx] : 0;
+                const float2 xy = s.xy[j];
+                const float4 co = s.co[j];
+                const float4 col = s_rgb[j];
+                const int pos_j = start + j;
+                float acc[NV];
+#pragma unroll
+                for (int k = 0; k < NV; k++) acc[k] = 0.f;
+                bool any = false;
+                for (int q = 0; q < 64; q++) {
+                    const int last_q = __builtin_amdgcn_readlane(last, q);
+                    if (last_q <= start) continue;   // this pixel blends nothing of this batch
+                    const float px = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p.px), q));
+                    const float py = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p.py), q));
+                    const float dx = px - xy.x, dy = py - xy.y;
+                    const float u = __builtin_fmaf(co.y, dy, co.x * dx);
+                    const float qq = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+                    const float power = -0.5f * qq;
+                    bool act = have & (pos_j < last_q) & !(power > 0.0f) & !(power < cfg.power_min);
+                    if (__ballot(act) == 0) continue;
+                    float G = exp_c(act ? power : 0.0f);
+                    const float sG = co.w * G;
+                    float alpha = fminf(cfg.alpha_max, sG);
+                    act = act & (alpha >= cfg.alpha_min);
+                    if (__ballot(act) == 0) continue;
+                    any = true;
+                    alpha = act ? alpha : 0.f;
+                    G = act ? G : 0.f;
+                    const float d0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dC0), q));
+                    const float d1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dC1), q));
+                    const float d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dC2), q));
+                    const float T_behind = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(T_st), q));
+                    const float S_behind = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(S_st), q));
+                    const float cd = __builtin_fmaf(col.z, d2, __builtin_fmaf(col.y, d1, col.x * d0));   // dC . c
+                    float M = 1.0f - alpha, Bc = alpha * cd;
+                    wave_scan_affine(M, Bc);
+                    // maps of the lanes before this one (the entries behind it)
+                    float Mx = __shfl_up(M, 1, 64), Bx = __shfl_up(Bc, 1, 64);
+                    if (lane == 0) { Mx = 1.0f; Bx = 0.0f; }
+                    const float T = T_behind * __builtin_amdgcn_rcpf(M);   // in front of this entry
+                    const float S = __builtin_fmaf(Mx, S_behind, Bx);      // dC . (colour behind this entry)
+                    const float w = alpha * T;
+                    acc[0] = __builtin_fmaf(w, d0, acc[0]);
+                    acc[1] = __builtin_fmaf(w, d1, acc[1]);
+                    acc[2] = __builtin_fmaf(w, d2, acc[2]);
+                    float dL_dalpha = T * (cd - S);
+                    dL_dalpha = sG > cfg.alpha_max ? 0.f : dL_dalpha;   // capped alpha is a constant
+                    acc[3] = __builtin_fmaf(G, dL_dalpha, acc[3]);
+                    const float gq = -0.5f * (co.w * G) * dL_dalpha;
+                    const float gx = gq * dx, gy = gq * dy;
+                    acc[4] = __builtin_fmaf(gx, dx, acc[4]);
+                    acc[5] = __builtin_fmaf(gx, dy, acc[5]);
+                    acc[6] = __builtin_fmaf(gy, dy, acc[6]);
+                    acc[7] += gx;
+                    acc[8] += gy;
+                    if (ABS) {
+                        const float ag = fabsf(gq);
+                        acc[NV - 2] = __builtin_fmaf(ag, fabsf(__builtin_fmaf(co.y, dy, 2.0f * co.x * dx)), acc[NV - 2]);
+                        acc[NV - 1] = __builtin_fmaf(ag, fabsf(__builtin_fmaf(co.y, dx, 2.0f * co.z * dy)), acc[NV - 1]);
+                    }
+                    // pixel q moves in front of the chunk: the last lane holds the composition of all its maps
+                    const float M_all = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(M), 63));
+                    const float B_all = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(Bc), 63));
+                    const float T_new = T_behind * __builtin_amdgcn_rcpf(M_all);
+                    const float S_new = __builtin_fmaf(M_all, S_behind, B_all);
+                    T_st = lane == q ? T_new : T_st;
+                    S_st = lane == q ? S_new : S_st;
+                }
+                if (any && have) {
+#pragma unroll
+                    for (int k = 0; k < NV; k++)
+                        if (acc[k] != 0.f) atomicAdd(&s_acc[j][k], acc[k]);
+                }
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < m) {
+            const float* a = s_acc[threadIdx.x];
+            const float4 co = s.co[threadIdx.x];  // co.y holds 2b
+            float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
+            rec[0] = make_float4(a[0], a[1], a[2], a[3]);
+            rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
+            rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
+        }
+    }
+    // pairs behind the furthest blended Gaussian of the tile received nothing
+    for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
+        const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
+        const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
+        const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
+        const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
+                             ((uint32_t)(tile % cam.tiles_x) - x0);
+        float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
+        rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
+        rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
 // Count pass: re-walks the forward loop for the mask pixels only (other pixels cannot add to a
 // count) up to each pixel's n_contrib, and counts per Gaussian the pixels where it is blended
 // (and, in weight mode, alpha*T > alpha_min).  A ballot + population count gives each sub-tile's
@@ -835,20 +1061,28 @@ hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* 
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad)
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad, bool per_splat)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    if (abs_grad)
-        hipLaunchKernelGGL(k_render_bwd<true>, dim3(tiles), dim3(256), 0, st, cam, cfg,
-                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
-                           reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
-                           reinterpret_cast<float4*>(pair_grad));
-    else
-        hipLaunchKernelGGL(k_render_bwd<false>, dim3(tiles), dim3(256), 0, st, cam, cfg,
-                           reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
-                           reinterpret_cast<const float4*>(splats), final_T, n_contrib, dL_dimage,
-                           reinterpret_cast<float4*>(pair_grad));
+    const uint2* r2 = reinterpret_cast<const uint2*>(ranges);
+    const float4* sp = reinterpret_cast<const float4*>(splats);
+    float4* pg = reinterpret_cast<float4*>(pair_grad);
+    const dim3 grid(tiles), block(256);
+    if (per_splat) {
+        if (abs_grad)
+            hipLaunchKernelGGL(k_render_bwd_splat<true>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
+                               n_contrib, dL_dimage, pg);
+        else
+            hipLaunchKernelGGL(k_render_bwd_splat<false>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp,
+                               final_T, n_contrib, dL_dimage, pg);
+    } else if (abs_grad) {
+        hipLaunchKernelGGL(k_render_bwd<true>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
+                           n_contrib, dL_dimage, pg);
+    } else {
+        hipLaunchKernelGGL(k_render_bwd<false>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
+                           n_contrib, dL_dimage, pg);
+    }
     return hipGetLastError();
 }
 
