@@ -573,7 +573,7 @@ __device__ __forceinline__ void cmpx(uint64_t& a, uint64_t& b, bool up)
 }
 
 // The sort proper, with G (8 or 16) words per register group; k holds N + 2 N / G words.
-template <int G>
+template <int G, int THREADS>
 __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_t tile, uint32_t first,
                                               const uint64_t* __restrict__ bucket, uint64_t* __restrict__ keys_out,
                                               uint32_t* __restrict__ vals_out)
@@ -581,7 +581,7 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
     constexpr int LG = G == 8 ? 3 : 4;
     static_assert(G == 8 || G == 16, "group of 8 or 16 words");
     auto at = [](int e) { return e + ((e >> LG) << 1); };   // word e of the sequence -> its place in k
-    for (int i = threadIdx.x; i < N; i += 256) k[at(i)] = i < n ? bucket[first + i] : ~0ull;
+    for (int i = threadIdx.x; i < N; i += THREADS) k[at(i)] = i < n ? bucket[first + i] : ~0ull;
     __syncthreads();
     // one group through registers: FIRST = the complete stages 2 .. G, otherwise the steps at distances
     // G/2 .. 1 of a later stage, whose direction `up` is the same for the whole group
@@ -613,11 +613,11 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
             q[h] = make_uint4((uint32_t)v[2 * h], (uint32_t)(v[2 * h] >> 32), (uint32_t)v[2 * h + 1],
                               (uint32_t)(v[2 * h + 1] >> 32));
     };
-    for (int g = threadIdx.x; g < (N >> LG); g += 256) local(g, true, ((G * g) & G) == 0);
+    for (int g = threadIdx.x; g < (N >> LG); g += THREADS) local(g, true, ((G * g) & G) == 0);
     __syncthreads();
     for (int k2 = 2 * G; k2 <= N; k2 <<= 1) {
         for (int j = k2 >> 1; j >= G; j >>= 1) {
-            for (int t = threadIdx.x; t < (N >> 1); t += 256) {
+            for (int t = threadIdx.x; t < (N >> 1); t += THREADS) {
                 const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 const int hi = lo | j;
                 const bool up = (lo & k2) == 0;
@@ -626,18 +626,18 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
             }
             __syncthreads();
         }
-        for (int g = threadIdx.x; g < (N >> LG); g += 256) local(g, false, ((G * g) & k2) == 0);
+        for (int g = threadIdx.x; g < (N >> LG); g += THREADS) local(g, false, ((G * g) & k2) == 0);
         __syncthreads();
     }
-    for (int i = threadIdx.x; i < n; i += 256) {
+    for (int i = threadIdx.x; i < n; i += THREADS) {
         const uint64_t v = k[at(i)];
         keys_out[first + i] = ((uint64_t)tile << 32) | (v >> 32);
         vals_out[first + i] = (uint32_t)v;
     }
 }
 
-template <int CAP>
-__global__ __launch_bounds__(256) void k_tile_sort(const uint2* __restrict__ ranges,
+template <int CAP, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__ ranges,
                                                    const uint32_t* __restrict__ tile_order,
                                                    const uint64_t* __restrict__ bucket, int len_lo,
                                                    uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
@@ -652,9 +652,9 @@ __global__ __launch_bounds__(256) void k_tile_sort(const uint2* __restrict__ ran
     // groups of 16 words make fewer passes over LDS but leave N / 16 threads busy in the register phases:
     // measured better from 1024 words on
     if (N <= TILE_SORT_GROUP16_FROM / 2)
-        tile_sort_lds<8>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
+        tile_sort_lds<8, THREADS>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
     else
-        tile_sort_lds<16>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
+        tile_sort_lds<16, THREADS>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
 }
 
 // ---- radix sort -------------------------------------------------------------------------
@@ -893,11 +893,12 @@ hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projecte
                                reinterpret_cast<float4*>(pair_grad), RecAlloc{});
     }
     if (P > 0) {
-        hipLaunchKernelGGL(k_tile_sort<TILE_SORT_SMALL>, dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket, 0,
-                           keys_out, vals_out);
+        // the long lists first: few workgroups, each a long chain of steps, which 1024 threads shorten
         if (max_len > TILE_SORT_SMALL)
-            hipLaunchKernelGGL(k_tile_sort<TILE_SORT_MAX>, dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket,
-                               TILE_SORT_SMALL, keys_out, vals_out);
+            hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MAX, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
+                               bucket, TILE_SORT_SMALL, keys_out, vals_out);
+        hipLaunchKernelGGL((k_tile_sort<TILE_SORT_SMALL, 256>), dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket,
+                           0, keys_out, vals_out);
     }
     return hipGetLastError();
 }
