@@ -557,10 +557,11 @@ __global__ __launch_bounds__(1024) void k_tile_scan(const uint32_t* __restrict__
 // a power of two with all-ones words) and writes the final keys tile << 32 | depth_bits and the Gaussian
 // indices.  The network is bound by LDS traffic (every step reads and writes every word), so the steps at
 // distances 4, 2, 1 of a stage -- which stay inside aligned groups of 8 words -- are done in registers: a thread
-// loads a group, runs the three steps (all of the stages 2, 4, 8 at the start) and stores it back, which makes 21
-// passes over LDS of the 36 steps of a 256-word sort; long lists use groups of 16 words (distances 8 .. 1).
+// loads a group, runs the three steps (all of the stages 2, 4, 8 at the start) and stores it back; the steps at
+// larger distances are taken three at a time as well, on groups of 8 words the right distance apart, which makes
+// 13 passes over LDS of the 36 steps of a 256-word sort.  Long lists use groups of 16 words (four steps a pass).
 // Groups are 16 bytes further apart in LDS than their size so that the 16-byte accesses of neighbouring lanes fall
-// into different banks.  Steps at larger distances: thread t does compare-exchange t (+256, ...).  (Replacing the workgroup barrier by a wavefront-level one for the steps at
+// into different banks.  (Replacing the workgroup barrier by a wavefront-level one for the steps at
 // distance <= 64, a register/shuffle variant of those steps, and giving short lists to single wavefronts were
 // all measured slower.)
 // Handles the tiles whose length is in (len_lo, CAP]; the others are left to another launch.
@@ -572,7 +573,34 @@ __device__ __forceinline__ void cmpx(uint64_t& a, uint64_t& b, bool up)
     b = y;
 }
 
-// The sort proper, with G (8 or 16) words per register group; k holds N + 2 N / G words.
+// GG words at distance 2^a from each other through registers: the GG/2 .. 1 steps of stage k2 at distances
+// 2^a GG/2 .. 2^a.  The words of a group agree in every index bit outside [a, a + log2 GG), the stage's bit
+// among them, so one direction serves the group.  Ends with a workgroup barrier.
+template <int GG, int LG, int THREADS>
+__device__ __forceinline__ void tile_sort_strided(uint64_t* k, int N, int a, int k2)
+{
+    constexpr int LGG = GG == 2 ? 1 : GG == 4 ? 2 : GG == 8 ? 3 : 4;
+    auto at = [](int e) { return e + ((e >> LG) << 1); };
+    for (int g = threadIdx.x; g < N / GG; g += THREADS) {
+        const int e0 = ((g >> a) << (a + LGG)) | (g & ((1 << a) - 1));
+        const bool up = (e0 & k2) == 0;
+        uint64_t v[GG];
+#pragma unroll
+        for (int q = 0; q < GG; q++) v[q] = k[at(e0 + (q << a))];
+#pragma unroll
+        for (int jj = GG / 2; jj > 0; jj >>= 1)
+#pragma unroll
+            for (int q = 0; q < GG; q++)
+                if ((q & jj) == 0) cmpx(v[q], v[q | jj], up);
+#pragma unroll
+        for (int q = 0; q < GG; q++) k[at(e0 + (q << a))] = v[q];
+    }
+    __syncthreads();
+}
+
+// The sort proper, with G (8 or 16) words per register group; k holds N + 2 N / G words.  A stage's steps are
+// taken log2 G at a time, from the largest distance down: first the odd ones out (a smaller group), then groups
+// of G words ever closer together, last the contiguous groups with 16-byte LDS accesses.
 template <int G, int THREADS>
 __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_t tile, uint32_t first,
                                               const uint64_t* __restrict__ bucket, uint64_t* __restrict__ keys_out,
@@ -583,8 +611,8 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
     auto at = [](int e) { return e + ((e >> LG) << 1); };   // word e of the sequence -> its place in k
     for (int i = threadIdx.x; i < N; i += THREADS) k[at(i)] = i < n ? bucket[first + i] : ~0ull;
     __syncthreads();
-    // one group through registers: FIRST = the complete stages 2 .. G, otherwise the steps at distances
-    // G/2 .. 1 of a later stage, whose direction `up` is the same for the whole group
+    // one contiguous group through registers: FIRST = the complete stages 2 .. G, otherwise the steps at
+    // distances G/2 .. 1 of a later stage, whose direction `up` is the same for the whole group
     auto local = [&](int g, bool first_stages, bool up) {
         uint4* q = reinterpret_cast<uint4*>(&k[(G + 2) * g]);
         uint64_t v[G];
@@ -615,17 +643,14 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
     };
     for (int g = threadIdx.x; g < (N >> LG); g += THREADS) local(g, true, ((G * g) & G) == 0);
     __syncthreads();
-    for (int k2 = 2 * G; k2 <= N; k2 <<= 1) {
-        for (int j = k2 >> 1; j >= G; j >>= 1) {
-            for (int t = threadIdx.x; t < (N >> 1); t += THREADS) {
-                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int hi = lo | j;
-                const bool up = (lo & k2) == 0;
-                const uint64_t a = k[at(lo)], b = k[at(hi)];
-                if ((a > b) == up) { k[at(lo)] = b; k[at(hi)] = a; }
-            }
-            __syncthreads();
-        }
+    for (int k2 = 2 * G, m = LG + 1; k2 <= N; k2 <<= 1, m++) {   // m = log2 k2: the stage has steps 2^(m-1) .. 1
+        int top = m;
+        const int odd = (m - LG) % LG;
+        if (odd == 1) tile_sort_strided<2, LG, THREADS>(k, N, top - 1, k2);
+        if (odd == 2) tile_sort_strided<4, LG, THREADS>(k, N, top - 2, k2);
+        if (odd == 3) tile_sort_strided<8, LG, THREADS>(k, N, top - 3, k2);
+        top -= odd;
+        for (; top > LG; top -= LG) tile_sort_strided<G, LG, THREADS>(k, N, top - LG, k2);
         for (int g = threadIdx.x; g < (N >> LG); g += THREADS) local(g, false, ((G * g) & k2) == 0);
         __syncthreads();
     }
