@@ -11,9 +11,11 @@
  *   fs_render_fwd_loss / fs_error_mask_fused
  *                        the forward pass with the L1 term and the error map fused into it
  *   fs_render_bwd        gradient of a loss w.r.t. every Gaussian parameter     (chain rule of Eqs. (2)-(5))
+ *   fs_set_backward_mode per-pixel (default) or per-splat-parallel mapping of it (Sec. 5.3: the baseline's backward)
  *   fs_error_mask        per-pixel L1 error map and high-error mask             (Sec. 4.2, first three equations)
  *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
  *                        one view per call                                      (Sec. 4.2, Eq. for s_d)
+ *   fs_set_score_record  whether the forward passes keep the per-pair record that this count is taken from
  *   fs_photo_loss        E = (1-lambda) L1 + lambda (1 - SSIM) and dE/dC        (Sec. 4.3 E_photo; Sec. 4.5 Eq. for L)
  *   fs_prune_score_accumulate / fs_prune_score_normalize
  *                        s_p = N(sum over views of count * E_photo)             (Sec. 4.3, Eq. for s_p)
