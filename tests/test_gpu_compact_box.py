@@ -120,3 +120,21 @@ def test_lists_too_long_for_the_per_tile_sort_whole_path(compact_box):
     g = gpu_pipeline(c, sc, cam, target=tgt)
     check_all(g, r, sc)
     c.close()
+
+
+@pytest.mark.parametrize("compact_box", [0, 1])
+def test_radix_ordering_whole_path(compact_box):
+    """sort_mode = FS_SORT_RADIX: prefix sums, index-ordered emission, global radix sort -- and everything downstream
+    of it (image, gradients through the per-pair records at their prefix-sum places, mask, counts) against the oracle."""
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.compact_box = compact_box
+    cfg.sort_mode = B.FS_SORT_RADIX
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(78, 9000, 203, 117, sh_degree=2, log_scale=(-2.6, 0.8), spread=1.4)
+    cam = sc.cameras[0]
+    tgt = np.random.default_rng(4).uniform(0, 1, (3, cam.height, cam.width)).astype(np.float32)
+    r = oracle_pipeline(Oracle(np.float32, Config(compact_box=bool(compact_box))), sc, cam, target=tgt)
+    g = gpu_pipeline(c, sc, cam, target=tgt, want_abs=True)
+    check_all(g, r, sc)
+    c.close()
