@@ -295,7 +295,9 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
         const bool row_alive = ((__ballot(!done) >> (threadIdx.x & 48)) & 0xffffull) != 0;
         const int longest = wave_max_of_rows(row_alive ? mine : 0);
         // Straight-line body with selects: lanes past their list's end (or finished) read a stale
-        // slot and discard the result; only two wave-uniform branches per iteration.
+        // slot and discard the result; one wave-uniform branch per iteration.  (Skipping the rest of an
+        // iteration when no lane passes the range test does not pay: four rows look at four different
+        // Gaussians, so all of them missing is rare, and the test costs more than it saves.)
         for (int k = 0; k < longest; k++) {
             if (__ballot(!done) == 0) break;
             const int j = s.list[sub][k];
@@ -306,7 +308,6 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
             const float power = -0.5f * q;
             bool ok = (k < mine) & !done & !(power > 0.0f) & !(power < cfg.power_min);
-            if (__ballot(ok) == 0) continue;
             const float4 col = s_rgb[j];
             const float G = exp_c(power);
             const float alpha = fminf(cfg.alpha_max, co.w * G);
@@ -529,8 +530,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
             const float power = -0.5f * q;
             bool act = (k >= 0) & (start + j < last) & !(power > 0.0f) & !(power < cfg.power_min);
-            if (__ballot(act) == 0) continue;
-            float G = exp_c(power);
+            float G = exp_c(power);   // (whatever the exponent of a lane that fails the test: its result is dropped)
             const float sG = co.w * G;
             float alpha = fminf(cfg.alpha_max, sG);
             act = act & (alpha >= cfg.alpha_min);
