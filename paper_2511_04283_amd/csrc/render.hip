@@ -573,10 +573,12 @@ __global__ __launch_bounds__(256) void k_render_bwd(
                 const float ay = ag * fabsf(__builtin_fmaf(co.y, dx, 2.0f * co.z * dy));
                 const float r2 = row_reduce2(ax, ay, lane);
                 // lane 10 (even) holds the total of ax -> slot 9, lane 9 (odd) that of ay -> slot 10
-                if (li < 11 && ((act_mask >> (lane & 48)) & 0xffffull) != 0)
-                    atomicAdd(&s_acc[j][li < 9 ? li : 19 - li], li < 8 ? packed : (li == 8 ? ninth : r2));
-            } else if (li < 9 && ((act_mask >> (lane & 48)) & 0xffffull) != 0) {
-                atomicAdd(&s_acc[j][li], li < 8 ? packed : ninth);
+                // (a row none of whose pixels blends the Gaussian has zero totals: nothing to add)
+                const float tot = li < 8 ? packed : (li == 8 ? ninth : r2);
+                if (li < 11 && tot != 0.f) atomicAdd(&s_acc[j][li < 9 ? li : 19 - li], tot);
+            } else {
+                const float tot = li < 8 ? packed : ninth;
+                if (li < 9 && tot != 0.f) atomicAdd(&s_acc[j][li], tot);
             }
         }
         __syncthreads();
