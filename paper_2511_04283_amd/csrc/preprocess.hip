@@ -308,8 +308,11 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     constexpr int F = 3 * K;                      // SH floats per Gaussian
     constexpr int ROW = F + 1;                    // padded row: lane-strided LDS access without bank conflicts
     constexpr int CH = 128;                       // pair records per chunk and wavefront
-    constexpr int WAVE_FLOATS = 64 * ROW > CH * PAIR_REC ? 64 * ROW : CH * PAIR_REC;
-    // one buffer per wavefront, used in turn for the pair records, the SH coefficients and the SH gradients
+    constexpr int HALF = 32;                      // Gaussians whose SH rows are in LDS at a time
+    constexpr int WAVE_FLOATS = HALF * ROW > CH * PAIR_REC ? HALF * ROW : CH * PAIR_REC;
+    // one buffer per wavefront, used in turn for the pair records and, half a wavefront at a time, for the SH
+    // coefficients and their gradients (kept this small so that more wavefronts fit a compute unit: the kernel
+    // is bound by memory and needs them to keep enough loads in flight)
     __shared__ __attribute__((aligned(16))) float s_buf[4][(WAVE_FLOATS + 3) / 4 * 4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool in_range = i < n;
@@ -349,48 +352,111 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         }
     }
 
-    // ---- SH coefficients of the wavefront's 64 Gaussians: one contiguous block of 64*F floats, copied
-    //      to LDS with coalesced loads (a lane reading its own F floats straight from memory would touch
-    //      64 different cache lines per instruction) ----
+    // ---- SH coefficients of HALF consecutive Gaussians of the wavefront: one contiguous block of HALF*F floats,
+    //      copied to LDS with coalesced loads (a lane reading its own F floats straight from memory would touch
+    //      64 different cache lines per instruction); the gradients go back the same way ----
     float* rows = s_buf[wave];
-    float* c = rows + lane * ROW;                 // this lane's coefficients, later its gradients
+    float* c = rows + (lane & (HALF - 1)) * ROW;  // this lane's coefficients, later its gradients
     const int64_t wave_first = (int64_t)blockIdx.x * blockDim.x + wave * 64;
     const int valid_rows = (int)min((int64_t)64, max((int64_t)0, n - wave_first));
-    {
-        const float* src = sh + wave_first * F;
-        if (valid_rows == 64) {
-            // full wavefront: 16 F aligned float4s, all loads issued before the first LDS write
-            constexpr int NV = (16 * F + 63) / 64;
+    constexpr int NV = (HALF / 4 * F + 63) / 64;  // float4 per lane for a full half
+    auto load_half = [&](int h) {
+        const int vr = min(HALF, max(0, valid_rows - h * HALF));
+        const float* src = sh + (wave_first + h * HALF) * F;
+        if (vr == HALF) {
+            // all loads issued before the first LDS write
             const float4* src4 = reinterpret_cast<const float4*>(src);
             float4 v[NV];
 #pragma unroll
             for (int it = 0; it < NV; it++) {
                 const int q = lane + 64 * it;
-                v[it] = q < 16 * F ? src4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                v[it] = q < HALF / 4 * F ? src4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
             for (int it = 0; it < NV; it++) {
                 const int q = lane + 64 * it;
-                if (q < 16 * F) {
+                if (q < HALF / 4 * F) {
                     const float comp[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
                     int row = (4 * q) / F, col = 4 * q - row * F;
 #pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        rows[row * ROW + col] = comp[j];
+                    for (int jj = 0; jj < 4; jj++) {
+                        rows[row * ROW + col] = comp[jj];
                         if (++col == F) { col = 0; row++; }
                     }
                 }
             }
         } else {
-            for (int e = lane; e < 64 * F; e += 64) {
+            for (int e = lane; e < HALF * F; e += 64) {
                 const int row = e / F;
-                if (row < valid_rows) rows[row * ROW + (e - row * F)] = src[e];
+                if (row < vr) rows[row * ROW + (e - row * F)] = src[e];
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-    }
+    };
+    auto store_half = [&](int h) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int vr = min(HALF, max(0, valid_rows - h * HALF));
+        float* dst = d_sh + (wave_first + h * HALF) * F;
+        if (vr == HALF) {
+            float4* dst4 = reinterpret_cast<float4*>(dst);
+#pragma unroll
+            for (int it = 0; it < NV; it++) {
+                const int q = lane + 64 * it;
+                if (q < HALF / 4 * F) {
+                    float comp[4];
+                    int row = (4 * q) / F, col = 4 * q - row * F;
+#pragma unroll
+                    for (int jj = 0; jj < 4; jj++) {
+                        comp[jj] = rows[row * ROW + col];
+                        if (++col == F) { col = 0; row++; }
+                    }
+                    dst4[q] = make_float4(comp[0], comp[1], comp[2], comp[3]);
+                }
+            }
+        } else {
+            for (int e = lane; e < HALF * F; e += 64) {
+                const int row = e / F;
+                if (row < vr) dst[e] = rows[row * ROW + (e - row * F)];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
 
+    // ---- colour -> SH coefficients (and the weights the view direction's gradient needs), half a wavefront at a
+    //      time; done before the projection is recomputed so that few registers are live across it.  A Gaussian
+    //      with tiles_touched > 0 passed the forward pass's culling, so that count stands in for visibility here.
+    const bool vis0 = in_range && touched[i] > 0;
+    float d[3] = {0.f, 0.f, 1.f}, len = 1.f;
+    float wk[K];
+#pragma unroll
+    for (int k = 0; k < K; k++) wk[k] = 0.f;
+    for (int h = 0; h < 64 / HALF; h++) {
+        load_half(h);
+        if ((lane / HALF) == h && in_range) {
+            float Y[K], gcol[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < K; k++) Y[k] = 0.f;
+            if (vis0) {
+                view_dir(means, i, cam, d, len);
+                sh_basis(DEG, d[0], d[1], d[2], Y);
+                gcol[0] = clamped[3 * i] ? 0.f : ra.x;
+                gcol[1] = clamped[3 * i + 1] ? 0.f : ra.y;
+                gcol[2] = clamped[3 * i + 2] ? 0.f : ra.z;
+            }
+            // (culled Gaussians: gcol = 0, so their gradients come out as zeros)
+#pragma unroll
+            for (int k = 0; k < K; k++) {
+                wk[k] = gcol[0] * c[3 * k] + gcol[1] * c[3 * k + 1] + gcol[2] * c[3 * k + 2];
+                c[3 * k + 0] = gcol[0] * Y[k];   // the coefficient has been read: its slot now holds its gradient
+                c[3 * k + 1] = gcol[1] * Y[k];
+                c[3 * k + 2] = gcol[2] * Y[k];
+            }
+        }
+        store_half(h);
+    }
     Splat s;
     s.visible = false;
     if (in_range) {
@@ -400,15 +466,15 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     if (in_range && !s.visible) {
         for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
         *reinterpret_cast<float4*>(d_quats + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int k = 0; k < F; k++) c[k] = 0.f;
         d_opac[i] = 0.f;
         d_mean2d[2 * i] = 0.f; d_mean2d[2 * i + 1] = 0.f;
         if (d_conic) for (int k = 0; k < 3; k++) d_conic[3 * i + k] = 0.f;
         if (d_rgb) for (int k = 0; k < 3; k++) d_rgb[3 * i + k] = 0.f;
         if (d_abs) { d_abs[2 * i] = 0.f; d_abs[2 * i + 1] = 0.f; }
     }
-    if (in_range && s.visible) {
-        const float g_rgb3[3] = {ra.x, ra.y, ra.z};
+    const bool vis = in_range && s.visible;
+    const float g_rgb3[3] = {ra.x, ra.y, ra.z};
+    if (vis) {
         const float g_conic3[3] = {rb.x, rb.y, rb.z};
         const float g_m2[2] = {rb.w, rc};
         d_opac[i] = ra.w;
@@ -416,21 +482,6 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         if (d_conic) { d_conic[3 * i] = g_conic3[0]; d_conic[3 * i + 1] = g_conic3[1]; d_conic[3 * i + 2] = g_conic3[2]; }
         if (d_rgb) { d_rgb[3 * i] = g_rgb3[0]; d_rgb[3 * i + 1] = g_rgb3[1]; d_rgb[3 * i + 2] = g_rgb3[2]; }
         if (d_abs) { d_abs[2 * i] = rabs_x; d_abs[2 * i + 1] = rabs_y; }
-        // ---- colour -> SH coefficients and, through the view direction, the mean ----
-        float d[3], len;
-        view_dir(means, i, cam, d, len);
-        float Y[K];
-        sh_basis(DEG, d[0], d[1], d[2], Y);
-        float gcol[3];
-        for (int ch = 0; ch < 3; ch++) gcol[ch] = clamped[3 * i + ch] ? 0.f : g_rgb3[ch];
-        float wk[K];
-#pragma unroll
-        for (int k = 0; k < K; k++) {
-            wk[k] = gcol[0] * c[3 * k] + gcol[1] * c[3 * k + 1] + gcol[2] * c[3 * k + 2];
-            c[3 * k + 0] = gcol[0] * Y[k];   // the coefficient has been read: its slot now holds its gradient
-            c[3 * k + 1] = gcol[1] * Y[k];
-            c[3 * k + 2] = gcol[2] * Y[k];
-        }
         float gd[3];
         sh_dir_grad<DEG>(d[0], d[1], d[2], wk, gd);
         const float dot = gd[0] * d[0] + gd[1] * d[1] + gd[2] * d[2];
@@ -506,35 +557,6 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         gq.w = 2.f * (-2.f * z * gR[0][0] - w * gR[0][1] + x * gR[0][2] + w * gR[1][0] - 2.f * z * gR[1][1] +
                       y * gR[1][2] + x * gR[2][0] + y * gR[2][1]);
         *reinterpret_cast<float4*>(d_quats + 4 * i) = gq;
-    }
-    // ---- SH gradients of the wavefront back to memory, coalesced ----
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    {
-        float* dst = d_sh + wave_first * F;
-        if (valid_rows == 64) {
-            constexpr int NV = (16 * F + 63) / 64;
-            float4* dst4 = reinterpret_cast<float4*>(dst);
-#pragma unroll
-            for (int it = 0; it < NV; it++) {
-                const int q = lane + 64 * it;
-                if (q < 16 * F) {
-                    float comp[4];
-                    int row = (4 * q) / F, col = 4 * q - row * F;
-#pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        comp[j] = rows[row * ROW + col];
-                        if (++col == F) { col = 0; row++; }
-                    }
-                    dst4[q] = make_float4(comp[0], comp[1], comp[2], comp[3]);
-                }
-            }
-        } else {
-            for (int e = lane; e < 64 * F; e += 64) {
-                const int row = e / F;
-                if (row < valid_rows) dst[e] = rows[row * ROW + (e - row * F)];
-            }
-        }
     }
 }
 
