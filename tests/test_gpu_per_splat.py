@@ -103,3 +103,13 @@ def test_per_splat_against_per_pixel_config3_full():
     b.close()
     assert np.abs(ga["grads"]["means"]).max() > 0
     assert_grads_close(gb["grads"], {k: v.astype(np.float64) for k, v in ga["grads"].items()}, rtol=2e-4, floor=4e-4)
+
+
+def test_unknown_backward_mode_is_rejected():
+    from paper_2511_04283_amd import binding as B
+    c = B.Context("cuda:0")
+    with pytest.raises(RuntimeError):
+        c.fs_set_backward_mode(7)
+    c.fs_set_backward_mode(B.FS_BWD_PER_SPLAT)
+    c.fs_set_backward_mode(B.FS_BWD_PER_PIXEL)
+    c.close()
