@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the FastGS rasterizer hot path on one MI355X.
 
-One step = one pass of the whole hot path over one synthetic view of the workload:
-fs_preprocess, fs_bin_sort, fs_render_fwd, fs_l1_grad, fs_render_bwd, fs_error_mask,
-fs_score_accumulate (every row of the scope table), inputs resident in HBM.  The headline
-workload is benchmark config 3 (500k Gaussians, SH degree 3, 1600x1064).
+One step = one pass of the whole hot path over one synthetic view of the workload: projection,
+pair ordering, forward compositing, the L1 term, backward, error mask and the per-Gaussian count pass
+(fs_preprocess, fs_bin_sort, fs_render_fwd_loss, fs_render_bwd, fs_error_mask_fused, fs_score_accumulate;
+--separate-calls for the unfused entry points), inputs resident in HBM.  The headline workload is
+benchmark config 3 (500k Gaussians, SH degree 3, 1600x1064).
 
 Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this build is
 single-GPU by construction.
