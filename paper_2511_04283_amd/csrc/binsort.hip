@@ -461,6 +461,10 @@ __global__ __launch_bounds__(64 * (TILE_COPIES / 64)) void k_tile_sum(uint32_t* 
                                                                      uint32_t* __restrict__ tile_total)
 {
     constexpr int GROUPS = TILE_COPIES / 64;
+    // Order of the workgroups' shares within a tile's segment: workgroups are handed to the 8 XCDs in turn, so
+    // those with the same index mod 8 share an L2; putting their shares next to each other lets the 8-byte words
+    // they scatter into a segment fill whole lines in one L2 before they are written back.
+    auto row_at = [](int pos) { return (pos % (TILE_COPIES / 8)) * 8 + pos / (TILE_COPIES / 8); };
     __shared__ uint32_t gsum[GROUPS][64];
     const int g = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int t = blockIdx.x * 64 + lane;
@@ -468,7 +472,7 @@ __global__ __launch_bounds__(64 * (TILE_COPIES / 64)) void k_tile_sum(uint32_t* 
     uint32_t sum = 0;
 #pragma unroll
     for (int k = 0; k < 64; k++) {
-        part[k] = t < num_tiles ? count[(size_t)(g * 64 + k) * num_tiles + t] : 0u;
+        part[k] = t < num_tiles ? count[(size_t)row_at(g * 64 + k) * num_tiles + t] : 0u;
         sum += part[k];
     }
     gsum[g][lane] = sum;
@@ -482,7 +486,7 @@ __global__ __launch_bounds__(64 * (TILE_COPIES / 64)) void k_tile_sum(uint32_t* 
     if (t >= num_tiles) return;
 #pragma unroll
     for (int k = 0; k < 64; k++) {
-        count[(size_t)(g * 64 + k) * num_tiles + t] = run;
+        count[(size_t)row_at(g * 64 + k) * num_tiles + t] = run;
         run += part[k];
     }
     if (g == 0) tile_total[t] = all;
