@@ -426,3 +426,39 @@ def test_counts_from_the_forward_record_equal_the_walk_and_the_oracle(orc32, mod
     c.fs_score_accumulate(proj, bins, fcam, fT, nc, ones, cnt_all)
     assert np.array_equal(cnt_all.cpu().numpy(), o.score(p_o, b_o, cam, np.ones((H, W), np.uint8), np.zeros(sc.n, np.int32)))
     c.close()
+
+
+def test_pair_order_over_seeded_random_shapes(orc32):
+    """Two dozen seeded shapes (Gaussian counts from 1 to 30 000, images from a single tile to 60 x 40 tiles, narrow
+    and wide scale distributions, both box rules) through fs_preprocess + fs_bin_sort on one context per rule:
+    pair count, keys, order and ranges bit-exact, tile order a permutation."""
+    from paper_2511_04283_amd import binding as B
+    rng = np.random.default_rng(20251104)
+    for compact_box in (0, 1):
+        cfg = B.default_config()
+        cfg.compact_box = compact_box
+        cfg.cb_beta = 0.8
+        c = B.Context("cuda:0", cfg)
+        o = Oracle(np.float32, Config(compact_box=bool(compact_box), cb_beta=0.8))
+        for case in range(12):
+            n = int(rng.choice([1, 2, 63, 64, 65, 257, 1000, 4097, 30000]))
+            W = int(rng.integers(1, 960))
+            H = int(rng.integers(1, 640))
+            ls = (float(rng.uniform(-4.0, -1.5)), float(rng.uniform(0.2, 1.0)))
+            sc = scenes.tiny_scene(1000 + 31 * case + compact_box, n, W, H, sh_degree=0, log_scale=ls,
+                                   spread=float(rng.uniform(0.5, 1.6)))
+            cam = sc.cameras[0]
+            g = B.Gaussians.from_scene(sc, c.device)
+            fcam = B.make_camera(cam)
+            proj = c.fs_preprocess(g, fcam)
+            bins = c.fs_bin_sort(proj, fcam)
+            p_o = o.preprocess(sc, cam)
+            b_o = o.bin_sort(p_o, cam)
+            tag = (compact_box, case, n, W, H)
+            assert bins.num_pairs == b_o.num_pairs, tag
+            assert np.array_equal(bins.copy_keys().cpu().numpy().view(np.uint64), b_o.keys_sorted), tag
+            assert np.array_equal(bins.copy_gauss().cpu().numpy().view(np.uint32), b_o.gauss_sorted), tag
+            assert np.array_equal(bins.copy_ranges().cpu().numpy().view(np.uint32), b_o.tile_ranges), tag
+            T = ((W + 15) // 16) * ((H + 15) // 16)
+            assert np.array_equal(np.sort(bins.copy_order().cpu().numpy()), np.arange(T)), tag
+        c.close()
