@@ -434,7 +434,9 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
 #pragma unroll
     for (int k = 0; k < K; k++) wk[k] = 0.f;
     for (int h = 0; h < 64 / HALF; h++) {
-        load_half(h);
+        // (culled Gaussians come in runs -- whole clusters outside the frustum -- so a half often needs no
+        // coefficients at all: its gradients are zeros whatever the buffer holds)
+        if (__ballot(vis0 && (lane / HALF) == h) != 0) load_half(h);
         if ((lane / HALF) == h && in_range) {
             float Y[K], gcol[3] = {0.f, 0.f, 0.f};
 #pragma unroll
@@ -459,9 +461,8 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     }
     Splat s;
     s.visible = false;
-    if (in_range) {
+    if (vis0) {   // (tiles_touched = 0: culled in the forward pass, or a Compact Box none of whose tiles meets the ellipse)
         project(means, scales, quats, opac[i], i, cam, cfg, s);
-        s.visible = s.visible && touched[i] > 0;   // Compact Box: a box none of whose tiles meets the ellipse
     }
     if (in_range && !s.visible) {
         for (int k = 0; k < 3; k++) { d_means[3 * i + k] = 0.f; d_scales[3 * i + k] = 0.f; }
