@@ -469,3 +469,78 @@ def activate_bwd(raw_scales, raw_quats, raw_opac, d_scales, d_quats, d_opac):
     nrm = np.sqrt((raw_quats * raw_quats).sum(1, keepdims=True))
     d_raw_q = (d_quats - q * (q * d_quats).sum(1, keepdims=True)) / nrm
     return d_scales * s, d_raw_q, d_opac * o * (1.0 - o)
+
+
+def activate_inv(scales, opacities, lo=1e-4, hi=1.0 - 1e-4):
+    """Used -> stored parameters (the inverse of `activate` for the scale and the opacity): raw scale = ln s,
+    raw opacity = ln(o' / (1 - o')) with o' = the opacity limited to [lo, hi] (a stored opacity of exactly 0 or 1
+    has no finite logit).  In the arrays' type."""
+    o = np.minimum(np.maximum(opacities, opacities.dtype.type(lo)), opacities.dtype.type(hi))
+    return np.log(scales), np.log(o / (1 - o))
+
+
+def _quat_rotation(q):
+    """R(q) of unit quaternions q = (w, x, y, z), [m, 3, 3]: the R_i of Sec. 3 Eq. (2)."""
+    w, x, y, z = (q[:, k] for k in range(4))
+    R = np.empty((q.shape[0], 3, 3), q.dtype)
+    R[:, 0, 0] = 1 - 2 * (y * y + z * z); R[:, 0, 1] = 2 * (x * y - w * z); R[:, 0, 2] = 2 * (x * z + w * y)
+    R[:, 1, 0] = 2 * (x * y + w * z); R[:, 1, 1] = 1 - 2 * (x * x + z * z); R[:, 1, 2] = 2 * (y * z - w * x)
+    R[:, 2, 0] = 2 * (x * z - w * y); R[:, 2, 1] = 2 * (y * z + w * x); R[:, 2, 2] = 1 - 2 * (x * x + y * y)
+    return R
+
+
+def split_children(means, scales, quats, parents, normals, phi=1.6):
+    """Splitting (supplement, "Implementation Details": the paper keeps vanilla 3DGS's densification and
+    selects the Gaussians to split with the absolute gradient).  Every selected parent p is replaced by two
+    children: child c is placed at a sample of the parent's own density,
+        mu_c = mu_p + R(q_p) (s_p * xi_c),    xi_c ~ N(0, I_3) supplied by the caller (normals[r, c, :]),
+    with scales s_p / phi (phi = 1.6 = 0.8 x the number of children in vanilla 3DGS) and the parent's rotation,
+    opacity and colour.  means [n,3], scales [n,3] (activated), quats [n,4] (unit), parents [m] indices,
+    normals [m,2,3].  Returns (child_means [2m,3], child_scales [2m,3]); child c of the r-th parent is row
+    c*m + r.  The copies of the other attributes and the removal of the parents are row gathers."""
+    p = np.asarray(parents, dtype=np.int64)
+    dt = means.dtype
+    xi = np.asarray(normals, dt)
+    R = _quat_rotation(np.asarray(quats, dt)[p])
+    s = np.asarray(scales, dt)[p]
+    mu = np.asarray(means, dt)[p]
+    out_m, out_s = [], []
+    for c in range(2):
+        local = s * xi[:, c, :]
+        off = np.stack([(R[:, r, 0] * local[:, 0] + R[:, r, 1] * local[:, 1]) + R[:, r, 2] * local[:, 2] for r in range(3)], 1)
+        out_m.append(mu + off)
+        out_s.append(s / dt.type(phi))
+    return np.concatenate(out_m), np.concatenate(out_s)
+
+
+def sample_by_score(candidates, scores, exponentials, k=None):
+    """"Sampling half of the candidate Gaussians according to their pruning scores" (supplement,
+    "Implementation Details": pruning before iteration 15 000).  Read as weighted sampling without
+    replacement: of the m candidates, k = floor(m / 2) are drawn one after the other, each time with
+    probability proportional to the score s_p among those still left.  That process is realised with one
+    independent Exp(1) variate e_i per Gaussian, supplied by the caller: the k candidates with the smallest
+    arrival times e_i / s_p_i are the sample (an exponential clock of rate s_p_i per candidate; the order of
+    the first arrivals is exactly successive sampling proportional to the rates).  A candidate with a score
+    <= 0 never arrives (time +inf) and is only taken when nothing else is left; equal times go to the lower
+    index.  The division is made in the type of `scores`.  Returns the uint8 mask of the sample."""
+    c = np.asarray(candidates) != 0
+    w = np.asarray(scores)
+    e = np.asarray(exponentials, w.dtype)
+    idx = np.nonzero(c)[0]
+    m = idx.size
+    if k is None:
+        k = m // 2
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.where(w[idx] > 0, e[idx] / w[idx], np.inf).astype(w.dtype)
+    order = np.lexsort((idx, t))          # by time, ties by index
+    out = np.zeros(c.shape[0], np.uint8)
+    out[idx[order[:k]]] = 1
+    return out
+
+
+def combine_masks(clone, split, prune):
+    """What the three decisions do to the array of Gaussians when they are applied together: a pruned
+    Gaussian is neither cloned nor split; a split parent is replaced by its children (removed); everything
+    else stays.  Returns (keep, clone_eff, split_eff) as uint8."""
+    c, s, p = (np.asarray(a) != 0 for a in (clone, split, prune))
+    return (~p & ~s).astype(np.uint8), (c & ~p).astype(np.uint8), (s & ~p).astype(np.uint8)

@@ -76,3 +76,146 @@ def test_selection_rules_truth_table():
     assert split.tolist() == [0, 0, 0, 1, 0, 0, 0, 0]
     assert prune.tolist() == [0, 0, 0, 0, 0, 1, 1, 0]
     assert not (clone & split).any()
+
+
+def test_densify_accumulate_hand_worked_table():
+    """Three Gaussians, two views, worked by hand.  Gaussian 0: gradient (3, 4) then (6, 8): norms 5 and 10;
+    its absolute gradient (5, 12) then (8, 15): norms 13 and 17.  Gaussian 1 is invisible in the first view
+    (its entries there must be ignored and the view not counted) and has (0, -2) / (1.5, 2) in the second.
+    Gaussian 2 is never visible."""
+    g = np.zeros(3); a = np.zeros(3); d = np.zeros(3, np.int64)
+    dm1 = np.array([[3.0, 4.0], [100.0, 100.0], [7.0, 7.0]])
+    da1 = np.array([[5.0, 12.0], [100.0, 100.0], [7.0, 7.0]])
+    oracle.densify_accumulate(dm1, da1, np.array([4, 0, 0]), g, a, d)
+    assert g.tolist() == [5.0, 0.0, 0.0] and a.tolist() == [13.0, 0.0, 0.0] and d.tolist() == [1, 0, 0]
+    dm2 = np.array([[-6.0, 8.0], [0.0, -2.0], [9.0, 9.0]])
+    da2 = np.array([[8.0, 15.0], [1.5, 2.0], [9.0, 9.0]])
+    oracle.densify_accumulate(dm2, da2, np.array([1, 2, 0]), g, a, d)
+    assert g.tolist() == [15.0, 2.0, 0.0] and a.tolist() == [30.0, 2.5, 0.0] and d.tolist() == [2, 1, 0]
+    # without the absolute gradient only the plain sums move
+    g2 = np.zeros(3); d2 = np.zeros(3, np.int64)
+    oracle.densify_accumulate(dm1, None, np.array([4, 0, 0]), g2, None, d2)
+    assert g2.tolist() == [5.0, 0.0, 0.0] and d2.tolist() == [1, 0, 0]
+
+
+def test_densify_accumulate_is_additive_over_views_and_abs_dominates():
+    """Sums over views in any order agree (to rounding), and with per-view |abs| >= |plain| component-wise the
+    accumulated absolute statistic is never below the plain one."""
+    rng = np.random.default_rng(5)
+    n, V = 200, 6
+    dm = rng.normal(size=(V, n, 2))
+    da = np.abs(dm) + rng.uniform(0, 1, size=(V, n, 2))
+    tt = rng.integers(0, 3, size=(V, n))
+    def run(order):
+        g = np.zeros(n); a = np.zeros(n); d = np.zeros(n, np.int64)
+        for v in order:
+            oracle.densify_accumulate(dm[v], da[v], tt[v], g, a, d)
+        return g, a, d
+    g0, a0, d0 = run(range(V))
+    g1, a1, d1 = run(reversed(range(V)))
+    assert np.allclose(g0, g1, rtol=1e-13) and np.allclose(a0, a1, rtol=1e-13) and np.array_equal(d0, d1)
+    assert np.array_equal(d0, (tt > 0).sum(0))
+    want = (np.sqrt((dm ** 2).sum(2)) * (tt > 0)).sum(0)
+    assert np.allclose(g0, want, rtol=1e-13)
+    assert (a0 >= g0 - 1e-12).all() and (a0 > g0).any()
+
+
+def test_combine_masks_truth_table():
+    clone = np.array([0, 1, 0, 0, 1, 1, 0, 1], np.uint8)
+    split = np.array([0, 0, 1, 0, 1, 0, 1, 1], np.uint8)
+    prune = np.array([0, 0, 0, 1, 0, 1, 1, 1], np.uint8)
+    keep, c, s = oracle.combine_masks(clone, split, prune)
+    assert keep.tolist() == [1, 1, 0, 0, 0, 0, 0, 0]      # stays iff neither pruned nor replaced by children
+    assert c.tolist() == [0, 1, 0, 0, 1, 0, 0, 0]         # a pruned Gaussian is not cloned
+    assert s.tolist() == [0, 0, 1, 0, 1, 0, 0, 0]         # ... nor split
+
+
+def test_activate_inv_inverts_activate():
+    rng = np.random.default_rng(9)
+    raw_s = rng.normal(-4, 1, size=(50, 3)); raw_o = rng.normal(0, 2, size=50)
+    raw_q = rng.normal(size=(50, 4))
+    s, q, o = oracle.activate(raw_s, raw_q, raw_o)
+    rs, ro = oracle.activate_inv(s, o)
+    assert np.allclose(rs, raw_s, atol=1e-12) and np.allclose(ro, raw_o, atol=1e-9)
+    # the limits: an opacity of exactly 0 or 1 maps to the logit of the limit, ln(lo / (1 - lo))
+    _, r = oracle.activate_inv(np.ones((2, 3)), np.array([0.0, 1.0]), lo=1e-3, hi=1 - 1e-3)
+    assert r == pytest.approx([np.log(1e-3 / (1 - 1e-3)), np.log((1 - 1e-3) / 1e-3)], rel=1e-9)
+
+
+def test_split_children_exact_small_cases():
+    """Axis-aligned parent: a child moves by s * xi along each axis.  A quarter turn about z carries the local
+    x axis to world +y (the rotation sense of Eq. (2)'s R).  Scales are divided by phi; rows are ordered
+    child-major."""
+    means = np.array([[1.0, 2.0, 3.0], [0.0, 0.0, 0.0], [5.0, 5.0, 5.0]])
+    scales = np.array([[0.5, 0.25, 2.0], [1.0, 2.0, 3.0], [9.0, 9.0, 9.0]])
+    h = np.sqrt(0.5)
+    quats = np.array([[1.0, 0, 0, 0], [h, 0, 0, h], [1.0, 0, 0, 0]])
+    normals = np.array([[[1.0, -2.0, 0.5], [0.0, 0.0, -1.0]],
+                        [[1.0, 0.0, 0.0], [0.0, 1.0, 2.0]]])
+    cm, cs = oracle.split_children(means, scales, quats, [0, 1], normals, phi=1.6)
+    assert cm.shape == (4, 3) and cs.shape == (4, 3)
+    assert cm[0] == pytest.approx([1.5, 1.5, 4.0])          # parent 0, child 0
+    assert cm[2] == pytest.approx([1.0, 2.0, 1.0])          # parent 0, child 1
+    assert cm[1] == pytest.approx([0.0, 1.0, 0.0], abs=1e-12)   # parent 1, child 0: local x -> world y
+    assert cm[3] == pytest.approx([-2.0, 0.0, 6.0], abs=1e-12)  # local y (2 * 1) -> world -x, local z stays
+    assert cs[0] == pytest.approx([0.5 / 1.6, 0.25 / 1.6, 2.0 / 1.6]) and cs[3] == pytest.approx([1 / 1.6, 2 / 1.6, 3 / 1.6])
+
+
+def test_split_children_are_samples_of_the_parent_density():
+    """Moments: over many normal draws the children of one parent have mean mu and covariance
+    Sigma_3D = R S S^T R^T (Eq. (2)); their own covariance is Sigma_3D / phi^2."""
+    rng = np.random.default_rng(3)
+    q = rng.normal(size=4); q /= np.linalg.norm(q)
+    s = np.array([0.3, 1.1, 0.05]); mu = np.array([2.0, -1.0, 7.0])
+    m = 200000
+    means = np.repeat(mu[None], m, 0); scales = np.repeat(s[None], m, 0); quats = np.repeat(q[None], m, 0)
+    cm, cs = oracle.split_children(means, scales, quats, np.arange(m), rng.normal(size=(m, 2, 3)), phi=1.6)
+    w, x, y, z = q
+    R = np.array([[1 - 2 * (y * y + z * z), 2 * (x * y - w * z), 2 * (x * z + w * y)],
+                  [2 * (x * y + w * z), 1 - 2 * (x * x + z * z), 2 * (y * z - w * x)],
+                  [2 * (x * z - w * y), 2 * (y * z + w * x), 1 - 2 * (x * x + y * y)]])
+    assert np.allclose(R @ R.T, np.eye(3), atol=1e-12) and np.linalg.det(R) == pytest.approx(1.0)
+    Sigma = R @ np.diag(s * s) @ R.T
+    assert np.allclose(cm.mean(0), mu, atol=4 * np.sqrt(np.diag(Sigma).max() / (2 * m)) + 1e-9)
+    cov = np.cov((cm - mu).T)
+    assert np.allclose(cov, Sigma, atol=0.01 * np.abs(Sigma).max())
+    child_S = R @ np.diag((cs[0] ** 2)) @ R.T
+    assert np.allclose(child_S, Sigma / 1.6 ** 2, rtol=1e-12)
+    # the two children of a parent use independent draws
+    d0, d1 = cm[:m] - mu, cm[m:] - mu
+    assert abs(np.mean(d0[:, 1] * d1[:, 1])) < 0.01 * Sigma[1, 1]
+
+
+def test_sample_by_score_exact_cases():
+    cand = np.array([1, 0, 1, 1, 1, 1], np.uint8)           # five candidates -> two are drawn
+    score = np.array([0.5, 9.0, 1.0, 0.25, 0.0, 2.0])
+    e = np.array([1.0, 0.001, 1.0, 0.05, 0.0001, 8.0])       # times: 2, -, 1, 0.2, inf, 4
+    out = oracle.sample_by_score(cand, score, e)
+    assert out.tolist() == [0, 0, 1, 1, 0, 0]
+    # equal times go to the lower index; a zero score is taken last, and only if it must be
+    out = oracle.sample_by_score(np.ones(4, np.uint8), np.array([1.0, 1.0, 0.0, 1.0]), np.array([2.0, 2.0, 0.0, 2.0]), k=2)
+    assert out.tolist() == [1, 1, 0, 0]
+    out = oracle.sample_by_score(np.ones(4, np.uint8), np.array([1.0, 1.0, 0.0, 1.0]), np.array([2.0, 2.0, 0.0, 2.0]), k=4)
+    assert out.tolist() == [1, 1, 1, 1]
+    assert oracle.sample_by_score(np.zeros(3, np.uint8), np.ones(3), np.ones(3)).sum() == 0
+    assert oracle.sample_by_score(np.array([0, 1, 0], np.uint8), np.ones(3), np.ones(3)).sum() == 0   # floor(1/2)
+
+
+def test_sample_by_score_matches_successive_sampling_probabilities():
+    """Inclusion probabilities of "draw k one after the other, each proportional to the score among the rest",
+    enumerated exactly for four candidates and k = 2, against the frequencies over many exponential draws."""
+    from itertools import permutations
+    w = np.array([1.0, 2.0, 3.0, 4.0])
+    incl = np.zeros(4)
+    for a, b in permutations(range(4), 2):
+        p = w[a] / w.sum() * w[b] / (w.sum() - w[a])
+        incl[a] += p; incl[b] += p
+    assert incl.sum() == pytest.approx(2.0)
+    rng = np.random.default_rng(17)
+    N = 60000
+    hits = np.zeros(4)
+    cand = np.ones(4, np.uint8)
+    for e in rng.exponential(size=(N, 4)):
+        hits += oracle.sample_by_score(cand, w, e)
+    assert np.allclose(hits / N, incl, atol=4 * 0.5 / np.sqrt(N))
+    assert hits[3] > hits[2] > hits[1] > hits[0]            # a higher pruning score is drawn more often
