@@ -22,9 +22,13 @@
  *   fs_adam_step / fs_grad_accumulate / fs_adam_interval / fs_activate / fs_activate_bwd
  *                        fused Adam update with the 32/64 schedule, parameter activations
  *                                                                               (Sec. 5.1, supplement)
- *   fs_densify_accumulate / fs_select / fs_compact / fs_gather_rows
+ *   fs_densify_accumulate / fs_select / fs_combine_masks / fs_compact / fs_gather_rows
  *                        gradient statistics, clone / split / prune masks, index lists and row copies
  *                                                                               (Sec. 4.2, 4.3, supplement)
+ *   fs_split_children / fs_sample_by_score / fs_counts_add / fs_activate_inv
+ *                        the children of split Gaussians, the early-phase sampling of half the pruning
+ *                        candidates by score, per-view count sums, stored parameters from used ones
+ *                                                                               (supplement, "Implementation Details")
  *
  * General rules
  *   - Every pointer inside the structs below is a DEVICE pointer (HIP, the ctx's device) owned
@@ -54,7 +58,7 @@ typedef enum {
     FS_EINVAL = -1,    /* null pointer, bad shape / degree / size                     */
     FS_ENOMEM = -2,    /* growing the ctx's scratch memory failed                      */
     FS_EHIP = -3,      /* a HIP runtime call failed (message has the HIP error name)  */
-    FS_ECAPACITY = -4  /* pair count does not fit the 32-bit index space              */
+    FS_ECAPACITY = -4  /* a count (Gaussians, pairs, candidate tiles) reaches 2^31      */
 } fs_status;
 
 enum { FS_SCORE_WEIGHT = 0, FS_SCORE_ALPHA = 1 };
@@ -115,7 +119,8 @@ typedef struct {
 } fs_projected;
 
 /* Output of fs_bin_sort.  Arrays are ctx-owned and stay valid until the next fs_bin_sort or
- * fs_destroy on the same ctx. */
+ * fs_destroy on the same ctx: no other call writes to them.  A later call that is handed the fs_bins
+ * of an earlier fs_bin_sort (or of another ctx) returns FS_EINVAL (see `generation`). */
 typedef struct {
     int64_t num_pairs;            /* P, host-visible on return                                        */
     const uint64_t *keys_sorted;  /* [P] tile_id << 32 | bits(depth), ascending; ties by Gaussian index */
@@ -135,6 +140,7 @@ typedef struct {
     const void *splats;           /* [n] 64-byte records (opaque): fs_bin_sort's copy of mean2d, conic_opacity, rgb,
                                      rect and record_offsets of every visible Gaussian, one cache line per gather.
                                      The render, backward and score calls read the splats from here.             */
+    uint64_t generation;          /* which fs_bin_sort of the ctx filled this struct (set by the library; 0 = none)   */
 } fs_bins;
 
 /* Output of fs_render_bwd, caller-owned, OVERWRITTEN (not accumulated). dconic and drgb may be
@@ -171,12 +177,17 @@ const char *fs_last_error(const fs_ctx *ctx);
  * radius ceil(3 sqrt(lambda_max)), tile rectangle, SH colour.  Errors: FS_EINVAL, FS_EHIP. */
 int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_projected *out);
 
-/* Steps a2-a5: exclusive scan of tiles_touched, one 64-bit key per (Gaussian, tile) pair, the keys in
- * ascending order (ties by Gaussian index) and per-tile ranges.  The order is that of a stable sort of
- * index-ordered keys; it is computed per tile (count, place, sort each tile's segment in LDS) or by a global
- * LSD radix sort (cfg.sort_mode; the result is identical).  n = number of Gaussians in `proj`.  Also packs the
- * projected splats into bins->splats; later calls that take `bins` must be given the same `proj`.
- * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (P >= 2^32). */
+/* Steps a2-a5: one 64-bit key tile_id << 32 | bits(depth) per (Gaussian, tile) pair, the keys in ascending order
+ * (ties by Gaussian index: the order a stable sort of index-ordered keys gives) and the per-tile ranges.
+ * Default path (FS_SORT_AUTO, while no tile's list exceeds 8192 entries and the image has at most 15360
+ * tiles): the pairs are counted per tile, the ranges follow from an exclusive scan over the TILES, every pair is
+ * placed into its tile's segment and each segment is sorted in LDS; no prefix sum over the Gaussians is made and
+ * bins->pair_offsets is NULL.  Otherwise (FS_SORT_RADIX, or as the fall-back): exclusive scan of tiles_touched
+ * (bins->pair_offsets), keys emitted in index order, a global stable LSD radix sort, ranges from the sorted keys.
+ * Both give bit-identical keys, order and ranges.  n = number of Gaussians in `proj`.  Also packs the projected
+ * splats into bins->splats and gives every pair the place of its backward record (bins->record_offsets); later
+ * calls that take `bins` must be given the same `proj`.  Reads 32 bytes back (synchronises the stream).
+ * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (n, P or the candidate tile count >= 2^31). */
 int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int64_t n, fs_bins *out);
 
 /* Step a6 (Eqs. (4),(5)): image [3,H,W] planar, final_T [H,W] (transmittance left at each pixel),
@@ -216,9 +227,11 @@ int fs_l1_grad(fs_ctx *ctx, const float *image, const float *target, int32_t hei
 
 /* Steps a8+a9: back-to-front gradient of the compositing, reduced per Gaussian, then chained
  * through the projection to the scene parameters.  final_T / n_contrib are fs_render_fwd's; bins
- * must be the result of the last fs_bin_sort on this ctx for the same proj (its pair_offsets are
- * used to give every Gaussian-tile pair its own slot of partial sums, so no atomics are needed
- * and the result is reproducible run to run).  Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP. */
+ * must be the result of the latest fs_bin_sort on this ctx for the same proj: every (Gaussian, tile) pair
+ * owns one record of partial sums in ctx scratch, at bins->record_offsets[i] + the tile's place in the
+ * Gaussian's rectangle, which the tile's workgroup stores once; the projection's backward kernel then adds up
+ * each Gaussian's contiguous records.  No global atomics.  Errors: FS_EINVAL (also: stale bins), FS_ENOMEM,
+ * FS_EHIP. */
 int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, const fs_projected *proj,
                   const fs_bins *bins, const float *final_T, const uint32_t *n_contrib,
                   const float *dL_dimage, fs_grads *out);
@@ -299,13 +312,47 @@ int fs_select(fs_ctx *ctx, int64_t n, const float *grad_accum, const float *abs_
               const fs_select_params *params, uint8_t *clone, uint8_t *split, uint8_t *prune);
 
 /* Stream compaction: indices[0..count) = ascending positions i with mask[i] != 0.  indices needs room for n
- * entries.  *count_host (host pointer) is set on return; the call synchronises the stream for that. */
+ * entries.  *count_host (host pointer) is set on return; the call synchronises the stream for that.  Uses
+ * scratch of its own: it may be called between fs_bin_sort and the calls that consume its fs_bins. */
 int fs_compact(fs_ctx *ctx, const uint8_t *mask, int64_t n, uint32_t *indices, int64_t *count_host);
 
 /* dst[r, 0..row_floats) = src[indices[r], 0..row_floats) for r < count: the copy that clone / prune-keep /
  * split-parent selection apply to each per-Gaussian array.  src and dst must not overlap. */
 int fs_gather_rows(fs_ctx *ctx, const float *src, int64_t row_floats, const uint32_t *indices, int64_t count,
                    float *dst);
+
+/* The three decisions applied together ([n] uint8 each): keep = not pruned and not split (a split parent is
+ * replaced by its children), clone_eff = clone and not pruned, split_eff = split and not pruned. */
+int fs_combine_masks(fs_ctx *ctx, int64_t n, const uint8_t *clone, const uint8_t *split, const uint8_t *prune,
+                     uint8_t *keep, uint8_t *clone_eff, uint8_t *split_eff);
+
+/* total[i] += view[i] (int32, n entries): the sum over the K views of the per-view counts that
+ * fs_prune_score_accumulate also needs one view at a time. */
+int fs_counts_add(fs_ctx *ctx, int32_t *total, const int32_t *view, int64_t n);
+
+/* Splitting (supplement, "Implementation Details": densification as in vanilla 3DGS, selected by the absolute
+ * gradient).  Each of the m parents p = parents[r] gets two children: child c sits at
+ *   mu_p + R(q_p) (s_p * xi[r,c,:])       xi: the CALLER's standard normal draws, normals [m,2,3],
+ * a sample of the parent's own density N(mu_p, Sigma_3D), and has scales s_p / phi (phi = 1.6 in vanilla 3DGS:
+ * 0.8 x the number of children).  means [n,3], scales [n,3] (activated), quats [n,4] (unit, 16-byte aligned).
+ * child_means, child_scales: [2m,3], row c*m + r.  Rotation, opacity and colour of a child are its parent's
+ * (fs_gather_rows with `parents`); removing the parents is a compaction (fs_combine_masks' keep).
+ * Errors: FS_EINVAL, FS_ECAPACITY (m >= 2^30), FS_EHIP. */
+int fs_split_children(fs_ctx *ctx, const float *means, const float *scales, const float *quats,
+                      const uint32_t *parents, int64_t m, const float *normals, float phi, float *child_means,
+                      float *child_scales);
+
+/* "Sampling half of the candidate Gaussians according to their pruning scores" (supplement, "Implementation
+ * Details": pruning before iteration 15 000), read as weighted sampling without replacement: of the m Gaussians
+ * with candidates[i] != 0, floor(m / 2) are drawn one after the other, each time with probability proportional
+ * to scores[i] (the pruning score s_p) among those left.  The random stream is the CALLER's: exponentials [n]
+ * holds one Exp(1) variate per Gaussian; the sample is the floor(m / 2) candidates with the smallest
+ * exponentials[i] / scores[i] (fp32 division; +inf for a score <= 0; equal values go to the lower index), which
+ * is that process exactly.  sample [n] uint8 is overwritten with the 0/1 mask of the drawn candidates;
+ * *sampled_host (host pointer, may be NULL) receives their number.  Reads 8 bytes back (synchronises the stream).
+ * Errors: FS_EINVAL, FS_ENOMEM, FS_ECAPACITY, FS_EHIP. */
+int fs_sample_by_score(fs_ctx *ctx, const uint8_t *candidates, const float *scores, const float *exponentials,
+                       int64_t n, uint8_t *sample, int64_t *sampled_host);
 
 /* ---- optimiser (Sec. 5.1: all methods train with Adam; supplement "Implementation Details": the update
  * schedule of the accelerated baseline) ---------------------------------------------------------------- */
@@ -337,6 +384,12 @@ int fs_activate_bwd(fs_ctx *ctx, int64_t n, const float *raw_scales, const float
                     const float *raw_opacities, const float *d_scales, const float *d_quats, const float *d_opacities,
                     float *d_raw_scales, float *d_raw_quats, float *d_raw_opacities);
 
+/* Used -> stored parameters, the inverse of fs_activate for scale and opacity: raw_scale = ln(scale),
+ * raw_opacity = ln(o / (1 - o)) with o = the opacity limited to [lo, hi], 0 < lo <= hi < 1 (an opacity of exactly
+ * 0 or 1 has no finite stored value).  A unit quaternion is its own stored value. */
+int fs_activate_inv(fs_ctx *ctx, int64_t n, const float *scales, const float *opacities, float lo, float hi,
+                    float *raw_scales, float *raw_opacities);
+
 /* ---- measurement helpers (no part of the method) ------------------------------------------
  * Per-kernel timing with HIP events recorded on the ctx stream around the launches of the
  * selected kernel groups.  fs_profile_enable(mask) clears the accumulated times and selects the
@@ -347,7 +400,7 @@ enum {
     FS_K_PREPROCESS = 0, /* k_preprocess                                  */
     FS_K_SCAN,           /* the three kernels of the tiles_touched scan   */
     FS_K_EMIT,           /* k_emit_pairs, or the per-tile counting kernels */
-    FS_K_RADIX_SORT,     /* the ordering: radix passes, or placement + per-tile sort */
+    FS_K_ORDER,          /* the ordering: placement + per-tile LDS sort, or the radix passes */
     FS_K_RANGES,         /* k_tile_ranges + k_tile_order (radix mode only) */
     FS_K_RENDER_FWD,     /* k_render_fwd                                  */
     FS_K_L1,             /* k_l1_grad (+ final reduction)                 */

@@ -13,7 +13,8 @@ from dataclasses import dataclass
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# FASTGS_HIP_LIB names another build of the same library (e.g. an experimental variant)
+# FASTGS_HIP_LIB names another build of the same library (e.g. an experimental variant); load_library says so on
+# stderr when it is used, so that no run takes a substituted library unnoticed
 LIB_PATH = os.environ.get("FASTGS_HIP_LIB") or os.path.join(_PKG, "libfastgs_hip.so")
 
 FS_OK = 0
@@ -27,9 +28,10 @@ EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_
            "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
+           "fs_combine_masks", "fs_counts_add", "fs_split_children", "fs_sample_by_score", "fs_activate_inv",
            "fs_adam_step", "fs_grad_accumulate", "fs_adam_interval", "fs_activate", "fs_activate_bwd",
            "fs_profile_enable", "fs_profile_read", "fs_measure_peaks")
-KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
+KERNEL_GROUPS = ("preprocess", "scan", "emit_pairs", "order_pairs", "tile_ranges", "render_fwd", "l1_grad", "photo_loss",
                  "render_bwd", "preprocess_bwd", "error_mask", "score")
 
 
@@ -62,7 +64,7 @@ class fs_bins(ctypes.Structure):
                 ("tile_ranges", ctypes.c_void_p), ("pair_offsets", ctypes.c_void_p),
                 ("num_records", ctypes.c_int64), ("record_offsets", ctypes.c_void_p),
                 ("record_counts", ctypes.c_void_p),
-                ("tile_order", ctypes.c_void_p), ("splats", ctypes.c_void_p)]
+                ("tile_order", ctypes.c_void_p), ("splats", ctypes.c_void_p), ("generation", ctypes.c_uint64)]
 
 
 class fs_select_params(ctypes.Structure):
@@ -88,6 +90,9 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_04283_amd.build` "
                            "(there is no CPU fallback)")
+    if os.environ.get("FASTGS_HIP_LIB"):
+        import sys
+        print(f"paper_2511_04283_amd: loading the library named by FASTGS_HIP_LIB: {LIB_PATH}", file=sys.stderr, flush=True)
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     P = ctypes.POINTER
@@ -121,6 +126,11 @@ def load_library() -> ctypes.CDLL:
     lib.fs_adam_interval.argtypes = [i32]
     lib.fs_activate.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp]
     lib.fs_activate_bwd.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.fs_combine_masks.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.fs_counts_add.argtypes = [vp, vp, vp, i64]
+    lib.fs_split_children.argtypes = [vp, vp, vp, vp, vp, i64, vp, f32, vp, vp]
+    lib.fs_sample_by_score.argtypes = [vp, vp, vp, vp, i64, vp, P(i64)]
+    lib.fs_activate_inv.argtypes = [vp, i64, vp, vp, f32, f32, vp, vp]
     lib.fs_measure_peaks.argtypes = [vp, i64, P(ctypes.c_double), P(ctypes.c_double)]
     lib.fs_profile_enable.argtypes = [vp, ctypes.c_uint32]
     lib.fs_profile_read.argtypes = [vp, i32, P(ctypes.c_char_p), P(ctypes.c_double), P(i64)]
@@ -486,6 +496,53 @@ class Context:
                                        _ptr(scales), _ptr(opacities), _ptr(s_p), ctypes.byref(params), _ptr(m[0]),
                                        _ptr(m[1]), _ptr(m[2])), "fs_select")
         return tuple(m)
+
+    def fs_combine_masks(self, clone, split, prune):
+        """(keep, clone_eff, split_eff) uint8 [n]."""
+        n = int(clone.shape[0])
+        for t, nm in ((clone, "clone"), (split, "split"), (prune, "prune")):
+            _chk(t, torch.uint8, (n,), nm)
+        out = [torch.empty(n, dtype=torch.uint8, device=self.device) for _ in range(3)]
+        self._check(self.lib.fs_combine_masks(self.handle, n, _ptr(clone), _ptr(split), _ptr(prune), _ptr(out[0]),
+                                              _ptr(out[1]), _ptr(out[2])), "fs_combine_masks")
+        return tuple(out)
+
+    def fs_counts_add(self, total, view):
+        n = int(total.shape[0])
+        _chk(total, torch.int32, (n,), "total"); _chk(view, torch.int32, (n,), "view")
+        self._check(self.lib.fs_counts_add(self.handle, _ptr(total), _ptr(view), n), "fs_counts_add")
+        return total
+
+    def fs_split_children(self, means, scales, quats, parents, normals, phi=1.6):
+        """(child_means [2m,3], child_scales [2m,3]); normals [m,2,3] are the caller's N(0,1) draws."""
+        n, m = int(means.shape[0]), int(parents.shape[0])
+        _chk(means, torch.float32, (n, 3), "means"); _chk(scales, torch.float32, (n, 3), "scales")
+        _chk(quats, torch.float32, (n, 4), "quats"); _chk(parents, torch.int32, (m,), "parents")
+        _chk(normals, torch.float32, (m, 2, 3), "normals")
+        cm = torch.empty((2 * m, 3), dtype=torch.float32, device=self.device)
+        cs = torch.empty((2 * m, 3), dtype=torch.float32, device=self.device)
+        self._check(self.lib.fs_split_children(self.handle, _ptr(means), _ptr(scales), _ptr(quats), _ptr(parents), m,
+                                               _ptr(normals), float(phi), _ptr(cm), _ptr(cs)), "fs_split_children")
+        return cm, cs
+
+    def fs_sample_by_score(self, candidates, scores, exponentials):
+        """uint8 [n] mask of floor(m / 2) of the m candidates; exponentials [n] are the caller's Exp(1) draws."""
+        n = int(candidates.shape[0])
+        _chk(candidates, torch.uint8, (n,), "candidates"); _chk(scores, torch.float32, (n,), "scores")
+        _chk(exponentials, torch.float32, (n,), "exponentials")
+        out = torch.empty(n, dtype=torch.uint8, device=self.device)
+        cnt = ctypes.c_int64(0)
+        self._check(self.lib.fs_sample_by_score(self.handle, _ptr(candidates), _ptr(scores), _ptr(exponentials), n,
+                                                _ptr(out), ctypes.byref(cnt)), "fs_sample_by_score")
+        return out, int(cnt.value)
+
+    def fs_activate_inv(self, scales, opacities, lo=1e-4, hi=1.0 - 1e-4):
+        n = int(opacities.shape[0])
+        _chk(scales, torch.float32, (n, 3), "scales"); _chk(opacities, torch.float32, (n,), "opacities")
+        rs, ro = torch.empty_like(scales), torch.empty_like(opacities)
+        self._check(self.lib.fs_activate_inv(self.handle, n, _ptr(scales), _ptr(opacities), float(lo), float(hi), _ptr(rs),
+                                             _ptr(ro)), "fs_activate_inv")
+        return rs, ro
 
     def fs_compact(self, mask):
         """Returns the int32 tensor of selected positions (ascending)."""

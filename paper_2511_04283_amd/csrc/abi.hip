@@ -37,6 +37,12 @@ struct fs_ctx {
     ScratchBuf err_map;       // float  [H*W]
     ScratchBuf ssim_maps;     // float  [3, 3*H*W] derivative maps of the SSIM term
     ScratchBuf partial;       // double reduction partials
+    ScratchBuf compact_pos;   // uint32 [n] fs_compact / fs_sample_by_score: positions of the selected elements
+    ScratchBuf compact_scan;  // ... and the block sums of their scan
+    ScratchBuf sel_keys[2];   // uint64 [m] fs_sample_by_score: arrival-time keys, ping-pong for the radix sort
+    ScratchBuf sel_vals[2];   // uint32 [m] candidate indices, ping-pong
+    ScratchBuf sel_hist;      // uint32 radix histograms of that sort
+    uint64_t generation = 0;  // bumped by every fs_bin_sort; fs_bins of an earlier one are refused
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
@@ -105,7 +111,7 @@ int ensure(fs_ctx* ctx, ScratchBuf& b, size_t bytes, const char* what)
         if (rc_ != FS_OK) return rc_; \
     } while (0)
 
-const char* const kGroupNames[FS_K_COUNT] = {"preprocess", "scan", "emit_pairs", "radix_sort", "tile_ranges",
+const char* const kGroupNames[FS_K_COUNT] = {"preprocess", "scan", "emit_pairs", "order_pairs", "tile_ranges",
                                              "render_fwd", "l1_grad", "photo_loss", "render_bwd", "preprocess_bwd",
                                              "error_mask", "score"};
 
@@ -181,6 +187,9 @@ bool proj_ok(const fs_projected* p)
     return p && p->mean2d && p->depth && p->conic_opacity && p->rgb && p->rect && p->tiles_touched && p->clamped;
 }
 
+// bins of an earlier fs_bin_sort (or of another ctx) point at memory that has been reused since
+bool bins_stale(const fs_ctx* ctx, const fs_bins* bins) { return bins->generation != ctx->generation || ctx->generation == 0; }
+
 // the record in ctx->pair_bits now describes the forward pass over these bins
 void note_bits(fs_ctx* ctx, const fs_bins* bins, int tiles)
 {
@@ -247,7 +256,9 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
                          &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
-                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial, &ctx->pair_bits};
+                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial, &ctx->pair_bits,
+                         &ctx->compact_pos, &ctx->compact_scan, &ctx->sel_keys[0], &ctx->sel_keys[1], &ctx->sel_vals[0],
+                         &ctx->sel_vals[1], &ctx->sel_hist};
     for (ScratchBuf* b : all)
         if (b->ptr) (void)hipFree(b->ptr);
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
@@ -284,6 +295,8 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     if (n > 0 && !proj_ok(proj)) return fail(ctx, FS_EINVAL, "fs_bin_sort: null array");
     if (n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: n does not fit 31 bits");
     ctx->bits_pairs = -1;
+    ctx->generation++;      // whatever earlier fs_bins of this ctx point at is overwritten from here on
+    out->generation = 0;    // (a call that fails leaves bins that every later call refuses)
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     hipStream_t st = ctx->stream;
     const int tiles = cd.tiles_x * cd.tiles_y;
@@ -368,7 +381,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     if (lds_sort) {
         // second half: placement into the tiles' segments (keys[1] serves as the bucket array) and the
         // per-tile LDS sort; ranges are already in place
-        ProfScope prof(ctx, FS_K_RADIX_SORT);
+        ProfScope prof(ctx, FS_K_ORDER);
         fs_projected none = {};
         FS_HIP(launch_tile_scatter_sort(st, n, proj ? *proj : none, cf,
                                         cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr)
@@ -396,7 +409,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
                            "k_emit_pairs");
             }
             // a4: 32 depth bits + the tile bits are live
-            ProfScope prof(ctx, FS_K_RADIX_SORT);
+            ProfScope prof(ctx, FS_K_ORDER);
             FS_HIP(launch_radix_sort(st, (int64_t)P, 32 + tile_bits(tiles), keys, vals, static_cast<uint32_t*>(ctx->hist.ptr),
                                      ctx->scan_tmp.ptr, ctx->total_dev, &res),
                    "radix sort");
@@ -415,6 +428,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     out->record_counts = cb ? static_cast<const uint32_t*>(ctx->rec_counts.ptr) : nullptr;
     out->splats = ctx->splats.ptr;
     out->tile_order = static_cast<const uint32_t*>(ctx->ranges.ptr) + 2 * (size_t)tiles;
+    out->generation = ctx->generation;
     return FS_OK;
 }
 
@@ -427,6 +441,7 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
         return fail(ctx, FS_EINVAL, "fs_render_fwd: bad arguments");
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd: null array");
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_render_fwd: bins do not come from this context's latest fs_bin_sort");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ctx->bits_pairs = -1;   // (what an earlier forward pass recorded for the count pass does not describe this one)
     const bool bits = ctx->record_bits && bins->num_pairs > 0;
@@ -449,6 +464,7 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
         return fail(ctx, FS_EINVAL, "fs_render_fwd_loss: bad arguments");
     if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats))
         return fail(ctx, FS_EINVAL, "fs_render_fwd_loss: null array");
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_render_fwd_loss: bins do not come from this context's latest fs_bin_sort");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     const int tiles = cd.tiles_x * cd.tiles_y;
     const int64_t pixels = (int64_t)cd.width * cd.height;
@@ -544,10 +560,9 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     hipStream_t st = ctx->stream;
     if (bins->num_pairs > 0 && (!bins->record_offsets || !bins->splats || bins->num_records < bins->num_pairs))
         return fail(ctx, FS_EINVAL, "fs_render_bwd: bins without record_offsets / splats");
-    // (with the Compact Box fs_bin_sort has already sized this buffer and zeroed the records of the
-    // candidate tiles that are no pairs; growing it here would lose them, and never happens)
-    if (bins->record_counts && (size_t)bins->num_records * PAIR_REC * sizeof(float) > ctx->pair_grad.cap)
-        return fail(ctx, FS_EINVAL, "fs_render_bwd: bins do not come from this context's last fs_bin_sort");
+    // (the records, their places and -- with the Compact Box -- the zeroed records of the candidate tiles that are
+    // no pairs all live in this ctx and belong to its latest fs_bin_sort)
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_render_bwd: bins do not come from this context's latest fs_bin_sort");
     FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_records ? bins->num_records : 1) * PAIR_REC * sizeof(float),
                   "pair gradients"));
     float* pair_grad = static_cast<float*>(ctx->pair_grad.ptr);
@@ -601,6 +616,7 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (bins->num_pairs == 0) return FS_OK;
     if (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats || !counts)
         return fail(ctx, FS_EINVAL, "fs_score_accumulate: null array");
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_score_accumulate: bins do not come from this context's latest fs_bin_sort");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ProfScope prof(ctx, FS_K_SCORE);
     if (ctx->bits_pairs == bins->num_pairs && ctx->bits_order == bins->gauss_sorted &&
@@ -691,9 +707,10 @@ int fs_compact(fs_ctx* ctx, const uint8_t* mask, int64_t n, uint32_t* indices, i
     *count_host = 0;
     if (n == 0) return FS_OK;
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
-    FS_TRY(ensure(ctx, ctx->rec_counts, (size_t)n * sizeof(uint32_t), "compaction positions"));
-    FS_TRY(ensure(ctx, ctx->scan_tmp, scan_tmp_bytes(n), "scan"));
-    FS_HIP(launch_compact(ctx->stream, n, mask, static_cast<uint32_t*>(ctx->rec_counts.ptr), ctx->scan_tmp.ptr,
+    // (scratch of its own: what fs_bin_sort left for the backward pass must survive a compaction in between)
+    FS_TRY(ensure(ctx, ctx->compact_pos, (size_t)n * sizeof(uint32_t), "compaction positions"));
+    FS_TRY(ensure(ctx, ctx->compact_scan, scan_tmp_bytes(n), "scan"));
+    FS_HIP(launch_compact(ctx->stream, n, mask, static_cast<uint32_t*>(ctx->compact_pos.ptr), ctx->compact_scan.ptr,
                           ctx->total_dev, indices),
            "compaction");
     FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, ctx->stream),
@@ -768,6 +785,94 @@ int fs_activate_bwd(fs_ctx* ctx, int64_t n, const float* raw_scales, const float
     FS_HIP(launch_activate_bwd(ctx->stream, n, raw_scales, raw_quats, raw_opacities, d_scales, d_quats, d_opacities,
                                d_raw_scales, d_raw_quats, d_raw_opacities),
            "k_activate_bwd");
+    return FS_OK;
+}
+
+int fs_combine_masks(fs_ctx* ctx, int64_t n, const uint8_t* clone, const uint8_t* split, const uint8_t* prune,
+                     uint8_t* keep, uint8_t* clone_eff, uint8_t* split_eff)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!clone || !split || !prune || !keep || !clone_eff || !split_eff)))
+        return fail(ctx, FS_EINVAL, "fs_combine_masks: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_combine_masks(ctx->stream, n, clone, split, prune, keep, clone_eff, split_eff), "k_combine_masks");
+    return FS_OK;
+}
+
+int fs_counts_add(fs_ctx* ctx, int32_t* total, const int32_t* view, int64_t n)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!total || !view))) return fail(ctx, FS_EINVAL, "fs_counts_add: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_counts_add(ctx->stream, n, total, view), "k_counts_add");
+    return FS_OK;
+}
+
+int fs_split_children(fs_ctx* ctx, const float* means, const float* scales, const float* quats, const uint32_t* parents,
+                      int64_t m, const float* normals, float phi, float* child_means, float* child_scales)
+{
+    if (!ctx) return FS_EINVAL;
+    if (m < 0 || !(phi > 0.f) || (m > 0 && (!means || !scales || !quats || !parents || !normals || !child_means || !child_scales)))
+        return fail(ctx, FS_EINVAL, "fs_split_children: bad arguments");
+    if (m >= (int64_t)1 << 30) return fail(ctx, FS_ECAPACITY, "fs_split_children: m does not fit 30 bits");
+    if (m > 0 && !aligned16(quats)) return fail(ctx, FS_EINVAL, "fs_split_children: quats must be 16-byte aligned");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_split_children(ctx->stream, m, means, scales, quats, parents, normals, phi, child_means, child_scales),
+           "k_split_children");
+    return FS_OK;
+}
+
+int fs_sample_by_score(fs_ctx* ctx, const uint8_t* candidates, const float* scores, const float* exponentials, int64_t n,
+                       uint8_t* sample, int64_t* sampled_host)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || (n > 0 && (!candidates || !scores || !exponentials || !sample)))
+        return fail(ctx, FS_EINVAL, "fs_sample_by_score: bad arguments");
+    if (n >= (int64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_sample_by_score: n does not fit 31 bits");
+    if (sampled_host) *sampled_host = 0;
+    if (n == 0) return FS_OK;
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    hipStream_t st = ctx->stream;
+    // the candidates' indices, and their number m (one read-back: the sample size floor(m / 2) sizes what follows)
+    FS_TRY(ensure(ctx, ctx->compact_pos, (size_t)n * sizeof(uint32_t), "compaction positions"));
+    FS_TRY(ensure(ctx, ctx->compact_scan, scan_tmp_bytes(n), "scan"));
+    for (int k = 0; k < 2; k++) {
+        FS_TRY(ensure(ctx, ctx->sel_keys[k], (size_t)n * sizeof(uint64_t), "sampling keys"));
+        FS_TRY(ensure(ctx, ctx->sel_vals[k], (size_t)n * sizeof(uint32_t), "sampling indices"));
+    }
+    uint64_t* keys[2] = {static_cast<uint64_t*>(ctx->sel_keys[0].ptr), static_cast<uint64_t*>(ctx->sel_keys[1].ptr)};
+    uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->sel_vals[0].ptr), static_cast<uint32_t*>(ctx->sel_vals[1].ptr)};
+    FS_HIP(launch_compact(st, n, candidates, static_cast<uint32_t*>(ctx->compact_pos.ptr), ctx->compact_scan.ptr,
+                          ctx->total_dev, vals[1]),
+           "compaction");
+    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, st), "hipMemcpyAsync");
+    FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
+    const int64_t m = (int64_t)ctx->total_host[0];
+    const int64_t k = m / 2;
+    int res = 0;
+    if (k > 0) {
+        // arrival times e / score as sort keys (ties by index), a stable radix sort on all 64 bits, the first k
+        const int64_t nb = radix_num_blocks(m);
+        FS_TRY(ensure(ctx, ctx->sel_hist, (size_t)nb * RADIX_DIGITS * sizeof(uint32_t), "histograms"));
+        FS_TRY(ensure(ctx, ctx->compact_scan, scan_tmp_bytes(RADIX_DIGITS * nb), "scan"));
+        FS_HIP(launch_sample_keys(st, m, vals[1], scores, exponentials, keys[0], vals[0]), "k_sample_keys");
+        FS_HIP(launch_radix_sort(st, m, 64, keys, vals, static_cast<uint32_t*>(ctx->sel_hist.ptr), ctx->compact_scan.ptr,
+                                 ctx->total_dev, &res),
+               "radix sort");
+    }
+    FS_HIP(launch_mark_indices(st, n, k, vals[res], sample), "k_mark_indices");
+    if (sampled_host) *sampled_host = k;
+    return FS_OK;
+}
+
+int fs_activate_inv(fs_ctx* ctx, int64_t n, const float* scales, const float* opacities, float lo, float hi,
+                    float* raw_scales, float* raw_opacities)
+{
+    if (!ctx) return FS_EINVAL;
+    if (n < 0 || !(lo > 0.f) || !(hi < 1.f) || !(lo <= hi) || (n > 0 && (!scales || !opacities || !raw_scales || !raw_opacities)))
+        return fail(ctx, FS_EINVAL, "fs_activate_inv: bad arguments");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_activate_inv(ctx->stream, n, scales, opacities, lo, hi, raw_scales, raw_opacities), "k_activate_inv");
     return FS_OK;
 }
 

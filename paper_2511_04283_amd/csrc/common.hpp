@@ -263,6 +263,19 @@ hipError_t launch_compact(hipStream_t st, int64_t n, const uint8_t* mask, uint32
 hipError_t launch_gather_rows(hipStream_t st, const float* src, int row_floats, const uint32_t* indices,
                               int64_t count, float* dst);
 
+hipError_t launch_combine_masks(hipStream_t st, int64_t n, const uint8_t* clone, const uint8_t* split,
+                                const uint8_t* prune, uint8_t* keep, uint8_t* clone_eff, uint8_t* split_eff);
+hipError_t launch_counts_add(hipStream_t st, int64_t n, int32_t* total, const int32_t* view);
+// children of m split parents: rows c*m + r of child_means / child_scales [2m,3]; normals [m,2,3]
+hipError_t launch_split_children(hipStream_t st, int64_t m, const float* means, const float* scales, const float* quats,
+                                 const uint32_t* parents, const float* normals, float phi, float* child_means,
+                                 float* child_scales);
+// keys[j] = bits(exponentials[i] / scores[i]) << 32 | i, vals[j] = i for the m listed candidates i = cand_idx[j]
+hipError_t launch_sample_keys(hipStream_t st, int64_t m, const uint32_t* cand_idx, const float* scores,
+                              const float* exponentials, uint64_t* keys, uint32_t* vals);
+// mask[0..n) = 0, then mask[idx[j]] = 1 for j < k
+hipError_t launch_mark_indices(hipStream_t st, int64_t n, int64_t k, const uint32_t* idx, uint8_t* mask);
+
 // optimiser and activations (optimizer.hip)
 hipError_t launch_adam(hipStream_t st, float* p, float* g, float* m, float* v, int64_t count, float lr, float beta1,
                        float beta2, float eps, int step, float grad_scale, bool zero_grad);
@@ -272,6 +285,8 @@ hipError_t launch_activate(hipStream_t st, int64_t n, const float* raw_s, const 
 hipError_t launch_activate_bwd(hipStream_t st, int64_t n, const float* raw_s, const float* raw_q, const float* raw_o,
                                const float* d_s, const float* d_q, const float* d_o, float* d_raw_s, float* d_raw_q,
                                float* d_raw_o);
+hipError_t launch_activate_inv(hipStream_t st, int64_t n, const float* s, const float* o, float lo, float hi,
+                               float* raw_s, float* raw_o);
 
 // reference measurements: streaming copy of `bytes` (multiple of 16), and 8 fma chains x iters per lane on
 // blocks x 256 lanes (out: blocks * 256 floats)

@@ -109,6 +109,20 @@ __global__ __launch_bounds__(256) void k_activate_bwd(int64_t n, const float* __
     d_raw_o[i] = d_o[i] * sg * (1.0f - sg);
 }
 
+// the inverse of k_activate for scale and opacity: raw scale = ln s, raw opacity = ln(o' / (1 - o')) with the
+// opacity limited to [lo, hi]
+__global__ __launch_bounds__(256) void k_activate_inv(int64_t n, const float* __restrict__ s,
+                                                      const float* __restrict__ o, float lo, float hi,
+                                                      float* __restrict__ raw_s, float* __restrict__ raw_o)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+#pragma unroll
+    for (int k = 0; k < 3; k++) raw_s[3 * i + k] = logf(s[3 * i + k]);
+    const float v = fminf(fmaxf(o[i], lo), hi);
+    raw_o[i] = logf(v / (1.0f - v));
+}
+
 // ---- reference measurements ------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_copy(const float4* __restrict__ src, float4* __restrict__ dst, int64_t nvec)
 {
@@ -174,6 +188,14 @@ hipError_t launch_activate_bwd(hipStream_t st, int64_t n, const float* raw_s, co
     hipLaunchKernelGGL(k_activate_bwd, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, raw_s,
                        reinterpret_cast<const float4*>(raw_q), raw_o, d_s, reinterpret_cast<const float4*>(d_q), d_o,
                        d_raw_s, reinterpret_cast<float4*>(d_raw_q), d_raw_o);
+    return hipGetLastError();
+}
+
+hipError_t launch_activate_inv(hipStream_t st, int64_t n, const float* s, const float* o, float lo, float hi,
+                               float* raw_s, float* raw_o)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_activate_inv, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, s, o, lo, hi, raw_s, raw_o);
     return hipGetLastError();
 }
 

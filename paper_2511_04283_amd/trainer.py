@@ -1,11 +1,10 @@
 """A FastGS training loop driven entirely through the C-ABI calls (Sec. 4 of the paper): training
 iterations with the photometric loss and Adam, the multi-view score pass (VCD's s_d, VCP's s_p), and
-densification by cloning plus pruning.  Orchestration only: every arithmetic step runs in the HIP
-kernels; PyTorch supplies device memory (allocation, concatenation of the per-Gaussian arrays).
-
-Not covered (the paper leaves the random streams undefined): sampling the children of a split and the
-"half of the candidates" sampling of early pruning.  Gaussians selected for splitting are reported, not
-changed.
+densification by cloning and splitting plus pruning (before iteration 15 000: of half the candidates,
+sampled by pruning score).  Orchestration only: every arithmetic step runs in the HIP kernels; PyTorch
+supplies device memory (allocation, zero filling, concatenation of the per-Gaussian arrays) and the two
+random streams the method draws from (standard normals for the split children, Exp(1) variates for the
+sampling), which are handed to the library as inputs.
 """
 from __future__ import annotations
 
@@ -32,6 +31,9 @@ class TrainConfig:
     size_limit: float = 0.05              # clone below, split above this largest scale
     mask_rule: int = B.FS_MASK_MEAN_STD
     mask_k: float = 1.0
+    split_phi: float = 1.6                # children's scales = parent's / phi (vanilla 3DGS: 0.8 x 2 children)
+    early_until: int = 15000              # before this iteration only a sampled half of the prune candidates goes
+    seed: int = 0                         # of the generator behind the normals and the exponentials
 
 
 class Trainer:
@@ -39,9 +41,10 @@ class Trainer:
         self.ctx, self.cfg, self.sh_degree = ctx, cfg or TrainConfig(), int(sh_degree)
         ctx.fs_set_score_record(False)   # training iterations are not followed by a count pass; score_views turns it on
         f = lambda t: t.detach().to(ctx.device, torch.float32).contiguous().clone()
-        op = f(opacities).clamp(1e-4, 1 - 1e-4)
-        self.p = dict(means=f(means), sh=f(sh), raw_scales=torch.log(f(scales)), raw_quats=f(quats),
-                      raw_opacities=torch.log(op / (1 - op)))
+        raw_s, raw_o = ctx.fs_activate_inv(f(scales), f(opacities), 1e-4, 1 - 1e-4)
+        self.p = dict(means=f(means), sh=f(sh), raw_scales=raw_s, raw_quats=f(quats), raw_opacities=raw_o)
+        self.rng = torch.Generator(device=ctx.device)
+        self.rng.manual_seed(self.cfg.seed)
         self._reset_state()
         self.iteration = 0
 
@@ -121,36 +124,50 @@ class Trainer:
             ctx.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, view)
             out3, _ = ctx.fs_photo_loss(image, target, c.lam, want_grad=False)
             ctx.fs_prune_score_accumulate(view, out3[2:3], acc)
-            counts += view   # (memory plumbing: a plain integer add of two device arrays)
+            ctx.fs_counts_add(counts, view)
         ctx.fs_set_score_record(False)
         return counts, ctx.fs_prune_score_normalize(acc)
 
-    # -- densify by cloning, prune; Adam state of the survivors is kept, clones start at zero ------
-    def densify_and_prune(self, cams, targets, prune: bool = True) -> dict:
+    # -- densify (clone, split) and prune; Adam state of the survivors is kept, new Gaussians start at zero ------
+    def densify_and_prune(self, cams, targets, prune: bool = True, early: bool | None = None) -> dict:
+        """One densification step.  Rows afterwards: the kept Gaussians (neither pruned nor split), the clones, the
+        first children of the split parents, their second children.  `early` (default: iteration < early_until):
+        only half of the prune candidates, sampled by their pruning score, are removed."""
         ctx, c = self.ctx, self.cfg
+        dev = ctx.device
         counts, s_p = self.score_views(cams, targets)
         g = self.gaussians()
         prm = B.fs_select_params(tau_grad=c.tau_grad, tau_abs=c.tau_abs, tau_d=c.tau_d, size_limit=c.size_limit,
                                  min_opacity=c.min_opacity, tau_p=c.tau_p, K=len(cams))
         clone, split, prune_mask = ctx.fs_select(self.grad_accum, self.abs_accum, self.denom, counts, g.scales, g.opacities,
                                                  s_p, prm)
+        n_before = self.n
         if not prune:
             prune_mask = torch.zeros_like(prune_mask)
-        keep = ctx.fs_compact((1 - prune_mask).contiguous())
-        # a Gaussian that is pruned is not cloned
-        clone_idx = ctx.fs_compact((clone * (1 - prune_mask)).contiguous())
-        n_before = self.n
+        elif early if early is not None else self.iteration < c.early_until:
+            expo = torch.empty(n_before, dtype=torch.float32, device=dev).exponential_(1.0, generator=self.rng)
+            prune_mask, _ = ctx.fs_sample_by_score(prune_mask, s_p, expo)
+        keep_m, clone_m, split_m = ctx.fs_combine_masks(clone, split, prune_mask)
+        keep, clone_idx, split_idx = ctx.fs_compact(keep_m), ctx.fs_compact(clone_m), ctx.fs_compact(split_m)
+        m = int(split_idx.shape[0])
+        normals = torch.randn((m, 2, 3), dtype=torch.float32, device=dev, generator=self.rng)
+        child_means, child_scales = ctx.fs_split_children(self.p["means"], g.scales, g.quats, split_idx, normals, c.split_phi)
+        child_opac = ctx.fs_gather_rows(g.opacities, split_idx)
+        child_raw_scales, _ = ctx.fs_activate_inv(child_scales, torch.cat([child_opac, child_opac]), 1e-4, 1 - 1e-4)
+        children = dict(means=child_means, raw_scales=child_raw_scales)
+        n_new = int(clone_idx.shape[0]) + 2 * m
         for d in (self.p, self.m, self.v, self.acc):
             for k in GROUPS:
                 kept = ctx.fs_gather_rows(d[k], keep)
                 if d is self.p:
-                    new = ctx.fs_gather_rows(d[k], clone_idx)
+                    par = ctx.fs_gather_rows(d[k], split_idx)       # children inherit what the split does not change
+                    new = [ctx.fs_gather_rows(d[k], clone_idx), children.get(k, torch.cat([par, par]))]
                 else:
-                    new = torch.zeros((clone_idx.shape[0],) + tuple(d[k].shape[1:]), device=ctx.device)
-                d[k] = torch.cat([kept, new]).contiguous()
-        n, dev = self.n, ctx.device
+                    new = [torch.zeros((n_new,) + tuple(d[k].shape[1:]), device=dev)]
+                d[k] = torch.cat([kept] + new).contiguous()
+        n = self.n
         self.grad_accum = torch.zeros(n, device=dev)
         self.abs_accum = torch.zeros(n, device=dev)
         self.denom = torch.zeros(n, dtype=torch.int32, device=dev)
-        return dict(before=n_before, kept=int(keep.shape[0]), cloned=int(clone_idx.shape[0]),
-                    split_candidates=int(split.sum().item()), after=n)
+        return dict(before=n_before, kept=int(keep.shape[0]), cloned=int(clone_idx.shape[0]), split=m,
+                    pruned=int(n_before - keep.shape[0] - m), after=n)

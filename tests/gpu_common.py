@@ -53,6 +53,13 @@ def gpu_pipeline(ctx, sc, cam, target=None, dL=None, mask_rule=0, mask_k=1.0, wa
     return out
 
 
+def assert_image_close(got, ref, rtol=1e-4):
+    """The image bar: |got - ref| <= 1e-4 * |ref| per value, with |ref| floored at 1e-2 (colours are O(1); the floor
+    keeps near-black pixels from demanding more than fp32 can give)."""
+    err = np.abs(np.asarray(got, np.float64) - np.asarray(ref, np.float64))
+    assert (err <= rtol * np.maximum(np.abs(ref), 1e-2)).all(), float(err.max())
+
+
 def assert_grads_close(got: dict, ref: dict, rtol=1e-3, floor=2e-3):
     """|got - ref| <= rtol*|ref| + min(floor, floor*max|ref|) per gradient tensor (the benchmark's
     1e-3 relative / 2e-3 absolute-floor bar, never looser than its literal statement)."""

@@ -30,7 +30,7 @@ def test_default_config_and_struct_layouts_match_header():
     assert abs(c.alpha_min - 1 / 255) < 1e-9 and abs(c.alpha_max - 0.99) < 1e-7 and abs(c.T_min - 1e-4) < 1e-10
     assert ctypes.sizeof(B.fs_config) == 56 and ctypes.sizeof(B.fs_camera) == 72
     assert ctypes.sizeof(B.fs_gaussians) == 56 and ctypes.sizeof(B.fs_projected) == 56
-    assert ctypes.sizeof(B.fs_bins) == 80 and ctypes.sizeof(B.fs_grads) == 72 and ctypes.sizeof(B.fs_select_params) == 28
+    assert ctypes.sizeof(B.fs_bins) == 88 and ctypes.sizeof(B.fs_grads) == 72 and ctypes.sizeof(B.fs_select_params) == 28
 
 
 def test_null_context_is_rejected_without_touching_a_gpu():

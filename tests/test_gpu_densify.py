@@ -102,3 +102,107 @@ def test_statistics_masks_compaction_and_gather(ctx):
     assert ctx.fs_compact(torch.zeros(777, dtype=torch.uint8, device=dev)).numel() == 0
     assert np.array_equal(ctx.fs_compact(torch.ones(777, dtype=torch.uint8, device=dev)).cpu().numpy(), np.arange(777))
     assert ctx.fs_compact(torch.ones(1, dtype=torch.uint8, device=dev)).cpu().numpy().tolist() == [0]
+
+
+def test_combine_masks_counts_add_and_inverse_activations(ctx):
+    import torch
+    dev = ctx.device
+    rng = np.random.default_rng(21)
+    n = 40_001
+    cl, sp, pr = (rng.integers(0, 2, n).astype(np.uint8) for _ in range(3))
+    got = ctx.fs_combine_masks(*(torch.from_numpy(a).to(dev) for a in (cl, sp, pr)))
+    for a, b in zip(got, oracle.combine_masks(cl, sp, pr)):
+        assert np.array_equal(a.cpu().numpy(), b)
+    tot = rng.integers(0, 1000, n).astype(np.int32); view = rng.integers(0, 1000, n).astype(np.int32)
+    t = torch.from_numpy(tot.copy()).to(dev)
+    ctx.fs_counts_add(t, torch.from_numpy(view).to(dev))
+    assert np.array_equal(t.cpu().numpy(), tot + view)
+    s = np.exp(rng.normal(-4, 1.5, (n, 3))).astype(np.float32)
+    o = rng.uniform(0, 1, n).astype(np.float32)
+    o[:5] = [0.0, 1.0, 1e-4, 0.5, 1 - 1e-4]
+    rs, ro = ctx.fs_activate_inv(torch.from_numpy(s).to(dev), torch.from_numpy(o).to(dev), 1e-4, 1 - 1e-4)
+    ws, wo = oracle.activate_inv(s.astype(np.float64), o.astype(np.float64), 1e-4, 1 - 1e-4)
+    # fp32 logarithm of an fp32 ratio: a few ulp of the result, plus the ratio's rounding where o is near 1
+    assert np.allclose(rs.cpu().numpy(), ws, rtol=2e-6, atol=2e-6)
+    assert np.allclose(ro.cpu().numpy(), wo, rtol=2e-5, atol=2e-5)
+    # and it inverts fs_activate
+    s2, _, o2 = ctx.fs_activate(rs, torch.ones((n, 4), device=dev), ro)
+    assert np.allclose(s2.cpu().numpy(), s, rtol=2e-6)
+    assert np.allclose(o2.cpu().numpy(), np.clip(o, 1e-4, 1 - 1e-4), rtol=2e-5, atol=1e-7)
+
+
+def test_split_children_against_the_oracle(ctx):
+    import torch
+    dev = ctx.device
+    rng = np.random.default_rng(33)
+    n, m = 20_000, 7_003
+    means = rng.normal(0, 5, (n, 3)).astype(np.float32)
+    scales = np.exp(rng.normal(-3, 1, (n, 3))).astype(np.float32)
+    q = rng.normal(size=(n, 4)); q /= np.linalg.norm(q, axis=1, keepdims=True)
+    q = q.astype(np.float32)
+    parents = np.sort(rng.choice(n, m, replace=False)).astype(np.int32)
+    normals = rng.normal(size=(m, 2, 3)).astype(np.float32)
+    cm, cs = ctx.fs_split_children(*(torch.from_numpy(a).to(dev) for a in (means, scales, q, parents, normals)), 1.6)
+    wm, ws = oracle.split_children(means, scales, q, parents, normals, 1.6)       # fp32, same operation order
+    assert np.array_equal(cs.cpu().numpy(), ws)                                    # one correctly rounded division
+    assert np.allclose(cm.cpu().numpy(), wm, rtol=1e-6, atol=1e-6)
+    wm64, _ = oracle.split_children(means.astype(np.float64), scales.astype(np.float64), q.astype(np.float64), parents,
+                                    normals.astype(np.float64), 1.6)
+    assert np.allclose(cm.cpu().numpy(), wm64, rtol=1e-5, atol=1e-5)
+    # no parents: nothing to do
+    e = ctx.fs_split_children(torch.from_numpy(means).to(dev), torch.from_numpy(scales).to(dev), torch.from_numpy(q).to(dev),
+                              torch.empty(0, dtype=torch.int32, device=dev), torch.empty((0, 2, 3), device=dev))
+    assert e[0].shape == (0, 3) and e[1].shape == (0, 3)
+
+
+@pytest.mark.parametrize("n,frac", [(100_003, 0.3), (5_000, 1.0), (7, 0.5), (1, 1.0), (3000, 0.0)])
+def test_sample_by_score_is_the_oracles_sample(ctx, n, frac):
+    """Bit-exact: the arrival times are one correctly rounded fp32 division on both sides and the order is unique."""
+    import torch
+    dev = ctx.device
+    rng = np.random.default_rng(n)
+    cand = (rng.uniform(size=n) < frac).astype(np.uint8)
+    score = rng.uniform(0, 1, n).astype(np.float32)
+    score[rng.uniform(size=n) < 0.1] = 0.0               # candidates that only low opacity nominated
+    expo = rng.exponential(size=n).astype(np.float32)
+    if n > 100:                                          # planted ties: equal times go to the lower index
+        score[10:40] = np.float32(0.5); expo[10:40] = np.float32(0.25); cand[10:40] = 1
+    got, k = ctx.fs_sample_by_score(torch.from_numpy(cand).to(dev), torch.from_numpy(score).to(dev),
+                                    torch.from_numpy(expo).to(dev))
+    want = oracle.sample_by_score(cand, score, expo)
+    assert k == int(cand.sum()) // 2 == int(want.sum())
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+def test_compaction_between_bin_sort_and_backward_keeps_the_bins():
+    """fs_compact has scratch of its own: with the Compact Box (whose record counts live in the ctx) a compaction
+    between fs_bin_sort and fs_render_bwd changes no gradient; bins of an earlier fs_bin_sort are refused."""
+    import torch
+    from paper_2511_04283_amd import binding as B
+    cfg = B.default_config()
+    cfg.compact_box = 1
+    c = B.Context("cuda:0", cfg)
+    sc = scenes.tiny_scene(77, 6000, 160, 96, sh_degree=1, log_scale=(-2.6, 0.7), spread=1.3)
+    cam = sc.cameras[0]
+    fcam = B.make_camera(cam)
+    g = B.Gaussians.from_scene(sc, c.device)
+    tgt = torch.rand(3, cam.height, cam.width, device=c.device)
+    proj = c.fs_preprocess(g, fcam)
+    bins = c.fs_bin_sort(proj, fcam)
+    image, fT, nc = c.fs_render_fwd(proj, bins, fcam)
+    dL = c.fs_l1_grad(image, tgt)
+    ref = {k: v.cpu().numpy().astype(np.float64) for k, v in c.fs_render_bwd(g, fcam, proj, bins, fT, nc, dL).items()}
+    idx = c.fs_compact((torch.rand(3 * sc.n, device=c.device) < 0.5).to(torch.uint8))   # larger than n: forces growth
+    assert idx.numel() > 0
+    again = c.fs_render_bwd(g, fcam, proj, bins, fT, nc, dL)
+    # (two runs of the backward pass agree to rounding, not bit for bit: partial sums meet in LDS in arrival order)
+    assert np.abs(ref["means"]).max() > 0
+    assert_grads_close({k: v.cpu().numpy() for k, v in again.items()}, ref, rtol=2e-4, floor=1e-4)
+    old = bins
+    bins2 = c.fs_bin_sort(proj, fcam)
+    with pytest.raises(RuntimeError, match="latest fs_bin_sort"):
+        c.fs_render_bwd(g, fcam, proj, old, fT, nc, dL)
+    with pytest.raises(RuntimeError, match="latest fs_bin_sort"):
+        c.fs_render_fwd(proj, old, fcam)
+    c.fs_render_fwd(proj, bins2, fcam)
+    c.close()

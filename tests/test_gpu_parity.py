@@ -6,7 +6,7 @@ import pytest
 
 from oracle import Config, Oracle
 from paper_2511_04283_amd import scenes
-from gpu_common import assert_grads_close, gpu_pipeline
+from gpu_common import assert_grads_close, assert_image_close, gpu_pipeline
 
 pytestmark = pytest.mark.gpu
 
@@ -51,8 +51,7 @@ def check_all(g, r, sc, image_rtol=1e-4):
     # a6
     assert np.array_equal(g["n_contrib"], r["n_contrib"])
     assert np.abs(g["final_T"] - r["final_T"]).max() <= 1e-6
-    err = np.abs(g["image"] - r["image"])
-    assert (err <= image_rtol * np.maximum(np.abs(r["image"]), 1e-2)).all(), float(err.max())
+    assert_image_close(g["image"], r["image"], image_rtol)
     if "loss" in r and "loss" in g:
         assert g["loss"] == pytest.approx(r["loss"], rel=1e-6)
         assert np.array_equal(g["dL"], r["dL"])
@@ -225,7 +224,7 @@ def test_pair_order_is_the_same_whichever_way_it_is_computed(orc32, n, W, H, mod
     if n <= 40000:
         img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
         assert np.array_equal(g["n_contrib"], nc)
-        assert np.abs(g["image"] - img).max() <= 1e-4
+        assert_image_close(g["image"], img)
     c.close()
 
 
@@ -244,7 +243,7 @@ def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
     assert np.array_equal(g["tile_ranges"], b_o.tile_ranges)
     img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
     assert np.array_equal(g["n_contrib"], nc)
-    assert np.abs(g["image"] - img).max() <= 1e-4
+    assert_image_close(g["image"], img)
 
 
 @pytest.mark.parametrize("mode", [0, 1])
@@ -311,7 +310,7 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
         if n <= 9000:
             img, fT, nc = o.render_fwd_mt(p_o, b_o, cam, threads=8)
             assert np.array_equal(g["n_contrib"], nc), (seed, n)
-            assert np.abs(g["image"] - img).max() <= 1e-4
+            assert_image_close(g["image"], img)
     assert seen_long
     c.close()
 

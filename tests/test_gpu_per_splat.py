@@ -87,10 +87,10 @@ def test_per_splat_against_per_pixel_config2_cut():
     check_all(gb, r, sc)
 
 
-def test_per_splat_against_per_pixel_config3_full():
+def test_per_splat_config3_full_against_the_oracle_and_the_per_pixel_kernel():
     """Benchmark size (500k Gaussians, 1600x1064, 1.36 M pairs), the launch configuration bench.py times: every
-    gradient of the per-splat mapping against the per-pixel kernel's (which the full-size tests hold against the
-    oracle), to a fifth of the gradient tolerance."""
+    gradient of the per-splat mapping against the oracle at the gradient tolerance, and against the per-pixel
+    kernel's to a fifth of it."""
     from paper_2511_04283_amd import binding as B
     sc = scenes.make_scene(3)
     cam = sc.cameras[0]
@@ -103,6 +103,14 @@ def test_per_splat_against_per_pixel_config3_full():
     b.close()
     assert np.abs(ga["grads"]["means"]).max() > 0
     assert_grads_close(gb["grads"], {k: v.astype(np.float64) for k, v in ga["grads"].items()}, rtol=2e-4, floor=4e-4)
+    o = Oracle(np.float32)
+    proj = o.preprocess(sc, cam)
+    bins = o.bin_sort(proj, cam)
+    img, fT, nc = o.render_fwd_mt(proj, bins, cam, threads=14)
+    _, dL = o.l1(img, tgt)
+    ref = o.backward_mt(sc, cam, proj, bins, dL, threads=14)
+    assert np.array_equal(gb["n_contrib"], nc)
+    assert_grads_close(gb["grads"], ref)
 
 
 def test_unknown_backward_mode_is_rejected():
