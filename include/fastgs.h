@@ -253,6 +253,18 @@ int fs_set_backward_mode(fs_ctx *ctx, int32_t mode);
 int fs_error_mask(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
                   int32_t rule, float k, uint8_t *mask, float *threshold_out);
 
+/* fs_error_mask for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, outputs and arithmetic, but the error map and the
+ * reduction partials live in a static device array of the library (about 16.8 MB on every GPU a context has
+ * been created on, held until the process ends) instead of growable ctx scratch.  The call allocates and frees
+ * nothing.  Images of more than FS_NOALLOC_MAX_PIXELS pixels are refused with FS_ECAPACITY (and a message);
+ * FS_EINVAL as for fs_error_mask.  All contexts on one GPU share the array: calls that may overlap on one GPU
+ * (different streams) race and must be ordered by the caller; consecutive calls on one stream are safe, and no
+ * call depends on what an earlier one left in the array. */
+#define FS_NOALLOC_MAX_PIXELS (4 * 1024 * 1024)
+int fs_error_mask_noalloc(fs_ctx *ctx, const float *image, const float *target, int32_t height, int32_t width,
+                          int32_t rule, float k, uint8_t *mask, float *threshold_out);
+
 /* Step a11: for one view, counts[i] += number of pixels p with mask[p] = 1 at which Gaussian i
  * is blended by the forward pass (and, in FS_SCORE_WEIGHT mode, with alpha_i T_i > alpha_min).
  * counts [n] int32 is ACCUMULATED: zero it before the first view; s_d = counts / K.

@@ -25,7 +25,7 @@ FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_score_accumulate",
+           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_error_mask_noalloc", "fs_score_accumulate",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_combine_masks", "fs_counts_add", "fs_split_children", "fs_sample_by_score", "fs_activate_inv",
@@ -113,6 +113,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_set_backward_mode.argtypes = [vp, i32]
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
+    lib.fs_error_mask_noalloc.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
     lib.fs_photo_loss.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     lib.fs_prune_score_accumulate.argtypes = [vp, vp, i64, vp, vp]
@@ -417,6 +418,13 @@ class Context:
             threshold_out = torch.empty(1, dtype=torch.float32, device=self.device)
         self._check(self.lib.fs_error_mask(self.handle, _ptr(image), _ptr(target), H, W, int(rule), float(k), _ptr(mask),
                                            _ptr(threshold_out)), "fs_error_mask")
+        return mask, threshold_out
+
+    def fs_error_mask_noalloc(self, image, target, mask, threshold_out, rule=FS_MASK_MEAN_STD, k=1.0):
+        """fs_error_mask on the library's static scratch; the outputs are the caller's (nothing is allocated)."""
+        _, H, W = image.shape
+        self._check(self.lib.fs_error_mask_noalloc(self.handle, _ptr(image), _ptr(target), H, W, int(rule), float(k),
+                                                   _ptr(mask), _ptr(threshold_out)), "fs_error_mask_noalloc")
         return mask, threshold_out
 
     def fs_photo_loss(self, image, target, lam=0.2, dL_dimage=None, out3=None, want_grad=True):

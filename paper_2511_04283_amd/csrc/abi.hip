@@ -64,7 +64,30 @@ struct fs_ctx {
     int64_t prof_launches[FS_K_COUNT] = {};
 };
 
+// ---- scratch of the entry point that allocates nothing (fs_error_mask_noalloc) ---------------------------------
+// One file-scope device array per GPU the library runs on, held until the process ends: the error map of up to
+// FS_NOALLOC_MAX_PIXELS pixels, one float for the threshold, and the reduction partials.  In host code the array's
+// name is only a handle: its device address is looked up once per device (noalloc_setup, called by fs_create with
+// that device current) and kernels are handed that address.
+constexpr size_t NOALLOC_ERR_BYTES = ((size_t)FS_NOALLOC_MAX_PIXELS + 64) * sizeof(float);   // (+ the threshold slot)
+constexpr size_t NOALLOC_PARTIAL_BYTES = (size_t)4 * RED_BLOCKS * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[NOALLOC_ERR_BYTES + NOALLOC_PARTIAL_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static void* g_noalloc_ptr[NOALLOC_MAX_DEVICES] = {};
+
 namespace {
+
+// `device` must be current.  Returns hipSuccess when the address is (already) known.
+hipError_t noalloc_setup(int device)
+{
+    if (device < 0 || device >= NOALLOC_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (g_noalloc_ptr[device]) return hipSuccess;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_noalloc_ptr[device] = ptr;
+    return hipSuccess;
+}
 
 int fail(fs_ctx* c, int code, const char* fmt, const char* a = "")
 {
@@ -237,6 +260,11 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->cfg = c;
     ctx->err[0] = 0;
+    if (noalloc_setup(device) != hipSuccess) {
+        (void)hipGetLastError();
+        fs_destroy(ctx);
+        return FS_EHIP;
+    }
     if (hipMalloc(reinterpret_cast<void**>(&ctx->alloc_dev), 2 * sizeof(uint64_t)) != hipSuccess ||
         hipMemset(ctx->alloc_dev, 0, 2 * sizeof(uint64_t)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void**>(&ctx->total_dev), 4 * sizeof(uint64_t)) != hipSuccess ||
@@ -602,6 +630,29 @@ int fs_error_mask(fs_ctx* ctx, const float* image, const float* target, int32_t 
     FS_HIP(launch_error_mask(ctx->stream, image, target, pixels, rule, k, err, static_cast<double*>(ctx->partial.ptr),
                              mask, thr),
            "k_err_*");
+    return FS_OK;
+}
+
+int fs_error_mask_noalloc(fs_ctx* ctx, const float* image, const float* target, int32_t height, int32_t width,
+                          int32_t rule, float k, uint8_t* mask, float* threshold_out)
+{
+    if (!ctx) return FS_EINVAL;
+    if (!image || !target || !mask || height <= 0 || width <= 0 ||
+        (rule != FS_MASK_MEAN_STD && rule != FS_MASK_MINMAX_TAU))
+        return fail(ctx, FS_EINVAL, "fs_error_mask_noalloc: bad arguments");
+    const int64_t pixels = (int64_t)height * width;
+    if (pixels > (int64_t)FS_NOALLOC_MAX_PIXELS)
+        return fail(ctx, FS_ECAPACITY, "fs_error_mask_noalloc: more than FS_NOALLOC_MAX_PIXELS pixels (use fs_error_mask)");
+    unsigned char* base = ctx->device >= 0 && ctx->device < NOALLOC_MAX_DEVICES
+                              ? static_cast<unsigned char*>(g_noalloc_ptr[ctx->device]) : nullptr;
+    if (!base) return fail(ctx, FS_EHIP, "fs_error_mask_noalloc: no static scratch on this device");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    // every word the kernels read is written earlier in the same call (the error map by k_err_map, all 4 x
+    // RED_BLOCKS partials by its and k_err_var's workgroups), so nothing of an earlier call's contents matters
+    float* err = reinterpret_cast<float*>(base);
+    double* partial = reinterpret_cast<double*>(base + NOALLOC_ERR_BYTES);
+    float* thr = threshold_out ? threshold_out : err + pixels;
+    FS_HIP(launch_error_mask(ctx->stream, image, target, pixels, rule, k, err, partial, mask, thr), "k_err_*");
     return FS_OK;
 }
 
