@@ -47,7 +47,7 @@ struct fs_ctx {
     uint64_t* total_host = nullptr;  // pinned host copy
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
     bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
-    ScratchBuf tile_partial;         // double [4, tiles]: per-tile sums of the fused forward pass
+    ScratchBuf tile_partial;         // double [5, tiles]: per-tile sums of the fused forward pass
     ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES]: per pair, the pixels of its tile at which the score counts it
     bool per_splat_bwd = false;      // fs_set_backward_mode
     bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
@@ -501,7 +501,7 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
     const bool bits = ctx->record_bits && bins->num_pairs > 0;
     FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
     FS_TRY(ensure(ctx, ctx->partial, (size_t)fused_partials() * sizeof(double), "partials"));
-    FS_TRY(ensure(ctx, ctx->tile_partial, (size_t)4 * tiles * sizeof(double), "tile partials"));
+    FS_TRY(ensure(ctx, ctx->tile_partial, (size_t)5 * tiles * sizeof(double), "tile partials"));
     if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, (size_t)bins->num_pairs * PAIR_BITS_BYTES, "score bits"));
     {
         ProfScope prof(ctx, FS_K_RENDER_FWD);
@@ -647,8 +647,8 @@ int fs_error_mask_noalloc(fs_ctx* ctx, const float* image, const float* target, 
                               ? static_cast<unsigned char*>(g_noalloc_ptr[ctx->device]) : nullptr;
     if (!base) return fail(ctx, FS_EHIP, "fs_error_mask_noalloc: no static scratch on this device");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
-    // every word the kernels read is written earlier in the same call (the error map by k_err_map, all 4 x
-    // RED_BLOCKS partials by its and k_err_var's workgroups), so nothing of an earlier call's contents matters
+    // every word the kernels read is written earlier in the same call (the error map and all 4 x RED_BLOCKS
+    // partials by k_err_map's workgroups), so nothing of an earlier call's contents matters
     float* err = reinterpret_cast<float*>(base);
     double* partial = reinterpret_cast<double*>(base + NOALLOC_ERR_BYTES);
     float* thr = threshold_out ? threshold_out : err + pixels;

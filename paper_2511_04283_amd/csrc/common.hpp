@@ -209,7 +209,7 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
                              uint32_t* n_contrib, void* pair_bits);
 
 // forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
-// tile_partial: 4 * tiles doubles, err: H*W floats, dL may be null; pair_bits as for launch_render_fwd
+// tile_partial: 5 * tiles doubles, err: H*W floats, dL may be null; pair_bits as for launch_render_fwd
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
@@ -217,12 +217,12 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
 // the count pass from those bits: counts[g] += |bits(pair) & mask(tile)| over the pairs of every tile
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* gauss_sorted,
                              const void* pair_bits, const uint8_t* mask, int32_t* counts);
-// partial: >= fused_partials() doubles
+// stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,
-                                     double* partial, double* loss_out);
+                                     double* stats, double* loss_out);
 hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, float k, const float* err,
-                                      double* partial, uint8_t* mask, float* thr);
+                                      const double* stats, uint8_t* mask, float* thr);
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,

@@ -63,7 +63,23 @@ __global__ __launch_bounds__(RED_THREADS) void k_l1_final(const double* __restri
     if (threadIdx.x == 0) *loss_out = s / (double)count;
 }
 
-// e = ((|d0| + |d1|) + |d2|) / 3 per pixel; partial sums / minima / maxima per workgroup.
+// The threshold of the mask from the error map's statistics (Sec. 4.2, second and third equations): mean + k * std
+// with the population variance taken as mean(e^2) - mean(e)^2 in double precision (e lies in [0, 1] and the sums
+// are exact to about 1e-13, far below what the single-precision threshold resolves), or min + k * (max - min).
+__device__ __forceinline__ float threshold_from_stats(double sum, double lo, double hi, double sumsq, int64_t pixels,
+                                                      int rule, float k)
+{
+    if (rule == FS_MASK_MEAN_STD) {
+        const double mean = sum / (double)pixels;
+        double var = sumsq / (double)pixels - mean * mean;
+        var = var > 0.0 ? var : 0.0;
+        return (float)(mean + (double)k * sqrt(var));
+    }
+    const float l = (float)lo, h = (float)hi;
+    return l + k * (h - l);
+}
+
+// e = ((|d0| + |d1|) + |d2|) / 3 per pixel; partial sums / minima / maxima / sums of squares per workgroup.
 // VEC = 4: four neighbouring pixels per thread with 16-byte accesses (pixels a multiple of 4, arrays aligned).
 template <int VEC>
 __global__ __launch_bounds__(RED_THREADS) void k_err_map(const float* __restrict__ image,
@@ -71,11 +87,12 @@ __global__ __launch_bounds__(RED_THREADS) void k_err_map(const float* __restrict
                                                         float* __restrict__ err, double* __restrict__ partial)
 {
     __shared__ double smem[4];
-    double s = 0.0, lo = 1.0e300, hi = -1.0e300;
+    double s = 0.0, sq = 0.0, lo = 1.0e300, hi = -1.0e300;
     const int64_t stride = (int64_t)RED_BLOCKS * RED_THREADS;
     auto one = [&](float i0, float i1, float i2, float t0, float t1, float t2) {
         const float e = ((fabsf(i0 - t0) + fabsf(i1 - t1)) + fabsf(i2 - t2)) / 3.0f;
         s += (double)e;
+        sq += (double)e * (double)e;
         lo = (double)e < lo ? (double)e : lo;
         hi = (double)e > hi ? (double)e : hi;
         return e;
@@ -103,31 +120,36 @@ __global__ __launch_bounds__(RED_THREADS) void k_err_map(const float* __restrict
     s = block_reduce<RED_SUM>(s, smem);
     lo = block_reduce<RED_MIN>(lo, smem);
     hi = block_reduce<RED_MAX>(hi, smem);
+    sq = block_reduce<RED_SUM>(sq, smem);
     if (threadIdx.x == 0) {
         partial[blockIdx.x] = s;
         partial[RED_BLOCKS + blockIdx.x] = lo;
         partial[2 * RED_BLOCKS + blockIdx.x] = hi;
+        partial[3 * RED_BLOCKS + blockIdx.x] = sq;
     }
 }
 
-// Folds the per-tile partials that the fused forward kernel leaves ([4][tiles]: sum |d|, sum / min / max of e)
-// into the RED_BLOCKS-wide layout the final kernels read: partial[0..] = sum e, [RED_BLOCKS..] = min,
-// [2 RED_BLOCKS..] = max, and the L1 sums at [4 RED_BLOCKS..].  Thread b adds tiles b, b + RED_BLOCKS, ... in order.
-__global__ __launch_bounds__(RED_THREADS) void k_fold_tile_partials(const double* __restrict__ tile_partial, int tiles,
-                                                                   double* __restrict__ partial)
+// After the fused forward kernel: one workgroup adds up its per-tile partials ([5][tiles]: sum |d|; sum, min,
+// max, sum of squares of e) in a fixed order (thread b takes tiles b, b + 1024, ...; then a shuffle tree) and leaves
+// stats[0..3] = {sum e, min e, max e, sum e^2} and the L1 loss.
+constexpr int FOLD_THREADS = 1024;
+__global__ __launch_bounds__(FOLD_THREADS) void k_fold_tile_stats(const double* __restrict__ tile_partial, int tiles,
+                                                                  int64_t count, double* __restrict__ stats,
+                                                                  double* __restrict__ loss_out)
 {
-    const int b = blockIdx.x * RED_THREADS + threadIdx.x;   // < RED_BLOCKS
-    double l1 = 0.0, s = 0.0, lo = 1.0e300, hi = -1.0e300;
-    for (int t0 = b; t0 < tiles; t0 += 4 * RED_BLOCKS) {   // 16 loads in flight per round, added in a fixed order
-        double v[4][4];
+    __shared__ double sm[5][FOLD_THREADS / 64];
+    double l1 = 0.0, s = 0.0, sq = 0.0, lo = 1.0e300, hi = -1.0e300;
+    for (int t0 = threadIdx.x; t0 < tiles; t0 += 4 * FOLD_THREADS) {   // 20 loads in flight per round
+        double v[4][5];
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            const int t = t0 + u * RED_BLOCKS;
+            const int t = t0 + u * FOLD_THREADS;
             const bool in = t < tiles;
             v[u][0] = in ? tile_partial[t] : 0.0;
             v[u][1] = in ? tile_partial[(size_t)tiles + t] : 0.0;
             v[u][2] = in ? tile_partial[2 * (size_t)tiles + t] : 1.0e300;
             v[u][3] = in ? tile_partial[3 * (size_t)tiles + t] : -1.0e300;
+            v[u][4] = in ? tile_partial[4 * (size_t)tiles + t] : 0.0;
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
@@ -135,53 +157,47 @@ __global__ __launch_bounds__(RED_THREADS) void k_fold_tile_partials(const double
             s += v[u][1];
             lo = v[u][2] < lo ? v[u][2] : lo;
             hi = v[u][3] > hi ? v[u][3] : hi;
+            sq += v[u][4];
         }
     }
-    partial[b] = s;
-    partial[RED_BLOCKS + b] = lo;
-    partial[2 * RED_BLOCKS + b] = hi;
-    partial[4 * RED_BLOCKS + b] = l1;
-}
-
-// second pass of the two-pass variance: partial sums of (e - mean)^2
-__global__ __launch_bounds__(RED_THREADS) void k_err_var(const float* __restrict__ err, int64_t pixels,
-                                                        double* __restrict__ partial)
-{
-    __shared__ double smem[4];
-    __shared__ double mean_s;
-    const double tot = final_reduce<RED_SUM>(partial, smem);
-    if (threadIdx.x == 0) mean_s = tot / (double)pixels;
-    __syncthreads();
-    const double mean = mean_s;
-    double s = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * RED_THREADS + threadIdx.x; i < pixels; i += (int64_t)RED_BLOCKS * RED_THREADS) {
-        const double d = (double)err[i] - mean;
-        s += d * d;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        l1 += shfl_down_f64(l1, d);
+        s += shfl_down_f64(s, d);
+        sq += shfl_down_f64(sq, d);
+        const double a = shfl_down_f64(lo, d), b = shfl_down_f64(hi, d);
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
     }
-    s = block_reduce<RED_SUM>(s, smem);
-    if (threadIdx.x == 0) partial[3 * RED_BLOCKS + blockIdx.x] = s;
+    if ((threadIdx.x & 63) == 0) {
+        const int w = threadIdx.x >> 6;
+        sm[0][w] = l1; sm[1][w] = s; sm[2][w] = lo; sm[3][w] = hi; sm[4][w] = sq;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        l1 = 0.0; s = 0.0; sq = 0.0; lo = 1.0e300; hi = -1.0e300;
+        for (int w = 0; w < FOLD_THREADS / 64; w++) {
+            l1 += sm[0][w];
+            s += sm[1][w];
+            lo = sm[2][w] < lo ? sm[2][w] : lo;
+            hi = sm[3][w] > hi ? sm[3][w] : hi;
+            sq += sm[4][w];
+        }
+        stats[0] = s; stats[1] = lo; stats[2] = hi; stats[3] = sq;
+        if (loss_out) *loss_out = l1 / (double)count;
+    }
 }
 
-// threshold from the partials (one workgroup), written as one float
+// threshold from the RED_BLOCKS-wide partials of k_err_map (one workgroup), written as one float
 __global__ __launch_bounds__(RED_THREADS) void k_err_threshold(const double* __restrict__ partial, int64_t pixels,
                                                               int rule, float k, float* __restrict__ thr)
 {
     __shared__ double smem[4];
-    if (rule == FS_MASK_MEAN_STD) {
-        const double tot = final_reduce<RED_SUM>(partial, smem);
-        const double var = final_reduce<RED_SUM>(partial + 3 * RED_BLOCKS, smem);
-        if (threadIdx.x == 0) {
-            const double mean = tot / (double)pixels;
-            *thr = (float)(mean + (double)k * sqrt(var / (double)pixels));
-        }
-    } else {
-        const double lo = final_reduce<RED_MIN>(partial + RED_BLOCKS, smem);
-        const double hi = final_reduce<RED_MAX>(partial + 2 * RED_BLOCKS, smem);
-        if (threadIdx.x == 0) {
-            const float l = (float)lo, h = (float)hi;
-            *thr = l + k * (h - l);
-        }
-    }
+    const double tot = final_reduce<RED_SUM>(partial, smem);
+    const double lo = final_reduce<RED_MIN>(partial + RED_BLOCKS, smem);
+    const double hi = final_reduce<RED_MAX>(partial + 2 * RED_BLOCKS, smem);
+    const double sq = final_reduce<RED_SUM>(partial + 3 * RED_BLOCKS, smem);
+    if (threadIdx.x == 0) *thr = threshold_from_stats(tot, lo, hi, sq, pixels, rule, k);
 }
 
 __global__ __launch_bounds__(256) void k_err_mask(const float* __restrict__ err, int64_t pixels,
@@ -189,6 +205,18 @@ __global__ __launch_bounds__(256) void k_err_mask(const float* __restrict__ err,
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < pixels) mask[i] = err[i] > *thr;
+}
+
+// the mask straight from the four statistics that k_fold_tile_stats left (every thread forms the threshold itself;
+// the first one also stores it)
+__global__ __launch_bounds__(256) void k_err_mask_stats(const float* __restrict__ err, int64_t pixels,
+                                                        const double* __restrict__ stats, int rule, float k,
+                                                        uint8_t* __restrict__ mask, float* __restrict__ thr_out)
+{
+    const float thr = threshold_from_stats(stats[0], stats[1], stats[2], stats[3], pixels, rule, k);
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) *thr_out = thr;
+    if (i < pixels) mask[i] = err[i] > thr;
 }
 
 // ---- photometric loss: (1 - lambda) L1 + lambda (1 - SSIM) ---------------------------------------
@@ -463,7 +491,7 @@ __global__ __launch_bounds__(256) void k_prune_normalize(const double* __restric
 
 int l1_partials() { return RED_BLOCKS; }
 int mask_partials() { return RED_BLOCKS; }
-int fused_partials() { return 5 * RED_BLOCKS; }
+int fused_partials() { return 4; }
 
 hipError_t launch_l1_grad(hipStream_t st, const float* image, const float* target, int64_t count, float* dL,
                           double* partial, double* loss_out)
@@ -490,8 +518,6 @@ hipError_t launch_error_mask(hipStream_t st, const float* image, const float* ta
         hipLaunchKernelGGL(k_err_map<4>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, pixels, err, partial);
     else
         hipLaunchKernelGGL(k_err_map<1>, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, image, target, pixels, err, partial);
-    if (rule == FS_MASK_MEAN_STD)
-        hipLaunchKernelGGL(k_err_var, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, err, pixels, partial);
     hipLaunchKernelGGL(k_err_threshold, dim3(1), dim3(RED_THREADS), 0, st, partial, pixels, rule, k, thr);
     hipLaunchKernelGGL(k_err_mask, dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0, st, err, pixels, thr, mask);
     return hipGetLastError();
@@ -534,26 +560,21 @@ hipError_t launch_prune_normalize(hipStream_t st, const double* acc, int64_t n, 
     return hipGetLastError();
 }
 
-// After the fused forward kernel: fold its per-tile partials, optionally finish the L1 loss.
+// After the fused forward kernel: its per-tile partials -> stats[0..3] and, optionally, the L1 loss.
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,
-                                     double* partial, double* loss_out)
+                                     double* stats, double* loss_out)
 {
-    hipLaunchKernelGGL(k_fold_tile_partials, dim3(RED_BLOCKS / RED_THREADS), dim3(RED_THREADS), 0, st, tile_partial, tiles,
-                       partial);
-    if (loss_out)
-        hipLaunchKernelGGL(k_l1_final, dim3(1), dim3(RED_THREADS), 0, st, partial + 4 * RED_BLOCKS, count, loss_out);
+    hipLaunchKernelGGL(k_fold_tile_stats, dim3(1), dim3(FOLD_THREADS), 0, st, tile_partial, tiles, count, stats, loss_out);
     return hipGetLastError();
 }
 
-// fs_error_mask without its first pass: the error map and its partial sums are already in place
+// fs_error_mask without its first pass: the error map and its statistics are already in place
 hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, float k, const float* err,
-                                      double* partial, uint8_t* mask, float* thr)
+                                      const double* stats, uint8_t* mask, float* thr)
 {
     if (pixels <= 0) return hipSuccess;
-    if (rule == FS_MASK_MEAN_STD)
-        hipLaunchKernelGGL(k_err_var, dim3(RED_BLOCKS), dim3(RED_THREADS), 0, st, err, pixels, partial);
-    hipLaunchKernelGGL(k_err_threshold, dim3(1), dim3(RED_THREADS), 0, st, partial, pixels, rule, k, thr);
-    hipLaunchKernelGGL(k_err_mask, dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0, st, err, pixels, thr, mask);
+    hipLaunchKernelGGL(k_err_mask_stats, dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0, st, err, pixels, stats, rule, k,
+                       mask, thr);
     return hipGetLastError();
 }
 

@@ -220,8 +220,8 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 
 // FUSED: the epilogue also does, per pixel, what the L1 term (FastGS Sec. 4.5) and the error map of the
 // multi-view score (Sec. 4.2) need from the finished colour -- dL/dC = sign(C - target) * scale, the error
-// e = ((|d0| + |d1|) + |d2|) / 3 -- and leaves this tile's partial sums (sum of |d|, sum / min / max of e)
-// at tile_partial[q * num_tiles + tile], so that the image is not read again for them.
+// e = ((|d0| + |d1|) + |d2|) / 3 -- and leaves this tile's partial sums (sum of |d|; sum, min, max and sum of squares
+// of e) at tile_partial[q * num_tiles + tile], so that the image is not read again for them.
 //
 // BITS: the kernel also records, for every pair of the tile's list (by its position in the sorted order), at which
 // of the tile's 256 pixels the Gaussian is counted by the multi-view score (Sec. 4.2): where it is blended and, in
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             nt_store(make_uint4(0u, 0u, 0u, 0u), pair_bits + (size_t)pos * 2 + 1);
         }
     }
-    double l1 = 0.0, esum = 0.0, emin = 1.0e300, emax = -1.0e300;
+    double l1 = 0.0, esum = 0.0, esq = 0.0, emin = 1.0e300, emax = -1.0e300;
     if (p.inside) {
         const size_t hw = (size_t)cam.width * cam.height;
         const size_t pix = (size_t)p.y * cam.width + p.x;
@@ -367,6 +367,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             err[pix] = e;
             l1 = ((double)fabsf(d0) + (double)fabsf(d1)) + (double)fabsf(d2);
             esum = emin = emax = (double)e;
+            esq = (double)e * (double)e;
         }
     }
     if (FUSED) {
@@ -378,15 +379,17 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
         for (int d = 32; d >= 1; d >>= 1) {
             l1 += shfl_down_f64(l1, d);
             esum += shfl_down_f64(esum, d);
+            esq += shfl_down_f64(esq, d);
             fmin_e = fminf(fmin_e, __shfl_down(fmin_e, d, 64));
             fmax_e = fmaxf(fmax_e, __shfl_down(fmax_e, d, 64));
         }
-        // (the staging masks serve as the 4 x 4 doubles of scratch: they are only live inside stage_batch, between
+        // (the staging masks serve as the 4 x 5 doubles of scratch: they are only live inside stage_batch, between
         // its two barriers, and every wavefront has left its last stage_batch before any of them gets here)
-        double (*s_part)[4] = reinterpret_cast<double (*)[4]>(&s.bits[0][0]);
+        static_assert(sizeof(s.bits) >= 4 * 5 * sizeof(double), "scratch for the per-wavefront partials");
+        double (*s_part)[5] = reinterpret_cast<double (*)[5]>(&s.bits[0][0]);
         if ((threadIdx.x & 63) == 0) {
             double* w = s_part[threadIdx.x >> 6];
-            w[0] = l1; w[1] = esum; w[2] = (double)fmin_e; w[3] = (double)fmax_e;
+            w[0] = l1; w[1] = esum; w[2] = (double)fmin_e; w[3] = (double)fmax_e; w[4] = esq;
         }
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -395,6 +398,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             tile_partial[nt + tile] = (s_part[0][1] + s_part[1][1]) + (s_part[2][1] + s_part[3][1]);
             tile_partial[2 * nt + tile] = fmin(fmin(s_part[0][2], s_part[1][2]), fmin(s_part[2][2], s_part[3][2]));
             tile_partial[3 * nt + tile] = fmax(fmax(s_part[0][3], s_part[1][3]), fmax(s_part[2][3], s_part[3][3]));
+            tile_partial[4 * nt + tile] = (s_part[0][4] + s_part[1][4]) + (s_part[2][4] + s_part[3][4]);
         }
     }
 }
