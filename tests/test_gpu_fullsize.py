@@ -147,26 +147,50 @@ def test_config5_full(ctx, orc32):
     _check(g, r)
 
 
-def test_config5_wide_tail_27m_pairs_binning(ctx, orc32):
-    """Wide-tail variant of config 5 (27 M pairs): integer stages in full, image and n_contrib on a
-    seeded 4 % sample of tiles."""
+def test_config5_wide_tail_27m_pairs(ctx, orc32):
+    """Wide-tail variant of config 5 (27 M pairs): the integer stages in full; image, n_contrib, every gradient
+    and the counts on a seeded 4 % sample of tiles.  The loss gradient is the L1 gradient inside the sampled tiles
+    and zero elsewhere, so that the GPU's per-Gaussian sums over ALL tiles are the oracle's sums over the sample;
+    likewise the count pass runs on a seeded mask that is empty outside the sample."""
+    import torch
+    from paper_2511_04283_amd import binding as B
     sc = scenes.make_scene(5, scale_sigma=1.2)
     cam = sc.cameras[0]
-    g = gpu_pipeline(ctx, sc, cam)
     p_o = orc32.preprocess(sc, cam)
     b_o = orc32.bin_sort(p_o, cam)
+    T = b_o.tile_ranges.shape[0]
+    tiles = np.sort(np.random.default_rng(7).choice(T, T // 25, replace=False)).astype(np.int32)
+    TX = (cam.width + 15) // 16
+    sel = np.zeros((cam.height, cam.width), bool)
+    for t in tiles:
+        sel[(t // TX) * 16:(t // TX) * 16 + 16, (t % TX) * 16:(t % TX) * 16 + 16] = True
+    img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, tile_list=tiles, threads=THREADS)
+    tgt = scenes.target_image(5, 0, cam)
+    _, dL_full = orc32.l1(img, tgt)
+    dL = np.where(sel[None], dL_full, 0).astype(np.float32)
+    mask = ((np.random.default_rng(8).uniform(size=sel.shape) < 0.2) & sel).astype(np.uint8)
+
+    g = gpu_pipeline(ctx, sc, cam, dL=dL)
     assert b_o.num_pairs > 20_000_000 and g["num_pairs"] == b_o.num_pairs
     assert np.array_equal(g["rect"], p_o.rect)
     assert np.array_equal(g["keys_sorted"], b_o.keys_sorted)
     assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted)
     assert np.array_equal(g["tile_ranges"], b_o.tile_ranges)
-    T = b_o.tile_ranges.shape[0]
-    tiles = np.sort(np.random.default_rng(7).choice(T, T // 25, replace=False)).astype(np.int32)
-    img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, tile_list=tiles, threads=THREADS)
-    TX = (cam.width + 15) // 16
-    sel = np.zeros((cam.height, cam.width), bool)
-    for t in tiles:
-        sel[(t // TX) * 16:(t // TX) * 16 + 16, (t % TX) * 16:(t % TX) * 16 + 16] = True
     assert np.array_equal(g["n_contrib"][sel], nc[sel])
     err = np.abs(g["image"] - img)[:, sel]
     assert (err <= 1e-4 * np.maximum(np.abs(img[:, sel]), 1e-2)).all()
+    # (both sides are handed the same loss gradient, so no sign of image - target is decided twice)
+    ref = orc32.backward_mt(sc, cam, p_o, b_o, dL, tile_list=tiles, threads=THREADS)
+    assert np.abs(ref["means"]).max() > 0
+    assert_grads_close(g["grads"], ref)
+    # counts
+    gs = B.Gaussians.from_scene(sc, ctx.device)
+    fcam = B.make_camera(cam)
+    proj = ctx.fs_preprocess(gs, fcam)
+    bins = ctx.fs_bin_sort(proj, fcam)
+    image, final_T, n_contrib = ctx.fs_render_fwd(proj, bins, fcam)
+    counts = torch.zeros(sc.n, dtype=torch.int32, device=ctx.device)
+    ctx.fs_score_accumulate(proj, bins, fcam, final_T, n_contrib, torch.from_numpy(mask).to(ctx.device), counts)
+    want = orc32.score_mt(p_o, b_o, cam, mask, np.zeros(sc.n, np.int32), tile_list=tiles, threads=THREADS)
+    assert want.sum() > 1000
+    assert np.array_equal(counts.cpu().numpy(), want)
