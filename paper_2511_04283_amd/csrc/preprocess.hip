@@ -316,6 +316,26 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     __shared__ __attribute__((aligned(16))) float s_buf[4][(WAVE_FLOATS + 3) / 4 * 4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool in_range = i < n;
+    // (a Gaussian with tiles_touched > 0 passed the forward pass's culling: the count stands in for visibility)
+    const bool vis0 = in_range && touched[i] > 0;
+    const int64_t wave_first = (int64_t)blockIdx.x * blockDim.x + wave * 64;
+    const int valid_rows = (int)min((int64_t)64, max((int64_t)0, n - wave_first));
+    constexpr int NV = (HALF / 4 * F + 63) / 64;  // float4 per lane for the SH rows of a full half
+    // The SH rows of the first half are requested before the pair records are streamed, so that the two latencies
+    // overlap (they wait in registers: the LDS buffer serves the records first).
+    float4 vh[NV];
+    int pre = -1;   // the half whose rows are on their way into vh (uniform over the wavefront)
+    auto request_half = [&](int h) {
+        if (valid_rows < (h + 1) * HALF || __ballot(vis0 && (lane / HALF) == h) == 0) return;
+        const float4* src4 = reinterpret_cast<const float4*>(sh + (wave_first + h * HALF) * F);
+#pragma unroll
+        for (int it = 0; it < NV; it++) {
+            const int q = lane + 64 * it;
+            vh[it] = q < HALF / 4 * F ? src4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        pre = h;
+    };
+    request_half(0);
 
     // ---- screen-space gradients: sum of this Gaussian's pair records, in tile order ----------
     // The 64 Gaussians of a wavefront own one contiguous run of records.  The wavefront streams that
@@ -332,16 +352,45 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
             hi_all = max(hi_all, (uint32_t)__shfl_xor((int)hi_all, d, 64));
         }
         float4* buf = reinterpret_cast<float4*>(s_buf[wave]);
+        // Chunk k+1 is requested as soon as chunk k has gone from registers to LDS, so that its latency passes
+        // while chunk k is added up.  (All loads of a chunk are issued before the first LDS write: written as one
+        // loop, each load would be waited for in turn.)
+        constexpr int LPL = CH * (PAIR_REC / 4) / 64;
+        float4 v[LPL];
+        auto request = [&](uint32_t cs) {
+            const uint32_t nq = min((uint32_t)CH, hi_all - cs) * (PAIR_REC / 4);
+            const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
+#pragma unroll
+            for (int u = 0; u < LPL; u++) {
+                const uint32_t q = lane + 64 * u;
+                v[u] = q < nq ? src[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        };
+        if (lo_all < hi_all) request(lo_all);
         for (uint32_t cs = lo_all; cs < hi_all; cs += CH) {
             const uint32_t nrec = min((uint32_t)CH, hi_all - cs);
-            const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
-            for (uint32_t q = lane; q < nrec * (PAIR_REC / 4); q += 64) buf[q] = src[q];
+#pragma unroll
+            for (int u = 0; u < LPL; u++) {
+                const uint32_t q = lane + 64 * u;
+                if (q < nrec * (PAIR_REC / 4)) buf[q] = v[u];
+            }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            if (cs + CH < hi_all) request(cs + CH);
             const uint32_t r0 = max(off, cs), r1 = min(off + cnt, cs + nrec);
-            for (uint32_t r = r0; r < r1; r++) {
-                const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1];
-                const float4 c4 = buf[(r - cs) * 3 + 2];
+            uint32_t r = r0;
+            for (; r + 2 <= r1; r += 2) {   // two records per trip: their LDS reads overlap
+                const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1], c4 = buf[(r - cs) * 3 + 2];
+                const float4 a2 = buf[(r - cs) * 3 + 3], b2 = buf[(r - cs) * 3 + 4], c5 = buf[(r - cs) * 3 + 5];
+                ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
+                rb.x += b.x; rb.y += b.y; rb.z += b.z; rb.w += b.w;
+                rc += c4.x; rabs_x += c4.y; rabs_y += c4.z;
+                ra.x += a2.x; ra.y += a2.y; ra.z += a2.z; ra.w += a2.w;
+                rb.x += b2.x; rb.y += b2.y; rb.z += b2.z; rb.w += b2.w;
+                rc += c5.x; rabs_x += c5.y; rabs_y += c5.z;
+            }
+            if (r < r1) {
+                const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1], c4 = buf[(r - cs) * 3 + 2];
                 ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
                 rb.x += b.x; rb.y += b.y; rb.z += b.z; rb.w += b.w;
                 rc += c4.x;
@@ -357,13 +406,28 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     //      64 different cache lines per instruction); the gradients go back the same way ----
     float* rows = s_buf[wave];
     float* c = rows + (lane & (HALF - 1)) * ROW;  // this lane's coefficients, later its gradients
-    const int64_t wave_first = (int64_t)blockIdx.x * blockDim.x + wave * 64;
-    const int valid_rows = (int)min((int64_t)64, max((int64_t)0, n - wave_first));
-    constexpr int NV = (HALF / 4 * F + 63) / 64;  // float4 per lane for a full half
+    // float4 number q of a half's block -> its four floats into the padded rows
+    auto commit = [&](const float4 (&v)[NV]) {
+#pragma unroll
+        for (int it = 0; it < NV; it++) {
+            const int q = lane + 64 * it;
+            if (q < HALF / 4 * F) {
+                const float comp[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
+                int row = (4 * q) / F, col = 4 * q - row * F;
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) {
+                    rows[row * ROW + col] = comp[jj];
+                    if (++col == F) { col = 0; row++; }
+                }
+            }
+        }
+    };
     auto load_half = [&](int h) {
         const int vr = min(HALF, max(0, valid_rows - h * HALF));
         const float* src = sh + (wave_first + h * HALF) * F;
-        if (vr == HALF) {
+        if (pre == h) {
+            commit(vh);
+        } else if (vr == HALF) {
             // all loads issued before the first LDS write
             const float4* src4 = reinterpret_cast<const float4*>(src);
             float4 v[NV];
@@ -372,19 +436,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
                 const int q = lane + 64 * it;
                 v[it] = q < HALF / 4 * F ? src4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-#pragma unroll
-            for (int it = 0; it < NV; it++) {
-                const int q = lane + 64 * it;
-                if (q < HALF / 4 * F) {
-                    const float comp[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
-                    int row = (4 * q) / F, col = 4 * q - row * F;
-#pragma unroll
-                    for (int jj = 0; jj < 4; jj++) {
-                        rows[row * ROW + col] = comp[jj];
-                        if (++col == F) { col = 0; row++; }
-                    }
-                }
-            }
+            commit(v);
         } else {
             for (int e = lane; e < HALF * F; e += 64) {
                 const int row = e / F;
@@ -426,9 +478,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
     };
 
     // ---- colour -> SH coefficients (and the weights the view direction's gradient needs), half a wavefront at a
-    //      time; done before the projection is recomputed so that few registers are live across it.  A Gaussian
-    //      with tiles_touched > 0 passed the forward pass's culling, so that count stands in for visibility here.
-    const bool vis0 = in_range && touched[i] > 0;
+    //      time; done before the projection is recomputed so that few registers are live across it.
     float d[3] = {0.f, 0.f, 1.f}, len = 1.f;
     float wk[K];
 #pragma unroll
@@ -437,6 +487,8 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         // (culled Gaussians come in runs -- whole clusters outside the frustum -- so a half often needs no
         // coefficients at all: its gradients are zeros whatever the buffer holds)
         if (__ballot(vis0 && (lane / HALF) == h) != 0) load_half(h);
+        // (requesting the second half's rows here, while the first is worked on, was measured slower: the registers
+        // they wait in take a wavefront per SIMD away)
         if ((lane / HALF) == h && in_range) {
             float Y[K], gcol[3] = {0.f, 0.f, 0.f};
 #pragma unroll
