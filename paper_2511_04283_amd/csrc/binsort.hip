@@ -613,7 +613,22 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
     constexpr int LG = G == 8 ? 3 : 4;
     static_assert(G == 8 || G == 16, "group of 8 or 16 words");
     auto at = [](int e) { return e + ((e >> LG) << 1); };   // word e of the sequence -> its place in k
-    for (int i = threadIdx.x; i < N; i += THREADS) k[at(i)] = i < n ? bucket[first + i] : ~0ull;
+    {
+        // (all of a thread's loads are issued before the first LDS write: written as one loop, each load would be
+        // waited for in turn; a workgroup's capacity is at most 8 words per thread)
+        constexpr int PER = 8;
+        uint64_t w[PER];
+#pragma unroll
+        for (int u = 0; u < PER; u++) {
+            const int i = threadIdx.x + u * THREADS;
+            w[u] = i < n ? bucket[first + i] : ~0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < PER; u++) {
+            const int i = threadIdx.x + u * THREADS;
+            if (i < N) k[at(i)] = w[u];
+        }
+    }
     __syncthreads();
     // one contiguous group through registers: FIRST = the complete stages 2 .. G, otherwise the steps at
     // distances G/2 .. 1 of a later stage, whose direction `up` is the same for the whole group
@@ -671,6 +686,7 @@ __global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__
                                                    const uint64_t* __restrict__ bucket, int len_lo,
                                                    uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
 {
+    static_assert(CAP <= 8 * THREADS, "tile_sort_lds loads at most 8 words per thread");
     __shared__ __align__(16) uint64_t k[CAP + CAP / 4];
     const uint32_t tile = tile_order[blockIdx.x];
     const uint2 r = ranges[tile];

@@ -1010,14 +1010,20 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
     if (__syncthreads_or(on) == 0) return;
     const uint4 m0 = reinterpret_cast<const uint4*>(s_m)[0], m1 = reinterpret_cast<const uint4*>(s_m)[1];
     for (;;) {
+        // (the next round's record is requested before this round's is counted)
+        const uint32_t next = pos + 256;
+        uint4 a2 = make_uint4(0u, 0u, 0u, 0u), c2 = a2;
+        uint32_t g2 = 0;
+        if (next < range.y) {
+            a2 = nt_load(pair_bits + (size_t)next * 2);
+            c2 = nt_load(pair_bits + (size_t)next * 2 + 1);
+            g2 = gauss_sorted[next];
+        }
         const int n = __popc(a.x & m0.x) + __popc(a.y & m0.y) + __popc(a.z & m0.z) + __popc(a.w & m0.w) +
                       __popc(c.x & m1.x) + __popc(c.y & m1.y) + __popc(c.z & m1.z) + __popc(c.w & m1.w);
         if (n != 0) atomicAdd(&counts[g], n);   // (all zeros for a thread past the end of the list)
-        pos += 256;
-        if (pos >= range.y) break;
-        a = nt_load(pair_bits + (size_t)pos * 2);
-        c = nt_load(pair_bits + (size_t)pos * 2 + 1);
-        g = gauss_sorted[pos];
+        if (next >= range.y) break;
+        pos = next; a = a2; c = c2; g = g2;
     }
 }
 
