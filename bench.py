@@ -15,7 +15,6 @@ refused: this build is single-GPU by construction.
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -41,12 +40,8 @@ KERNEL_OF_GROUP = {"preprocess": "k_preprocess", "scan": "k_scan_*", "emit_pairs
 
 def kernel_source_digest() -> str:
     """Digest of the HIP sources: a traffic summary under profiles/ only applies to the kernels it was measured on."""
-    h = hashlib.sha256()
-    d = os.path.join(ROOT, "paper_2511_04283_amd", "csrc")
-    for f in sorted(os.listdir(d)):
-        if f.endswith((".hip", ".hpp")):
-            h.update(open(os.path.join(d, f), "rb").read())
-    return h.hexdigest()[:16]
+    from paper_2511_04283_amd.build import source_digest
+    return source_digest()
 
 
 def main() -> int:

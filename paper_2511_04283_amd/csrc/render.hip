@@ -132,7 +132,7 @@ __device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_
         const float4 co = make_float4(r0.z, r0.w, r1.x, r1.y);
         s.xy[t] = xy;
         s.co[t] = make_float4(co.x, co.y + co.y, co.z, co.w);
-        if (WITH_RGB) s_rgb[t] = make_float4(r1.z, r1.w, r2.x, 0.f);
+        if (WITH_RGB) s_rgb[t] = make_float4(r1.z, r1.w, r2.x, -0.5f * r1.y);   // (the backward pass uses -sigma / 2)
         if (ID_MODE == 1) s_id[t] = g;
         if (ID_MODE == 2) {
             const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
@@ -505,7 +505,8 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         dC1 = dL_dimage[hw + pix];
         dC2 = dL_dimage[2 * hw + pix];
     }
-    float B0 = cfg.bg[0], B1 = cfg.bg[1], B2 = cfg.bg[2];
+    // dC . (colour composited behind the Gaussian at hand): all that dL/dalpha = T (dC . c - S) needs of it
+    float S = __builtin_fmaf(dC2, cfg.bg[2], __builtin_fmaf(dC1, cfg.bg[1], dC0 * cfg.bg[0]));
 
     // unfilled slots must hold finite numbers (lanes past their list's end compute with them and
     // contribute exact zeros)
@@ -528,6 +529,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         // a row none of whose pixels reaches into this batch does not lengthen the wavefront's loop
         const bool row_walks = ((__ballot(start < last) >> (lane & 48)) & 0xffffull) != 0;
         const int longest = wave_max_of_rows(row_walks ? mine : 0);
+        const int last_here = last - start;   // slots below this one hold entries this pixel blended (or examined)
         for (int it = 0; it < longest; it++) {
             const int k = mine - 1 - it;      // every row walks its own list from the back
             const int j = s.list[sub][k & (BATCH - 1)];
@@ -537,7 +539,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             const float u = __builtin_fmaf(co.y, dy, co.x * dx);
             const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
             const float power = -0.5f * q;
-            bool act = (k >= 0) & (start + j < last) & !(power > 0.0f) & !(power < cfg.power_min);
+            bool act = (k >= 0) & (j < last_here) & !(power > 0.0f) & !(power < cfg.power_min);
             float G = exp_c(power);   // (whatever the exponent of a lane that fails the test: its result is dropped)
             const float sG = co.w * G;
             float alpha = fminf(cfg.alpha_max, sG);
@@ -545,25 +547,23 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             const uint64_t act_mask = __ballot(act);
             if (act_mask == 0) continue;
             // lanes that do not blend this Gaussian run the same arithmetic with alpha = G = 0:
-            // every one of their 9 contributions is then an exact zero
+            // every one of their 9 contributions is then an exact zero (and T / (1 - 0) leaves T as it is)
             alpha = act ? alpha : 0.f;
             G = act ? G : 0.f;
-            const float4 col = s_rgb[j];
-            const float Tfront = T * __builtin_amdgcn_rcpf(1.0f - alpha);  // transmittance in front of this Gaussian
-            T = act ? Tfront : T;
+            const float4 col = s_rgb[j];                             // (r, g, b, -sigma / 2)
+            T = T * __builtin_amdgcn_rcpf(1.0f - alpha);             // transmittance in front of this Gaussian
             const float w = alpha * T;
             float v[9];
             v[0] = w * dC0;
             v[1] = w * dC1;
             v[2] = w * dC2;
-            const float e0 = col.x - B0, e1 = col.y - B1, e2 = col.z - B2;
-            float dL_dalpha = T * __builtin_fmaf(e2, dC2, __builtin_fmaf(e1, dC1, e0 * dC0));
-            B0 = __builtin_fmaf(alpha, e0, B0);
-            B1 = __builtin_fmaf(alpha, e1, B1);
-            B2 = __builtin_fmaf(alpha, e2, B2);
+            const float cd = __builtin_fmaf(col.z, dC2, __builtin_fmaf(col.y, dC1, col.x * dC0));   // dC . c
+            const float diff = cd - S;
+            float dL_dalpha = T * diff;
+            S = __builtin_fmaf(alpha, diff, S);
             dL_dalpha = sG > cfg.alpha_max ? 0.f : dL_dalpha;  // capped alpha is a constant
             v[3] = G * dL_dalpha;                              // d/d sigma
-            const float gq = -0.5f * (co.w * G) * dL_dalpha;   // d/d q
+            const float gq = col.w * v[3];                     // d/d q = -1/2 sigma G dL/dalpha
             const float gx = gq * dx, gy = gq * dy;
             v[4] = gx * dx;
             v[5] = gx * dy;
