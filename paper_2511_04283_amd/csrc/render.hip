@@ -82,13 +82,24 @@ __device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
     return pixel_of_thread(cam, tile, (int)threadIdx.x);
 }
 
-// LDS image of one batch of a tile's list, shared by the three kernels.
+// LDS image of one batch of a tile's list, shared by the kernels.  A staged Gaussian is one record of RS 16-byte
+// words, so that the loops form one address per entry: (mu_x, mu_y, a, 2b), (c, sigma, r, g) and, with WITH_RGB,
+// (b, -sigma/2, -, -).
+template <bool WITH_RGB>
 struct Stage {
-    float2 xy[BATCH];          // mu_2D
-    float4 co[BATCH];          // (a, 2b, c, sigma)
+    static constexpr int RS = WITH_RGB ? 3 : 2;
+    float4 rec[BATCH * RS];
     uint64_t bits[16][4];      // per sub-tile, per staging wavefront: which of its 64 slots the sub-tile visits
     uint8_t list[16][BATCH];   // per sub-tile (index wave*4 + row): batch slots to visit, in list order
     int len[16];               // length of each sub-tile's list
+    __device__ __forceinline__ const float4* at(int j) const { return rec + j * RS; }
+    // unfilled slots must hold finite numbers: lanes past their list's end compute with a stale slot and
+    // contribute exact zeros
+    __device__ __forceinline__ void clear(int t)
+    {
+#pragma unroll
+        for (int q = 0; q < RS; q++) rec[t * RS + q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 };
 
 template <int CTRL>
@@ -117,7 +128,7 @@ __device__ __forceinline__ uint32_t dpp_shr_add(uint32_t v)
 // ID_MODE: 0 = s_id unused, 1 = s_id[t] <- Gaussian index, 2 = s_id[t] <- index of the pair's
 // gradient record (where the pair was emitted before the sort: offset + place in the rectangle).
 template <bool WITH_RGB, int ID_MODE>
-__device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_id, const CamDev& cam,
+__device__ __forceinline__ int stage_batch(Stage<WITH_RGB>& s, uint32_t* s_id, const CamDev& cam,
                                            const CfgDev& cfg, int tile, const uint32_t* __restrict__ gauss_sorted,
                                            const float4* __restrict__ splats, uint32_t first, int m)
 {
@@ -130,9 +141,9 @@ __device__ __forceinline__ int stage_batch(Stage& s, float4* s_rgb, uint32_t* s_
         const float4 r0 = rec[0], r1 = rec[1], r2 = rec[2];
         const float2 xy = make_float2(r0.x, r0.y);
         const float4 co = make_float4(r0.z, r0.w, r1.x, r1.y);
-        s.xy[t] = xy;
-        s.co[t] = make_float4(co.x, co.y + co.y, co.z, co.w);
-        if (WITH_RGB) s_rgb[t] = make_float4(r1.z, r1.w, r2.x, -0.5f * r1.y);   // (the backward pass uses -sigma / 2)
+        s.rec[t * s.RS] = make_float4(xy.x, xy.y, co.x, co.y + co.y);
+        s.rec[t * s.RS + 1] = make_float4(co.z, co.w, r1.z, r1.w);
+        if (WITH_RGB) s.rec[t * s.RS + 2] = make_float4(r2.x, -0.5f * co.w, 0.f, 0.f);   // (the backward pass uses -sigma / 2)
         if (ID_MODE == 1) s_id[t] = g;
         if (ID_MODE == 2) {
             const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
@@ -238,8 +249,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                                                     float* __restrict__ dL, float* __restrict__ err,
                                                     double* __restrict__ tile_partial, uint4* __restrict__ pair_bits)
 {
-    __shared__ Stage s;
-    __shared__ float4 s_rgb[BATCH];
+    __shared__ Stage<true> s;
     __shared__ __align__(16) uint16_t s_pb[BITS ? BATCH : 1][16];  // this batch's bits, [slot][sub-tile]
 
     const int tile = (int)tile_order[blockIdx.x];  // longest lists first
@@ -254,9 +264,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
 
     // Slots a batch does not fill must still hold finite numbers: lanes past the end of their list
     // read a stale slot and multiply its colour by a zero weight.
-    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
-    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
-    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.clear(threadIdx.x);
 
     // BITS: row t of s_pb is zeroed and written out by thread t alone; the other wavefronts set bits in it between
     // a batch's staging barriers and the barrier at the top of the next batch
@@ -289,8 +297,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             pending_m = m;
             reached = start + m;
         }
-        const int mine = stage_batch<true, 0>(s, s_rgb, nullptr, cam, cfg, tile, gauss_sorted, splats,
-                                              range.x + start, m);
+        const int mine = stage_batch<true, 0>(s, nullptr, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         // a row whose 16 pixels have all finished does not lengthen the wavefront's loop
         const bool row_alive = ((__ballot(!done) >> (threadIdx.x & 48)) & 0xffffull) != 0;
         const int longest = wave_max_of_rows(row_alive ? mine : 0);
@@ -298,28 +305,30 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
         // slot and discard the result; one wave-uniform branch per iteration.  (Skipping the rest of an
         // iteration when no lane passes the range test does not pay: four rows look at four different
         // Gaussians, so all of them missing is rare, and the test costs more than it saves.)
+        int lastj = -1;   // batch slot of the last Gaussian this pixel blended in this batch
         for (int k = 0; k < longest; k++) {
-            if (__ballot(!done) == 0) break;
+            // (every fourth trip: a wavefront whose pixels have all terminated leaves the loop)
+            if ((k & 3) == 0 && __ballot(!done) == 0) break;
             const int j = s.list[sub][k];
-            const float2 xy = s.xy[j];
-            const float4 co = s.co[j];
-            const float dx = p.px - xy.x, dy = p.py - xy.y;
-            const float u = __builtin_fmaf(co.y, dy, co.x * dx);
-            const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+            const float4* e = s.at(j);
+            const float4 r0 = e[0], r1 = e[1];           // (mu_x, mu_y, a, 2b), (c, sigma, r, g)
+            const float dx = p.px - r0.x, dy = p.py - r0.y;
+            const float u = __builtin_fmaf(r0.w, dy, r0.z * dx);
+            const float q = __builtin_fmaf(dx, u, (r1.x * dy) * dy);
             const float power = -0.5f * q;
             bool ok = (k < mine) & !done & !(power > 0.0f) & !(power < cfg.power_min);
-            const float4 col = s_rgb[j];
+            const float colb = e[2].x;
             const float G = exp_c(power);
-            const float alpha = fminf(cfg.alpha_max, co.w * G);
+            const float alpha = fminf(cfg.alpha_max, r1.y * G);
             ok = ok & (alpha >= cfg.alpha_min);
             const float Tn = T * (1.0f - alpha);
             const bool stop = ok & (Tn < cfg.T_min);
             const bool blend = ok & !stop;
             done = done | stop;
             const float w = blend ? alpha * T : 0.0f;  // a zero weight leaves C unchanged bit for bit
-            C0 = __builtin_fmaf(col.x, w, C0);
-            C1 = __builtin_fmaf(col.y, w, C1);
-            C2 = __builtin_fmaf(col.z, w, C2);
+            C0 = __builtin_fmaf(r1.z, w, C0);
+            C1 = __builtin_fmaf(r1.w, w, C1);
+            C2 = __builtin_fmaf(colb, w, C2);
             if (BITS) {
                 // (kept behind the colour update: scheduled ahead of it, the LDS store below would sit between the
                 // colour's LDS read and the wait for it, and every iteration would wait for the store as well)
@@ -331,8 +340,9 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                 if ((threadIdx.x & 15) == 0 && k < mine) s_pb[j][sub] = (uint16_t)(hb >> (threadIdx.x & 48));
             }
             T = blend ? Tn : T;
-            last = blend ? (uint32_t)(start + j + 1) : last;
+            lastj = blend ? j : lastj;
         }
+        last = lastj >= 0 ? (uint32_t)(start + lastj + 1) : last;
     }
     if (BITS) {
         if (pending >= 0) {
@@ -478,8 +488,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
     const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
     const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
 {
-    __shared__ Stage s;
-    __shared__ float4 s_rgb[BATCH];
+    __shared__ Stage<true> s;
     __shared__ uint32_t s_id[BATCH];
     constexpr int NV = ABS ? 11 : 9;
     // The sub-tiles' sums of a Gaussian meet in double precision: on this chip the LDS atomic add of a double is
@@ -510,9 +519,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
 
     // unfilled slots must hold finite numbers (lanes past their list's end compute with them and
     // contribute exact zeros)
-    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
-    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
-    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.clear(threadIdx.x);
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     atomicMax(&s_max, last);
@@ -525,7 +532,7 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         __syncthreads();  // the previous batch's flush has read s_acc / s_id
 #pragma unroll
         for (int k = 0; k < NV; k++) s_acc[threadIdx.x][k] = (acc_t)0;
-        const int mine = stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
+        const int mine = stage_batch<true, 2>(s, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         // a row none of whose pixels reaches into this batch does not lengthen the wavefront's loop
         const bool row_walks = ((__ballot(start < last) >> (lane & 48)) & 0xffffull) != 0;
         const int longest = wave_max_of_rows(row_walks ? mine : 0);
@@ -533,15 +540,15 @@ __global__ __launch_bounds__(256) void k_render_bwd(
         for (int it = 0; it < longest; it++) {
             const int k = mine - 1 - it;      // every row walks its own list from the back
             const int j = s.list[sub][k & (BATCH - 1)];
-            const float2 xy = s.xy[j];
-            const float4 co = s.co[j];
-            const float dx = p.px - xy.x, dy = p.py - xy.y;
-            const float u = __builtin_fmaf(co.y, dy, co.x * dx);
-            const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
+            const float4* e = s.at(j);
+            const float4 r0 = e[0], r1 = e[1];           // (mu_x, mu_y, a, 2b), (c, sigma, r, g)
+            const float dx = p.px - r0.x, dy = p.py - r0.y;
+            const float u = __builtin_fmaf(r0.w, dy, r0.z * dx);
+            const float q = __builtin_fmaf(dx, u, (r1.x * dy) * dy);
             const float power = -0.5f * q;
             bool act = (k >= 0) & (j < last_here) & !(power > 0.0f) & !(power < cfg.power_min);
             float G = exp_c(power);   // (whatever the exponent of a lane that fails the test: its result is dropped)
-            const float sG = co.w * G;
+            const float sG = r1.y * G;
             float alpha = fminf(cfg.alpha_max, sG);
             act = act & (alpha >= cfg.alpha_min);
             const uint64_t act_mask = __ballot(act);
@@ -550,20 +557,20 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             // every one of their 9 contributions is then an exact zero (and T / (1 - 0) leaves T as it is)
             alpha = act ? alpha : 0.f;
             G = act ? G : 0.f;
-            const float4 col = s_rgb[j];                             // (r, g, b, -sigma / 2)
+            const float2 r2 = *reinterpret_cast<const float2*>(e + 2);   // (b, -sigma / 2)
             T = T * __builtin_amdgcn_rcpf(1.0f - alpha);             // transmittance in front of this Gaussian
             const float w = alpha * T;
             float v[9];
             v[0] = w * dC0;
             v[1] = w * dC1;
             v[2] = w * dC2;
-            const float cd = __builtin_fmaf(col.z, dC2, __builtin_fmaf(col.y, dC1, col.x * dC0));   // dC . c
+            const float cd = __builtin_fmaf(r2.x, dC2, __builtin_fmaf(r1.w, dC1, r1.z * dC0));   // dC . c
             const float diff = cd - S;
             float dL_dalpha = T * diff;
             S = __builtin_fmaf(alpha, diff, S);
             dL_dalpha = sG > cfg.alpha_max ? 0.f : dL_dalpha;  // capped alpha is a constant
             v[3] = G * dL_dalpha;                              // d/d sigma
-            const float gq = col.w * v[3];                     // d/d q = -1/2 sigma G dL/dalpha
+            const float gq = r2.y * v[3];                      // d/d q = -1/2 sigma G dL/dalpha
             const float gx = gq * dx, gy = gq * dy;
             v[4] = gx * dx;
             v[5] = gx * dy;
@@ -575,10 +582,10 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             // lanes 0..7 of a row hold the totals of values 0..7, lane 8 adds the ninth
             const int li = lane & 15;
             if (ABS) {
-                // |dq/dmu . g| per pixel: (2a dx + 2b dy, 2b dx + 2c dy) scaled by |g|  (co.y holds 2b)
+                // |dq/dmu . g| per pixel: (2a dx + 2b dy, 2b dx + 2c dy) scaled by |g|  (r0.w holds 2b)
                 const float ag = fabsf(gq);
-                const float ax = ag * fabsf(__builtin_fmaf(co.y, dy, 2.0f * co.x * dx));
-                const float ay = ag * fabsf(__builtin_fmaf(co.y, dx, 2.0f * co.z * dy));
+                const float ax = ag * fabsf(__builtin_fmaf(r0.w, dy, 2.0f * r0.z * dx));
+                const float ay = ag * fabsf(__builtin_fmaf(r0.w, dx, 2.0f * r1.x * dy));
                 const float r2 = row_reduce2(ax, ay, lane);
                 // lane 10 (even) holds the total of ax -> slot 9, lane 9 (odd) that of ay -> slot 10
                 // (a row none of whose pixels blends the Gaussian has zero totals: nothing to add)
@@ -594,7 +601,8 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             float a[NV];
 #pragma unroll
             for (int k = 0; k < NV; k++) a[k] = (float)s_acc[threadIdx.x][k];
-            const float4 co = s.co[threadIdx.x];  // co.y holds 2b
+            const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
+            const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
             float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
             rec[0] = make_float4(a[0], a[1], a[2], a[3]);
             // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
@@ -664,8 +672,7 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
     const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
     const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
 {
-    __shared__ Stage s;
-    __shared__ float4 s_rgb[BATCH];
+    __shared__ Stage<true> s;
     __shared__ uint32_t s_id[BATCH];
     constexpr int NV = ABS ? 11 : 9;
     __shared__ double s_acc[BATCH][NV];   // (double: the cheaper LDS atomic add on this chip, see k_render_bwd)
@@ -691,9 +698,7 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
     }
     float S_st = __builtin_fmaf(dC2, cfg.bg[2], __builtin_fmaf(dC1, cfg.bg[1], dC0 * cfg.bg[0]));
 
-    s.xy[threadIdx.x] = make_float2(0.f, 0.f);
-    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
-    s_rgb[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.clear(threadIdx.x);
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     atomicMax(&s_max, last);
@@ -709,7 +714,7 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
         __syncthreads();  // the previous batch's flush has read s_acc / s_id, its walk s_qlist
 #pragma unroll
         for (int k = 0; k < NV; k++) s_acc[threadIdx.x][k] = 0.0;
-        stage_batch<true, 2>(s, s_rgb, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
+        stage_batch<true, 2>(s, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         // the quadrant's list: lane l looks at slots 4 l .. 4 l + 3 of the union of its four sub-tiles' masks
         uint32_t b4 = 0;
         {
@@ -744,9 +749,10 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
                 const int idx = c_end - 1 - lane;
                 const bool have = idx >= 0;
                 const int j = have ? (int)s_qlist[wave][idx] : 0;
-                const float2 xy = s.xy[j];
-                const float4 co = s.co[j];
-                const float4 col = s_rgb[j];
+                const float4 f0 = s.at(j)[0], f1 = s.at(j)[1], f2 = s.at(j)[2];
+                const float2 xy = make_float2(f0.x, f0.y);
+                const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);    // (a, 2b, c, sigma)
+                const float4 col = make_float4(f1.z, f1.w, f2.x, 0.f);
                 const int pos_j = start + j;
                 float acc[NV];
 #pragma unroll
@@ -823,7 +829,8 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
             float a[NV];
 #pragma unroll
             for (int k = 0; k < NV; k++) a[k] = (float)s_acc[threadIdx.x][k];
-            const float4 co = s.co[threadIdx.x];  // co.y holds 2b
+            const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
+            const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
             float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
             rec[0] = make_float4(a[0], a[1], a[2], a[3]);
             rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
@@ -855,7 +862,7 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
                                                const uint32_t* __restrict__ n_contrib,
                                                const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
 {
-    __shared__ Stage s;
+    __shared__ Stage<false> s;
     __shared__ uint32_t s_id[BATCH];
     __shared__ int s_cnt[BATCH];
     __shared__ int s_max;
@@ -868,8 +875,7 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     const int sub = (threadIdx.x >> 6) * 4 + (lane >> 4);
     int last = 0;
     if (p.inside && mask[pix]) last = (int)n_contrib[pix];
-    s.xy[threadIdx.x] = make_float2(0.f, 0.f);  // unfilled slots must hold finite numbers
-    s.co[threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    s.clear(threadIdx.x);
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     atomicMax(&s_max, last);
@@ -910,14 +916,15 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
             const int m = min(BATCH, total - start);
             __syncthreads();  // the previous batch's flush has read s_cnt / s_id
             s_cnt[threadIdx.x] = 0;
-            stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
+            stage_batch<false, 1>(s, s_id, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
             if (wave_on) {
                 const int len = start < my_last ? s.len[my_sub] : 0;
                 // two list entries per trip: their alphas are independent, only the transmittance chains
                 for (int k = 0; __ballot(k < len) != 0; k += 2) {
                     const int j0 = s.list[my_sub][k & (BATCH - 1)], j1 = s.list[my_sub][(k + 1) & (BATCH - 1)];
-                    const float2 xy0 = s.xy[j0], xy1 = s.xy[j1];
-                    const float4 co0 = s.co[j0], co1 = s.co[j1];
+                    const float4 a0 = s.at(j0)[0], b0 = s.at(j0)[1], a1 = s.at(j1)[0], b1 = s.at(j1)[1];
+                    const float2 xy0 = make_float2(a0.x, a0.y), xy1 = make_float2(a1.x, a1.y);
+                    const float4 co0 = make_float4(a0.z, a0.w, b0.x, b0.y), co1 = make_float4(a1.z, a1.w, b1.x, b1.y);
                     const float dx0 = pw.px - xy0.x, dy0 = pw.py - xy0.y;
                     const float dx1 = pw.px - xy1.x, dy1 = pw.py - xy1.y;
                     const float q0 = __builtin_fmaf(dx0, __builtin_fmaf(co0.y, dy0, co0.x * dx0), (co0.z * dy0) * dy0);
@@ -950,7 +957,7 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
         const int m = min(BATCH, total - start);
         __syncthreads();  // the previous batch's flush has read s_cnt / s_id
         s_cnt[threadIdx.x] = 0;
-        const int mine = stage_batch<false, 1>(s, nullptr, s_id, cam, cfg, tile, gauss_sorted, splats,
+        const int mine = stage_batch<false, 1>(s, s_id, cam, cfg, tile, gauss_sorted, splats,
                                                range.x + start, m);
         // a row none of whose pixels is still walking (no mask pixel, or all past their last Gaussian)
         // has nothing to count in this batch
@@ -960,8 +967,9 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
             const int longest = wave_max_of_rows(row_walks ? mine : 0);
             for (int k = 0; k < longest; k++) {
                 const int j = s.list[sub][k];
-                const float2 xy = s.xy[j];
-                const float4 co = s.co[j];
+                const float4 a0 = s.at(j)[0], b0 = s.at(j)[1];
+                const float2 xy = make_float2(a0.x, a0.y);
+                const float4 co = make_float4(a0.z, a0.w, b0.x, b0.y);
                 const float dx = p.px - xy.x, dy = p.py - xy.y;
                 const float u = __builtin_fmaf(co.y, dy, co.x * dx);
                 const float q = __builtin_fmaf(dx, u, (co.z * dy) * dy);
