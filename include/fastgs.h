@@ -81,7 +81,7 @@ typedef struct {
                             (p-mu_2D)^T Sigma_2D^-1 (p-mu_2D) <= cb_beta * 2 ln(sigma / alpha_min)  (0)          */
     float cb_beta;       /* Compact Box threshold scale beta in (0, 1]; 1 keeps every pixel with alpha >= alpha_min (1) */
     int32_t sort_mode;   /* how fs_bin_sort orders the pairs; the result is the same either way.  FS_SORT_AUTO: per-tile
-                            segments sorted in LDS while no tile's list exceeds 8192 entries, else the global radix sort;
+                            segments sorted in LDS while no tile's list exceeds 16384 entries, else the global radix sort;
                             FS_SORT_RADIX: always the global stable LSD radix sort on tile << 32 | depth bits (0)   */
 } fs_config;
 
@@ -179,7 +179,7 @@ int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_p
 
 /* Steps a2-a5: one 64-bit key tile_id << 32 | bits(depth) per (Gaussian, tile) pair, the keys in ascending order
  * (ties by Gaussian index: the order a stable sort of index-ordered keys gives) and the per-tile ranges.
- * Default path (FS_SORT_AUTO, while no tile's list exceeds 8192 entries and the image has at most 15360
+ * Default path (FS_SORT_AUTO, while no tile's list exceeds 16384 entries and the image has at most 15360
  * tiles): the pairs are counted per tile, the ranges follow from an exclusive scan over the TILES, every pair is
  * placed into its tile's segment and each segment is sorted in LDS; no prefix sum over the Gaussians is made and
  * bins->pair_offsets is NULL.  Otherwise (FS_SORT_RADIX, or as the fall-back): exclusive scan of tiles_touched

@@ -392,7 +392,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
     if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
     const uint64_t max_len = bucketed ? ctx->total_host[3] : 0;
-    const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_MAX;
+    const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_HUGE;
     if (cb) FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(NR ? NR : 1) * PAIR_REC * sizeof(float), "pair gradients"));
 
     const int64_t nb = radix_num_blocks((int64_t)P);

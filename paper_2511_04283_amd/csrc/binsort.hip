@@ -605,7 +605,7 @@ __device__ __forceinline__ void tile_sort_strided(uint64_t* k, int N, int a, int
 // The sort proper, with G (8 or 16) words per register group; k holds N + 2 N / G words.  A stage's steps are
 // taken log2 G at a time, from the largest distance down: first the odd ones out (a smaller group), then groups
 // of G words ever closer together, last the contiguous groups with 16-byte LDS accesses.
-template <int G, int THREADS>
+template <int G, int THREADS, int CAP>
 __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_t tile, uint32_t first,
                                               const uint64_t* __restrict__ bucket, uint64_t* __restrict__ keys_out,
                                               uint32_t* __restrict__ vals_out)
@@ -615,8 +615,8 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
     auto at = [](int e) { return e + ((e >> LG) << 1); };   // word e of the sequence -> its place in k
     {
         // (all of a thread's loads are issued before the first LDS write: written as one loop, each load would be
-        // waited for in turn; a workgroup's capacity is at most 8 words per thread)
-        constexpr int PER = 8;
+        // waited for in turn)
+        constexpr int PER = (CAP + THREADS - 1) / THREADS;
         uint64_t w[PER];
 #pragma unroll
         for (int u = 0; u < PER; u++) {
@@ -686,8 +686,8 @@ __global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__
                                                    const uint64_t* __restrict__ bucket, int len_lo,
                                                    uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
 {
-    static_assert(CAP <= 8 * THREADS, "tile_sort_lds loads at most 8 words per thread");
-    __shared__ __align__(16) uint64_t k[CAP + CAP / 4];
+    // (groups of 8 words are padded by a quarter, groups of 16, which every list beyond 512 words uses, by an eighth)
+    __shared__ __align__(16) uint64_t k[CAP + CAP / (CAP > 8192 ? 8 : 4)];
     const uint32_t tile = tile_order[blockIdx.x];
     const uint2 r = ranges[tile];
     const int n = (int)(r.y - r.x);
@@ -697,9 +697,9 @@ __global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__
     // groups of 16 words make fewer passes over LDS but leave N / 16 threads busy in the register phases:
     // measured better from 1024 words on
     if (N <= TILE_SORT_GROUP16_FROM / 2)
-        tile_sort_lds<8, THREADS>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
+        tile_sort_lds<8, THREADS, CAP>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
     else
-        tile_sort_lds<16, THREADS>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
+        tile_sort_lds<16, THREADS, CAP>(k, N, n, tile, r.x, bucket, keys_out, vals_out);
 }
 
 // ---- radix sort -------------------------------------------------------------------------
@@ -939,6 +939,9 @@ hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projecte
     }
     if (P > 0) {
         // the long lists first: few workgroups, each a long chain of steps, which 1024 threads shorten
+        if (max_len > TILE_SORT_MAX)
+            hipLaunchKernelGGL((k_tile_sort<TILE_SORT_HUGE, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
+                               bucket, TILE_SORT_MAX, keys_out, vals_out);
         if (max_len > TILE_SORT_SMALL)
             hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MAX, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
                                bucket, TILE_SORT_SMALL, keys_out, vals_out);

@@ -165,7 +165,7 @@ hipError_t launch_emit_pairs_cb(hipStream_t st, int64_t n, const fs_projected& p
                                 const uint32_t* offsets, const uint32_t* rec_offsets, int tiles_x, int64_t P,
                                 uint64_t* keys, uint32_t* vals, float* splats, float* pair_grad);
 
-// Tile-bucketed ordering (used when no tile's list is longer than TILE_SORT_MAX; otherwise the global
+// Tile-bucketed ordering (used when no tile's list is longer than TILE_SORT_HUGE; otherwise the global
 // radix sort below): per-tile counts and ranges, then placement into the tiles' segments and an LDS sort
 // of every segment.  ranges/tile_order/tile_total: [num_tiles]; tile_count: [TILE_COPIES, num_tiles], turned by
 // launch_tile_count into each copy's start within its tile (the `cursor` of launch_tile_scatter_sort).
@@ -178,7 +178,9 @@ constexpr int TILE_PAIR_THREADS = 1024;
 constexpr int TILE_LDS_MAX_TILES = 15360;  // their per-tile counters live in LDS (60 KB)
 constexpr int TILE_SORT_GROUP16_FROM = 1024;  // padded list length from which a thread merges 16 words in registers, not 8
 constexpr int TILE_SORT_SMALL = 2048;  // longest list one workgroup sorts with 16 KB of LDS
-constexpr int TILE_SORT_MAX = 8192;    // ... with 64 KB
+constexpr int TILE_SORT_MAX = 8192;    // ... with 80 KB
+constexpr int TILE_SORT_HUGE = 16384;  // ... with 144 KB (a compute unit of this chip has 160 KB): the longest list of the
+                                       // per-tile ordering; anything longer takes the radix path
 hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
                              int num_tiles, uint32_t* tile_count, uint32_t* tile_total, uint2* ranges,
                              uint32_t* tile_order, uint64_t* totals, uint32_t* rec_offsets, uint32_t* rec_counts,

@@ -200,7 +200,8 @@ def test_error_codes(ctx):
     (3000, 203, 117, 0, 0, 2048),          # per-tile LDS sort, 16 KB variant
     (40000, 70, 50, 0, 2049, 8192),        # lists that need the 64 KB variant
     (40000, 70, 50, 1, 2049, 8192),
-    (90000, 40, 33, 0, 8193, 10 ** 9),     # lists beyond LDS: automatic fall-back to the radix sort
+    (45000, 40, 33, 0, 8193, 16384),       # a list that needs the 144 KB variant
+    (90000, 40, 33, 0, 16385, 10 ** 9),    # lists beyond LDS: automatic fall-back to the radix sort
 ])
 def test_pair_order_is_the_same_whichever_way_it_is_computed(orc32, n, W, H, mode, lo, hi):
     """Keys, order and ranges bit-exact for both orderings of fs_bin_sort, at list lengths that reach
@@ -221,7 +222,7 @@ def test_pair_order_is_the_same_whichever_way_it_is_computed(orc32, n, W, H, mod
     assert np.array_equal(g["keys_sorted"], b_o.keys_sorted)
     assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted)
     assert np.array_equal(g["tile_ranges"], b_o.tile_ranges)
-    if n <= 40000:
+    if n <= 45000:
         img, fT, nc = orc32.render_fwd_mt(p_o, b_o, cam, threads=8)
         assert np.array_equal(g["n_contrib"], nc)
         assert_image_close(g["image"], img)
