@@ -186,7 +186,9 @@ int fs_preprocess(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, fs_p
  * (bins->pair_offsets), keys emitted in index order, a global stable LSD radix sort, ranges from the sorted keys.
  * Both give bit-identical keys, order and ranges.  n = number of Gaussians in `proj`.  Also packs the projected
  * splats into bins->splats and gives every pair the place of its backward record (bins->record_offsets); later
- * calls that take `bins` must be given the same `proj`.  Reads 32 bytes back (synchronises the stream).
+ * calls that take `bins` must be given the same `proj`.  Reads 32 bytes back (the host waits for the counting
+ * kernels, not for the whole stream: from a context's second per-tile ordering on, placement and sorts are enqueued
+ * ahead of that wait, bounded by what the context's buffers hold, and repeated if the totals say they did not fit).
  * Errors: FS_EINVAL, FS_ENOMEM, FS_EHIP, FS_ECAPACITY (n, P or the candidate tile count >= 2^31). */
 int fs_bin_sort(fs_ctx *ctx, const fs_projected *proj, const fs_camera *cam, int64_t n, fs_bins *out);
 

@@ -43,6 +43,9 @@ struct fs_ctx {
     ScratchBuf sel_vals[2];   // uint32 [m] candidate indices, ping-pong
     ScratchBuf sel_hist;      // uint32 radix histograms of that sort
     uint64_t generation = 0;  // bumped by every fs_bin_sort; fs_bins of an earlier one are refused
+    hipEvent_t totals_event = nullptr;   // recorded behind the read-back of fs_bin_sort's totals
+    int64_t spec_max_len = 0;            // longest list of the previous per-tile ordering on this ctx (0: none): what
+                                         // fs_bin_sort enqueues ahead of its read-back is chosen by it
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
@@ -260,6 +263,12 @@ int fs_create(fs_ctx** out, int device, void* hip_stream, const fs_config* cfg)
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->cfg = c;
     ctx->err[0] = 0;
+    if (hipEventCreateWithFlags(&ctx->totals_event, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->totals_event = nullptr;
+        fs_destroy(ctx);
+        return FS_EHIP;
+    }
     if (noalloc_setup(device) != hipSuccess) {
         (void)hipGetLastError();
         fs_destroy(ctx);
@@ -292,6 +301,7 @@ void fs_destroy(fs_ctx* ctx)
     if (ctx->total_dev) (void)hipFree(ctx->total_dev);
     if (ctx->alloc_dev) (void)hipFree(ctx->alloc_dev);
     if (ctx->total_host) (void)hipHostFree(ctx->total_host);
+    if (ctx->totals_event) (void)hipEventDestroy(ctx->totals_event);
     for (auto& v : ctx->prof_pending)
         for (auto& pr : v) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     for (hipEvent_t e : ctx->prof_free) (void)hipEventDestroy(e);
@@ -383,16 +393,51 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     }
     FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
            "hipMemcpyAsync");
-    FS_HIP(hipStreamSynchronize(st), "hipStreamSynchronize");
+    FS_HIP(hipEventRecord(ctx->totals_event, st), "hipEventRecord");
+    // Per-tile ordering, second half (placement into the tiles' segments -- keys[1] serves as the bucket array -- and
+    // the per-tile LDS sorts; the ranges are already in place).  When this ctx has ordered pairs per tile before, the
+    // second half is enqueued right here, ahead of the host's wait for the totals, sized by what the buffers hold and by
+    // the previous call's longest list: otherwise the GPU idles for the whole round trip (wait, wake-up, launch) once per
+    // call.  The kernels write nothing beyond the capacities they are given; what the totals then say was not covered
+    // (a longer list's sort variant, or buffers that have to grow first) is enqueued afterwards.
+    const uint32_t* recs_p = cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr) : static_cast<const uint32_t*>(ctx->offsets.ptr);
+    fs_projected none = {};
+    uint64_t cap_pairs = 0, cap_recs = 0;
+    int spec_variants = 0;
+    if (bucketed && ctx->spec_max_len > 0 && n > 0) {
+        cap_pairs = ctx->keys[0].cap / sizeof(uint64_t);
+        if (ctx->keys[1].cap / sizeof(uint64_t) < cap_pairs) cap_pairs = ctx->keys[1].cap / sizeof(uint64_t);
+        if (ctx->vals[0].cap / sizeof(uint32_t) < cap_pairs) cap_pairs = ctx->vals[0].cap / sizeof(uint32_t);
+        if (cap_pairs > 0x7fffffffull) cap_pairs = 0x7fffffffull;
+        cap_recs = cb ? ctx->pair_grad.cap / (PAIR_REC * sizeof(float)) : 0;
+        if (cap_recs > 0x7fffffffull) cap_recs = 0x7fffffffull;
+        if (cap_pairs > 0 && (!cb || cap_recs > 0)) {
+            ProfScope prof(ctx, FS_K_ORDER);
+            spec_variants = tile_sort_variants(ctx->spec_max_len);
+            FS_HIP(launch_tile_scatter(st, n, proj ? *proj : none, cf, recs_p, cd.tiles_x, tiles, (uint32_t)cap_pairs,
+                                       (uint32_t)cap_recs, reinterpret_cast<const uint2*>(ranges_p), tcount_p,
+                                       static_cast<uint64_t*>(ctx->keys[1].ptr), static_cast<float*>(ctx->splats.ptr),
+                                       static_cast<float*>(ctx->pair_grad.ptr)),
+                   "k_tile_pairs (placement)");
+            FS_HIP(launch_tile_sorts(st, tiles, spec_variants, (uint32_t)cap_pairs, reinterpret_cast<const uint2*>(ranges_p),
+                                     order_p, static_cast<const uint64_t*>(ctx->keys[1].ptr),
+                                     static_cast<uint64_t*>(ctx->keys[0].ptr), static_cast<uint32_t*>(ctx->vals[0].ptr)),
+                   "k_tile_sort");
+        }
+    }
+    FS_HIP(hipEventSynchronize(ctx->totals_event), "hipEventSynchronize");
     // bucketed: {sum of tiles_touched, records, pairs counted per tile, longest list}; else {pairs, records (CB)}
     const uint64_t P = bucketed ? ctx->total_host[2] : ctx->total_host[0];
     const uint64_t NR = cb || bucketed ? ctx->total_host[1] : P;
+    ctx->spec_max_len = 0;
     if (bucketed && (ctx->total_host[0] != P || (!cb && NR != P)))
         return fail(ctx, FS_EINVAL, "fs_bin_sort: tiles_touched does not match rect (proj from another configuration?)");
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
     if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
     const uint64_t max_len = bucketed ? ctx->total_host[3] : 0;
     const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_HUGE;
+    // did what was enqueued ahead cover this call?  (growing a buffer below waits for the stream first)
+    const bool spec_fits = spec_variants != 0 && P <= cap_pairs && (!cb || NR <= cap_recs);
     if (cb) FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(NR ? NR : 1) * PAIR_REC * sizeof(float), "pair gradients"));
 
     const int64_t nb = radix_num_blocks((int64_t)P);
@@ -407,17 +452,20 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};
     int res = 0;
     if (lds_sort) {
-        // second half: placement into the tiles' segments (keys[1] serves as the bucket array) and the
-        // per-tile LDS sort; ranges are already in place
         ProfScope prof(ctx, FS_K_ORDER);
-        fs_projected none = {};
-        FS_HIP(launch_tile_scatter_sort(st, n, proj ? *proj : none, cf,
-                                        cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr)
-                                           : static_cast<const uint32_t*>(ctx->offsets.ptr),
-                                        cd.tiles_x, tiles, (int64_t)P, (int)max_len, reinterpret_cast<const uint2*>(ranges_p),
-                                        tcount_p, order_p, keys[1], keys[0], vals[0], static_cast<float*>(ctx->splats.ptr),
-                                        static_cast<float*>(ctx->pair_grad.ptr)),
-               "tile-bucketed ordering");
+        int variants = P > 0 ? tile_sort_variants((int64_t)max_len) : 0;
+        if (spec_fits) {
+            variants &= ~spec_variants;   // placement and these sorts have run (or are running) already
+        } else {
+            FS_HIP(launch_tile_scatter(st, n, proj ? *proj : none, cf, recs_p, cd.tiles_x, tiles, (uint32_t)P, (uint32_t)NR,
+                                       reinterpret_cast<const uint2*>(ranges_p), tcount_p, keys[1],
+                                       static_cast<float*>(ctx->splats.ptr), static_cast<float*>(ctx->pair_grad.ptr)),
+                   "k_tile_pairs (placement)");
+        }
+        FS_HIP(launch_tile_sorts(st, tiles, variants, (uint32_t)P, reinterpret_cast<const uint2*>(ranges_p), order_p, keys[1],
+                                 keys[0], vals[0]),
+               "k_tile_sort");
+        ctx->spec_max_len = max_len > 0 ? (int64_t)max_len : 1;
     } else {
         // (lists too long for the per-tile sort: the radix path's prefix sums have not been made yet)
         if (bucketed) FS_TRY(prefix_sums());

@@ -306,7 +306,9 @@ __global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4*
 // does.  SCATTER = false: count[tile] += 1 per pair.  SCATTER = true: slot = first[tile] + counter[tile]++
 // (k_tile_sum has turned each copy's counter into that copy's start within the tile's segment),
 // bucket[slot] = depth_bits << 32 | index; also packs the splat records and, with
-// the Compact Box, zeroes the gradient records of the candidates that are no pairs.
+// the Compact Box, zeroes the gradient records of the candidates that are no pairs.  In this mode `P` and `rec_limit`
+// are the numbers of words / records the buffers hold: nothing is written at or beyond them (the kernel may be
+// enqueued before the host has seen the real totals).
 //
 // Step (1) also hands every Gaussian the place of its backward records (one per tile of its rectangle): a
 // workgroup first adds up the records of all its Gaussians and reserves them with one add on a global counter
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
                                                     const float* __restrict__ rgb, CfgDev cfg,
                                                     const uint32_t* __restrict__ rec_offsets, int tiles_x,
                                                     int num_tiles, uint32_t* __restrict__ tile_counter,
-                                                    const uint2* __restrict__ ranges, uint32_t P,
+                                                    const uint2* __restrict__ ranges, uint32_t P, uint32_t rec_limit,
                                                     uint64_t* __restrict__ bucket, float4* __restrict__ splats,
                                                     float4* __restrict__ pair_grad, RecAlloc ra)
 {
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
                 if (hit) {
                     const uint32_t slot = atomicAdd(&s_tile[tile], 1u);
                     if (slot < P) bucket[slot] = ((uint64_t)od << 32) | (uint32_t)(i - lane + s);
-                } else if (CB && live) {
+                } else if (CB && live && (uint64_t)oroff + k < rec_limit) {
                     float4* g = pair_grad + ((size_t)oroff + k) * (PAIR_REC / 4);
                     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
                     g[0] = z; g[1] = z; g[2] = z;
@@ -683,7 +685,7 @@ __device__ __forceinline__ void tile_sort_lds(uint64_t* k, int N, int n, uint32_
 template <int CAP, int THREADS>
 __global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__ ranges,
                                                    const uint32_t* __restrict__ tile_order,
-                                                   const uint64_t* __restrict__ bucket, int len_lo,
+                                                   const uint64_t* __restrict__ bucket, int len_lo, uint32_t limit,
                                                    uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
 {
     // (groups of 8 words are padded by a quarter, groups of 16, which every list beyond 512 words uses, by an eighth)
@@ -691,7 +693,8 @@ __global__ __launch_bounds__(THREADS) void k_tile_sort(const uint2* __restrict__
     const uint32_t tile = tile_order[blockIdx.x];
     const uint2 r = ranges[tile];
     const int n = (int)(r.y - r.x);
-    if (n <= len_lo || n > CAP) return;   // (uniform over the workgroup)
+    // (uniform over the workgroup; `limit` = the words the buffers hold: a segment that reaches beyond it is left alone)
+    if (n <= len_lo || n > CAP || r.y > limit) return;
     int N = 16;
     while (N < n) N <<= 1;
     // groups of 16 words make fewer passes over LDS but leave N / 16 threads busy in the register phases:
@@ -905,10 +908,10 @@ hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj
         const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
         if (cfg.compact_box)
             hipLaunchKernelGGL((k_tile_pairs<true, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
-                               nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr, ra);
+                               nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, 0u, nullptr, nullptr, nullptr, ra);
         else
             hipLaunchKernelGGL((k_tile_pairs<false, false>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb,
-                               cfg, nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, nullptr, nullptr, nullptr, ra);
+                               cfg, nullptr, tiles_x, num_tiles, tile_count, nullptr, 0u, 0u, nullptr, nullptr, nullptr, ra);
     }
     hipLaunchKernelGGL(k_tile_sum, dim3((unsigned)((num_tiles + 63) / 64)), dim3(64 * (TILE_COPIES / 64)), 0, st, tile_count,
                        num_tiles, tile_total);
@@ -917,37 +920,47 @@ hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj
     return hipGetLastError();
 }
 
-hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
-                                    const uint32_t* rec_offsets, int tiles_x, int num_tiles, int64_t P, int max_len,
-                                    const uint2* ranges, uint32_t* cursor, const uint32_t* tile_order, uint64_t* bucket,
-                                    uint64_t* keys_out, uint32_t* vals_out, float* splats, float* pair_grad)
+hipError_t launch_tile_scatter(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
+                               const uint32_t* rec_offsets, int tiles_x, int num_tiles, uint32_t pair_limit,
+                               uint32_t rec_limit, const uint2* ranges, uint32_t* cursor, uint64_t* bucket, float* splats,
+                               float* pair_grad)
 {
-    if (n > 0) {
-        const dim3 grid(TILE_COPIES), block(TILE_PAIR_THREADS);
-        const size_t lds = (size_t)num_tiles * sizeof(uint32_t);
-        const ushort4* rect = reinterpret_cast<const ushort4*>(proj.rect);
-        const float2* m2 = reinterpret_cast<const float2*>(proj.mean2d);
-        const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
-        if (cfg.compact_box)
-            hipLaunchKernelGGL((k_tile_pairs<true, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
-                               rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
-                               reinterpret_cast<float4*>(pair_grad), RecAlloc{});
-        else
-            hipLaunchKernelGGL((k_tile_pairs<false, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
-                               rec_offsets, tiles_x, num_tiles, cursor, ranges, (uint32_t)P, bucket, reinterpret_cast<float4*>(splats),
-                               reinterpret_cast<float4*>(pair_grad), RecAlloc{});
-    }
-    if (P > 0) {
-        // the long lists first: few workgroups, each a long chain of steps, which 1024 threads shorten
-        if (max_len > TILE_SORT_MAX)
-            hipLaunchKernelGGL((k_tile_sort<TILE_SORT_HUGE, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
-                               bucket, TILE_SORT_MAX, keys_out, vals_out);
-        if (max_len > TILE_SORT_SMALL)
-            hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MAX, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
-                               bucket, TILE_SORT_SMALL, keys_out, vals_out);
+    if (n <= 0) return hipSuccess;
+    const dim3 grid(TILE_COPIES), block(TILE_PAIR_THREADS);
+    const size_t lds = (size_t)num_tiles * sizeof(uint32_t);
+    const ushort4* rect = reinterpret_cast<const ushort4*>(proj.rect);
+    const float2* m2 = reinterpret_cast<const float2*>(proj.mean2d);
+    const float4* co = reinterpret_cast<const float4*>(proj.conic_opacity);
+    if (cfg.compact_box)
+        hipLaunchKernelGGL((k_tile_pairs<true, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
+                           rec_offsets, tiles_x, num_tiles, cursor, ranges, pair_limit, rec_limit, bucket,
+                           reinterpret_cast<float4*>(splats), reinterpret_cast<float4*>(pair_grad), RecAlloc{});
+    else
+        hipLaunchKernelGGL((k_tile_pairs<false, true>), grid, block, lds, st, n, rect, proj.depth, m2, co, proj.rgb, cfg,
+                           rec_offsets, tiles_x, num_tiles, cursor, ranges, pair_limit, rec_limit, bucket,
+                           reinterpret_cast<float4*>(splats), reinterpret_cast<float4*>(pair_grad), RecAlloc{});
+    return hipGetLastError();
+}
+
+int tile_sort_variants(int64_t max_len)
+{
+    return 1 | (max_len > TILE_SORT_SMALL ? 2 : 0) | (max_len > TILE_SORT_MAX ? 4 : 0);
+}
+
+hipError_t launch_tile_sorts(hipStream_t st, int num_tiles, int variants, uint32_t pair_limit, const uint2* ranges,
+                             const uint32_t* tile_order, const uint64_t* bucket, uint64_t* keys_out, uint32_t* vals_out)
+{
+    if (num_tiles <= 0) return hipSuccess;
+    // the long lists first: few workgroups, each a long chain of steps, which 1024 threads shorten
+    if (variants & 4)
+        hipLaunchKernelGGL((k_tile_sort<TILE_SORT_HUGE, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
+                           bucket, TILE_SORT_MAX, pair_limit, keys_out, vals_out);
+    if (variants & 2)
+        hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MAX, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
+                           bucket, TILE_SORT_SMALL, pair_limit, keys_out, vals_out);
+    if (variants & 1)
         hipLaunchKernelGGL((k_tile_sort<TILE_SORT_SMALL, 256>), dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket,
-                           0, keys_out, vals_out);
-    }
+                           0, pair_limit, keys_out, vals_out);
     return hipGetLastError();
 }
 

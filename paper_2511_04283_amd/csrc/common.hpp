@@ -185,10 +185,17 @@ hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj
                              int num_tiles, uint32_t* tile_count, uint32_t* tile_total, uint2* ranges,
                              uint32_t* tile_order, uint64_t* totals, uint32_t* rec_offsets, uint32_t* rec_counts,
                              uint64_t* counters);
-hipError_t launch_tile_scatter_sort(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
-                                    const uint32_t* rec_offsets, int tiles_x, int num_tiles, int64_t P, int max_len,
-                                    const uint2* ranges, uint32_t* cursor, const uint32_t* tile_order, uint64_t* bucket,
-                                    uint64_t* keys_out, uint32_t* vals_out, float* splats, float* pair_grad);
+// Placement and the per-tile sorts.  pair_limit / rec_limit: how many words / gradient records the buffers hold; the
+// kernels write nothing at or beyond them and leave alone a segment that reaches beyond pair_limit, so they may be
+// enqueued before the host knows the totals.  variants: bit 0 lists of up to TILE_SORT_SMALL entries, bit 1 up to
+// TILE_SORT_MAX, bit 2 up to TILE_SORT_HUGE (tile_sort_variants(longest list) = the ones a longest list needs).
+hipError_t launch_tile_scatter(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
+                               const uint32_t* rec_offsets, int tiles_x, int num_tiles, uint32_t pair_limit,
+                               uint32_t rec_limit, const uint2* ranges, uint32_t* cursor, uint64_t* bucket, float* splats,
+                               float* pair_grad);
+int tile_sort_variants(int64_t max_len);
+hipError_t launch_tile_sorts(hipStream_t st, int num_tiles, int variants, uint32_t pair_limit, const uint2* ranges,
+                             const uint32_t* tile_order, const uint64_t* bucket, uint64_t* keys_out, uint32_t* vals_out);
 
 constexpr int RADIX_BLOCK_KEYS = 2048;  // keys ranked by one workgroup per pass
 constexpr int RADIX_BITS = 9;            // widest digit

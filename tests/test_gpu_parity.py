@@ -273,8 +273,12 @@ def test_tile_order_is_a_permutation_with_the_longest_lists_first(n, W, H, mode)
 def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_box):
     """A context keeps its scratch buffers from call to call and grows them when a call needs more. One
     context therefore goes through: a first call, a much larger scene (buffers grow), smaller ones (buffers
-    larger than needed), long lists after short ones and short after long (the two LDS sort variants), a
-    scene without pairs, and another tile grid. Keys, order, ranges and n_contrib bit-exact every time."""
+    larger than needed), long lists after short ones and short after long (the LDS sort variants), lists beyond
+    LDS (the radix path) between per-tile orderings, a scene without pairs, and another tile grid. From its second
+    per-tile ordering on, fs_bin_sort enqueues placement and sorts before it has read the totals back, sized by the
+    previous call: every transition above is one where that guess is right, too small, or too large. Keys, order,
+    ranges and n_contrib bit-exact every time; on the small scenes the gradients as well (with the Compact Box the
+    placement also zeroes the records of the candidates that are no pairs)."""
     from paper_2511_04283_amd import binding as B
     cfg = B.default_config()
     cfg.compact_box = compact_box
@@ -288,8 +292,13 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
              (704, 40000, 70, 50, (-3.2, 0.7)),     # ... and again
              (705, 1500, 70, 50, (-3.2, 0.7)),      # short after long
              (706, 0, 70, 50, (-3.2, 0.7)),         # nothing to order
-             (707, 5000, 333, 219, (-3.0, 0.6))]    # another tile grid
-    seen_long = False
+             (707, 5000, 333, 219, (-3.0, 0.6)),    # another tile grid
+             (708, 45000, 40, 33, (-3.2, 0.7)),     # a list beyond 8192 after short ones
+             (709, 2500, 40, 33, (-3.2, 0.7)),      # short after that
+             (710, 90000, 40, 33, (-3.2, 0.7)),     # lists beyond LDS: the radix path, whatever was enqueued ahead
+             (711, 2500, 40, 33, (-3.2, 0.7)),      # per-tile again after the radix path
+             (712, 2600, 40, 33, (-3.2, 0.7))]
+    seen_long = seen_huge = seen_radix = False
     for seed, n, W, H, ls in cases:
         if n == 0:
             cam = scenes.Camera(W, H, 60.0, 60.0, W / 2.0, H / 2.0)
@@ -298,12 +307,15 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
         else:
             sc = scenes.tiny_scene(seed, n, W, H, sh_degree=0, log_scale=ls, spread=1.1)
             cam = sc.cameras[0]
-        g = gpu_pipeline(c, sc, cam)
+        small = 0 < n <= 9000
+        dL = np.random.default_rng(seed).standard_normal((3, H, W)).astype(np.float32) if small else None
+        g = gpu_pipeline(c, sc, cam, dL=dL)
         p_o = o.preprocess(sc, cam)
         b_o = o.bin_sort(p_o, cam)
         L = b_o.tile_ranges[:, 1].astype(np.int64) - b_o.tile_ranges[:, 0]
         seen_long |= bool(L.max() > 2048)
-        assert L.max() <= 8192
+        seen_huge |= bool(8192 < L.max() <= 16384)
+        seen_radix |= bool(L.max() > 16384)
         assert g["num_pairs"] == b_o.num_pairs, (seed, n)
         assert np.array_equal(g["keys_sorted"], b_o.keys_sorted), (seed, n)
         assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted), (seed, n)
@@ -312,7 +324,9 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
             img, fT, nc = o.render_fwd_mt(p_o, b_o, cam, threads=8)
             assert np.array_equal(g["n_contrib"], nc), (seed, n)
             assert_image_close(g["image"], img)
-    assert seen_long
+        if small:
+            assert_grads_close(g["grads"], o.backward(sc, cam, p_o, b_o, dL))
+    assert seen_long and seen_huge and seen_radix
     c.close()
 
 
