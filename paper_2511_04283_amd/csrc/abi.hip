@@ -452,19 +452,20 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};
     int res = 0;
     if (lds_sort) {
-        ProfScope prof(ctx, FS_K_ORDER);
         int variants = P > 0 ? tile_sort_variants((int64_t)max_len) : 0;
-        if (spec_fits) {
-            variants &= ~spec_variants;   // placement and these sorts have run (or are running) already
-        } else {
-            FS_HIP(launch_tile_scatter(st, n, proj ? *proj : none, cf, recs_p, cd.tiles_x, tiles, (uint32_t)P, (uint32_t)NR,
-                                       reinterpret_cast<const uint2*>(ranges_p), tcount_p, keys[1],
-                                       static_cast<float*>(ctx->splats.ptr), static_cast<float*>(ctx->pair_grad.ptr)),
-                   "k_tile_pairs (placement)");
+        if (spec_fits) variants &= ~spec_variants;   // placement and these sorts have run (or are running) already
+        if (!spec_fits || variants) {
+            ProfScope prof(ctx, FS_K_ORDER);
+            if (!spec_fits) {
+                FS_HIP(launch_tile_scatter(st, n, proj ? *proj : none, cf, recs_p, cd.tiles_x, tiles, (uint32_t)P,
+                                           (uint32_t)NR, reinterpret_cast<const uint2*>(ranges_p), tcount_p, keys[1],
+                                           static_cast<float*>(ctx->splats.ptr), static_cast<float*>(ctx->pair_grad.ptr)),
+                       "k_tile_pairs (placement)");
+            }
+            FS_HIP(launch_tile_sorts(st, tiles, variants, (uint32_t)P, reinterpret_cast<const uint2*>(ranges_p), order_p,
+                                     keys[1], keys[0], vals[0]),
+                   "k_tile_sort");
         }
-        FS_HIP(launch_tile_sorts(st, tiles, variants, (uint32_t)P, reinterpret_cast<const uint2*>(ranges_p), order_p, keys[1],
-                                 keys[0], vals[0]),
-               "k_tile_sort");
         ctx->spec_max_len = max_len > 0 ? (int64_t)max_len : 1;
     } else {
         // (lists too long for the per-tile sort: the radix path's prefix sums have not been made yet)
@@ -721,7 +722,7 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (ctx->bits_pairs == bins->num_pairs && ctx->bits_order == bins->gauss_sorted &&
         ctx->bits_tiles == cd.tiles_x * cd.tiles_y) {
         // the latest forward pass over these bins recorded where each pair is counted: no second walk
-        FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, bins->gauss_sorted, ctx->pair_bits.ptr, mask, counts),
+        FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, bins->tile_order, bins->gauss_sorted, ctx->pair_bits.ptr, mask, counts),
                "k_score_bits");
         return FS_OK;
     }

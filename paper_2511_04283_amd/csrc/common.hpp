@@ -224,8 +224,9 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
                                    float* err, double* tile_partial, void* pair_bits);
 // the count pass from those bits: counts[g] += |bits(pair) & mask(tile)| over the pairs of every tile
-hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* gauss_sorted,
-                             const void* pair_bits, const uint8_t* mask, int32_t* counts);
+// (tiles are taken in tile_order)
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
+                             const uint32_t* gauss_sorted, const void* pair_bits, const uint8_t* mask, int32_t* counts);
 // stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,

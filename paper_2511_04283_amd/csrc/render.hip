@@ -994,12 +994,13 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 // layout as a pair's bits, then one population count per pair of the tile's list.  Tiles without mask pixels
 // read nothing else.
 __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges,
+                                                    const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
                                                     const uint4* __restrict__ pair_bits,
                                                     const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
 {
     __shared__ __align__(16) uint16_t s_m[16];
-    const int tile = (int)blockIdx.x;
+    const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const Pixel p = pixel_of_thread(cam, tile);
     const int lane = threadIdx.x & 63;
     const uint2 range = ranges[tile];
@@ -1077,12 +1078,12 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
     return hipGetLastError();
 }
 
-hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* gauss_sorted,
-                             const void* pair_bits, const uint8_t* mask, int32_t* counts)
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
+                             const uint32_t* gauss_sorted, const void* pair_bits, const uint8_t* mask, int32_t* counts)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_score_bits, dim3(tiles), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges), gauss_sorted,
+    hipLaunchKernelGGL(k_score_bits, dim3(tiles), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                        static_cast<const uint4*>(pair_bits), mask, counts);
     return hipGetLastError();
 }
