@@ -35,10 +35,12 @@
  *     by the caller unless marked "ctx-owned"; structs themselves live in host memory.
  *   - Arrays are dense, row-major, 4-byte aligned (16-byte for [n,4] float arrays); fp32 unless
  *     stated.  Nothing is freed or reallocated on the caller's behalf.
- *   - Work is enqueued on the stream given to fs_create.  fs_bin_sort reads 32 bytes back (the
- *     pair count and what it needs to choose its path), fs_compact 8 bytes (the count), and
- *     fs_measure_peaks / fs_profile_read wait for their measurements: these synchronise that
- *     stream; all other calls return as soon as the work is enqueued.
+ *   - Work is enqueued on the stream given to fs_create, and a call may return with its work still in
+ *     flight there: the arrays it was given must stay valid, and must only be touched by work ordered
+ *     after it on that stream, until then.  fs_compact reads 8 bytes back (the count), fs_sample_by_score
+ *     8, and fs_measure_peaks / fs_profile_read wait for their measurements: these synchronise the
+ *     stream.  fs_bin_sort reads 32 bytes back (the pair count and what it needs to choose its path) and
+ *     waits for the kernels that make them, but may return with its last kernels still running.
  *   - Every call returns FS_OK (0) or a negative fs_status and never throws or aborts;
  *     fs_last_error gives a message for the last failure on that ctx.
  *   - n = 0 Gaussians and P = 0 pairs are valid (the image is the background).

@@ -18,14 +18,33 @@ constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_ITEMS;  // 2048 values per workgr
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
-// Inclusive scan across the 64 lanes of a wavefront (log-step shuffles).
+// Inclusive scan across the 64 lanes of a wavefront with data-parallel-primitive moves instead of shuffles through
+// LDS: four shifts within the rows of 16 lanes (zeros move in at a row's start), then lane 15 of rows 0 and 2 is
+// added to every lane of the row after it, then lane 31 to every lane of rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(v, d, 64);
-        if ((int)lane_id() >= d) v += o;
-    }
+    v += dpp_or_zero<0x111, 0xF>(v);   // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);   // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);   // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);   // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+// The same with max (on unsigned values, for which zero is the neutral element).
+__device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v)
+{
+    v = max(v, dpp_or_zero<0x111, 0xF>(v));
+    v = max(v, dpp_or_zero<0x112, 0xF>(v));
+    v = max(v, dpp_or_zero<0x114, 0xF>(v));
+    v = max(v, dpp_or_zero<0x118, 0xF>(v));
+    v = max(v, dpp_or_zero<0x142, 0xA>(v));
+    v = max(v, dpp_or_zero<0x143, 0xC>(v));
     return v;
 }
 
@@ -172,9 +191,11 @@ __global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __
         const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
         const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
         const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
-        uint32_t row = (uint32_t)((float)k / (float)ow);    // estimate, corrected below (exact for any k)
-        while (row * ow > k) row--;
-        while ((row + 1) * ow <= k) row++;
+        // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
+        // either way, never a loop that bad operands could keep a wavefront in
+        uint32_t row = (uint32_t)((float)k / (float)ow);
+        row -= row * ow > k ? 1u : 0u;
+        row += (row + 1) * ow <= k ? 1u : 0u;
         const uint32_t col = k - row * ow;
         const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
         if (j0 + lane < total) {
@@ -258,9 +279,11 @@ __global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4*
         const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
         const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
         const float oQ = __shfl(Q, (int)s, 64);
+        // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
+        // either way, never a loop that bad operands could keep a wavefront in
         uint32_t row = (uint32_t)((float)k / (float)ow);
-        while (row * ow > k) row--;
-        while ((row + 1) * ow <= k) row++;
+        row -= row * ow > k ? 1u : 0u;
+        row += (row + 1) * ow <= k ? 1u : 0u;
         const uint32_t col = k - row * ow;
         const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
         const bool hit = live && cb_tile_hit(omx, omy, oA, oB, oC, oQ, (int)tx, (int)ty);
@@ -342,6 +365,8 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
     for (int t = threadIdx.x; t < num_tiles; t += TILE_PAIR_THREADS) s_tile[t] = SCATTER ? ranges[t].x + my_row[t] : 0u;
     __syncthreads();
     const uint32_t lane = lane_id();
+    __shared__ uint32_t s_mark[TILE_PAIR_THREADS / 64][64];
+    uint32_t* const mark = s_mark[threadIdx.x >> 6];   // this wavefront's own
     uint32_t rec_next = 0;   // (counting) where the records of this wavefront's next round start
     if (!SCATTER) {
         __shared__ uint32_t s_wave_recs[TILE_PAIR_THREADS / 64];
@@ -398,7 +423,7 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
         }
         const uint32_t inc = wave_inclusive_scan(cnt);
         const uint32_t excl = inc - cnt;
-        const uint32_t total = (uint32_t)__shfl((int)inc, 63, 64);
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
         const uint32_t rect_xy = (uint32_t)r.x | (uint32_t)r.y << 16;
         if (!SCATTER) {
             if (valid) {
@@ -407,22 +432,35 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
             }
             rec_next += total;
         }
+        uint32_t carry = 0;   // 1 + the lane whose rectangle holds candidate j0 - 1 (uniform)
         for (uint32_t j0 = 0; j0 < total; j0 += 64) {
             const bool live = j0 + lane < total;
             const uint32_t j = min(j0 + lane, total - 1);
-            uint32_t s = 0;
-#pragma unroll
-            for (uint32_t step = 32; step >= 1; step >>= 1) {
-                const uint32_t t = s + step;
-                const uint32_t e = (uint32_t)__shfl((int)excl, (int)t, 64);
-                s = e <= j ? t : s;
-            }
+            // Whose candidate is number j?  Every Gaussian with candidates leaves 1 + its lane at the slot of its first
+            // one (if that falls into this window of 64; the slots are distinct), and a running maximum over the slots
+            // spreads it over the rest of its run; the window's first slots belong to `carry`.  One trip through LDS
+            // (a wavefront's LDS operations complete in the order they were issued) instead of the six dependent
+            // shuffles of a binary search over the prefix sums.
+            mark[lane] = 0u;
+            const uint32_t rel = excl - j0;
+            if (cnt != 0u && rel < 64u) mark[rel] = lane + 1u;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            uint32_t own = mark[lane];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            own = wave_inclusive_max(lane == 0u ? max(own, carry) : own);
+            carry = (uint32_t)__builtin_amdgcn_readlane((int)own, 63);
+            const uint32_t s = (own - 1u) & 63u;   // (own >= 1 wherever live: candidate 0 is some lane's first)
             const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);
             const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
             const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
+            // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
+            // either way, never a loop that bad operands could keep a wavefront in
             uint32_t row = (uint32_t)((float)k / (float)ow);
-            while (row * ow > k) row--;
-            while ((row + 1) * ow <= k) row++;
+            row -= row * ow > k ? 1u : 0u;
+            row += (row + 1) * ow <= k ? 1u : 0u;
             const uint32_t col = k - row * ow;
             const uint32_t tx = (oxy & 0xffffu) + col, ty = (oxy >> 16) + row;
             bool hit = live;
