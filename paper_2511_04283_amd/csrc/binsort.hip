@@ -191,9 +191,9 @@ __global__ __launch_bounds__(256) void k_emit_pairs(int64_t n, const ushort4* __
         const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
         const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
         const uint32_t od = (uint32_t)__shfl((int)dbits, (int)s, 64);
-        // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
-        // either way, never a loop that bad operands could keep a wavefront in
-        uint32_t row = (uint32_t)((float)k / (float)ow);
+        // estimate with the fast reciprocal, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.02):
+        // corrected by one step either way, never by a loop that bad operands could keep a wavefront in
+        uint32_t row = (uint32_t)((float)k * __builtin_amdgcn_rcpf((float)ow));
         row -= row * ow > k ? 1u : 0u;
         row += (row + 1) * ow <= k ? 1u : 0u;
         const uint32_t col = k - row * ow;
@@ -279,9 +279,9 @@ __global__ __launch_bounds__(256) void k_emit_pairs_cb(int64_t n, const ushort4*
         const float omx = __shfl(mx, (int)s, 64), omy = __shfl(my, (int)s, 64);
         const float oA = __shfl(A, (int)s, 64), oB = __shfl(B, (int)s, 64), oC = __shfl(C, (int)s, 64);
         const float oQ = __shfl(Q, (int)s, 64);
-        // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
-        // either way, never a loop that bad operands could keep a wavefront in
-        uint32_t row = (uint32_t)((float)k / (float)ow);
+        // estimate with the fast reciprocal, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.02):
+        // corrected by one step either way, never by a loop that bad operands could keep a wavefront in
+        uint32_t row = (uint32_t)((float)k * __builtin_amdgcn_rcpf((float)ow));
         row -= row * ow > k ? 1u : 0u;
         row += (row + 1) * ow <= k ? 1u : 0u;
         const uint32_t col = k - row * ow;
@@ -373,11 +373,23 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
         __shared__ uint32_t s_tt[TILE_PAIR_THREADS / 64];
         __shared__ uint32_t s_base[2];
         uint32_t recs = 0, tt = 0;
-        for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i < n;
-             i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
-            const ushort4 r = rect[i];
-            recs += (r.z > r.x ? (uint32_t)(r.z - r.x) : 0u) * (r.w > r.y ? (uint32_t)(r.w - r.y) : 0u);
-            tt += ra.tiles_touched[i];
+        // (four rounds' loads are requested together: with one wavefront's worth of loads in flight per round the
+        // loop would take one memory latency per round)
+        const int64_t stride = (int64_t)gridDim.x * TILE_PAIR_THREADS;
+        for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i < n; i += 4 * stride) {
+            ushort4 r[4];
+            uint32_t t4[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const bool in = i + q * stride < n;
+                r[q] = in ? rect[i + q * stride] : make_ushort4(0, 0, 0, 0);
+                t4[q] = in ? ra.tiles_touched[i + q * stride] : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                recs += (r[q].z > r[q].x ? (uint32_t)(r[q].z - r[q].x) : 0u) * (r[q].w > r[q].y ? (uint32_t)(r[q].w - r[q].y) : 0u);
+                tt += t4[q];
+            }
         }
         recs = wave_inclusive_scan(recs);
         tt = wave_inclusive_scan(tt);
@@ -400,14 +412,28 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
         for (int w = 0; w < (int)(threadIdx.x >> 6); w++) rec_next += s_base[1] ? 0u : s_wave_recs[w];
     }
     // (every wavefront of the workgroup walks its own 64 Gaussians per round; no barrier inside the rounds)
-    for (int64_t i = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x; i - lane < n;
-         i += (int64_t)gridDim.x * TILE_PAIR_THREADS) {
+    // (the next round's rectangle, record place and depth are requested before this round's candidates are walked)
+    const int64_t i_first = (int64_t)blockIdx.x * TILE_PAIR_THREADS + threadIdx.x;
+    const int64_t round_stride = (int64_t)gridDim.x * TILE_PAIR_THREADS;
+    ushort4 r_next = i_first < n ? rect[i_first] : make_ushort4(0, 0, 0, 0);
+    uint32_t roff_next = (SCATTER && i_first < n) ? rec_offsets[i_first] : 0u;
+    uint32_t dbits_next = (SCATTER && i_first < n) ? __float_as_uint(depth[i_first]) : 0u;
+    for (int64_t i = i_first; i - lane < n; i += round_stride) {
         const bool valid = i < n;
-        const ushort4 r = valid ? rect[i] : make_ushort4(0, 0, 0, 0);
+        const ushort4 r = r_next;
+        const uint32_t roff = roff_next;
         const uint32_t w = r.z > r.x ? (uint32_t)(r.z - r.x) : 0u, h = r.w > r.y ? (uint32_t)(r.w - r.y) : 0u;
         const uint32_t cnt = w * h;
-        const uint32_t roff = (SCATTER && valid) ? rec_offsets[i] : 0u;
-        const uint32_t dbits = (SCATTER && cnt) ? __float_as_uint(depth[i]) : 0u;
+        const uint32_t dbits = cnt ? dbits_next : 0u;
+        {
+            const int64_t i2 = i + round_stride;
+            const bool in = i2 < n;
+            r_next = in ? rect[i2] : make_ushort4(0, 0, 0, 0);
+            if (SCATTER) {
+                roff_next = in ? rec_offsets[i2] : 0u;
+                dbits_next = in ? __float_as_uint(depth[i2]) : 0u;
+            }
+        }
         float mx = 0.f, my = 0.f, A = 1.f, B = 0.f, C = 1.f, Q = 0.f;
         if (cnt && (CB || SCATTER)) {
             const float2 m = mean2d[i];
@@ -456,9 +482,9 @@ __global__ __launch_bounds__(TILE_PAIR_THREADS) void k_tile_pairs(int64_t n, con
             const uint32_t k = j - (uint32_t)__shfl((int)excl, (int)s, 64);
             const uint32_t ow = (uint32_t)__shfl((int)w, (int)s, 64);
             const uint32_t oxy = (uint32_t)__shfl((int)rect_xy, (int)s, 64);
-            // estimate, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.01): corrected by one step
-            // either way, never a loop that bad operands could keep a wavefront in
-            uint32_t row = (uint32_t)((float)k / (float)ow);
+            // estimate with the fast reciprocal, off by at most one (k < 2^32 and ow < 2^16 make the quotient's error < 0.02):
+            // corrected by one step either way, never by a loop that bad operands could keep a wavefront in
+            uint32_t row = (uint32_t)((float)k * __builtin_amdgcn_rcpf((float)ow));
             row -= row * ow > k ? 1u : 0u;
             row += (row + 1) * ow <= k ? 1u : 0u;
             const uint32_t col = k - row * ow;
