@@ -35,7 +35,7 @@ GROUPS = {
     "order_pairs": ["k_tile_pairs<false, true>", "k_tile_pairs<true, true>", "k_tile_sort<"],
     "render_fwd": ["k_render_fwd<true, true>"],
     "l1_grad": ["k_fold_tile_stats"],
-    "render_bwd": ["k_render_bwd<false>"],
+    "render_bwd": ["k_render_bwd<false>", "k_render_bwd_splat<false>"],
     "preprocess_bwd": ["k_preprocess_bwd<"],
     "error_mask": ["k_err_mask_stats"],
     "score": ["k_score_bits"],
@@ -80,6 +80,8 @@ def main() -> int:
     ap.add_argument("--sq")
     ap.add_argument("--bench", required=True, help="file with the JSON line bench.py printed in the --stats run")
     ap.add_argument("--bench-args", default="", help="bench.py arguments of the profiled runs besides --config (for the text)")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="write no traffic_cfg<N>.json (for runs of a variant, whose traffic bench.py must not pick up)")
     ap.add_argument("--out", default="profiles")
     a = ap.parse_args()
 
@@ -143,9 +145,10 @@ def main() -> int:
           "command": f"rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) --output-format csv -d <dir> -o p -- {cmd}",
           "summary": f"profiles/{a.name}.md"}
     suffix = "_wide_tail" if "wide_tail" in bench["config"]["workload"] else ""
-    with open(os.path.join(a.out, f"traffic_cfg{a.config}{suffix}.json"), "w") as f:
-        json.dump(tj, f, indent=1)
-        f.write("\n")
+    if not a.no_traffic:
+        with open(os.path.join(a.out, f"traffic_cfg{a.config}{suffix}.json"), "w") as f:
+            json.dump(tj, f, indent=1)
+            f.write("\n")
 
     fmt = lambda v, p="{:.2f}": "—" if v is None else p.format(v)
     with open(os.path.join(a.out, a.name + ".md"), "w") as f:
@@ -192,7 +195,7 @@ def main() -> int:
         f.write(f"\nbench.py of that run: ms_per_step = {bench['ms_per_step']}, value = {bench['value']} {bench['unit']}; dominant group "
                 f"`{ro.get('group')}` ({ro.get('kernel')}): {ro.get('achieved')} {ro.get('unit')} = {ro.get('frac')} of {ro.get('peak')} "
                 f"(event-timed {ro.get('avg_launch_ms')} ms per launch under the profiler).\n")
-    print(f"wrote {a.out}/{a.name}.md and traffic_cfg{a.config}{suffix}.json")
+    print(f"wrote {a.out}/{a.name}.md" + ("" if a.no_traffic else f" and traffic_cfg{a.config}{suffix}.json"))
     return 0
 
 
