@@ -287,6 +287,24 @@ __device__ __forceinline__ void sh_dir_grad(float x, float y, float z, const flo
     g[0] = gx; g[1] = gy; g[2] = gz;
 }
 
+// Sum over the 64 lanes of a wavefront, left in lane 63: four shifts within the rows of 16 lanes (zeros move in at a
+// row's start), then lane 15 of rows 0 and 2 is added to the row after it, then lane 31 to rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_to_last(float v)
+{
+    v += dpp_or_zero_f<0x111, 0xF>(v);   // row_shr:1
+    v += dpp_or_zero_f<0x112, 0xF>(v);   // row_shr:2
+    v += dpp_or_zero_f<0x114, 0xF>(v);   // row_shr:4
+    v += dpp_or_zero_f<0x118, 0xF>(v);   // row_shr:8
+    v += dpp_or_zero_f<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero_f<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // Reverse of project().  First the screen-space gradients of Gaussian i are formed by adding up
 // its pairs' records (contiguous: pair_offsets[i] .. + tiles_touched[i], each record = dL/drgb 3,
 // dL/dsigma, dL/dconic 3, dL/dmu_2D 2, padded to PAIR_REC floats), in a fixed order; then they are
@@ -378,8 +396,43 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
             __builtin_amdgcn_wave_barrier();
             if (cs + CH < hi_all) request(cs + CH);
             const uint32_t r0 = max(off, cs), r1 = min(off + cnt, cs + nrec);
+            // A Gaussian with many records in the chunk (a large splat: one per tile of its rectangle) would keep its
+            // lane busy for as many trips while the other 63 wait.  Such runs are added up by the whole wavefront
+            // instead, one after the other: lane l takes records l and l + 64 of the run, a sum over the lanes follows,
+            // and the owner adds the total.  (The order of the additions is fixed either way.)
+            constexpr uint32_t BIG = 32;   // (8: slower everywhere; 16 .. 64: within 2 % of each other, 32 best)
+            const bool big = r1 > r0 && r1 - r0 >= BIG;
+            for (uint64_t todo = __ballot(big); todo != 0; todo &= todo - 1) {
+                const int o = __builtin_ctzll(todo);
+                const uint32_t q0 = (uint32_t)__builtin_amdgcn_readlane((int)r0, o) - cs;   // the run within the chunk:
+                const uint32_t q1 = (uint32_t)__builtin_amdgcn_readlane((int)r1, o) - cs;   // [q0, q1), q1 <= nrec <= CH
+                float t[11];
+#pragma unroll
+                for (int k = 0; k < 11; k++) t[k] = 0.f;
+#pragma unroll
+                for (uint32_t h = 0; h < CH / 64; h++) {
+                    const uint32_t q = q0 + lane + 64 * h;
+                    if (q < q1) {
+                        const float4 a = buf[q * 3], b = buf[q * 3 + 1], c4 = buf[q * 3 + 2];
+                        t[0] += a.x; t[1] += a.y; t[2] += a.z; t[3] += a.w;
+                        t[4] += b.x; t[5] += b.y; t[6] += b.z; t[7] += b.w;
+                        t[8] += c4.x; t[9] += c4.y; t[10] += c4.z;
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 11; k++) t[k] = wave_sum_to_last(t[k]);
+                float tot[11];
+#pragma unroll
+                for (int k = 0; k < 11; k++) tot[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t[k]), 63));
+                if (lane == o) {
+                    ra.x += tot[0]; ra.y += tot[1]; ra.z += tot[2]; ra.w += tot[3];
+                    rb.x += tot[4]; rb.y += tot[5]; rb.z += tot[6]; rb.w += tot[7];
+                    rc += tot[8]; rabs_x += tot[9]; rabs_y += tot[10];
+                }
+            }
+            const uint32_t r1s = big ? r0 : r1;   // the short runs: every lane its own
             uint32_t r = r0;
-            for (; r + 2 <= r1; r += 2) {   // two records per trip: their LDS reads overlap
+            for (; r + 2 <= r1s; r += 2) {   // two records per trip: their LDS reads overlap
                 const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1], c4 = buf[(r - cs) * 3 + 2];
                 const float4 a2 = buf[(r - cs) * 3 + 3], b2 = buf[(r - cs) * 3 + 4], c5 = buf[(r - cs) * 3 + 5];
                 ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
@@ -389,7 +442,7 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
                 rb.x += b2.x; rb.y += b2.y; rb.z += b2.z; rb.w += b2.w;
                 rc += c5.x; rabs_x += c5.y; rabs_y += c5.z;
             }
-            if (r < r1) {
+            if (r < r1s) {
                 const float4 a = buf[(r - cs) * 3], b = buf[(r - cs) * 3 + 1], c4 = buf[(r - cs) * 3 + 2];
                 ra.x += a.x; ra.y += a.y; ra.z += a.z; ra.w += a.w;
                 rb.x += b.x; rb.y += b.y; rb.z += b.z; rb.w += b.w;

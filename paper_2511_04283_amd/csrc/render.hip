@@ -476,7 +476,9 @@ __device__ __forceinline__ float row_reduce2(float a, float b, int lane)
 // pair had when it was emitted (pair_offsets[g] + its place in g's tile rectangle): the flush is a
 // plain store (rgb 3, sigma, conic 3, mu_2D 2), every pair of the tile is written exactly once (zeros
 // for the ones nothing blended), and the per-Gaussian sum over its contiguous records is left to the
-// projection's backward kernel.  No global atomics, and the result does not depend on scheduling.
+// projection's backward kernel.  No global atomics.  The only sums whose order depends on scheduling are those of a
+// Gaussian's (up to 16) sub-tile totals within a tile, taken in double precision in LDS: the record is the same from
+// run to run unless the exponents of those terms span more than 29 bits.
 //
 // ABS adds the absolute positional gradient (used by FastGS for the split decision): per pixel the
 // magnitudes |dL/dmu_x|, |dL/dmu_y| of its own contribution, summed like the other values and stored
