@@ -44,8 +44,8 @@ struct fs_ctx {
     ScratchBuf sel_hist;      // uint32 radix histograms of that sort
     uint64_t generation = 0;  // bumped by every fs_bin_sort; fs_bins of an earlier one are refused
     hipEvent_t totals_event = nullptr;   // recorded behind the read-back of fs_bin_sort's totals
-    int64_t spec_max_len = 0;            // longest list of the previous per-tile ordering on this ctx (0: none): what
-                                         // fs_bin_sort enqueues ahead of its read-back is chosen by it
+    int spec_set = 0;                    // the sort launches (TS_*) the previous per-tile ordering on this ctx would have
+                                         // chosen (0: none): what fs_bin_sort enqueues ahead of its read-back
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
     uint64_t* total_host = nullptr;  // pinned host copy
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
@@ -396,15 +396,15 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     FS_HIP(hipEventRecord(ctx->totals_event, st), "hipEventRecord");
     // Per-tile ordering, second half (placement into the tiles' segments -- keys[1] serves as the bucket array -- and
     // the per-tile LDS sorts; the ranges are already in place).  When this ctx has ordered pairs per tile before, the
-    // second half is enqueued right here, ahead of the host's wait for the totals, sized by what the buffers hold and by
-    // the previous call's longest list: otherwise the GPU idles for the whole round trip (wait, wake-up, launch) once per
+    // second half is enqueued right here, ahead of the host's wait for the totals, sized by what the buffers hold, with
+    // the sort launches the previous call's lists would have chosen: otherwise the GPU idles for the whole round trip (wait, wake-up, launch) once per
     // call.  The kernels write nothing beyond the capacities they are given; what the totals then say was not covered
     // (a longer list's sort variant, or buffers that have to grow first) is enqueued afterwards.
     const uint32_t* recs_p = cb ? static_cast<const uint32_t*>(ctx->rec_offsets.ptr) : static_cast<const uint32_t*>(ctx->offsets.ptr);
     fs_projected none = {};
     uint64_t cap_pairs = 0, cap_recs = 0;
     int spec_variants = 0;
-    if (bucketed && ctx->spec_max_len > 0 && n > 0) {
+    if (bucketed && ctx->spec_set != 0 && n > 0) {
         cap_pairs = ctx->keys[0].cap / sizeof(uint64_t);
         if (ctx->keys[1].cap / sizeof(uint64_t) < cap_pairs) cap_pairs = ctx->keys[1].cap / sizeof(uint64_t);
         if (ctx->vals[0].cap / sizeof(uint32_t) < cap_pairs) cap_pairs = ctx->vals[0].cap / sizeof(uint32_t);
@@ -413,7 +413,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
         if (cap_recs > 0x7fffffffull) cap_recs = 0x7fffffffull;
         if (cap_pairs > 0 && (!cb || cap_recs > 0)) {
             ProfScope prof(ctx, FS_K_ORDER);
-            spec_variants = tile_sort_variants(ctx->spec_max_len);
+            spec_variants = ctx->spec_set;
             FS_HIP(launch_tile_scatter(st, n, proj ? *proj : none, cf, recs_p, cd.tiles_x, tiles, (uint32_t)cap_pairs,
                                        (uint32_t)cap_recs, reinterpret_cast<const uint2*>(ranges_p), tcount_p,
                                        static_cast<uint64_t*>(ctx->keys[1].ptr), static_cast<float*>(ctx->splats.ptr),
@@ -429,7 +429,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     // bucketed: {sum of tiles_touched, records, pairs counted per tile, longest list}; else {pairs, records (CB)}
     const uint64_t P = bucketed ? ctx->total_host[2] : ctx->total_host[0];
     const uint64_t NR = cb || bucketed ? ctx->total_host[1] : P;
-    ctx->spec_max_len = 0;
+    ctx->spec_set = 0;
     if (bucketed && (ctx->total_host[0] != P || (!cb && NR != P)))
         return fail(ctx, FS_EINVAL, "fs_bin_sort: tiles_touched does not match rect (proj from another configuration?)");
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
@@ -452,8 +452,10 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     uint32_t* vals[2] = {static_cast<uint32_t*>(ctx->vals[0].ptr), static_cast<uint32_t*>(ctx->vals[1].ptr)};
     int res = 0;
     if (lds_sort) {
-        int variants = P > 0 ? tile_sort_variants((int64_t)max_len) : 0;
-        if (spec_fits) variants &= ~spec_variants;   // placement and these sorts have run (or are running) already
+        // (lists of more than 1024 entries on average: enough tiles beyond 2048 to give them a launch of their own)
+        const bool long_lists = P > (uint64_t)1024 * (uint64_t)tiles;
+        // placement and the sorts enqueued ahead have run (or are running) already: what do they leave to do?
+        const int variants = P > 0 ? tile_sort_variants((int64_t)max_len, long_lists, spec_fits ? spec_variants : 0) : 0;
         if (!spec_fits || variants) {
             ProfScope prof(ctx, FS_K_ORDER);
             if (!spec_fits) {
@@ -466,7 +468,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
                                      keys[1], keys[0], vals[0]),
                    "k_tile_sort");
         }
-        ctx->spec_max_len = max_len > 0 ? (int64_t)max_len : 1;
+        ctx->spec_set = tile_sort_variants((int64_t)max_len, long_lists, 0);
     } else {
         // (lists too long for the per-tile sort: the radix path's prefix sums have not been made yet)
         if (bucketed) FS_TRY(prefix_sums());

@@ -1006,23 +1006,35 @@ hipError_t launch_tile_scatter(hipStream_t st, int64_t n, const fs_projected& pr
     return hipGetLastError();
 }
 
-int tile_sort_variants(int64_t max_len)
+int tile_sort_variants(int64_t max_len, bool long_lists, int have)
 {
-    return 1 | (max_len > TILE_SORT_SMALL ? 2 : 0) | (max_len > TILE_SORT_MAX ? 4 : 0);
+    // which length classes still need a launch: (0, SMALL], (SMALL, MID], (MID, MAX], (MAX, HUGE]
+    int v = 0;
+    if (!(have & TS_SMALL)) v |= TS_SMALL;
+    const bool need_mid = max_len > TILE_SORT_SMALL && !(have & (TS_MID | TS_MIDMAX));
+    const bool need_max = max_len > TILE_SORT_MID && !(have & (TS_MAX | TS_MIDMAX));
+    if (need_mid && need_max) v |= long_lists ? (TS_MID | TS_MAX) : TS_MIDMAX;
+    else if (need_mid) v |= long_lists || (have & TS_MAX) ? TS_MID : TS_MIDMAX;
+    else if (need_max) v |= TS_MAX;
+    if (max_len > TILE_SORT_MAX && !(have & TS_HUGE)) v |= TS_HUGE;
+    return v;
 }
 
 hipError_t launch_tile_sorts(hipStream_t st, int num_tiles, int variants, uint32_t pair_limit, const uint2* ranges,
                              const uint32_t* tile_order, const uint64_t* bucket, uint64_t* keys_out, uint32_t* vals_out)
 {
     if (num_tiles <= 0) return hipSuccess;
-    // the long lists first: few workgroups, each a long chain of steps, which 1024 threads shorten
-    if (variants & 4)
+    // the long lists first: few workgroups, each a long chain of steps, which more threads shorten
+    if (variants & TS_HUGE)
         hipLaunchKernelGGL((k_tile_sort<TILE_SORT_HUGE, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
                            bucket, TILE_SORT_MAX, pair_limit, keys_out, vals_out);
-    if (variants & 2)
+    if (variants & (TS_MAX | TS_MIDMAX))
         hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MAX, 1024>), dim3(num_tiles), dim3(1024), 0, st, ranges, tile_order,
+                           bucket, (variants & TS_MIDMAX) ? TILE_SORT_SMALL : TILE_SORT_MID, pair_limit, keys_out, vals_out);
+    if (variants & TS_MID)
+        hipLaunchKernelGGL((k_tile_sort<TILE_SORT_MID, 512>), dim3(num_tiles), dim3(512), 0, st, ranges, tile_order,
                            bucket, TILE_SORT_SMALL, pair_limit, keys_out, vals_out);
-    if (variants & 1)
+    if (variants & TS_SMALL)
         hipLaunchKernelGGL((k_tile_sort<TILE_SORT_SMALL, 256>), dim3(num_tiles), dim3(256), 0, st, ranges, tile_order, bucket,
                            0, pair_limit, keys_out, vals_out);
     return hipGetLastError();

@@ -177,8 +177,9 @@ constexpr int TILE_COPIES = 256;        // workgroups of the counting / placemen
 constexpr int TILE_PAIR_THREADS = 1024;
 constexpr int TILE_LDS_MAX_TILES = 15360;  // their per-tile counters live in LDS (60 KB)
 constexpr int TILE_SORT_GROUP16_FROM = 1024;  // padded list length from which a thread merges 16 words in registers, not 8
-constexpr int TILE_SORT_SMALL = 2048;  // longest list one workgroup sorts with 16 KB of LDS
-constexpr int TILE_SORT_MAX = 8192;    // ... with 80 KB
+constexpr int TILE_SORT_SMALL = 2048;  // longest list one workgroup sorts with 20 KB of LDS (256 threads)
+constexpr int TILE_SORT_MID = 4096;    // ... with 40 KB (512 threads: four such workgroups fit a compute unit, two of the next)
+constexpr int TILE_SORT_MAX = 8192;    // ... with 80 KB (1024 threads)
 constexpr int TILE_SORT_HUGE = 16384;  // ... with 144 KB (a compute unit of this chip has 160 KB): the longest list of the
                                        // per-tile ordering; anything longer takes the radix path
 hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg, int tiles_x,
@@ -187,13 +188,19 @@ hipError_t launch_tile_count(hipStream_t st, int64_t n, const fs_projected& proj
                              uint64_t* counters);
 // Placement and the per-tile sorts.  pair_limit / rec_limit: how many words / gradient records the buffers hold; the
 // kernels write nothing at or beyond them and leave alone a segment that reaches beyond pair_limit, so they may be
-// enqueued before the host knows the totals.  variants: bit 0 lists of up to TILE_SORT_SMALL entries, bit 1 up to
-// TILE_SORT_MAX, bit 2 up to TILE_SORT_HUGE (tile_sort_variants(longest list) = the ones a longest list needs).
+// enqueued before the host knows the totals.
 hipError_t launch_tile_scatter(hipStream_t st, int64_t n, const fs_projected& proj, const CfgDev& cfg,
                                const uint32_t* rec_offsets, int tiles_x, int num_tiles, uint32_t pair_limit,
                                uint32_t rec_limit, const uint2* ranges, uint32_t* cursor, uint64_t* bucket, float* splats,
                                float* pair_grad);
-int tile_sort_variants(int64_t max_len);
+// The sort launches, by the list lengths they take: (0, SMALL], (SMALL, MID], (MID, MAX], (MAX, HUGE], and
+// (SMALL, MAX] in one launch (TS_MIDMAX, instead of TS_MID and TS_MAX).  The lists between SMALL and MID get a launch of
+// their own (four of its workgroups fit a compute unit, two of the MAX kind) when the lists are long throughout
+// (`long_lists`: there are then enough of them to fill the chip); when only a few tiles are that long, every launch is
+// a chain of steps that nothing overlaps with, and one launch fewer is the better deal.
+// tile_sort_variants: the launches still needed for lists of up to max_len entries when those in `have` are enqueued.
+enum { TS_SMALL = 1, TS_MID = 2, TS_MAX = 4, TS_HUGE = 8, TS_MIDMAX = 16 };
+int tile_sort_variants(int64_t max_len, bool long_lists, int have);
 hipError_t launch_tile_sorts(hipStream_t st, int num_tiles, int variants, uint32_t pair_limit, const uint2* ranges,
                              const uint32_t* tile_order, const uint64_t* bucket, uint64_t* keys_out, uint32_t* vals_out);
 

@@ -297,15 +297,25 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
              (709, 2500, 40, 33, (-3.2, 0.7)),      # short after that
              (710, 90000, 40, 33, (-3.2, 0.7)),     # lists beyond LDS: the radix path, whatever was enqueued ahead
              (711, 2500, 40, 33, (-3.2, 0.7)),      # per-tile again after the radix path
-             (712, 2600, 40, 33, (-3.2, 0.7))]
-    seen_long = seen_huge = seen_radix = False
-    for seed, n, W, H, ls in cases:
+             (712, 2600, 40, 33, (-3.2, 0.7)),
+             # the sort launches differ with the mix of list lengths: lists long throughout (more than 1024 entries on
+             # average) get a launch for (2048, 4096] and one for (4096, 8192], a few long lists among short ones a
+             # single launch for (2048, 8192]; what was enqueued ahead comes from the previous call's choice
+             (715, 22000, 70, 50, (-3.2, 0.7)),           # long throughout, none beyond 4096
+             (703, 40000, 70, 50, (-3.2, 0.7)),           # ... now some beyond 4096: only that launch is missing
+             (713, 12000, 203, 117, (-3.6, 0.5), 0.25),   # a few long lists (up to 5989) among short ones
+             (715, 22000, 70, 50, (-3.2, 0.7)),           # long throughout after the single launch
+             (713, 12000, 203, 117, (-3.6, 0.5), 0.25),
+             (709, 2500, 40, 33, (-3.2, 0.7))]
+    seen_long = seen_huge = seen_radix = seen_few_long = False
+    for seed, n, W, H, ls, *rest in cases:
+        spread = rest[0] if rest else 1.1
         if n == 0:
             cam = scenes.Camera(W, H, 60.0, 60.0, W / 2.0, H / 2.0)
             sc = scenes.Scene("empty", 0, np.zeros((0, 3), np.float32), np.zeros((0, 3), np.float32),
                               np.zeros((0, 4), np.float32), np.zeros(0, np.float32), np.zeros((0, 1, 3), np.float32), [cam], 0)
         else:
-            sc = scenes.tiny_scene(seed, n, W, H, sh_degree=0, log_scale=ls, spread=1.1)
+            sc = scenes.tiny_scene(seed, n, W, H, sh_degree=0, log_scale=ls, spread=spread)
             cam = sc.cameras[0]
         small = 0 < n <= 9000
         dL = np.random.default_rng(seed).standard_normal((3, H, W)).astype(np.float32) if small else None
@@ -316,6 +326,7 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
         seen_long |= bool(L.max() > 2048)
         seen_huge |= bool(8192 < L.max() <= 16384)
         seen_radix |= bool(L.max() > 16384)
+        seen_few_long |= bool(L.max() > 4096 and b_o.num_pairs <= 1024 * L.size)
         assert g["num_pairs"] == b_o.num_pairs, (seed, n)
         assert np.array_equal(g["keys_sorted"], b_o.keys_sorted), (seed, n)
         assert np.array_equal(g["gauss_sorted"], b_o.gauss_sorted), (seed, n)
@@ -326,7 +337,7 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
             assert_image_close(g["image"], img)
         if small:
             assert_grads_close(g["grads"], o.backward(sc, cam, p_o, b_o, dL))
-    assert seen_long and seen_huge and seen_radix
+    assert seen_long and seen_huge and seen_radix and seen_few_long
     c.close()
 
 
