@@ -102,6 +102,17 @@ struct Stage {
     }
 };
 
+// Sub-tile st = wave*4 + row of a tile sits at column kx = (wave&1)*2 + (row&1), line ky = (wave>>1)*2 + (row>>1).
+// The 16-bit sets (bit st) of the sub-tiles in one column, one line, on one diagonal kx + ky = s or kx - ky = d.
+struct SubTiles {
+    static constexpr int kx(int st) { return ((st >> 2) & 1) * 2 + (st & 1); }
+    static constexpr int ky(int st) { return (st >> 3) * 2 + ((st >> 1) & 1); }
+    static constexpr uint32_t col(int k) { uint32_t m = 0; for (int st = 0; st < 16; st++) m |= kx(st) == k ? 1u << st : 0u; return m; }
+    static constexpr uint32_t line(int k) { uint32_t m = 0; for (int st = 0; st < 16; st++) m |= ky(st) == k ? 1u << st : 0u; return m; }
+    static constexpr uint32_t sum(int s) { uint32_t m = 0; for (int st = 0; st < 16; st++) m |= kx(st) + ky(st) == s ? 1u << st : 0u; return m; }
+    static constexpr uint32_t dif(int d) { uint32_t m = 0; for (int st = 0; st < 16; st++) m |= kx(st) - ky(st) == d ? 1u << st : 0u; return m; }
+};
+
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_shr_add(uint32_t v)
 {
@@ -163,14 +174,17 @@ __device__ __forceinline__ int stage_batch(Stage<WITH_RGB>& s, uint32_t* s_id, c
             const float hy = __builtin_amdgcn_sqrtf(Q * syy) * 1.002f + 0.01f;
             // sub-tile column k has its centre at +4k+2 from the tile origin; pixel centres reach 1.5 from it
             const float ox = xy.x - (float)((tile % cam.tiles_x) * TILE), oy = xy.y - (float)((tile / cam.tiles_x) * TILE);
-            uint32_t colx = 0, rowy = 0;
+            // Every test below concerns a whole family of sub-tiles at once (a column, a line, a diagonal), so each is
+            // made once and switches on the family's 16-bit pattern (SubTiles::col ...): 22 tests and a few ANDs instead
+            // of four tests per sub-tile.
+            uint32_t colm = 0, rowm = 0;
 #pragma unroll
             for (int k = 0; k < 4; k++) {
-                colx |= (fabsf(ox - (float)(4 * k + 2)) <= hx + 1.5f) ? 1u << k : 0u;
-                rowy |= (fabsf(oy - (float)(4 * k + 2)) <= hy + 1.5f) ? 1u << k : 0u;
+                colm |= (fabsf(ox - (float)(4 * k + 2)) <= hx + 1.5f) ? SubTiles::col(k) : 0u;
+                rowm |= (fabsf(oy - (float)(4 * k + 2)) <= hy + 1.5f) ? SubTiles::line(k) : 0u;
             }
             // NaN half-widths (degenerate conic) keep the Gaussian everywhere: the exact test decides
-            if (!(hx == hx) || !(hy == hy)) { colx = 15u; rowy = 15u; }
+            if (!(hx == hx) || !(hy == hy)) { colm = 0xffffu; rowm = 0xffffu; }
             // The same set also lies between the tangent lines at +-45 degrees: |dx + dy| <= sqrt(Q (Sxx + Syy + 2 Sxy)),
             // |dx - dy| <= sqrt(Q (Sxx + Syy - 2 Sxy)) with Sxy = -b/det; a sub-tile's pixel centres reach 3 from
             // its centre in these sums.  This trims the corners of the box for slanted, elongated Gaussians.
@@ -179,15 +193,14 @@ __device__ __forceinline__ int stage_batch(Stage<WITH_RGB>& s, uint32_t* s_id, c
             const float hv = __builtin_amdgcn_sqrtf(fmaxf(Q * (sxx + syy - 2.0f * sxy), 0.f)) * 1.002f + 0.02f;
             const float su = ox + oy, sv = ox - oy;
             const bool nan8 = !(hu == hu) || !(hv == hv);
-            // sub-tile st = wave*4 + row sits at column (wave&1)*2 + (row&1), line (wave>>1)*2 + (row>>1)
+            // the sub-tile in column kx, line ky has its centre at sum 4 (kx + ky) + 4 and difference 4 (kx - ky)
+            uint32_t summ = 0, difm = 0;
 #pragma unroll
-            for (int st = 0; st < 16; st++) {
-                const int kx = ((st >> 2) & 1) * 2 + (st & 1), ky = (st >> 3) * 2 + ((st >> 1) & 1);
-                const bool box = (colx >> kx & 1u) && (rowy >> ky & 1u);
-                const bool diag = (fabsf(su - (float)(4 * (kx + ky) + 4)) <= hu + 3.0f) &&
-                                  (fabsf(sv - (float)(4 * (kx - ky))) <= hv + 3.0f);
-                sub_mask |= (box && (diag || nan8)) ? 1u << st : 0u;
+            for (int d = 0; d < 7; d++) {
+                summ |= (fabsf(su - (float)(4 * d + 4)) <= hu + 3.0f) ? SubTiles::sum(d) : 0u;
+                difm |= (fabsf(sv - (float)(4 * (d - 3))) <= hv + 3.0f) ? SubTiles::dif(d - 3) : 0u;
             }
+            sub_mask = colm & rowm & (nan8 ? 0xffffu : (summ & difm));
         }
     }
     // phase 1: one 64-bit keep mask per (sub-tile, staging wavefront)
