@@ -234,6 +234,27 @@ __device__ __forceinline__ int stage_batch(Stage<WITH_RGB>& s, uint32_t* s_id, c
     return mine;
 }
 
+// One step of a sum (three doubles) and a minimum / maximum (bit patterns of non-negative floats, which order like
+// unsigned integers) over the lanes of a wavefront: every lane combines its values with those of the lane the DPP
+// control names; a lane without such a source (the start of a row, a row the mask leaves out) adds zero and keeps
+// its extrema.  SHIFT: a shift within the rows (all rows take part, a missing source reads as zero).
+template <int CTRL, int ROW_MASK, bool SHIFT>
+__device__ __forceinline__ void wave_step(double& a, double& b, double& c, uint32_t& lo, uint32_t& hi)
+{
+    auto moved = [](double v) {
+        const long long bits = __double_as_longlong(v);
+        const int l = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)bits, CTRL, ROW_MASK, 0xF, SHIFT);
+        const int h = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((unsigned long long)bits >> 32), CTRL, ROW_MASK, 0xF, SHIFT);
+        return __longlong_as_double((long long)(((unsigned long long)(uint32_t)h << 32) | (uint32_t)l));
+    };
+    a += moved(a);
+    b += moved(b);
+    c += moved(c);
+    // (the minimum must not meet the zero a missing source reads as: its own value stands in)
+    lo = min(lo, (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, ROW_MASK, 0xF, false));
+    hi = max(hi, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, ROW_MASK, 0xF, SHIFT));
+}
+
 // Longest of the four sub-tile lists of the calling wavefront (`mine` is uniform within a row).
 __device__ __forceinline__ int wave_max_of_rows(int mine)
 {
@@ -394,23 +415,24 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
         }
     }
     if (FUSED) {
-        // per-wavefront partials by shuffles (sums in double, extrema of the fp32 errors in float: exact), combined
-        // across the four wavefronts through LDS with a single barrier
-        float fmin_e = (float)emin == (float)emin && emin < 1.0e299 ? (float)emin : 3.0e38f;
-        float fmax_e = emax > -1.0e299 ? (float)emax : -3.0e38f;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            l1 += shfl_down_f64(l1, d);
-            esum += shfl_down_f64(esum, d);
-            esq += shfl_down_f64(esq, d);
-            fmin_e = fminf(fmin_e, __shfl_down(fmin_e, d, 64));
-            fmax_e = fmaxf(fmax_e, __shfl_down(fmax_e, d, 64));
-        }
+        // per-wavefront partials (sums in double, extrema of the fp32 errors in float: exact) by DPP moves -- four
+        // shifts within the rows of 16 lanes, lane 15 of rows 0 and 2 into the row after it, lane 31 into rows 2 and
+        // 3 -- which leave the totals in lane 63; combined across the four wavefronts through LDS with a single barrier
+        // (errors are >= 0: threads outside the image carry +3e38 for the minimum and 0 for the maximum)
+        uint32_t lo_e = __float_as_uint((float)emin == (float)emin && emin < 1.0e299 ? (float)emin : 3.0e38f);
+        uint32_t hi_e = __float_as_uint(emax > -1.0e299 ? (float)emax : 0.0f);
+        wave_step<0x111, 0xF, true>(l1, esum, esq, lo_e, hi_e);
+        wave_step<0x112, 0xF, true>(l1, esum, esq, lo_e, hi_e);
+        wave_step<0x114, 0xF, true>(l1, esum, esq, lo_e, hi_e);
+        wave_step<0x118, 0xF, true>(l1, esum, esq, lo_e, hi_e);
+        wave_step<0x142, 0xA, false>(l1, esum, esq, lo_e, hi_e);
+        wave_step<0x143, 0xC, false>(l1, esum, esq, lo_e, hi_e);
+        const float fmin_e = __uint_as_float(lo_e), fmax_e = __uint_as_float(hi_e);
         // (the staging masks serve as the 4 x 5 doubles of scratch: they are only live inside stage_batch, between
         // its two barriers, and every wavefront has left its last stage_batch before any of them gets here)
         static_assert(sizeof(s.bits) >= 4 * 5 * sizeof(double), "scratch for the per-wavefront partials");
         double (*s_part)[5] = reinterpret_cast<double (*)[5]>(&s.bits[0][0]);
-        if ((threadIdx.x & 63) == 0) {
+        if ((threadIdx.x & 63) == 63) {
             double* w = s_part[threadIdx.x >> 6];
             w[0] = l1; w[1] = esum; w[2] = (double)fmin_e; w[3] = (double)fmax_e; w[4] = esq;
         }
