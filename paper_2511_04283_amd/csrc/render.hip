@@ -84,7 +84,7 @@ __device__ __forceinline__ Pixel pixel_of_thread(const CamDev& cam, int tile)
 
 // LDS image of one batch of a tile's list, shared by the kernels.  A staged Gaussian is one record of RS 16-byte
 // words, so that the loops form one address per entry: (mu_x, mu_y, a, 2b), (c, sigma, r, g) and, with WITH_RGB,
-// (b, -sigma/2, -, -).
+// (r, g, b, -sigma/2).
 template <bool WITH_RGB>
 struct Stage {
     static constexpr int RS = WITH_RGB ? 3 : 2;
@@ -154,7 +154,8 @@ __device__ __forceinline__ int stage_batch(Stage<WITH_RGB>& s, uint32_t* s_id, c
         const float4 co = make_float4(r0.z, r0.w, r1.x, r1.y);
         s.rec[t * s.RS] = make_float4(xy.x, xy.y, co.x, co.y + co.y);
         s.rec[t * s.RS + 1] = make_float4(co.z, co.w, r1.z, r1.w);
-        if (WITH_RGB) s.rec[t * s.RS + 2] = make_float4(r2.x, -0.5f * co.w, 0.f, 0.f);   // (the backward pass uses -sigma / 2)
+        // (the backward pass takes the colour and -sigma / 2 with one aligned 16-byte read)
+        if (WITH_RGB) s.rec[t * s.RS + 2] = make_float4(r1.z, r1.w, r2.x, -0.5f * co.w);
         if (ID_MODE == 1) s_id[t] = g;
         if (ID_MODE == 2) {
             const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
@@ -260,7 +261,8 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 {
     const int a = __builtin_amdgcn_readlane(mine, 0), b = __builtin_amdgcn_readlane(mine, 16);
     const int c = __builtin_amdgcn_readlane(mine, 32), d = __builtin_amdgcn_readlane(mine, 48);
-    return max(max(a, b), max(c, d));
+    // (read back through a scalar register: a loop bound the compiler knows to be uniform is counted by the scalar unit)
+    return __builtin_amdgcn_readfirstlane(max(max(a, b), max(c, d)));
 }
 
 // FUSED: the epilogue also does, per pixel, what the L1 term (FastGS Sec. 4.5) and the error map of the
@@ -351,7 +353,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             const float q = __builtin_fmaf(dx, u, (r1.x * dy) * dy);
             const float power = -0.5f * q;
             bool ok = (k < mine) & !done & !(power > 0.0f) & !(power < cfg.power_min);
-            const float colb = e[2].x;
+            const float colb = e[2].z;
             const float G = exp_c(power);
             const float alpha = fminf(cfg.alpha_max, r1.y * G);
             ok = ok & (alpha >= cfg.alpha_min);
@@ -594,20 +596,20 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             // every one of their 9 contributions is then an exact zero (and T / (1 - 0) leaves T as it is)
             alpha = act ? alpha : 0.f;
             G = act ? G : 0.f;
-            const float2 r2 = *reinterpret_cast<const float2*>(e + 2);   // (b, -sigma / 2)
+            const float4 r2 = e[2];   // (r, g, b, -sigma / 2)
             T = T * __builtin_amdgcn_rcpf(1.0f - alpha);             // transmittance in front of this Gaussian
             const float w = alpha * T;
             float v[9];
             v[0] = w * dC0;
             v[1] = w * dC1;
             v[2] = w * dC2;
-            const float cd = __builtin_fmaf(r2.x, dC2, __builtin_fmaf(r1.w, dC1, r1.z * dC0));   // dC . c
+            const float cd = __builtin_fmaf(r2.z, dC2, __builtin_fmaf(r2.y, dC1, r2.x * dC0));   // dC . c
             const float diff = cd - S;
             float dL_dalpha = T * diff;
             S = __builtin_fmaf(alpha, diff, S);
             dL_dalpha = sG > cfg.alpha_max ? 0.f : dL_dalpha;  // capped alpha is a constant
             v[3] = G * dL_dalpha;                              // d/d sigma
-            const float gq = r2.y * v[3];                      // d/d q = -1/2 sigma G dL/dalpha
+            const float gq = r2.w * v[3];                      // d/d q = -1/2 sigma G dL/dalpha
             const float gx = gq * dx, gy = gq * dy;
             v[4] = gx * dx;
             v[5] = gx * dy;
@@ -789,7 +791,7 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
                 const float4 f0 = s.at(j)[0], f1 = s.at(j)[1], f2 = s.at(j)[2];
                 const float2 xy = make_float2(f0.x, f0.y);
                 const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);    // (a, 2b, c, sigma)
-                const float4 col = make_float4(f1.z, f1.w, f2.x, 0.f);
+                const float4 col = make_float4(f2.x, f2.y, f2.z, 0.f);
                 const int pos_j = start + j;
                 float acc[NV];
 #pragma unroll
