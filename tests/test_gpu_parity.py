@@ -247,6 +247,30 @@ def test_more_tiles_than_the_lds_counters_hold(ctx, orc32):
     assert_image_close(g["image"], img)
 
 
+def test_as_many_tiles_as_the_lds_counters_hold(orc32):
+    """1920 x 2048 px = 120 x 128 = 15 360 tiles: the most the per-tile LDS counters of the tile-bucketed ordering take
+    (60 KB of dynamic LDS beside the kernels' static arrays).  Two calls on one context: the second one enqueues its
+    placement ahead of the read-back.  Keys, order and ranges bit-exact both times."""
+    from paper_2511_04283_amd import binding as B
+    c = B.Context("cuda:0")
+    for seed, n in ((41, 5000), (42, 7000)):
+        sc = scenes.tiny_scene(seed, n, 1920, 2048, sh_degree=0, log_scale=(-2.5, 0.8), spread=1.0)
+        cam = sc.cameras[0]
+        g = B.Gaussians.from_scene(sc, c.device)
+        fcam = B.make_camera(cam)
+        bins = c.fs_bin_sort(c.fs_preprocess(g, fcam), fcam)
+        p_o = orc32.preprocess(sc, cam)
+        b_o = orc32.bin_sort(p_o, cam)
+        assert b_o.tile_ranges.shape[0] == 15360 and b_o.num_pairs > 10000
+        assert bins.num_pairs == b_o.num_pairs
+        assert np.array_equal(bins.copy_keys().cpu().numpy().view(np.uint64), b_o.keys_sorted)
+        assert np.array_equal(bins.copy_gauss().cpu().numpy().view(np.uint32), b_o.gauss_sorted)
+        assert np.array_equal(bins.copy_ranges().cpu().numpy().view(np.uint32), b_o.tile_ranges)
+        order = bins.copy_order().cpu().numpy().astype(np.int64)
+        assert np.array_equal(np.sort(order), np.arange(15360))
+    c.close()
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("n,W,H", [(3000, 203, 117), (60000, 640, 400), (500, 1600, 1064)])
 def test_tile_order_is_a_permutation_with_the_longest_lists_first(n, W, H, mode):
