@@ -218,22 +218,24 @@ hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_so
                               uint32_t* ranges, uint32_t* tile_order);
 
 // pair_bits: null, or PAIR_BITS_BYTES per pair, which receive the pixels of its tile at which the multi-view score
-// counts the pair's Gaussian (see launch_score_bits)
+// counts the pair's Gaussian (see launch_score_bits); pair_flags: with it, one byte per pair: whether any bit is set
+// (rows of pairs without one are not written)
 constexpr int PAIR_BITS_BYTES = 32;
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib, void* pair_bits);
+                             uint32_t* n_contrib, void* pair_bits, void* pair_flags);
 
 // forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
 // tile_partial: 5 * tiles doubles, err: H*W floats, dL may be null; pair_bits as for launch_render_fwd
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial, void* pair_bits);
+                                   float* err, double* tile_partial, void* pair_bits, void* pair_flags);
 // the count pass from those bits: counts[g] += |bits(pair) & mask(tile)| over the pairs of every tile
 // (tiles are taken in tile_order)
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
-                             const uint32_t* gauss_sorted, const void* pair_bits, const uint8_t* mask, int32_t* counts);
+                             const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
+                             int32_t* counts);
 // stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,

@@ -273,8 +273,8 @@ __device__ __forceinline__ int wave_max_of_rows(int mine)
 // BITS: the kernel also records, for every pair of the tile's list (by its position in the sorted order), at which
 // of the tile's 256 pixels the Gaussian is counted by the multi-view score (Sec. 4.2): where it is blended and, in
 // FS_SCORE_WEIGHT mode, alpha T > alpha_min.  32 bytes per pair: 16 sub-tiles (index wave*4 + row) x 16 bits (lane
-// within the row), zeros for pairs the loop never reached.  With these the count pass is a population count per
-// pair instead of a second walk over the lists (k_score_bits).
+// within the row); one more byte per pair says whether any of them is set, and only then is the row written.  With
+// these the count pass is a population count per pair instead of a second walk over the lists (k_score_bits).
 template <bool FUSED, bool BITS>
 __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges,
                                                     const uint32_t* __restrict__ tile_order,
@@ -283,7 +283,8 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib,
                                                     const float* __restrict__ target, float scale,
                                                     float* __restrict__ dL, float* __restrict__ err,
-                                                    double* __restrict__ tile_partial, uint4* __restrict__ pair_bits)
+                                                    double* __restrict__ tile_partial, uint4* __restrict__ pair_bits,
+                                                    uint8_t* __restrict__ pair_flags)
 {
     __shared__ Stage<true> s;
     __shared__ __align__(16) uint16_t s_pb[BITS ? BATCH : 1][16];  // this batch's bits, [slot][sub-tile]
@@ -310,11 +311,19 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     auto write_bits = [&](int first, int count) {
         if ((int)threadIdx.x < count) {
             const uint4* row = reinterpret_cast<const uint4*>(s_pb[threadIdx.x]);
-            uint4* dst = pair_bits + ((size_t)range.x + first + threadIdx.x) * 2;
-            // (streaming stores: the record is read once, by the count pass, and should not displace the step's
-            // other arrays from the caches)
-            nt_store(row[0], dst);
-            nt_store(row[1], dst + 1);
+            const size_t pos = (size_t)range.x + first + threadIdx.x;
+            const uint4 lo = row[0], hi = row[1];
+            // a pair that is counted nowhere (a third of them: the rectangle's corners, entries behind the last
+            // blended one) only leaves a zero flag; the count pass then does not read its row
+            const bool any = ((lo.x | lo.y) | (lo.z | lo.w) | (hi.x | hi.y) | (hi.z | hi.w)) != 0u;
+            pair_flags[pos] = any ? 1 : 0;
+            if (any) {
+                // (streaming stores: the record is read once, by the count pass, and should not displace the step's
+                // other arrays from the caches)
+                uint4* dst = pair_bits + pos * 2;
+                nt_store(lo, dst);
+                nt_store(hi, dst + 1);
+            }
         }
     };
     for (int start = 0; start < total; start += BATCH) {
@@ -386,10 +395,7 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             write_bits(pending, pending_m);
         }
         // pairs the loop never reached (every pixel had finished) are blended nowhere
-        for (uint32_t pos = range.x + reached + threadIdx.x; pos < range.y; pos += 256) {
-            nt_store(make_uint4(0u, 0u, 0u, 0u), pair_bits + (size_t)pos * 2);
-            nt_store(make_uint4(0u, 0u, 0u, 0u), pair_bits + (size_t)pos * 2 + 1);
-        }
+        for (uint32_t pos = range.x + reached + threadIdx.x; pos < range.y; pos += 256) pair_flags[pos] = 0;
     }
     double l1 = 0.0, esum = 0.0, esq = 0.0, emin = 1.0e300, emax = -1.0e300;
     if (p.inside) {
@@ -1036,6 +1042,7 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
                                                     const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
                                                     const uint4* __restrict__ pair_bits,
+                                                    const uint8_t* __restrict__ pair_flags,
                                                     const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
 {
     __shared__ __align__(16) uint16_t s_m[16];
@@ -1048,7 +1055,7 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
     uint32_t pos = range.x + threadIdx.x;
     uint4 a = make_uint4(0u, 0u, 0u, 0u), c = a;
     uint32_t g = 0;
-    if (pos < range.y) {
+    if (pos < range.y && pair_flags[pos] != 0) {
         a = nt_load(pair_bits + (size_t)pos * 2);
         c = nt_load(pair_bits + (size_t)pos * 2 + 1);
         g = gauss_sorted[pos];
@@ -1062,7 +1069,7 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
         const uint32_t next = pos + 256;
         uint4 a2 = make_uint4(0u, 0u, 0u, 0u), c2 = a2;
         uint32_t g2 = 0;
-        if (next < range.y) {
+        if (next < range.y && pair_flags[next] != 0) {
             a2 = nt_load(pair_bits + (size_t)next * 2);
             c2 = nt_load(pair_bits + (size_t)next * 2 + 1);
             g2 = gauss_sorted[next];
@@ -1079,7 +1086,7 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib, void* pair_bits)
+                             uint32_t* n_contrib, void* pair_bits, void* pair_flags)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
@@ -1087,19 +1094,19 @@ hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
         hipLaunchKernelGGL((k_render_fwd<false, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
-                           nullptr, nullptr, static_cast<uint4*>(pair_bits));
+                           nullptr, nullptr, static_cast<uint4*>(pair_bits), static_cast<uint8_t*>(pair_flags));
     else
         hipLaunchKernelGGL((k_render_fwd<false, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
-                           nullptr, nullptr, nullptr);
+                           nullptr, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial, void* pair_bits)
+                                   float* err, double* tile_partial, void* pair_bits, void* pair_flags)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
@@ -1108,22 +1115,23 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
         hipLaunchKernelGGL((k_render_fwd<true, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
-                           tile_partial, static_cast<uint4*>(pair_bits));
+                           tile_partial, static_cast<uint4*>(pair_bits), static_cast<uint8_t*>(pair_flags));
     else
         hipLaunchKernelGGL((k_render_fwd<true, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
-                           tile_partial, nullptr);
+                           tile_partial, nullptr, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
-                             const uint32_t* gauss_sorted, const void* pair_bits, const uint8_t* mask, int32_t* counts)
+                             const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
+                             int32_t* counts)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     hipLaunchKernelGGL(k_score_bits, dim3(tiles), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
-                       static_cast<const uint4*>(pair_bits), mask, counts);
+                       static_cast<const uint4*>(pair_bits), static_cast<const uint8_t*>(pair_flags), mask, counts);
     return hipGetLastError();
 }
 
