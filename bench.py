@@ -238,10 +238,12 @@ def main() -> int:
         sp_ms = (time.perf_counter() - t3) * 1e3 / reps
         score_pass = {"views": len(cams), "ms": round(sp_ms, 4), "ms_per_view": round(sp_ms / len(cams), 4),
                       "gaussians_with_s_d_above_5": int((counts.to(torch.float32) / len(cams) > 5.0).sum().item())}
-        step()   # (the work counts below describe view 0)
 
     # units of work of one step (exact, from the path's own outputs)
+    step()   # (the work counts describe view 0; the forward pass of this step leaves its record for the count pass)
+    torch.cuda.synchronize()
     bins = state["bins"]
+    state["rows_per_tile"] = ctx.fs_score_record_rows(bins, fcam) if int(bins.num_pairs) > 0 else None
     P, R = int(bins.num_pairs), int(bins.struct.num_records)
     ranges = bins.copy_ranges().to(torch.int64)
     tile_len = ranges[:, 1] - ranges[:, 0]
@@ -269,6 +271,11 @@ def main() -> int:
     mpad[:H, :W] = mask
     tile_has_mask = mpad.view(th, 16, tw, 16).amax(dim=(1, 3)).reshape(-1) != 0
     pairs_masked_tiles = int(tile_len[tile_has_mask].sum().item())
+    # ... and, of those, the pairs the record holds a row for (counted at some pixel of their tile)
+    if state.get("rows_per_tile") is not None:
+        rows_masked_tiles = int(state["rows_per_tile"].to(torch.int64)[tile_has_mask].sum().item())
+    else:
+        rows_masked_tiles = pairs_masked_tiles
 
     # algorithmic work per launch of each kernel group (the design doc section 7 states the per-unit figures)
     g_in = 4 * (3 + 3 + 4 + 1 + 3 * K)            # bytes of one Gaussian's parameters (236 at degree 3)
@@ -282,7 +289,7 @@ def main() -> int:
         "render_bwd": ("alu", BWD_FLOPS_PER_EVAL * evals + BWD_FLOPS_PER_BLEND * blends),
         "preprocess_bwd": ("hbm", 48 * R + n * 8 + n_vis * (g_in + 3) + n * (g_in + 8)),
         "error_mask": ("hbm", pixels * (4 + 1) if fused else pixels * (24 + 4 + 4 + 1)),
-        "score": ("hbm", pairs_masked_tiles * (32 + 4) + pixels),
+        "score": ("hbm", pairs_masked_tiles * 1 + rows_masked_tiles * (32 + 4) + pixels),
     }
     if args.radix_sort or args.per_splat_bwd or args.compact_box:
         for k in ("emit_pairs", "order_pairs"):      # (the models above describe the default ordering)

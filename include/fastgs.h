@@ -278,6 +278,14 @@ int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bi
                         const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
                         int32_t *counts);
 
+/* The size of the record behind fs_set_score_record, per tile: rows_per_tile [tiles_y * tiles_x] int32 (device,
+ * OVERWRITTEN) receives, for every tile, how many pairs of its list the score of Sec. 4.2 counts at one or more of the
+ * tile's pixels under the all-ones mask -- the pairs the record keeps 32 bytes for, and all that a count pass from the
+ * record reads.  A diagnostic (bench.py prices the count pass with it); nothing on the path needs it.
+ * Errors: FS_EINVAL when the latest forward pass on the ctx left no record for `bins` (record switched off, no
+ * pairs, other bins); FS_EHIP. */
+int fs_score_record_rows(fs_ctx *ctx, const fs_bins *bins, const fs_camera *cam, int32_t *rows_per_tile);
+
 /* Photometric loss of one view (Sec. 4.3: E_photo; Sec. 4.5: the training loss has the same form):
  *   E = (1 - lambda) * L1 + lambda * (1 - SSIM),  L1 = mean |image - target| over the 3*H*W values.
  * SSIM (the paper cites the index without restating it): per channel, local means / variances /

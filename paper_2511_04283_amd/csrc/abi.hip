@@ -58,6 +58,7 @@ struct fs_ctx {
     int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
     const void* bits_order = nullptr;  // ... with this gauss_sorted, on this many tiles; -1: they describe nothing
     int bits_tiles = 0;
+    int64_t longest_list = 0;        // longest tile list of the latest fs_bin_sort (0: not known, the radix ordering)
     int64_t fused_pixels = 0;        // > 0: err_map / partial hold the error map of the last fs_render_fwd_loss
 
     // per-group event timing (measurement only)
@@ -442,6 +443,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     if (P >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: pair count does not fit 31 bits");
     if (NR >= (uint64_t)1 << 31) return fail(ctx, FS_ECAPACITY, "fs_bin_sort: candidate tile count does not fit 31 bits");
     const uint64_t max_len = bucketed ? ctx->total_host[3] : 0;
+    ctx->longest_list = (int64_t)max_len;
     const bool lds_sort = bucketed && max_len <= (uint64_t)TILE_SORT_HUGE;
     // did what was enqueued ahead cover this call?  (growing a buffer below waits for the stream first)
     const bool spec_fits = spec_variants != 0 && P <= cap_pairs && (!cb || NR <= cap_recs);
@@ -733,13 +735,29 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
         ctx->bits_tiles == cd.tiles_x * cd.tiles_y) {
         // the latest forward pass over these bins recorded where each pair is counted: no second walk
         FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, bins->tile_order, bins->gauss_sorted, ctx->pair_bits.ptr,
-                                 pair_flags_of(ctx, bins->num_pairs), mask, counts),
+                                 pair_flags_of(ctx, bins->num_pairs), mask, counts, ctx->longest_list),
                "k_score_bits");
         return FS_OK;
     }
     FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                         static_cast<const float*>(bins->splats), n_contrib, mask, counts),
            "k_score");
+    return FS_OK;
+}
+
+int fs_score_record_rows(fs_ctx* ctx, const fs_bins* bins, const fs_camera* cam, int32_t* rows_per_tile)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!make_cam(cam, cd) || !bins || !rows_per_tile) return fail(ctx, FS_EINVAL, "fs_score_record_rows: bad arguments");
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_score_record_rows: bins do not come from this context's latest fs_bin_sort");
+    const int tiles = cd.tiles_x * cd.tiles_y;
+    if (ctx->bits_pairs != bins->num_pairs || ctx->bits_order != bins->gauss_sorted || ctx->bits_tiles != tiles)
+        return fail(ctx, FS_EINVAL, "fs_score_record_rows: the latest forward pass on this context left no record for these bins");
+    if (!bins->tile_ranges) return fail(ctx, FS_EINVAL, "fs_score_record_rows: null array");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    FS_HIP(launch_record_rows(ctx->stream, tiles, bins->tile_ranges, pair_flags_of(ctx, bins->num_pairs), rows_per_tile),
+           "k_record_rows");
     return FS_OK;
 }
 

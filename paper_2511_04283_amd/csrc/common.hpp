@@ -235,7 +235,8 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
 // (tiles are taken in tile_order)
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
                              const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
-                             int32_t* counts);
+                             int32_t* counts, int64_t longest_list);
+hipError_t launch_record_rows(hipStream_t st, int tiles, const uint32_t* ranges, const void* pair_flags, int32_t* rows);
 // stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,

@@ -1037,19 +1037,27 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 
 // Count pass from the bits a k_render_fwd<., true> launch left: per tile, the mask of its 256 pixels in the same
 // layout as a pair's bits, then one population count per pair of the tile's list.  Tiles without mask pixels
-// read nothing else.
+// read nothing else.  Workgroup (x, y) takes entries [y * chunk, (y + 1) * chunk) of tile x's list, so that a list of
+// thousands of entries is not one workgroup's chain of dependent loads; a workgroup past the end of its list leaves
+// at once.
 __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges,
                                                     const uint32_t* __restrict__ tile_order,
                                                     const uint32_t* __restrict__ gauss_sorted,
                                                     const uint4* __restrict__ pair_bits,
                                                     const uint8_t* __restrict__ pair_flags,
-                                                    const uint8_t* __restrict__ mask, int32_t* __restrict__ counts)
+                                                    const uint8_t* __restrict__ mask, int32_t* __restrict__ counts,
+                                                    uint32_t chunk)
 {
     __shared__ __align__(16) uint16_t s_m[16];
     const int tile = (int)tile_order[blockIdx.x];  // longest lists first
+    uint2 range = ranges[tile];
+    if (gridDim.y > 1) {
+        if (range.y - range.x <= blockIdx.y * chunk) return;   // (uniform over the workgroup)
+        range.x += blockIdx.y * chunk;
+        range.y = min(range.y, range.x + chunk);
+    }
     const Pixel p = pixel_of_thread(cam, tile);
     const int lane = threadIdx.x & 63;
-    const uint2 range = ranges[tile];
     const bool on = p.inside && mask[(size_t)p.y * cam.width + p.x] != 0;
     // the first 256 pairs' bits are requested before the tile's mask is known, so that the two latencies overlap
     uint32_t pos = range.x + threadIdx.x;
@@ -1080,6 +1088,21 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
         if (next >= range.y) break;
         pos = next; a = a2; c = c2; g = g2;
     }
+}
+
+// Per tile, how many pairs of its list have a row in the record (a flag of 1): one wavefront per tile.
+__global__ __launch_bounds__(64) void k_record_rows(int tiles, const uint2* __restrict__ ranges,
+                                                   const uint8_t* __restrict__ pair_flags, int32_t* __restrict__ rows)
+{
+    const int tile = (int)blockIdx.x;
+    if (tile >= tiles) return;
+    const uint2 range = ranges[tile];
+    int n = 0;
+    for (uint32_t base = range.x; base < range.y; base += 64) {
+        const uint32_t pos = base + threadIdx.x;
+        n += __popcll(__ballot(pos < range.y && pair_flags[pos] != 0));
+    }
+    if (threadIdx.x == 0) rows[tile] = n;
 }
 
 }  // namespace
@@ -1126,12 +1149,25 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
 
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
                              const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
-                             int32_t* counts)
+                             int32_t* counts, int64_t longest_list)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_score_bits, dim3(tiles), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
-                       static_cast<const uint4*>(pair_bits), static_cast<const uint8_t*>(pair_flags), mask, counts);
+    // lists beyond SCORE_CHUNK entries are shared out among several workgroups (longest_list 0: not known, one each)
+    constexpr uint32_t SCORE_CHUNK = 4096;
+    const int64_t chunks = longest_list > 0 ? (longest_list + SCORE_CHUNK - 1) / SCORE_CHUNK : 1;
+    const unsigned gy = chunks <= 4096 ? (unsigned)chunks : 1u;   // (beyond any real list: every workgroup takes its whole list)
+    hipLaunchKernelGGL(k_score_bits, dim3(tiles, gy), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges),
+                       tile_order, gauss_sorted, static_cast<const uint4*>(pair_bits),
+                       static_cast<const uint8_t*>(pair_flags), mask, counts, SCORE_CHUNK);
+    return hipGetLastError();
+}
+
+hipError_t launch_record_rows(hipStream_t st, int tiles, const uint32_t* ranges, const void* pair_flags, int32_t* rows)
+{
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_record_rows, dim3(tiles), dim3(64), 0, st, tiles, reinterpret_cast<const uint2*>(ranges),
+                       static_cast<const uint8_t*>(pair_flags), rows);
     return hipGetLastError();
 }
 

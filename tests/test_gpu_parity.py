@@ -474,6 +474,17 @@ def test_counts_from_the_forward_record_equal_the_walk_and_the_oracle(orc32, mod
     cnt_all = torch.zeros(sc.n, dtype=torch.int32, device=c.device)
     c.fs_score_accumulate(proj, bins, fcam, fT, nc, ones, cnt_all)
     assert np.array_equal(cnt_all.cpu().numpy(), o.score(p_o, b_o, cam, np.ones((H, W), np.uint8), np.zeros(sc.n, np.int32)))
+    # (5) the size of the record: per tile, the pairs with a counted pixel somewhere in the tile
+    rows = c.fs_score_record_rows(bins, fcam).cpu().numpy()
+    ones_np = np.ones((H, W), np.uint8)
+    for t in range(rows.shape[0]):
+        in_tile = o.score(p_o, b_o, cam, ones_np, np.zeros(sc.n, np.int32), tile_list=[t])
+        assert rows[t] == np.count_nonzero(in_tile), t
+    assert 0 < rows.sum() <= bins.num_pairs
+    c.fs_set_score_record(False)
+    c.fs_render_fwd(proj, bins, fcam)
+    with pytest.raises(RuntimeError):
+        c.fs_score_record_rows(bins, fcam)      # no record behind the latest forward pass
     c.close()
 
 
