@@ -289,7 +289,7 @@ def main() -> int:
         "render_bwd": ("alu", BWD_FLOPS_PER_EVAL * evals + BWD_FLOPS_PER_BLEND * blends),
         "preprocess_bwd": ("hbm", 48 * R + n * 8 + n_vis * (g_in + 3) + n * (g_in + 8)),
         "error_mask": ("hbm", pixels * (4 + 1) if fused else pixels * (24 + 4 + 4 + 1)),
-        "score": ("hbm", pairs_masked_tiles * 1 + rows_masked_tiles * (32 + 4) + pixels),
+        "score": ("hbm", rows_masked_tiles * (32 + 4) + 8 * tiles + pixels),
     }
     if args.radix_sort or args.per_splat_bwd or args.compact_box:
         for k in ("emit_pairs", "order_pairs"):      # (the models above describe the default ordering)

@@ -217,7 +217,8 @@ int fs_error_mask_fused(fs_ctx *ctx, int32_t height, int32_t width, int32_t rule
                         float *threshold_out);
 
 /* Whether the forward passes (fs_render_fwd, fs_render_fwd_loss) also record, for every pair, at which pixels of its
- * tile the multi-view score (Sec. 4.2) counts the pair's Gaussian: 32 bytes per pair of ctx scratch.  On by default.
+ * tile the multi-view score (Sec. 4.2) counts the pair's Gaussian: up to 36 bytes per pair of ctx scratch (pairs that are
+ * counted nowhere leave nothing).  On by default.
  * When the latest forward pass on the ctx over `bins` made such a record, fs_score_accumulate takes its counts from it
  * (one population count per pair against the tile's mask) instead of walking the tile lists a second time; it then
  * reads neither final_T nor n_contrib, and the counts are the same.  The record costs the forward kernel some time
@@ -280,8 +281,8 @@ int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bi
 
 /* The size of the record behind fs_set_score_record, per tile: rows_per_tile [tiles_y * tiles_x] int32 (device,
  * OVERWRITTEN) receives, for every tile, how many pairs of its list the score of Sec. 4.2 counts at one or more of the
- * tile's pixels under the all-ones mask -- the pairs the record keeps 32 bytes for, and all that a count pass from the
- * record reads.  A diagnostic (bench.py prices the count pass with it); nothing on the path needs it.
+ * tile's pixels under the all-ones mask -- the pairs the record keeps a row of 32 + 4 bytes for, and all that a count
+ * pass from the record reads.  A diagnostic (bench.py prices the count pass with it); nothing on the path needs it.
  * Errors: FS_EINVAL when the latest forward pass on the ctx left no record for `bins` (record switched off, no
  * pairs, other bins); FS_EHIP. */
 int fs_score_record_rows(fs_ctx *ctx, const fs_bins *bins, const fs_camera *cam, int32_t *rows_per_tile);

@@ -51,8 +51,7 @@ struct fs_ctx {
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
     bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
     ScratchBuf tile_partial;         // double [5, tiles]: per-tile sums of the fused forward pass
-    ScratchBuf pair_bits;            // [P, PAIR_BITS_BYTES] then [P] bytes: per pair, the pixels of its tile at which the
-                                     // score counts it, and whether there is any
+    ScratchBuf pair_bits;            // the record of the forward passes for the count pass (score_record_at)
     bool per_splat_bwd = false;      // fs_set_backward_mode
     bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
     int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
@@ -217,12 +216,6 @@ bool proj_ok(const fs_projected* p)
 
 // bins of an earlier fs_bin_sort (or of another ctx) point at memory that has been reused since
 bool bins_stale(const fs_ctx* ctx, const fs_bins* bins) { return bins->generation != ctx->generation || ctx->generation == 0; }
-
-// the bytes behind the rows of ctx->pair_bits: one flag per pair (ensure gives PAIR_BITS_BYTES + 1 bytes per pair)
-void* pair_flags_of(const fs_ctx* ctx, int64_t num_pairs)
-{
-    return static_cast<uint8_t*>(ctx->pair_bits.ptr) + (size_t)num_pairs * PAIR_BITS_BYTES;
-}
 
 // the record in ctx->pair_bits now describes the forward pass over these bins
 void note_bits(fs_ctx* ctx, const fs_bins* bins, int tiles)
@@ -533,11 +526,11 @@ int fs_render_fwd(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, co
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
     ctx->bits_pairs = -1;   // (what an earlier forward pass recorded for the count pass does not describe this one)
     const bool bits = ctx->record_bits && bins->num_pairs > 0;
-    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, (size_t)bins->num_pairs * (PAIR_BITS_BYTES + 1), "score bits"));
+    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, score_record_bytes(bins->num_pairs, cd.tiles_x * cd.tiles_y), "score record"));
     ProfScope prof(ctx, FS_K_RENDER_FWD);
     FS_HIP(launch_render_fwd(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
                              static_cast<const float*>(bins->splats), image, final_T, n_contrib,
-                             bits ? ctx->pair_bits.ptr : nullptr, bits ? pair_flags_of(ctx, bins->num_pairs) : nullptr),
+                             bits ? score_record_at(ctx->pair_bits.ptr, bins->num_pairs) : ScoreRecord{nullptr, nullptr, nullptr}),
            "k_render_fwd");
     if (bits) note_bits(ctx, bins, cd.tiles_x * cd.tiles_y);
     return FS_OK;
@@ -562,14 +555,13 @@ int fs_render_fwd_loss(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bin
     FS_TRY(ensure(ctx, ctx->err_map, (size_t)(pixels + 1) * sizeof(float), "error map"));
     FS_TRY(ensure(ctx, ctx->partial, (size_t)fused_partials() * sizeof(double), "partials"));
     FS_TRY(ensure(ctx, ctx->tile_partial, (size_t)5 * tiles * sizeof(double), "tile partials"));
-    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, (size_t)bins->num_pairs * (PAIR_BITS_BYTES + 1), "score bits"));
+    if (bits) FS_TRY(ensure(ctx, ctx->pair_bits, score_record_bytes(bins->num_pairs, cd.tiles_x * cd.tiles_y), "score record"));
     {
         ProfScope prof(ctx, FS_K_RENDER_FWD);
         FS_HIP(launch_render_fwd_fused(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order,
                                        bins->gauss_sorted, static_cast<const float*>(bins->splats), image, final_T, n_contrib,
                                        target, dL_dimage, static_cast<float*>(ctx->err_map.ptr),
-                                       static_cast<double*>(ctx->tile_partial.ptr), bits ? ctx->pair_bits.ptr : nullptr,
-                                       bits ? pair_flags_of(ctx, bins->num_pairs) : nullptr),
+                                       static_cast<double*>(ctx->tile_partial.ptr), bits ? score_record_at(ctx->pair_bits.ptr, bins->num_pairs) : ScoreRecord{nullptr, nullptr, nullptr}),
                "k_render_fwd");
     }
     if (bits) note_bits(ctx, bins, tiles);
@@ -734,8 +726,8 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     if (ctx->bits_pairs == bins->num_pairs && ctx->bits_order == bins->gauss_sorted &&
         ctx->bits_tiles == cd.tiles_x * cd.tiles_y) {
         // the latest forward pass over these bins recorded where each pair is counted: no second walk
-        FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, bins->tile_order, bins->gauss_sorted, ctx->pair_bits.ptr,
-                                 pair_flags_of(ctx, bins->num_pairs), mask, counts, ctx->longest_list),
+        FS_HIP(launch_score_bits(ctx->stream, cd, bins->tile_ranges, score_record_at(ctx->pair_bits.ptr, bins->num_pairs),
+                                 mask, counts, ctx->longest_list),
                "k_score_bits");
         return FS_OK;
     }
@@ -756,7 +748,7 @@ int fs_score_record_rows(fs_ctx* ctx, const fs_bins* bins, const fs_camera* cam,
         return fail(ctx, FS_EINVAL, "fs_score_record_rows: the latest forward pass on this context left no record for these bins");
     if (!bins->tile_ranges) return fail(ctx, FS_EINVAL, "fs_score_record_rows: null array");
     FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
-    FS_HIP(launch_record_rows(ctx->stream, tiles, bins->tile_ranges, pair_flags_of(ctx, bins->num_pairs), rows_per_tile),
+    FS_HIP(launch_record_rows(ctx->stream, tiles, score_record_at(ctx->pair_bits.ptr, bins->num_pairs), rows_per_tile),
            "k_record_rows");
     return FS_OK;
 }

@@ -217,26 +217,45 @@ hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t
 hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
                               uint32_t* ranges, uint32_t* tile_order);
 
-// pair_bits: null, or PAIR_BITS_BYTES per pair, which receive the pixels of its tile at which the multi-view score
-// counts the pair's Gaussian (see launch_score_bits); pair_flags: with it, one byte per pair: whether any bit is set
-// (rows of pairs without one are not written)
+// The record a forward pass leaves for the count pass (see k_score_bits).  For every pair that the multi-view score
+// counts at one or more pixels of its tile: a row of PAIR_BITS_BYTES (which pixels) and the pair's Gaussian.  The rows of
+// a tile sit together at the start of the tile's segment of the pair arrays, [ranges[tile].x, + tile_rows[tile]), in no
+// particular order; pairs that are counted nowhere leave nothing.  rows == null: no record.
 constexpr int PAIR_BITS_BYTES = 32;
+struct ScoreRecord {
+    uint4* rows;           // [P, 2]
+    uint32_t* row_gauss;   // [P]
+    int32_t* tile_rows;    // [tiles]
+};
+inline size_t score_record_bytes(int64_t num_pairs, int tiles)
+{
+    return (size_t)num_pairs * (PAIR_BITS_BYTES + sizeof(uint32_t)) + (size_t)tiles * sizeof(int32_t);
+}
+inline ScoreRecord score_record_at(void* base, int64_t num_pairs)
+{
+    unsigned char* b = static_cast<unsigned char*>(base);
+    ScoreRecord r;
+    r.rows = reinterpret_cast<uint4*>(b);
+    r.row_gauss = reinterpret_cast<uint32_t*>(b + (size_t)num_pairs * PAIR_BITS_BYTES);
+    r.tile_rows = reinterpret_cast<int32_t*>(b + (size_t)num_pairs * (PAIR_BITS_BYTES + sizeof(uint32_t)));
+    return r;
+}
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib, void* pair_bits, void* pair_flags);
+                             uint32_t* n_contrib, const ScoreRecord& record);
 
 // forward pass with the L1 term and the error map fused into its epilogue (see k_render_fwd);
-// tile_partial: 5 * tiles doubles, err: H*W floats, dL may be null; pair_bits as for launch_render_fwd
+// tile_partial: 5 * tiles doubles, err: H*W floats, dL may be null; record as for launch_render_fwd
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial, void* pair_bits, void* pair_flags);
-// the count pass from those bits: counts[g] += |bits(pair) & mask(tile)| over the pairs of every tile
-// (tiles are taken in tile_order)
-hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
-                             const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
-                             int32_t* counts, int64_t longest_list);
-hipError_t launch_record_rows(hipStream_t st, int tiles, const uint32_t* ranges, const void* pair_flags, int32_t* rows);
+                                   float* err, double* tile_partial, const ScoreRecord& record);
+// the count pass from that record: counts[g] += |bits(row) & mask(tile)| over the rows of every tile
+// (longest_list: an upper bound of the rows of any tile, 0 if not known)
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
+                             const uint8_t* mask, int32_t* counts, int64_t longest_list);
+// rows[tile] <- the record's number of rows of the tile
+hipError_t launch_record_rows(hipStream_t st, int tiles, const ScoreRecord& record, int32_t* rows);
 // stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map
 int fused_partials();
 hipError_t launch_fold_tile_partials(hipStream_t st, const double* tile_partial, int tiles, int64_t count,

@@ -283,11 +283,11 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
                                                     float* __restrict__ final_T, uint32_t* __restrict__ n_contrib,
                                                     const float* __restrict__ target, float scale,
                                                     float* __restrict__ dL, float* __restrict__ err,
-                                                    double* __restrict__ tile_partial, uint4* __restrict__ pair_bits,
-                                                    uint8_t* __restrict__ pair_flags)
+                                                    double* __restrict__ tile_partial, ScoreRecord record)
 {
     __shared__ Stage<true> s;
     __shared__ __align__(16) uint16_t s_pb[BITS ? BATCH : 1][16];  // this batch's bits, [slot][sub-tile]
+    __shared__ uint32_t s_rows;                                    // rows of the record this tile has written so far
 
     const int tile = (int)tile_order[blockIdx.x];  // longest lists first
     const int sub = (threadIdx.x >> 6) * 4 + ((threadIdx.x & 63) >> 4);  // this lane's sub-tile list
@@ -307,22 +307,32 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
     // a batch's staging barriers and the barrier at the top of the next batch
     const float hit_above = cfg.score_mode == FS_SCORE_ALPHA ? 0.0f : cfg.alpha_min;
     int pending = -1, pending_m = 0;  // the batch whose bits are in s_pb and not yet in memory (uniform)
-    int reached = 0;                  // list positions below this one have been staged (uniform)
+    if (BITS && threadIdx.x == 0) s_rows = 0;   // (the first use lies behind the barrier at the top of the second batch)
     auto write_bits = [&](int first, int count) {
+        // A pair that is counted nowhere (at 500k Gaussians half of them: the rectangle's corners, entries behind the
+        // last blended one) leaves nothing.  The others' rows are packed at the start of the tile's segment: a
+        // wavefront reserves as many places as it has rows with one LDS atomic, so the order of the rows within the
+        // tile depends on which wavefront comes first (the count pass adds integers: its result does not).
+        uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
         if ((int)threadIdx.x < count) {
             const uint4* row = reinterpret_cast<const uint4*>(s_pb[threadIdx.x]);
-            const size_t pos = (size_t)range.x + first + threadIdx.x;
-            const uint4 lo = row[0], hi = row[1];
-            // a pair that is counted nowhere (a third of them: the rectangle's corners, entries behind the last
-            // blended one) only leaves a zero flag; the count pass then does not read its row
-            const bool any = ((lo.x | lo.y) | (lo.z | lo.w) | (hi.x | hi.y) | (hi.z | hi.w)) != 0u;
-            pair_flags[pos] = any ? 1 : 0;
+            lo = row[0];
+            hi = row[1];
+        }
+        const bool any = ((lo.x | lo.y) | (lo.z | lo.w) | (hi.x | hi.y) | (hi.z | hi.w)) != 0u;
+        const uint64_t bal = __ballot(any);
+        if (bal != 0) {   // (uniform over the wavefront)
+            uint32_t base = 0;
+            if ((threadIdx.x & 63) == 0) base = atomicAdd(&s_rows, (uint32_t)__popcll(bal));
+            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
             if (any) {
+                const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                const size_t at = (size_t)range.x + base + below;
                 // (streaming stores: the record is read once, by the count pass, and should not displace the step's
                 // other arrays from the caches)
-                uint4* dst = pair_bits + pos * 2;
-                nt_store(lo, dst);
-                nt_store(hi, dst + 1);
+                nt_store(lo, record.rows + at * 2);
+                nt_store(hi, record.rows + at * 2 + 1);
+                record.row_gauss[at] = gauss_sorted[(size_t)range.x + first + threadIdx.x];
             }
         }
     };
@@ -340,7 +350,6 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             row[1] = make_uint4(0u, 0u, 0u, 0u);
             pending = start;
             pending_m = m;
-            reached = start + m;
         }
         const int mine = stage_batch<true, 0>(s, nullptr, cam, cfg, tile, gauss_sorted, splats, range.x + start, m);
         // a row whose 16 pixels have all finished does not lengthen the wavefront's loop
@@ -394,8 +403,9 @@ __global__ __launch_bounds__(256) void k_render_fwd(CamDev cam, CfgDev cfg, cons
             __syncthreads();
             write_bits(pending, pending_m);
         }
-        // pairs the loop never reached (every pixel had finished) are blended nowhere
-        for (uint32_t pos = range.x + reached + threadIdx.x; pos < range.y; pos += 256) pair_flags[pos] = 0;
+        // (pairs the loop never reached -- every pixel had finished -- are blended nowhere and leave no row)
+        __syncthreads();
+        if (threadIdx.x == 0) record.tile_rows[tile] = (int32_t)s_rows;
     }
     double l1 = 0.0, esum = 0.0, esq = 0.0, emin = 1.0e300, emax = -1.0e300;
     if (p.inside) {
@@ -1035,139 +1045,128 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
     }
 }
 
-// Count pass from the bits a k_render_fwd<., true> launch left: per tile, the mask of its 256 pixels in the same
-// layout as a pair's bits, then one population count per pair of the tile's list.  Tiles without mask pixels
-// read nothing else.  Workgroup (x, y) takes entries [y * chunk, (y + 1) * chunk) of tile x's list, so that a list of
-// thousands of entries is not one workgroup's chain of dependent loads; a workgroup past the end of its list leaves
-// at once.
-__global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges,
-                                                    const uint32_t* __restrict__ tile_order,
-                                                    const uint32_t* __restrict__ gauss_sorted,
-                                                    const uint4* __restrict__ pair_bits,
-                                                    const uint8_t* __restrict__ pair_flags,
+// Count pass from the record a k_render_fwd<., true> launch left: per tile, the mask of its 256 pixels in the same
+// layout as a row's bits, then one population count per row of the tile.  Tiles without rows or without mask pixels
+// read nothing else.  Workgroup (x, y) takes rows [y * chunk, (y + 1) * chunk) of tile x (the last one whatever is
+// left), so that thousands of rows are not one workgroup's chain of dependent rounds; a workgroup past the tile's last
+// row leaves at once.  (Tiles in plain order: a tile's rows are few, and the detour over the order array would be one
+// more dependent load.)
+__global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges, ScoreRecord record,
                                                     const uint8_t* __restrict__ mask, int32_t* __restrict__ counts,
                                                     uint32_t chunk)
 {
     __shared__ __align__(16) uint16_t s_m[16];
-    const int tile = (int)tile_order[blockIdx.x];  // longest lists first
-    uint2 range = ranges[tile];
-    if (gridDim.y > 1) {
-        if (range.y - range.x <= blockIdx.y * chunk) return;   // (uniform over the workgroup)
-        range.x += blockIdx.y * chunk;
-        range.y = min(range.y, range.x + chunk);
-    }
+    const int tile = (int)blockIdx.x;
+    const uint32_t rows = (uint32_t)record.tile_rows[tile];
+    uint32_t first = blockIdx.y * chunk;
+    if (rows <= first) return;   // (uniform over the workgroup)
+    uint32_t end = blockIdx.y + 1 == gridDim.y ? rows : min(rows, first + chunk);
+    const uint32_t seg = ranges[tile].x;
+    first += seg;
+    end += seg;
     const Pixel p = pixel_of_thread(cam, tile);
     const int lane = threadIdx.x & 63;
     const bool on = p.inside && mask[(size_t)p.y * cam.width + p.x] != 0;
-    // the first 256 pairs' bits are requested before the tile's mask is known, so that the two latencies overlap
-    uint32_t pos = range.x + threadIdx.x;
+    // the first 256 rows are requested before the tile's mask is known, so that the two latencies overlap
+    uint32_t pos = first + threadIdx.x;
     uint4 a = make_uint4(0u, 0u, 0u, 0u), c = a;
     uint32_t g = 0;
-    if (pos < range.y && pair_flags[pos] != 0) {
-        a = nt_load(pair_bits + (size_t)pos * 2);
-        c = nt_load(pair_bits + (size_t)pos * 2 + 1);
-        g = gauss_sorted[pos];
+    if (pos < end) {
+        a = nt_load(record.rows + (size_t)pos * 2);
+        c = nt_load(record.rows + (size_t)pos * 2 + 1);
+        g = record.row_gauss[pos];
     }
     const uint64_t b = __ballot(on);
     if ((lane & 15) == 0) s_m[(threadIdx.x >> 6) * 4 + (lane >> 4)] = (uint16_t)((b >> (lane & 48)) & 0xffffull);
     if (__syncthreads_or(on) == 0) return;
     const uint4 m0 = reinterpret_cast<const uint4*>(s_m)[0], m1 = reinterpret_cast<const uint4*>(s_m)[1];
     for (;;) {
-        // (the next round's record is requested before this round's is counted)
+        // (the next round's rows are requested before this round's are counted)
         const uint32_t next = pos + 256;
         uint4 a2 = make_uint4(0u, 0u, 0u, 0u), c2 = a2;
         uint32_t g2 = 0;
-        if (next < range.y && pair_flags[next] != 0) {
-            a2 = nt_load(pair_bits + (size_t)next * 2);
-            c2 = nt_load(pair_bits + (size_t)next * 2 + 1);
-            g2 = gauss_sorted[next];
+        if (next < end) {
+            a2 = nt_load(record.rows + (size_t)next * 2);
+            c2 = nt_load(record.rows + (size_t)next * 2 + 1);
+            g2 = record.row_gauss[next];
         }
         const int n = __popc(a.x & m0.x) + __popc(a.y & m0.y) + __popc(a.z & m0.z) + __popc(a.w & m0.w) +
                       __popc(c.x & m1.x) + __popc(c.y & m1.y) + __popc(c.z & m1.z) + __popc(c.w & m1.w);
-        if (n != 0) atomicAdd(&counts[g], n);   // (all zeros for a thread past the end of the list)
-        if (next >= range.y) break;
+        if (n != 0) atomicAdd(&counts[g], n);   // (all zeros for a thread past the last row)
+        if (next >= end) break;
         pos = next; a = a2; c = c2; g = g2;
     }
 }
 
-// Per tile, how many pairs of its list have a row in the record (a flag of 1): one wavefront per tile.
-__global__ __launch_bounds__(64) void k_record_rows(int tiles, const uint2* __restrict__ ranges,
-                                                   const uint8_t* __restrict__ pair_flags, int32_t* __restrict__ rows)
+__global__ __launch_bounds__(256) void k_record_rows(int tiles, const int32_t* __restrict__ tile_rows, int32_t* __restrict__ rows)
 {
-    const int tile = (int)blockIdx.x;
-    if (tile >= tiles) return;
-    const uint2 range = ranges[tile];
-    int n = 0;
-    for (uint32_t base = range.x; base < range.y; base += 64) {
-        const uint32_t pos = base + threadIdx.x;
-        n += __popcll(__ballot(pos < range.y && pair_flags[pos] != 0));
-    }
-    if (threadIdx.x == 0) rows[tile] = n;
+    const int tile = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (tile < tiles) rows[tile] = tile_rows[tile];
 }
 
 }  // namespace
 
 hipError_t launch_render_fwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, float* image, float* final_T,
-                             uint32_t* n_contrib, void* pair_bits, void* pair_flags)
+                             uint32_t* n_contrib, const ScoreRecord& record)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    if (pair_bits)
+    const ScoreRecord none = {nullptr, nullptr, nullptr};
+    if (record.rows)
         hipLaunchKernelGGL((k_render_fwd<false, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
-                           nullptr, nullptr, static_cast<uint4*>(pair_bits), static_cast<uint8_t*>(pair_flags));
+                           nullptr, nullptr, record);
     else
         hipLaunchKernelGGL((k_render_fwd<false, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, nullptr, 0.f, nullptr,
-                           nullptr, nullptr, nullptr, nullptr);
+                           nullptr, nullptr, none);
     return hipGetLastError();
 }
 
 hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                                    const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats,
                                    float* image, float* final_T, uint32_t* n_contrib, const float* target, float* dL,
-                                   float* err, double* tile_partial, void* pair_bits, void* pair_flags)
+                                   float* err, double* tile_partial, const ScoreRecord& record)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
     const float scale = 1.0f / (float)((int64_t)3 * cam.width * cam.height);
-    if (pair_bits)
+    const ScoreRecord none = {nullptr, nullptr, nullptr};
+    if (record.rows)
         hipLaunchKernelGGL((k_render_fwd<true, true>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
-                           tile_partial, static_cast<uint4*>(pair_bits), static_cast<uint8_t*>(pair_flags));
+                           tile_partial, record);
     else
         hipLaunchKernelGGL((k_render_fwd<true, false>), dim3(tiles), dim3(256), 0, st, cam, cfg,
                            reinterpret_cast<const uint2*>(ranges), tile_order, gauss_sorted,
                            reinterpret_cast<const float4*>(splats), image, final_T, n_contrib, target, scale, dL, err,
-                           tile_partial, nullptr, nullptr);
+                           tile_partial, none);
     return hipGetLastError();
 }
 
-hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const uint32_t* tile_order,
-                             const uint32_t* gauss_sorted, const void* pair_bits, const void* pair_flags, const uint8_t* mask,
-                             int32_t* counts, int64_t longest_list)
+hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
+                             const uint8_t* mask, int32_t* counts, int64_t longest_list)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    // lists beyond SCORE_CHUNK entries are shared out among several workgroups (longest_list 0: not known, one each)
+    // a workgroup takes SCORE_CHUNK rows (the last one of a tile whatever is left); the longest list bounds the rows
+    // of any tile (0: not known)
     constexpr uint32_t SCORE_CHUNK = 4096;
-    const int64_t chunks = longest_list > 0 ? (longest_list + SCORE_CHUNK - 1) / SCORE_CHUNK : 1;
-    const unsigned gy = chunks <= 4096 ? (unsigned)chunks : 1u;   // (beyond any real list: every workgroup takes its whole list)
-    hipLaunchKernelGGL(k_score_bits, dim3(tiles, gy), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges),
-                       tile_order, gauss_sorted, static_cast<const uint4*>(pair_bits),
-                       static_cast<const uint8_t*>(pair_flags), mask, counts, SCORE_CHUNK);
+    int64_t chunks = longest_list > 0 ? (longest_list + SCORE_CHUNK - 1) / SCORE_CHUNK : 4;
+    if (chunks > 64) chunks = 64;
+    hipLaunchKernelGGL(k_score_bits, dim3(tiles, (unsigned)chunks), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges),
+                       record, mask, counts, SCORE_CHUNK);
     return hipGetLastError();
 }
 
-hipError_t launch_record_rows(hipStream_t st, int tiles, const uint32_t* ranges, const void* pair_flags, int32_t* rows)
+hipError_t launch_record_rows(hipStream_t st, int tiles, const ScoreRecord& record, int32_t* rows)
 {
     if (tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_record_rows, dim3(tiles), dim3(64), 0, st, tiles, reinterpret_cast<const uint2*>(ranges),
-                       static_cast<const uint8_t*>(pair_flags), rows);
+    hipLaunchKernelGGL(k_record_rows, dim3((tiles + 255) / 256), dim3(256), 0, st, tiles, record.tile_rows, rows);
     return hipGetLastError();
 }
 
