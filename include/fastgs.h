@@ -279,6 +279,16 @@ int fs_score_accumulate(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bi
                         const float *final_T, const uint32_t *n_contrib, const uint8_t *mask,
                         int32_t *counts);
 
+/* fs_error_mask_fused followed by fs_score_accumulate, as one call: mask [H,W] (OVERWRITTEN) and *threshold_out (may
+ * be NULL) from the error map that the latest fs_render_fwd_loss on the ctx left, then counts [n] += the view's counts
+ * under that mask (steps a10 + a11, Sec. 4.2).  Same results as the two calls.  When the forward pass left its record
+ * (fs_set_score_record) this is a single kernel launch: the count pass builds each tile's part of the mask on its
+ * way; otherwise the two kernels of the separate calls run, and n_contrib (of that forward pass) is read.
+ * Errors: FS_EINVAL (no pending error map of the camera's size, bins of another fs_bin_sort, null arrays), FS_EHIP. */
+int fs_mask_score_fused(fs_ctx *ctx, const fs_projected *proj, const fs_bins *bins, const fs_camera *cam,
+                        const uint32_t *n_contrib, int32_t rule, float k, uint8_t *mask, float *threshold_out,
+                        int32_t *counts);
+
 /* The size of the record behind fs_set_score_record, per tile: rows_per_tile [tiles_y * tiles_x] int32 (device,
  * OVERWRITTEN) receives, for every tile, how many pairs of its list the score of Sec. 4.2 counts at one or more of the
  * tile's pixels under the all-ones mask -- the pairs the record keeps a row of 32 + 4 bytes for, and all that a count

@@ -25,7 +25,7 @@ FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_error_mask_noalloc", "fs_score_accumulate", "fs_score_record_rows",
+           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_error_mask_noalloc", "fs_score_accumulate", "fs_score_record_rows", "fs_mask_score_fused",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_combine_masks", "fs_counts_add", "fs_split_children", "fs_sample_by_score", "fs_activate_inv",
@@ -116,6 +116,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_error_mask_noalloc.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_score_accumulate.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, vp, vp, vp]
     lib.fs_score_record_rows.argtypes = [vp, P(fs_bins), P(fs_camera), vp]
+    lib.fs_mask_score_fused.argtypes = [vp, P(fs_projected), P(fs_bins), P(fs_camera), vp, ctypes.c_int32, ctypes.c_float, vp, vp, vp]
     lib.fs_photo_loss.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     lib.fs_prune_score_accumulate.argtypes = [vp, vp, i64, vp, vp]
     lib.fs_prune_score_normalize.argtypes = [vp, vp, i64, vp]
@@ -577,6 +578,21 @@ class Context:
                                                  ctypes.byref(cam), _ptr(final_T), _ptr(n_contrib), _ptr(mask),
                                                  _ptr(counts)), "fs_score_accumulate")
         return counts
+
+    def fs_mask_score_fused(self, proj: Projected, bins: Bins, cam: fs_camera, n_contrib, counts, rule=FS_MASK_MEAN_STD,
+                            k=1.0, mask=None, threshold_out=None):
+        H, W = int(cam.height), int(cam.width)
+        if mask is None:
+            mask = torch.empty((H, W), dtype=torch.uint8, device=self.device)
+        if threshold_out is None:
+            threshold_out = torch.empty(1, dtype=torch.float32, device=self.device)
+        _chk(mask, torch.uint8, (H, W), "mask")
+        _chk(counts, torch.int32, (int(proj.depth.shape[0]),), "counts")
+        ps = proj.struct()
+        self._check(self.lib.fs_mask_score_fused(self.handle, ctypes.byref(ps), ctypes.byref(bins.struct), ctypes.byref(cam),
+                                                 _ptr(n_contrib), int(rule), float(k), _ptr(mask), _ptr(threshold_out),
+                                                 _ptr(counts)), "fs_mask_score_fused")
+        return mask, threshold_out, counts
 
     def fs_score_record_rows(self, bins: Bins, cam: fs_camera, rows_per_tile=None):
         tiles = ((int(cam.height) + 15) // 16) * ((int(cam.width) + 15) // 16)

@@ -737,6 +737,47 @@ int fs_score_accumulate(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bi
     return FS_OK;
 }
 
+int fs_mask_score_fused(fs_ctx* ctx, const fs_projected* proj, const fs_bins* bins, const fs_camera* cam,
+                        const uint32_t* n_contrib, int32_t rule, float k, uint8_t* mask, float* threshold_out, int32_t* counts)
+{
+    if (!ctx) return FS_EINVAL;
+    CamDev cd;
+    if (!make_cam(cam, cd) || !bins || !bins->tile_ranges || !bins->tile_order || !n_contrib || !mask ||
+        (rule != FS_MASK_MEAN_STD && rule != FS_MASK_MINMAX_TAU))
+        return fail(ctx, FS_EINVAL, "fs_mask_score_fused: bad arguments");
+    const int64_t pixels = (int64_t)cd.width * cd.height;
+    if (ctx->fused_pixels != pixels)
+        return fail(ctx, FS_EINVAL, "fs_mask_score_fused: no error map of this size from fs_render_fwd_loss is pending");
+    if (bins->num_pairs > 0 && (!proj_ok(proj) || !bins->gauss_sorted || !bins->splats || !counts))
+        return fail(ctx, FS_EINVAL, "fs_mask_score_fused: null array");
+    if (bins_stale(ctx, bins)) return fail(ctx, FS_EINVAL, "fs_mask_score_fused: bins do not come from this context's latest fs_bin_sort");
+    FS_HIP(hipSetDevice(ctx->device), "hipSetDevice");
+    float* err = static_cast<float*>(ctx->err_map.ptr);
+    float* thr = threshold_out ? threshold_out : err + pixels;
+    const int tiles = cd.tiles_x * cd.tiles_y;
+    if (bins->num_pairs > 0 && ctx->bits_pairs == bins->num_pairs && ctx->bits_order == bins->gauss_sorted &&
+        ctx->bits_tiles == tiles) {
+        // one launch: every tile's first workgroup makes (and stores) the tile's part of the mask on its way
+        ProfScope prof(ctx, FS_K_SCORE);
+        FS_HIP(launch_mask_score_bits(ctx->stream, cd, bins->tile_ranges, score_record_at(ctx->pair_bits.ptr, bins->num_pairs),
+                                      err, static_cast<const double*>(ctx->partial.ptr), rule, k, mask, thr, counts,
+                                      ctx->longest_list),
+               "k_score_bits");
+        return FS_OK;
+    }
+    {
+        ProfScope prof(ctx, FS_K_ERR_MASK);
+        FS_HIP(launch_error_mask_from_map(ctx->stream, pixels, rule, k, err, static_cast<double*>(ctx->partial.ptr), mask, thr),
+               "k_err_*");
+    }
+    if (bins->num_pairs == 0) return FS_OK;
+    ProfScope prof(ctx, FS_K_SCORE);
+    FS_HIP(launch_score(ctx->stream, cd, make_cfg(ctx->cfg), bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
+                        static_cast<const float*>(bins->splats), n_contrib, mask, counts),
+           "k_score");
+    return FS_OK;
+}
+
 int fs_score_record_rows(fs_ctx* ctx, const fs_bins* bins, const fs_camera* cam, int32_t* rows_per_tile)
 {
     if (!ctx) return FS_EINVAL;

@@ -217,6 +217,22 @@ hipError_t launch_radix_sort(hipStream_t st, int64_t P, int total_bits, uint64_t
 hipError_t launch_tile_ranges(hipStream_t st, int64_t P, const uint64_t* keys_sorted, int num_tiles,
                               uint32_t* ranges, uint32_t* tile_order);
 
+// The threshold of the mask from the error map's statistics (Sec. 4.2, second and third equations): mean + k * std
+// with the population variance taken as mean(e^2) - mean(e)^2 in double precision (e lies in [0, 1] and the sums
+// are exact to about 1e-13, far below what the single-precision threshold resolves), or min + k * (max - min).
+__device__ __forceinline__ float threshold_from_stats(double sum, double lo, double hi, double sumsq, int64_t pixels,
+                                                      int rule, float k)
+{
+    if (rule == FS_MASK_MEAN_STD) {
+        const double mean = sum / (double)pixels;
+        double var = sumsq / (double)pixels - mean * mean;
+        var = var > 0.0 ? var : 0.0;
+        return (float)(mean + (double)k * sqrt(var));
+    }
+    const float l = (float)lo, h = (float)hi;
+    return l + k * (h - l);
+}
+
 // The record a forward pass leaves for the count pass (see k_score_bits).  For every pair that the multi-view score
 // counts at one or more pixels of its tile: a row of PAIR_BITS_BYTES (which pixels) and the pair's Gaussian.  The rows of
 // a tile sit together at the start of the tile's segment of the pair arrays, [ranges[tile].x, + tile_rows[tile]), in no
@@ -254,6 +270,11 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
 // (longest_list: an upper bound of the rows of any tile, 0 if not known)
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
                              const uint8_t* mask, int32_t* counts, int64_t longest_list);
+// the same with the mask made on the way: mask[p] <- err[p] > threshold(stats, rule, k) for every pixel (stats: the four
+// doubles {sum, min, max, sum of squares} of the error map), *thr_out <- the threshold, then the count as above
+hipError_t launch_mask_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
+                                  const float* err, const double* stats, int rule, float k, uint8_t* mask, float* thr_out,
+                                  int32_t* counts, int64_t longest_list);
 // rows[tile] <- the record's number of rows of the tile
 hipError_t launch_record_rows(hipStream_t st, int tiles, const ScoreRecord& record, int32_t* rows);
 // stats: >= fused_partials() doubles: {sum, min, max, sum of squares} of the error map

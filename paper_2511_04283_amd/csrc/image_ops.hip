@@ -63,22 +63,6 @@ __global__ __launch_bounds__(RED_THREADS) void k_l1_final(const double* __restri
     if (threadIdx.x == 0) *loss_out = s / (double)count;
 }
 
-// The threshold of the mask from the error map's statistics (Sec. 4.2, second and third equations): mean + k * std
-// with the population variance taken as mean(e^2) - mean(e)^2 in double precision (e lies in [0, 1] and the sums
-// are exact to about 1e-13, far below what the single-precision threshold resolves), or min + k * (max - min).
-__device__ __forceinline__ float threshold_from_stats(double sum, double lo, double hi, double sumsq, int64_t pixels,
-                                                      int rule, float k)
-{
-    if (rule == FS_MASK_MEAN_STD) {
-        const double mean = sum / (double)pixels;
-        double var = sumsq / (double)pixels - mean * mean;
-        var = var > 0.0 ? var : 0.0;
-        return (float)(mean + (double)k * sqrt(var));
-    }
-    const float l = (float)lo, h = (float)hi;
-    return l + k * (h - l);
-}
-
 // e = ((|d0| + |d1|) + |d2|) / 3 per pixel; partial sums / minima / maxima / sums of squares per workgroup.
 // VEC = 4: four neighbouring pixels per thread with 16-byte accesses (pixels a multiple of 4, arrays aligned).
 template <int VEC>

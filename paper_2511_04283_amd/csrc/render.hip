@@ -1051,22 +1051,27 @@ __global__ __launch_bounds__(256) void k_score(CamDev cam, CfgDev cfg, const uin
 // left), so that thousands of rows are not one workgroup's chain of dependent rounds; a workgroup past the tile's last
 // row leaves at once.  (Tiles in plain order: a tile's rows are few, and the detour over the order array would be one
 // more dependent load.)
+// FROM_ERR: the mask is not read but made here, mask[p] = err[p] > threshold (Sec. 4.2), by the first workgroup of
+// every tile, which also stores it (mask_out) -- the mask kernel's launch saved.
+template <bool FROM_ERR>
 __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __restrict__ ranges, ScoreRecord record,
                                                     const uint8_t* __restrict__ mask, int32_t* __restrict__ counts,
-                                                    uint32_t chunk)
+                                                    uint32_t chunk, const float* __restrict__ err,
+                                                    const double* __restrict__ stats, int rule, float k,
+                                                    uint8_t* __restrict__ mask_out, float* __restrict__ thr_out)
 {
     __shared__ __align__(16) uint16_t s_m[16];
     const int tile = (int)blockIdx.x;
     const uint32_t rows = (uint32_t)record.tile_rows[tile];
     uint32_t first = blockIdx.y * chunk;
-    if (rows <= first) return;   // (uniform over the workgroup)
+    if (rows <= first && !(FROM_ERR && blockIdx.y == 0)) return;   // (uniform over the workgroup)
     uint32_t end = blockIdx.y + 1 == gridDim.y ? rows : min(rows, first + chunk);
     const uint32_t seg = ranges[tile].x;
     first += seg;
     end += seg;
     const Pixel p = pixel_of_thread(cam, tile);
     const int lane = threadIdx.x & 63;
-    const bool on = p.inside && mask[(size_t)p.y * cam.width + p.x] != 0;
+    const size_t pix = (size_t)p.y * cam.width + p.x;
     // the first 256 rows are requested before the tile's mask is known, so that the two latencies overlap
     uint32_t pos = first + threadIdx.x;
     uint4 a = make_uint4(0u, 0u, 0u, 0u), c = a;
@@ -1076,9 +1081,27 @@ __global__ __launch_bounds__(256) void k_score_bits(CamDev cam, const uint2* __r
         c = nt_load(record.rows + (size_t)pos * 2 + 1);
         g = record.row_gauss[pos];
     }
+    bool on;
+    if (FROM_ERR) {
+        const float thr = threshold_from_stats(stats[0], stats[1], stats[2], stats[3], (int64_t)cam.width * cam.height, rule, k);
+        on = p.inside && err[pix] > thr;
+        if (blockIdx.y == 0) {
+            if (tile == 0 && threadIdx.x == 0) *thr_out = thr;
+            if ((cam.width & 3) == 0 && (reinterpret_cast<uintptr_t>(mask_out) & 3) == 0) {
+                // four neighbouring pixels of a line are four neighbouring lanes: one 4-byte store for them
+                const uint32_t four = (uint32_t)(__ballot(on) >> (lane & 60)) & 0xfu;
+                if ((lane & 3) == 0 && p.inside)
+                    *reinterpret_cast<uint32_t*>(mask_out + pix) = (four & 1u) | (four & 2u) << 7 | (four & 4u) << 14 | (four & 8u) << 21;
+            } else if (p.inside) {
+                mask_out[pix] = on ? 1 : 0;
+            }
+        }
+    } else {
+        on = p.inside && mask[pix] != 0;
+    }
     const uint64_t b = __ballot(on);
     if ((lane & 15) == 0) s_m[(threadIdx.x >> 6) * 4 + (lane >> 4)] = (uint16_t)((b >> (lane & 48)) & 0xffffull);
-    if (__syncthreads_or(on) == 0) return;
+    if (__syncthreads_or(on) == 0 || first >= end) return;
     const uint4 m0 = reinterpret_cast<const uint4*>(s_m)[0], m1 = reinterpret_cast<const uint4*>(s_m)[1];
     for (;;) {
         // (the next round's rows are requested before this round's are counted)
@@ -1148,18 +1171,37 @@ hipError_t launch_render_fwd_fused(hipStream_t st, const CamDev& cam, const CfgD
     return hipGetLastError();
 }
 
+namespace {
+// a workgroup of k_score_bits takes SCORE_CHUNK rows (the last one of a tile whatever is left); the longest list bounds
+// the rows of any tile (0: not known)
+constexpr uint32_t SCORE_CHUNK = 4096;
+unsigned score_chunks(int64_t longest_list)
+{
+    int64_t chunks = longest_list > 0 ? (longest_list + SCORE_CHUNK - 1) / SCORE_CHUNK : 4;
+    return (unsigned)(chunks > 64 ? 64 : chunks);
+}
+}  // namespace
+
 hipError_t launch_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
                              const uint8_t* mask, int32_t* counts, int64_t longest_list)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
-    // a workgroup takes SCORE_CHUNK rows (the last one of a tile whatever is left); the longest list bounds the rows
-    // of any tile (0: not known)
-    constexpr uint32_t SCORE_CHUNK = 4096;
-    int64_t chunks = longest_list > 0 ? (longest_list + SCORE_CHUNK - 1) / SCORE_CHUNK : 4;
-    if (chunks > 64) chunks = 64;
-    hipLaunchKernelGGL(k_score_bits, dim3(tiles, (unsigned)chunks), dim3(256), 0, st, cam, reinterpret_cast<const uint2*>(ranges),
-                       record, mask, counts, SCORE_CHUNK);
+    hipLaunchKernelGGL(k_score_bits<false>, dim3(tiles, score_chunks(longest_list)), dim3(256), 0, st, cam,
+                       reinterpret_cast<const uint2*>(ranges), record, mask, counts, SCORE_CHUNK, nullptr, nullptr, 0, 0.f,
+                       nullptr, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_mask_score_bits(hipStream_t st, const CamDev& cam, const uint32_t* ranges, const ScoreRecord& record,
+                                  const float* err, const double* stats, int rule, float k, uint8_t* mask, float* thr_out,
+                                  int32_t* counts, int64_t longest_list)
+{
+    const int tiles = cam.tiles_x * cam.tiles_y;
+    if (tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_score_bits<true>, dim3(tiles, score_chunks(longest_list)), dim3(256), 0, st, cam,
+                       reinterpret_cast<const uint2*>(ranges), record, nullptr, counts, SCORE_CHUNK, err, stats, rule, k, mask,
+                       thr_out);
     return hipGetLastError();
 }
 

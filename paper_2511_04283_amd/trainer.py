@@ -119,9 +119,8 @@ class Trainer:
             bins = ctx.fs_bin_sort(proj, fcam)
             # forward pass with the error map and the per-pair record of counted pixels fused into it
             image, fT, nc, _ = ctx.fs_render_fwd_loss(proj, bins, fcam, target, want_grad=False)
-            mask, _ = ctx.fs_error_mask_fused(cam.height, cam.width, c.mask_rule, c.mask_k)
             view = torch.zeros(n, dtype=torch.int32, device=dev)
-            ctx.fs_score_accumulate(proj, bins, fcam, fT, nc, mask, view)
+            ctx.fs_mask_score_fused(proj, bins, fcam, nc, view, c.mask_rule, c.mask_k)   # mask, then the view's counts
             out3, _ = ctx.fs_photo_loss(image, target, c.lam, want_grad=False)
             ctx.fs_prune_score_accumulate(view, out3[2:3], acc)
             ctx.fs_counts_add(counts, view)

@@ -402,6 +402,46 @@ def test_fused_forward_gives_what_the_separate_calls_give(ctx, orc32, W, H, rule
         ctx.fs_error_mask_fused(H, W, rule, k)
 
 
+@pytest.mark.parametrize("W,H,rule,k", [(203, 117, 0, 1.0), (128, 96, 1, 0.35), (100, 37, 0, 0.5), (64, 48, 1, 0.2)])
+def test_mask_and_counts_in_one_call(ctx, orc32, W, H, rule, k):
+    """fs_mask_score_fused against fs_error_mask_fused + fs_score_accumulate and against the oracle: mask, threshold
+    and counts bit-exact -- with the forward pass's record (one kernel; widths that are and are not multiples of
+    four take different store paths) and without it (the two kernels of the separate calls)."""
+    import torch
+    from paper_2511_04283_amd import binding as B
+    sc = scenes.tiny_scene(900 + W, 5000, W, H, sh_degree=0, log_scale=(-2.7, 0.7), spread=1.2)
+    cam = sc.cameras[0]
+    tgt_np = np.random.default_rng(W + 1).uniform(0, 1, (3, H, W)).astype(np.float32)
+    g = B.Gaussians.from_scene(sc, ctx.device)
+    fcam = B.make_camera(cam)
+    tgt = torch.from_numpy(tgt_np).to(ctx.device)
+    p_o, b_o, img_o, _, _ = orc32.forward(sc, cam)
+    m_o, thr_o, _ = orc32.error_mask(img_o, tgt_np, rule=rule, k=k)
+    ref = orc32.score(p_o, b_o, cam, m_o, np.zeros(sc.n, np.int32))
+    assert ref.sum() > 0 and 0.01 < m_o.mean() < 0.95
+    proj = ctx.fs_preprocess(g, fcam)
+    bins = ctx.fs_bin_sort(proj, fcam)
+    for record in (True, False):
+        ctx.fs_set_score_record(record)
+        img, fT, nc, dL = ctx.fs_render_fwd_loss(proj, bins, fcam, tgt)
+        mask_a, thr_a = ctx.fs_error_mask_fused(H, W, rule, k)
+        cnt_a = torch.zeros(sc.n, dtype=torch.int32, device=ctx.device)
+        ctx.fs_score_accumulate(proj, bins, fcam, fT, nc, mask_a, cnt_a)
+        cnt_b = torch.full((sc.n,), 7, dtype=torch.int32, device=ctx.device)     # (the counts are added to)
+        mask_b = torch.full((H, W), 9, dtype=torch.uint8, device=ctx.device)
+        mask_b, thr_b, _ = ctx.fs_mask_score_fused(proj, bins, fcam, nc, cnt_b, rule, k, mask=mask_b)
+        assert torch.equal(mask_a, mask_b) and thr_a.item() == thr_b.item(), record
+        assert torch.equal(cnt_a + 7, cnt_b), record
+        assert np.array_equal(mask_b.cpu().numpy(), m_o), record
+        assert np.float32(thr_b.item()).view(np.uint32) == np.float32(thr_o).view(np.uint32), record
+        assert np.array_equal(cnt_a.cpu().numpy(), ref), record
+    ctx.fs_set_score_record(True)
+    # without a pending error map the call is refused
+    ctx.fs_l1_grad(img, tgt)
+    with pytest.raises(RuntimeError):
+        ctx.fs_mask_score_fused(proj, bins, fcam, nc, cnt_b, rule, k)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("case", ["transparent", "opaque", "long_lists"])
 def test_counts_from_the_forward_record_equal_the_walk_and_the_oracle(orc32, mode, case):
