@@ -38,7 +38,7 @@ GROUPS = {
     "render_bwd": ["k_render_bwd<false>", "k_render_bwd_splat<false>"],
     "preprocess_bwd": ["k_preprocess_bwd<"],
     "error_mask": ["k_err_mask_stats"],
-    "score": ["k_score_bits"],
+    "score": ["k_score_bits<true>"],   # (the mask is made inside the count pass: fs_mask_score_fused)
 }
 
 
