@@ -263,6 +263,9 @@ def main() -> int:
     blends_t = torch.zeros(n, dtype=torch.int32, device=dev)
     ctxA.fs_score_accumulate(projA, binsA, fcam, TA, ncA, torch.ones((H, W), dtype=torch.uint8, device=dev), blends_t)
     blends = int(blends_t.to(torch.int64).sum().item())               # blended (Gaussian, pixel) pairs
+    # pairs blended at one or more pixels of their tile: those that receive a gradient record in the sparse layout
+    # (in this score mode a pair has a row in the forward pass's record exactly then)
+    pairs_blended = int(ctxA.fs_score_record_rows(binsA, fcam).to(torch.int64).sum().item()) if int(binsA.num_pairs) > 0 else 0
     ctxA.close()
     del projA, imA, TA, ncA, blends_t
     # pairs of the tiles that hold at least one mask pixel (what the count pass has to read)
@@ -281,13 +284,15 @@ def main() -> int:
     g_in = 4 * (3 + 3 + 4 + 1 + 3 * K)            # bytes of one Gaussian's parameters (236 at degree 3)
     g_proj = 8 + 4 + 16 + 12 + 8 + 4 + 3           # bytes of one projected splat (fs_projected)
     copies = 256                                   # workgroups of the counting / placement kernels
+    # (the library's own rule for FS_RECORDS_AUTO: sparse per-pair gradient records when the lists are long on average)
+    sparse_records = P >= 320 * tiles
     work = {
         "preprocess": ("hbm", n * (12 + g_proj) + n_vis * (g_in - 12)),
         "emit_pairs": ("hbm", n * 16 + n_vis * 4 + 3 * 4 * tiles * copies + 16 * tiles),
         "order_pairs": ("hbm", n * 8 + n_vis * (44 + 64) + P * 8 + P * (8 + 12) + 4 * tiles * copies),
         "render_fwd": ("alu", FWD_FLOPS_PER_EVAL * evals + FWD_FLOPS_PER_BLEND * blends),
         "render_bwd": ("alu", BWD_FLOPS_PER_EVAL * evals + BWD_FLOPS_PER_BLEND * blends),
-        "preprocess_bwd": ("hbm", 48 * R + n * 8 + n_vis * (g_in + 3) + n * (g_in + 8)),
+        "preprocess_bwd": ("hbm", (48 * pairs_blended + 2 * R if sparse_records else 48 * R) + n * 8 + n_vis * (g_in + 3) + n * (g_in + 8)),
         "error_mask": ("hbm", pixels * (24 + 4 + 4 + 1)),     # (separate calls only; fused: part of the count pass)
         "score": ("hbm", rows_masked_tiles * (32 + 4) + 8 * tiles + (pixels * (4 + 1) if fused else pixels)),
     }
@@ -339,6 +344,7 @@ def main() -> int:
                                (f"+compact_box(beta={args.cb_beta:g})" if args.compact_box else ""),
                    "gaussians": n, "visible": n_vis, "sh_degree": sc.sh_degree, "image": [W, H],
                    "pairs": P, "max_tile_list": int(tile_len.max().item()),
+                   "backward_records": "sparse" if sparse_records else "dense", "pairs_blended_somewhere": pairs_blended,
                    "step": ("activate+" if args.train_iteration else "") + "preprocess+bin_sort+" +
                            ("render_fwd_loss(render_fwd+l1_grad+error map fused)" if fused else
                             "render_fwd+" + ("photo_loss" if args.photo_loss else "l1_grad")) + "+render_bwd+" +

@@ -12,6 +12,7 @@
  *                        the forward pass with the L1 term and the error map fused into it
  *   fs_render_bwd        gradient of a loss w.r.t. every Gaussian parameter     (chain rule of Eqs. (2)-(5))
  *   fs_set_backward_mode per-pixel (default) or per-splat-parallel mapping of it (Sec. 5.3: the baseline's backward)
+ *   fs_set_record_mode   dense or sparse per-pair gradient records between its two kernels
  *   fs_error_mask        per-pixel L1 error map and high-error mask             (Sec. 4.2, first three equations)
  *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
  *                        one view per call                                      (Sec. 4.2, Eq. for s_d)
@@ -250,6 +251,17 @@ int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, cons
  *   lists as sparse as the benchmark's it is the slower of the two, and it is kept for comparison. */
 enum { FS_BWD_PER_PIXEL = 0, FS_BWD_PER_SPLAT = 1 };
 int fs_set_backward_mode(fs_ctx *ctx, int32_t mode);
+
+/* How fs_render_bwd hands the per-pair gradients of the compositing (step a8) to the per-Gaussian sums (step a9);
+ * same results either way:
+ * FS_RECORDS_DENSE: every pair gets a 48-byte record, zeros where it received nothing; the sums read them all.
+ * FS_RECORDS_SPARSE: only pairs that received something (blended at some pixel of their tile) get a record and a
+ *   flag byte; the sums read the flags and the flagged records.  Pays where most pairs receive nothing -- deep,
+ *   opaque scenes whose lists are long and mostly end behind the pixels' last blended Gaussian -- and costs a few
+ *   microseconds otherwise (one more scattered byte per record, one more dependent load per chunk of records).
+ * FS_RECORDS_AUTO (default): sparse when the tile lists hold 320 pairs or more on average. */
+enum { FS_RECORDS_AUTO = 0, FS_RECORDS_DENSE = 1, FS_RECORDS_SPARSE = 2 };
+int fs_set_record_mode(fs_ctx *ctx, int32_t mode);
 
 /* Step a10: e = mean over channels of |image - target|; threshold t = mean(e) + k*std(e)
  * (FS_MASK_MEAN_STD; population std, fp64 accumulation) or min(e) + k*(max(e)-min(e))

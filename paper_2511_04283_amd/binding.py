@@ -21,11 +21,12 @@ FS_OK = 0
 FS_SCORE_WEIGHT, FS_SCORE_ALPHA = 0, 1
 FS_SORT_AUTO, FS_SORT_RADIX = 0, 1
 FS_BWD_PER_PIXEL, FS_BWD_PER_SPLAT = 0, 1
+FS_RECORDS_AUTO, FS_RECORDS_DENSE, FS_RECORDS_SPARSE = 0, 1, 2
 FS_MASK_MEAN_STD, FS_MASK_MINMAX_TAU = 0, 1
 _STATUS = {0: "FS_OK", -1: "FS_EINVAL", -2: "FS_ENOMEM", -3: "FS_EHIP", -4: "FS_ECAPACITY"}
 
 EXPORTS = ("fs_default_config", "fs_create", "fs_destroy", "fs_last_error", "fs_preprocess", "fs_bin_sort",
-           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_error_mask_noalloc", "fs_score_accumulate", "fs_score_record_rows", "fs_mask_score_fused",
+           "fs_render_fwd", "fs_render_fwd_loss", "fs_set_score_record", "fs_set_backward_mode", "fs_set_record_mode", "fs_error_mask_fused", "fs_l1_grad", "fs_render_bwd", "fs_error_mask", "fs_error_mask_noalloc", "fs_score_accumulate", "fs_score_record_rows", "fs_mask_score_fused",
            "fs_photo_loss", "fs_prune_score_accumulate", "fs_prune_score_normalize",
            "fs_densify_accumulate", "fs_select", "fs_compact", "fs_gather_rows",
            "fs_combine_masks", "fs_counts_add", "fs_split_children", "fs_sample_by_score", "fs_activate_inv",
@@ -111,6 +112,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_error_mask_fused.argtypes = [vp, i32, i32, i32, f32, vp, vp]
     lib.fs_set_score_record.argtypes = [vp, i32]
     lib.fs_set_backward_mode.argtypes = [vp, i32]
+    lib.fs_set_record_mode.argtypes = [vp, i32]
     lib.fs_render_bwd.argtypes = [vp, P(fs_gaussians), P(fs_camera), P(fs_projected), P(fs_bins), vp, vp, vp, P(fs_grads)]
     lib.fs_error_mask.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
     lib.fs_error_mask_noalloc.argtypes = [vp, vp, vp, i32, i32, i32, f32, vp, vp]
@@ -367,6 +369,9 @@ class Context:
 
     def fs_set_backward_mode(self, mode: int):
         self._check(self.lib.fs_set_backward_mode(self.handle, int(mode)), "fs_set_backward_mode")
+
+    def fs_set_record_mode(self, mode: int):
+        self._check(self.lib.fs_set_record_mode(self.handle, int(mode)), "fs_set_record_mode")
 
     def fs_set_score_record(self, on: bool):
         self._check(self.lib.fs_set_score_record(self.handle, 1 if on else 0), "fs_set_score_record")

@@ -52,7 +52,12 @@ struct fs_ctx {
     bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
     ScratchBuf tile_partial;         // double [5, tiles]: per-tile sums of the fused forward pass
     ScratchBuf pair_bits;            // the record of the forward passes for the count pass (score_record_at)
+    ScratchBuf rec_valid;            // uint8 [records]: 1 where k_render_bwd left a gradient record; k_preprocess_bwd puts
+                                     // every flag it finds back to 0, so the array is all zeros between calls
+    size_t rec_valid_zeroed = 0;     // the capacity of rec_valid that has been zeroed since its allocation
+    bool rec_valid_dirty = false;    // a call ended between the kernel that sets flags and the one that clears them
     bool per_splat_bwd = false;      // fs_set_backward_mode
+    int record_mode = FS_RECORDS_AUTO;   // fs_set_record_mode
     bool record_bits = true;         // the forward passes fill pair_bits (fs_set_score_record)
     int64_t bits_pairs = -1;         // pair_bits describe the latest forward pass over the bins of this many pairs,
     const void* bits_order = nullptr;  // ... with this gauss_sorted, on this many tiles; -1: they describe nothing
@@ -294,7 +299,7 @@ void fs_destroy(fs_ctx* ctx)
     (void)hipStreamSynchronize(ctx->stream);
     ScratchBuf* all[] = {&ctx->offsets, &ctx->scan_tmp, &ctx->keys[0], &ctx->keys[1], &ctx->vals[0], &ctx->vals[1],
                          &ctx->hist, &ctx->ranges, &ctx->pair_grad, &ctx->splats, &ctx->rec_counts, &ctx->rec_offsets,
-                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial, &ctx->pair_bits,
+                         &ctx->err_map, &ctx->ssim_maps, &ctx->partial, &ctx->tile_partial, &ctx->pair_bits, &ctx->rec_valid,
                          &ctx->compact_pos, &ctx->compact_scan, &ctx->sel_keys[0], &ctx->sel_keys[1], &ctx->sel_vals[0],
                          &ctx->sel_vals[1], &ctx->sel_hist};
     for (ScratchBuf* b : all)
@@ -581,6 +586,15 @@ int fs_set_backward_mode(fs_ctx* ctx, int32_t mode)
     return FS_OK;
 }
 
+int fs_set_record_mode(fs_ctx* ctx, int32_t mode)
+{
+    if (!ctx) return FS_EINVAL;
+    if (mode != FS_RECORDS_AUTO && mode != FS_RECORDS_DENSE && mode != FS_RECORDS_SPARSE)
+        return fail(ctx, FS_EINVAL, "fs_set_record_mode: unknown mode");
+    ctx->record_mode = mode;
+    return FS_OK;
+}
+
 int fs_set_score_record(fs_ctx* ctx, int32_t on)
 {
     if (!ctx) return FS_EINVAL;
@@ -647,21 +661,37 @@ int fs_render_bwd(fs_ctx* ctx, const fs_gaussians* g, const fs_camera* cam, cons
     FS_TRY(ensure(ctx, ctx->pair_grad, (size_t)(bins->num_records ? bins->num_records : 1) * PAIR_REC * sizeof(float),
                   "pair gradients"));
     float* pair_grad = static_cast<float*>(ctx->pair_grad.ptr);
+    // sparse records: one flag per record place, all zeros here (a fresh or left-over array is cleared first)
+    const int tiles = cd.tiles_x * cd.tiles_y;
+    const bool sparse = ctx->record_mode == FS_RECORDS_SPARSE ||
+                        (ctx->record_mode == FS_RECORDS_AUTO && bins->num_pairs >= (int64_t)320 * tiles);
+    uint8_t* rec_valid = nullptr;
+    if (sparse) {
+        FS_TRY(ensure(ctx, ctx->rec_valid, ((size_t)(bins->num_records ? bins->num_records : 1) + 3) / 4 * 4, "record flags"));
+        if (ctx->rec_valid_zeroed != ctx->rec_valid.cap || ctx->rec_valid_dirty) {
+            FS_HIP(launch_fill_u32(st, static_cast<uint32_t*>(ctx->rec_valid.ptr), 0u, (int64_t)(ctx->rec_valid.cap / 4)), "k_fill_u32");
+            ctx->rec_valid_zeroed = ctx->rec_valid.cap;
+        }
+        rec_valid = static_cast<uint8_t*>(ctx->rec_valid.ptr);
+        ctx->rec_valid_dirty = true;
+    }
     const CfgDev cf = make_cfg(ctx->cfg);
-    // a8: every pair's record is written exactly once
+    // a8: every pair's record is written exactly once (sparse: that of every pair that received something, and flagged)
     if (bins->num_pairs > 0) {
         ProfScope prof(ctx, FS_K_RENDER_BWD);
         FS_HIP(launch_render_bwd(st, cd, cf, bins->tile_ranges, bins->tile_order, bins->gauss_sorted,
-                                 static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad,
+                                 static_cast<const float*>(bins->splats), final_T, n_contrib, dL_dimage, pair_grad, rec_valid,
                                  out->dmean2d_abs != nullptr, ctx->per_splat_bwd),
                "k_render_bwd");
     }
-    // a9: per-Gaussian sum of its records, then the chain through the projection
+    // a9: per-Gaussian sum of its records (sparse: the flagged ones; the flags go back to 0), then the chain through
+    // the projection
     ProfScope prof(ctx, FS_K_PREPROCESS_BWD);
     FS_HIP(launch_preprocess_bwd(st, n, g->sh_degree, *g, cd, cf, proj->clamped, proj->tiles_touched,
                                  bins->record_counts ? bins->record_counts : proj->tiles_touched, bins->record_offsets,
-                                 pair_grad, *out),
+                                 pair_grad, rec_valid, *out),
            "k_preprocess_bwd");
+    if (sparse) ctx->rec_valid_dirty = false;
     return FS_OK;
 }
 

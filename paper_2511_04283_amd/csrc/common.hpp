@@ -144,7 +144,7 @@ hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussi
 constexpr int PAIR_REC = 12;
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                                  const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
-                                 const uint32_t* rec_counts, const uint32_t* rec_offsets, const float* pair_grad,
+                                 const uint32_t* rec_counts, const uint32_t* rec_offsets, const float* pair_grad, uint8_t* rec_valid,
                                  const fs_grads& out);
 
 // exclusive scan of n uint32 values; total (uint64) written to *total_dev. tmp: >= scan_tmp_bytes(n).
@@ -286,8 +286,8 @@ hipError_t launch_error_mask_from_map(hipStream_t st, int64_t pixels, int rule, 
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad,
-                             bool per_splat);
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, uint8_t* rec_valid,
+                             bool abs_grad, bool per_splat);
 
 hipError_t launch_score(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                         const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const uint32_t* n_contrib,

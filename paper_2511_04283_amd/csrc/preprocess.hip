@@ -310,13 +310,14 @@ __device__ __forceinline__ float wave_sum_to_last(float v)
 // dL/dsigma, dL/dconic 3, dL/dmu_2D 2, padded to PAIR_REC floats), in a fixed order; then they are
 // chained to the gradients of mean, scale, quaternion and SH coefficients (dL/d opacity needs no
 // chaining).  Outputs are overwritten; culled Gaussians get zeros.  Plain fp32 (not bit-pinned).
-template <int DEG>
+template <int DEG, bool SPARSE>
 __global__ __launch_bounds__(256) void k_preprocess_bwd(
     int64_t n, const float* __restrict__ means, const float* __restrict__ scales, const float* __restrict__ quats,
     const float* __restrict__ opac, const float* __restrict__ sh, CamDev cam, CfgDev cfg,
     const uint8_t* __restrict__ clamped, const uint32_t* __restrict__ touched,
     const uint32_t* __restrict__ rec_counts, const uint32_t* __restrict__ offsets,
-    const float4* __restrict__ pair_grad, float* __restrict__ d_means, float* __restrict__ d_scales,
+    const float4* __restrict__ pair_grad, uint8_t* __restrict__ rec_valid, float* __restrict__ d_means,
+    float* __restrict__ d_scales,
     float* __restrict__ d_quats, float* __restrict__ d_sh, float* __restrict__ d_opac,
     float* __restrict__ d_mean2d, float* __restrict__ d_conic /* may be null */,
     float* __restrict__ d_rgb /* may be null */, float* __restrict__ d_abs /* may be null */)
@@ -374,27 +375,68 @@ __global__ __launch_bounds__(256) void k_preprocess_bwd(
         // while chunk k is added up.  (All loads of a chunk are issued before the first LDS write: written as one
         // loop, each load would be waited for in turn.)
         constexpr int LPL = CH * (PAIR_REC / 4) / 64;
+        static_assert(CH == 128 && PAIR_REC == 12 && LPL == 6, "two records (flag bytes) per lane and chunk, three 16-byte words per record");
         float4 v[LPL];
+        // !SPARSE (dense records, rec_valid unused): every place holds a record; the chunk is read as one run of 16-byte words.
+        // Otherwise (sparse records) only the places whose flag the backward kernel set hold anything: the others are
+        // not read and count as zeros.  Lane l then takes the three words of records l and l + 64 of the chunk (its own
+        // two flags decide, no exchange between the lanes); a chunk's flags are requested one chunk ahead of its
+        // records, and the wavefront puts them back to zero, so that the array is all zeros again when the kernel ends
+        // (the places between lo_all and hi_all are this wavefront's own: no other one looks at their flags).
+        constexpr bool sparse = SPARSE;
+        uint8_t f0 = 0, f1 = 0;
+        auto request_flags = [&](uint32_t cs) {
+            const uint32_t p0 = cs + lane, p1 = cs + 64 + lane;
+            f0 = p0 < hi_all ? rec_valid[p0] : (uint8_t)0;
+            f1 = p1 < hi_all ? rec_valid[p1] : (uint8_t)0;
+        };
         auto request = [&](uint32_t cs) {
-            const uint32_t nq = min((uint32_t)CH, hi_all - cs) * (PAIR_REC / 4);
-            const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
+            if (sparse) {
+                const bool s0 = f0 != 0, s1 = f1 != 0;   // (the flags of chunk cs have arrived; zero beyond hi_all)
+                if (s0) rec_valid[cs + lane] = 0;
+                if (s1) rec_valid[cs + 64 + lane] = 0;
+                const float4* src = pair_grad + ((size_t)cs + lane) * (PAIR_REC / 4);
 #pragma unroll
-            for (int u = 0; u < LPL; u++) {
-                const uint32_t q = lane + 64 * u;
-                v[u] = q < nq ? src[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int k = 0; k < 3; k++) {
+                    v[k] = s0 ? src[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    v[3 + k] = s1 ? src[64 * 3 + k] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            } else {
+                const uint32_t nq = min((uint32_t)CH, hi_all - cs) * (PAIR_REC / 4);
+                const float4* src = pair_grad + (size_t)cs * (PAIR_REC / 4);
+#pragma unroll
+                for (int u = 0; u < LPL; u++) {
+                    const uint32_t q = lane + 64 * u;
+                    v[u] = q < nq ? src[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
         };
-        if (lo_all < hi_all) request(lo_all);
+        if (lo_all < hi_all) {
+            if (sparse) request_flags(lo_all);
+            request(lo_all);
+            if (sparse && lo_all + CH < hi_all) request_flags(lo_all + CH);
+        }
         for (uint32_t cs = lo_all; cs < hi_all; cs += CH) {
             const uint32_t nrec = min((uint32_t)CH, hi_all - cs);
+            if (sparse) {
 #pragma unroll
-            for (int u = 0; u < LPL; u++) {
-                const uint32_t q = lane + 64 * u;
-                if (q < nrec * (PAIR_REC / 4)) buf[q] = v[u];
+                for (int k = 0; k < 3; k++) {
+                    if ((uint32_t)lane < nrec) buf[lane * 3 + k] = v[k];
+                    if ((uint32_t)lane + 64 < nrec) buf[(lane + 64) * 3 + k] = v[3 + k];
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < LPL; u++) {
+                    const uint32_t q = lane + 64 * u;
+                    if (q < nrec * (PAIR_REC / 4)) buf[q] = v[u];
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            if (cs + CH < hi_all) request(cs + CH);
+            if (cs + CH < hi_all) {
+                request(cs + CH);
+                if (sparse && cs + 2 * CH < hi_all) request_flags(cs + 2 * CH);
+            }
             const uint32_t r0 = max(off, cs), r1 = min(off + cnt, cs + nrec);
             // A Gaussian with many records in the chunk (a large splat: one per tile of its rectangle) would keep its
             // lane busy for as many trips while the other 63 wait.  Such runs are added up by the whole wavefront
@@ -686,18 +728,24 @@ hipError_t launch_preprocess(hipStream_t st, int64_t n, int deg, const fs_gaussi
     return hipGetLastError();
 }
 
+// rec_valid: null = dense records (every place of pair_grad holds one), else the flags of the sparse records
 hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_gaussians& g, const CamDev& cam,
                                  const CfgDev& cfg, const uint8_t* clamped, const uint32_t* touched,
                                  const uint32_t* rec_counts, const uint32_t* rec_offsets, const float* pair_grad,
-                                 const fs_grads& o)
+                                 uint8_t* rec_valid, const fs_grads& o)
 {
     if (n == 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
-#define FS_LAUNCH(D)                                                                                      \
-    hipLaunchKernelGGL(k_preprocess_bwd<D>, grid, block, 0, st, n, g.means, g.scales, g.quats, g.opacities, g.sh, \
-                       cam, cfg, clamped, touched, rec_counts, rec_offsets,                                       \
-                       reinterpret_cast<const float4*>(pair_grad), o.dmeans, o.dscales, o.dquats, o.dsh,          \
+#define FS_LAUNCH_S(D, S)                                                                                          \
+    hipLaunchKernelGGL((k_preprocess_bwd<D, S>), grid, block, 0, st, n, g.means, g.scales, g.quats, g.opacities,    \
+                       g.sh, cam, cfg, clamped, touched, rec_counts, rec_offsets,                                   \
+                       reinterpret_cast<const float4*>(pair_grad), rec_valid, o.dmeans, o.dscales, o.dquats, o.dsh, \
                        o.dopacities, o.dmean2d, o.dconic, o.drgb, o.dmean2d_abs)
+#define FS_LAUNCH(D)                         \
+    do {                                     \
+        if (rec_valid) FS_LAUNCH_S(D, true); \
+        else FS_LAUNCH_S(D, false);          \
+    } while (0)
     switch (deg) {
         case 0: FS_LAUNCH(0); break;
         case 1: FS_LAUNCH(1); break;
@@ -705,6 +753,7 @@ hipError_t launch_preprocess_bwd(hipStream_t st, int64_t n, int deg, const fs_ga
         default: FS_LAUNCH(3); break;
     }
 #undef FS_LAUNCH
+#undef FS_LAUNCH_S
     return hipGetLastError();
 }
 

@@ -536,12 +536,12 @@ __device__ __forceinline__ float row_reduce2(float a, float b, int lane)
 // ABS adds the absolute positional gradient (used by FastGS for the split decision): per pixel the
 // magnitudes |dL/dmu_x|, |dL/dmu_y| of its own contribution, summed like the other values and stored
 // in the record's floats 9 and 10.
-template <bool ABS>
+template <bool ABS, bool SPARSE>
 __global__ __launch_bounds__(256) void k_render_bwd(
     CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
     const uint32_t* __restrict__ gauss_sorted,
     const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
-    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
+    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad, uint8_t* __restrict__ rec_valid)
 {
     __shared__ Stage<true> s;
     __shared__ uint32_t s_id[BATCH];
@@ -656,26 +656,39 @@ __global__ __launch_bounds__(256) void k_render_bwd(
             float a[NV];
 #pragma unroll
             for (int k = 0; k < NV; k++) a[k] = (float)s_acc[threadIdx.x][k];
-            const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
-            const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
-            float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
-            rec[0] = make_float4(a[0], a[1], a[2], a[3]);
-            // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
-            rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
-            rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
+            // SPARSE: a pair that received nothing (blended at no pixel of the tile) leaves no record; its flag stays 0
+            // and k_preprocess_bwd does not read the record's place
+            bool any = !SPARSE;
+            if (SPARSE) {
+#pragma unroll
+                for (int k = 0; k < NV; k++) any = any | (a[k] != 0.f);
+            }
+            if (any) {
+                const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
+                const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
+                const uint32_t idx = s_id[threadIdx.x];
+                float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
+                rec[0] = make_float4(a[0], a[1], a[2], a[3]);
+                // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
+                rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
+                rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
+                if (SPARSE) rec_valid[idx] = 1;
+            }
         }
     }
-    // pairs behind the furthest blended Gaussian of the tile received nothing
-    for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
-        const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
-        const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
-        const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
-        const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
-                             ((uint32_t)(tile % cam.tiles_x) - x0);
-        float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
-        rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // pairs behind the furthest blended Gaussian of the tile received nothing (SPARSE: their flags stay 0)
+    if (!SPARSE) {
+        for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
+            const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
+            const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
+            const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
+            const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
+                                 ((uint32_t)(tile % cam.tiles_x) - x0);
+            float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
+            rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
 }
 
@@ -720,12 +733,12 @@ __device__ __forceinline__ void wave_scan_affine(float& m, float& b)
 #undef FS_AFFINE_STEP
 }
 
-template <bool ABS>
+template <bool ABS, bool SPARSE>
 __global__ __launch_bounds__(256) void k_render_bwd_splat(
     CamDev cam, CfgDev cfg, const uint2* __restrict__ ranges, const uint32_t* __restrict__ tile_order,
     const uint32_t* __restrict__ gauss_sorted,
     const float4* __restrict__ splats, const float* __restrict__ final_T, const uint32_t* __restrict__ n_contrib,
-    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad)
+    const float* __restrict__ dL_dimage, float4* __restrict__ pair_grad, uint8_t* __restrict__ rec_valid)
 {
     __shared__ Stage<true> s;
     __shared__ uint32_t s_id[BATCH];
@@ -884,25 +897,39 @@ __global__ __launch_bounds__(256) void k_render_bwd_splat(
             float a[NV];
 #pragma unroll
             for (int k = 0; k < NV; k++) a[k] = (float)s_acc[threadIdx.x][k];
-            const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
-            const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
-            float4* rec = pair_grad + (size_t)s_id[threadIdx.x] * (PAIR_REC / 4);
-            rec[0] = make_float4(a[0], a[1], a[2], a[3]);
-            rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
-            rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
+            // SPARSE: a pair that received nothing (blended at no pixel of the tile) leaves no record; its flag stays 0
+            // and k_preprocess_bwd does not read the record's place
+            bool any = !SPARSE;
+            if (SPARSE) {
+#pragma unroll
+                for (int k = 0; k < NV; k++) any = any | (a[k] != 0.f);
+            }
+            if (any) {
+                const float4 f0 = s.at(threadIdx.x)[0], f1 = s.at(threadIdx.x)[1];
+                const float4 co = make_float4(f0.z, f0.w, f1.x, f1.y);  // (a, 2b, c, sigma)
+                const uint32_t idx = s_id[threadIdx.x];
+                float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
+                rec[0] = make_float4(a[0], a[1], a[2], a[3]);
+                // d = p - mu  =>  dq/dmu = -(2 a dx + 2b dy, 2b dx + 2 c dy)
+                rec[1] = make_float4(a[4], 2.0f * a[5], a[6], -(2.0f * co.x * a[7] + co.y * a[8]));
+                rec[2] = make_float4(-(co.y * a[7] + 2.0f * co.z * a[8]), ABS ? a[NV - 2] : 0.f, ABS ? a[NV - 1] : 0.f, 0.f);
+                if (SPARSE) rec_valid[idx] = 1;
+            }
         }
     }
-    // pairs behind the furthest blended Gaussian of the tile received nothing
-    for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
-        const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
-        const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
-        const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
-        const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
-                             ((uint32_t)(tile % cam.tiles_x) - x0);
-        float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
-        rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
-        rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // pairs behind the furthest blended Gaussian of the tile received nothing (SPARSE: their flags stay 0)
+    if (!SPARSE) {
+        for (uint32_t pos = range.x + total + threadIdx.x; pos < range.y; pos += 256) {
+            const float4 r2 = splats[(size_t)gauss_sorted[pos] * (SPLAT_REC / 4) + 2];
+            const uint32_t r01 = __float_as_uint(r2.z), r23 = __float_as_uint(r2.w);
+            const uint32_t x0 = r01 & 0xffffu, y0 = r01 >> 16, x1 = r23 & 0xffffu;
+            const uint32_t idx = __float_as_uint(r2.y) + ((uint32_t)(tile / cam.tiles_x) - y0) * (x1 - x0) +
+                                 ((uint32_t)(tile % cam.tiles_x) - x0);
+            float4* rec = pair_grad + (size_t)idx * (PAIR_REC / 4);
+            rec[0] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rec[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rec[2] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
 }
 
@@ -1214,7 +1241,8 @@ hipError_t launch_record_rows(hipStream_t st, int tiles, const ScoreRecord& reco
 
 hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cfg, const uint32_t* ranges,
                              const uint32_t* tile_order, const uint32_t* gauss_sorted, const float* splats, const float* final_T,
-                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, bool abs_grad, bool per_splat)
+                             const uint32_t* n_contrib, const float* dL_dimage, float* pair_grad, uint8_t* rec_valid,
+                             bool abs_grad, bool per_splat)
 {
     const int tiles = cam.tiles_x * cam.tiles_y;
     if (tiles == 0) return hipSuccess;
@@ -1222,20 +1250,24 @@ hipError_t launch_render_bwd(hipStream_t st, const CamDev& cam, const CfgDev& cf
     const float4* sp = reinterpret_cast<const float4*>(splats);
     float4* pg = reinterpret_cast<float4*>(pair_grad);
     const dim3 grid(tiles), block(256);
-    if (per_splat) {
-        if (abs_grad)
-            hipLaunchKernelGGL(k_render_bwd_splat<true>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
-                               n_contrib, dL_dimage, pg);
-        else
-            hipLaunchKernelGGL(k_render_bwd_splat<false>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp,
-                               final_T, n_contrib, dL_dimage, pg);
-    } else if (abs_grad) {
-        hipLaunchKernelGGL(k_render_bwd<true>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
-                           n_contrib, dL_dimage, pg);
-    } else {
-        hipLaunchKernelGGL(k_render_bwd<false>, grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T,
-                           n_contrib, dL_dimage, pg);
-    }
+    // rec_valid: null = dense records, else the flags of the sparse records
+#define FS_BWD(KERNEL, ABS, SPARSE)                                                                                  \
+    hipLaunchKernelGGL((KERNEL<ABS, SPARSE>), grid, block, 0, st, cam, cfg, r2, tile_order, gauss_sorted, sp, final_T, \
+                       n_contrib, dL_dimage, pg, rec_valid)
+#define FS_BWD_MODE(KERNEL)                         \
+    do {                                            \
+        if (abs_grad) {                             \
+            if (rec_valid) FS_BWD(KERNEL, true, true);   \
+            else FS_BWD(KERNEL, true, false);       \
+        } else {                                    \
+            if (rec_valid) FS_BWD(KERNEL, false, true);  \
+            else FS_BWD(KERNEL, false, false);      \
+        }                                           \
+    } while (0)
+    if (per_splat) FS_BWD_MODE(k_render_bwd_splat);
+    else FS_BWD_MODE(k_render_bwd);
+#undef FS_BWD_MODE
+#undef FS_BWD
     return hipGetLastError();
 }
 

@@ -35,7 +35,7 @@ GROUPS = {
     "order_pairs": ["k_tile_pairs<false, true>", "k_tile_pairs<true, true>", "k_tile_sort<"],
     "render_fwd": ["k_render_fwd<true, true>"],
     "l1_grad": ["k_fold_tile_stats"],
-    "render_bwd": ["k_render_bwd<false>", "k_render_bwd_splat<false>"],
+    "render_bwd": ["k_render_bwd<false,", "k_render_bwd_splat<false,"],
     "preprocess_bwd": ["k_preprocess_bwd<"],
     "error_mask": ["k_err_mask_stats"],
     "score": ["k_score_bits<true>"],   # (the mask is made inside the count pass: fs_mask_score_fused)

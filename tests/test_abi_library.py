@@ -40,6 +40,7 @@ def test_null_context_is_rejected_without_touching_a_gpu():
     assert lib.fs_bin_sort(None, None, None, 0, None) == -1
     assert lib.fs_last_error(None) == b"null context"
     assert lib.fs_set_score_record(None, 1) == -1 and lib.fs_set_backward_mode(None, 0) == -1
+    assert lib.fs_set_record_mode(None, 0) == -1
 
 
 def test_no_product_code_imports_the_oracle():

@@ -293,8 +293,9 @@ def test_tile_order_is_a_permutation_with_the_longest_lists_first(n, W, H, mode)
     c.close()
 
 
+@pytest.mark.parametrize("records", ["auto", "sparse"])
 @pytest.mark.parametrize("compact_box", [0, 1])
-def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_box):
+def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_box, records):
     """A context keeps its scratch buffers from call to call and grows them when a call needs more. One
     context therefore goes through: a first call, a much larger scene (buffers grow), smaller ones (buffers
     larger than needed), long lists after short ones and short after long (the LDS sort variants), lists beyond
@@ -302,12 +303,16 @@ def test_one_context_through_growing_and_shrinking_pair_counts(orc32, compact_bo
     per-tile ordering on, fs_bin_sort enqueues placement and sorts before it has read the totals back, sized by the
     previous call: every transition above is one where that guess is right, too small, or too large. Keys, order,
     ranges and n_contrib bit-exact every time; on the small scenes the gradients as well (with the Compact Box the
-    placement also zeroes the records of the candidates that are no pairs)."""
+    placement also zeroes the records of the candidates that are no pairs).  records: the layout of the backward
+    pass's per-pair records -- chosen per call by the lists' mean length, or sparse throughout (its flag array, too, is
+    kept from call to call, must grow, and must be all zeros again after every call)."""
     from paper_2511_04283_amd import binding as B
     cfg = B.default_config()
     cfg.compact_box = compact_box
     cfg.cb_beta = 0.7
     c = B.Context("cuda:0", cfg)
+    if records == "sparse":
+        c.fs_set_record_mode(B.FS_RECORDS_SPARSE)
     o = Oracle(np.float32, Config(compact_box=compact_box, cb_beta=0.7)) if compact_box else orc32
     cases = [(700, 2000, 203, 117, (-3.2, 0.7)),    # short lists
              (701, 30000, 203, 117, (-3.2, 0.7)),   # many more pairs: buffers grow
@@ -565,15 +570,17 @@ def test_pair_order_over_seeded_random_shapes(orc32):
 
 
 @pytest.mark.parametrize("per_splat", [False, True])
-def test_whole_path_over_seeded_random_shapes(orc32, per_splat):
+@pytest.mark.parametrize("records", ["dense", "sparse"])
+def test_whole_path_over_seeded_random_shapes(orc32, per_splat, records):
     """Ten seeded small shapes (1 to 2 500 Gaussians, all SH degrees, ragged images) through the whole path with
-    both mappings of the backward pass: every output against the oracle (integers bit-exact, image 1e-4, gradients
-    1e-3 with the floor), the absolute gradient included."""
+    both mappings of the backward pass and both layouts of its per-pair records: every output against the oracle
+    (integers bit-exact, image 1e-4, gradients 1e-3 with the floor), the absolute gradient included."""
     from paper_2511_04283_amd import binding as B
     rng = np.random.default_rng(7 + int(per_splat))
     c = B.Context("cuda:0")
     if per_splat:
         c.fs_set_backward_mode(B.FS_BWD_PER_SPLAT)
+    c.fs_set_record_mode(B.FS_RECORDS_SPARSE if records == "sparse" else B.FS_RECORDS_DENSE)
     for case in range(10):
         n = int(rng.choice([1, 33, 65, 100, 700, 2500]))
         W, H = int(rng.integers(17, 300)), int(rng.integers(17, 200))

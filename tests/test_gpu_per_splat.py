@@ -120,4 +120,8 @@ def test_unknown_backward_mode_is_rejected():
         c.fs_set_backward_mode(7)
     c.fs_set_backward_mode(B.FS_BWD_PER_SPLAT)
     c.fs_set_backward_mode(B.FS_BWD_PER_PIXEL)
+    with pytest.raises(RuntimeError):
+        c.fs_set_record_mode(3)
+    for mode in (B.FS_RECORDS_SPARSE, B.FS_RECORDS_DENSE, B.FS_RECORDS_AUTO):
+        c.fs_set_record_mode(mode)
     c.close()
