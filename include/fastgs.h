@@ -235,9 +235,9 @@ int fs_l1_grad(fs_ctx *ctx, const float *image, const float *target, int32_t hei
  * through the projection to the scene parameters.  final_T / n_contrib are fs_render_fwd's; bins
  * must be the result of the latest fs_bin_sort on this ctx for the same proj: every (Gaussian, tile) pair
  * owns one record of partial sums in ctx scratch, at bins->record_offsets[i] + the tile's place in the
- * Gaussian's rectangle, which the tile's workgroup stores once; the projection's backward kernel then adds up
- * each Gaussian's contiguous records.  No global atomics.  Errors: FS_EINVAL (also: stale bins), FS_ENOMEM,
- * FS_EHIP. */
+ * Gaussian's rectangle, which the tile's workgroup stores once (see fs_set_record_mode for when a pair that received
+ * nothing stores none); the projection's backward kernel then adds up each Gaussian's contiguous records.  No global
+ * atomics.  Errors: FS_EINVAL (also: stale bins), FS_ENOMEM, FS_EHIP. */
 int fs_render_bwd(fs_ctx *ctx, const fs_gaussians *g, const fs_camera *cam, const fs_projected *proj,
                   const fs_bins *bins, const float *final_T, const uint32_t *n_contrib,
                   const float *dL_dimage, fs_grads *out);
