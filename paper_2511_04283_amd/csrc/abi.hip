@@ -47,7 +47,7 @@ struct fs_ctx {
     int spec_set = 0;                    // the sort launches (TS_*) the previous per-tile ordering on this ctx would have
                                          // chosen (0: none): what fs_bin_sort enqueues ahead of its read-back
     uint64_t* total_dev = nullptr;   // device: totals [4]: pairs, backward records, pairs counted per tile, longest tile list
-    uint64_t* total_host = nullptr;  // pinned host copy
+    uint64_t* total_host = nullptr;  // pinned host block of four totals (copied from total_dev, or written by k_tile_scan)
     uint64_t* alloc_dev = nullptr;   // device: the two counters of the counting kernel (zero between calls)
     bool alloc_dirty = false;        // a call failed between the kernel that adds to them and the one that clears them
     ScratchBuf tile_partial;         // double [5, tiles]: per-tile sums of the fused forward pass
@@ -389,7 +389,7 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
         if (ctx->alloc_dirty) FS_HIP(launch_fill_u32(st, reinterpret_cast<uint32_t*>(ctx->alloc_dev), 0u, 4), "k_fill_u32");
         ctx->alloc_dirty = true;
         FS_HIP(launch_tile_count(st, n, proj ? *proj : none, cf, cd.tiles_x, tiles, tcount_p, ttotal_p,
-                                 reinterpret_cast<uint2*>(ranges_p), order_p, ctx->total_dev,
+                                 reinterpret_cast<uint2*>(ranges_p), order_p, ctx->total_host,
                                  static_cast<uint32_t*>(cb ? ctx->rec_offsets.ptr : ctx->offsets.ptr),
                                  cb ? static_cast<uint32_t*>(ctx->rec_counts.ptr) : nullptr, ctx->alloc_dev),
                "k_tile_pairs (count)");
@@ -397,8 +397,11 @@ int fs_bin_sort(fs_ctx* ctx, const fs_projected* proj, const fs_camera* cam, int
     } else {
         FS_TRY(prefix_sums());
     }
-    FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
-           "hipMemcpyAsync");
+    // (the per-tile ordering's scan kernel stores its four totals straight into the pinned host block, which the
+    // device can address: a copy behind it would be one more small kernel in front of the placement)
+    if (!bucketed)
+        FS_HIP(hipMemcpyAsync(ctx->total_host, ctx->total_dev, 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st),
+               "hipMemcpyAsync");
     FS_HIP(hipEventRecord(ctx->totals_event, st), "hipEventRecord");
     // Per-tile ordering, second half (placement into the tiles' segments -- keys[1] serves as the bucket array -- and
     // the per-tile LDS sorts; the ranges are already in place).  When this ctx has ordered pairs per tile before, the
