@@ -17,6 +17,8 @@
  *   fs_score_accumulate  per-Gaussian count of high-error pixels it contributes to,
  *                        one view per call                                      (Sec. 4.2, Eq. for s_d)
  *   fs_set_score_record  whether the forward passes keep the per-pair record that this count is taken from
+ *   fs_mask_score_fused  fs_error_mask_fused + fs_score_accumulate as one call (one kernel launch with the record)
+ *   fs_score_record_rows how many pairs of every tile that record holds a row for (a diagnostic)
  *   fs_photo_loss        E = (1-lambda) L1 + lambda (1 - SSIM) and dE/dC        (Sec. 4.3 E_photo; Sec. 4.5 Eq. for L)
  *   fs_prune_score_accumulate / fs_prune_score_normalize
  *                        s_p = N(sum over views of count * E_photo)             (Sec. 4.3, Eq. for s_p)
